@@ -1,0 +1,146 @@
+/*
+ * detonation.h — C ABI of the MI355X (gfx950) library for the per-step optimizer
+ * hot path of FlexDeMo / DeMo-SGD (arXiv 2502.06728, Algorithm 1) on one GPU's
+ * flat FSDP shard.
+ *
+ * The step has two halves with the inter-node exchange between them:
+ *
+ *   detonation_compress          m <- beta*m + g;  q <- ExtractFastComponents(m,s,k);
+ *                                m <- m - q;  emit q as a sparse payload
+ *   (all_gather of payloads over the replication group R — not part of this library)
+ *   detonation_decompress_step   Q <- mean of R payloads, back in parameter space,
+ *                                optional sign;  theta <- theta*(1-eta*lambda) - eta*Q
+ *
+ * Notation: n = shard length, s = chunk size, k = TopK, C = ceil(n/s) chunks.  The
+ * shard is cut into chunks of s consecutive elements, ignoring tensor boundaries;
+ * the last chunk is zero-extended and its pad positions are never written.  The
+ * transform is the orthonormal DCT-II  D[j][i] = a_j cos(pi (2i+1) j / (2s)),
+ * a_0 = sqrt(1/s), a_j = sqrt(2/s); its inverse is its transpose.
+ *
+ * Common rules for every entry point
+ *   - All data pointers are DEVICE pointers on the current HIP device.  `cfg` is a
+ *     HOST pointer, read before the call returns.
+ *   - The caller owns every buffer and keeps it alive until `stream` has run the
+ *     call.  The library allocates nothing, keeps no state between calls and never
+ *     synchronises: work is enqueued on `stream` (a hipStream_t; NULL = the default
+ *     stream) and the call returns.
+ *   - The return value is a deto_status.  Host-side arguments are validated; device
+ *     data is not (an out-of-range payload index is skipped, not reported).
+ *   - Buffers must not overlap each other.
+ */
+#ifndef DETONATION_H
+#define DETONATION_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DETO_OK = 0,
+    DETO_ERR_NULL = 1,         /* a required pointer is NULL */
+    DETO_ERR_BAD_CONFIG = 2,   /* chunk/topk/scheme/dtype/R/n/stride out of range */
+    DETO_ERR_UNSUPPORTED = 3,  /* valid request this build has no kernel for */
+    DETO_ERR_ALIGN = 4,        /* a pointer is not aligned to its element size */
+    DETO_ERR_HIP = 5           /* the HIP runtime refused the launch */
+} deto_status;
+
+/* Replication scheme (paper, "Replication Schemes").
+ *   TOPK   : DeMo — the k largest-magnitude DCT coefficients of each chunk; ties go
+ *            to the lower index.  Indices are part of the payload.
+ *   STRIDE : every (s/k)-th position of each chunk, indices o + j*floor(s/k),
+ *            o = step mod floor(s/k).  Indices are not transmitted.
+ *   RANDOM : k distinct positions per chunk, the first k places of a Fisher-Yates
+ *            shuffle driven by a counter-based generator keyed (seed, step, chunk),
+ *            so every replica regenerates them.  Indices are not transmitted. */
+typedef enum { DETO_SCHEME_TOPK = 0, DETO_SCHEME_STRIDE = 1, DETO_SCHEME_RANDOM = 2 } deto_scheme;
+
+typedef enum { DETO_F32 = 0, DETO_BF16 = 1 } deto_dtype;
+
+enum {
+    DETO_FLAG_SIGN = 1u, /* apply sign() (sign(0)=0) to the averaged update before the
+                            parameter step (paper, "Overall Setup", Appendix B) */
+    DETO_FLAG_DCT = 2u   /* STRIDE/RANDOM pick DCT coefficients instead of raw momentum
+                            entries.  TOPK always works on coefficients. */
+};
+
+typedef struct {
+    int32_t chunk;        /* s, 1..256 (the paper sweeps 16..256, Appendix B) */
+    int32_t topk;         /* k, 1..s; compression rate = k/s */
+    int32_t scheme;       /* deto_scheme */
+    uint32_t flags;       /* DETO_FLAG_* */
+    float decay;          /* beta, Algorithm 1 */
+    float lr;             /* eta, Algorithm 1 */
+    float weight_decay;   /* lambda, decoupled: theta*(1 - eta*lambda) */
+    uint64_t seed;        /* RANDOM: shared by all replicas */
+    uint64_t step;        /* optimizer step: STRIDE offset, RANDOM stream */
+} deto_config;
+
+/*
+ * Compress half (Algorithm 1: accumulate, ExtractFastComponents, remove q from m).
+ *
+ *   m1 = beta*momentum + grad                       (fp32)
+ *   c  = D * m1 per chunk           (or c = m1 for STRIDE/RANDOM without DETO_FLAG_DCT)
+ *   I  = the k indices the scheme keeps in each chunk, ascending
+ *   val_out[ch*k + j] = c[ch][I_j],  idx_out[ch*k + j] = I_j   (chunk-local, 0..s-1)
+ *   momentum = m1 - D^T * (c restricted to I)       (in place)
+ *
+ *   grad        device, [n] of grad_dtype (deto_dtype), read only
+ *   momentum    device, [n] fp32, in: m_t, out: m_{t+1}
+ *   idx_out     device, [C*k] int32; may be NULL for STRIDE/RANDOM
+ *   val_out     device, [C*k] fp32
+ *   coeff_dbg   device, [C*s] fp32 or NULL: receives c (zero-extended last chunk).
+ *               For parity checks only; leave NULL when timing.
+ *
+ * Errors: DETO_ERR_NULL (cfg, grad, momentum, val_out, or idx_out for TOPK, is NULL
+ * while n > 0), DETO_ERR_BAD_CONFIG, DETO_ERR_ALIGN, DETO_ERR_HIP.  n = 0 is a no-op.
+ */
+int detonation_compress(const deto_config* cfg, int64_t n,
+                        const void* grad, int grad_dtype,
+                        float* momentum,
+                        int32_t* idx_out, float* val_out,
+                        float* coeff_dbg,
+                        void* stream);
+
+/*
+ * Decompress-and-update half (Algorithm 1: Synchronize result -> parameter update).
+ *
+ *   a[ch][i] = (1/R) * sum_r sum_j [idx[r][ch][j] == i] * val[r][ch][j]
+ *   y  = D^T * a per chunk          (or y = a without the DCT domain)
+ *   Q  = sign(y) if DETO_FLAG_SIGN else y
+ *   params = round_to_dtype( params*(1 - eta*lambda) - eta*Q )   (in place)
+ *
+ *   R           number of replica payloads, 1..64
+ *   idx         device, replica r at idx + r*idx_replica_stride, each [C*k] int32 as an
+ *               all_gather leaves them; NULL for STRIDE/RANDOM (indices regenerated from
+ *               cfg, identical for every replica).  Duplicate indices add; indices
+ *               outside [0,s) are skipped.
+ *   val         device, replica r at val + r*val_replica_stride, each [C*k] fp32
+ *   strides     in elements, >= C*k (ignored when R == 1)
+ *   params      device, [n] of param_dtype, updated in place (bf16: round to nearest even)
+ *   presign_dbg device, [n] fp32 or NULL: receives y.  Parity checks only.
+ *
+ * Errors as for detonation_compress.  n = 0 is a no-op.
+ */
+int detonation_decompress_step(const deto_config* cfg, int64_t n, int32_t R,
+                               const int32_t* idx, int64_t idx_replica_stride,
+                               const float* val, int64_t val_replica_stride,
+                               void* params, int param_dtype,
+                               float* presign_dbg,
+                               void* stream);
+
+/* Payload entries per replica, ceil(n/s)*k (the paper's compression rate k/s times the
+ * padded shard length); -1 if cfg is invalid. */
+int64_t detonation_payload_entries(const deto_config* cfg, int64_t n);
+
+/* Static, human-readable name of a deto_status. */
+const char* detonation_status_string(int status);
+
+/* ABI version of this header: major*1000 + minor. */
+int detonation_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DETONATION_H */
