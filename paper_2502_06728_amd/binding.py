@@ -1,0 +1,150 @@
+"""ctypes binding of the C-ABI library (include/detonation.h).
+
+Argument marshalling only: device tensors in, raw pointers out; every step of the path
+runs in the HIP kernels.  There is no CPU fallback — if the library has not been built
+the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdetonation.so")
+
+SCHEME_TOPK, SCHEME_STRIDE, SCHEME_RANDOM = 0, 1, 2
+F32, BF16 = 0, 1
+FLAG_SIGN, FLAG_DCT = 1, 2
+
+EXPORTS = ("detonation_compress", "detonation_decompress_step", "detonation_payload_entries",
+           "detonation_status_string", "detonation_version")
+
+
+class deto_config(ctypes.Structure):
+    _fields_ = [("chunk", ctypes.c_int32), ("topk", ctypes.c_int32), ("scheme", ctypes.c_int32),
+                ("flags", ctypes.c_uint32), ("decay", ctypes.c_float), ("lr", ctypes.c_float),
+                ("weight_decay", ctypes.c_float), ("seed", ctypes.c_uint64),
+                ("step", ctypes.c_uint64)]
+
+
+@dataclass
+class Config:
+    """Host-side mirror of deto_config (Algorithm 1's eta, beta, s, k plus scheme and flags)."""
+    chunk: int = 64
+    topk: int = 8
+    scheme: int = SCHEME_TOPK
+    sign: bool = True
+    dct: bool = False
+    decay: float = 0.999
+    lr: float = 1e-3
+    weight_decay: float = 0.0
+    seed: int = 0
+    step: int = 0
+
+    def c(self) -> deto_config:
+        flags = (FLAG_SIGN if self.sign else 0) | (FLAG_DCT if self.dct else 0)
+        return deto_config(self.chunk, self.topk, self.scheme, flags, self.decay, self.lr,
+                           self.weight_decay, self.seed, self.step)
+
+
+class DetonationError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"detonation status {status}: {status_string(status)}")
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load libdetonation.so; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2502_06728_amd.build`")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+        cfgp = ctypes.POINTER(deto_config)
+        lib.detonation_compress.argtypes = [cfgp, i64, vp, ctypes.c_int, vp, vp, vp, vp, vp]
+        lib.detonation_compress.restype = ctypes.c_int
+        lib.detonation_decompress_step.argtypes = [cfgp, i64, i32, vp, i64, vp, i64, vp,
+                                                   ctypes.c_int, vp, vp]
+        lib.detonation_decompress_step.restype = ctypes.c_int
+        lib.detonation_payload_entries.argtypes = [cfgp, i64]
+        lib.detonation_payload_entries.restype = i64
+        lib.detonation_status_string.argtypes = [ctypes.c_int]
+        lib.detonation_status_string.restype = ctypes.c_char_p
+        lib.detonation_version.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load().detonation_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(load().detonation_version())
+
+
+def payload_entries(cfg: Config, n: int) -> int:
+    return int(load().detonation_payload_entries(ctypes.byref(cfg.c()), n))
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _dtype(t) -> int:
+    import torch
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _stream(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    h = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+    return ctypes.c_void_p(h)
+
+
+def _check(*tensors):
+    for t in tensors:
+        if t is not None and (not t.is_cuda or not t.is_contiguous()):
+            raise ValueError("tensors must be contiguous device tensors")
+
+
+def detonation_compress(cfg: Config, grad, momentum, idx_out, val_out, coeff_dbg=None,
+                        stream=None, n: int | None = None) -> None:
+    """Enqueue the compress half on `stream`.  momentum, idx_out, val_out (and coeff_dbg)
+    are written in place by the kernels."""
+    _check(grad, momentum, idx_out, val_out, coeff_dbg)
+    n = momentum.numel() if n is None else n
+    rc = load().detonation_compress(ctypes.byref(cfg.c()), n, _ptr(grad), _dtype(grad),
+                                    _ptr(momentum), _ptr(idx_out), _ptr(val_out),
+                                    _ptr(coeff_dbg), _stream(stream))
+    if rc != 0:
+        raise DetonationError(rc)
+
+
+def detonation_decompress_step(cfg: Config, R: int, idx, val, params, presign_dbg=None,
+                               stream=None, n: int | None = None,
+                               idx_replica_stride: int | None = None,
+                               val_replica_stride: int | None = None) -> None:
+    """Enqueue the decompress-and-update half on `stream`.  idx/val hold R payloads
+    (replica r at offset r*stride); params is updated in place."""
+    _check(idx, val, params, presign_dbg)
+    n = params.numel() if n is None else n
+    entries = payload_entries(cfg, n)
+    vs = entries if val_replica_stride is None else val_replica_stride
+    istr = entries if idx_replica_stride is None else idx_replica_stride
+    rc = load().detonation_decompress_step(ctypes.byref(cfg.c()), n, R, _ptr(idx), istr, _ptr(val),
+                                           vs, _ptr(params), _dtype(params), _ptr(presign_dbg),
+                                           _stream(stream))
+    if rc != 0:
+        raise DetonationError(rc)

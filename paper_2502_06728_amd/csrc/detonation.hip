@@ -1,0 +1,156 @@
+// C ABI of the library (see include/detonation.h): argument validation, resolution of
+// deto_config into kernel parameters, kernel selection and launch.  Nothing here computes
+// on the host and nothing is allocated; every call only enqueues kernels on the caller's
+// stream.
+#include "../../include/detonation.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+
+#include "deto_device.hip.h"
+#include "generic_kernels.hip.h"
+
+namespace {
+
+using deto::KParams;
+
+int validate(const deto_config* cfg) {
+    if (!cfg) return DETO_ERR_NULL;
+    if (cfg->chunk < 1 || cfg->chunk > deto::kMaxChunk) return DETO_ERR_BAD_CONFIG;
+    if (cfg->topk < 1 || cfg->topk > cfg->chunk) return DETO_ERR_BAD_CONFIG;
+    if (cfg->scheme < DETO_SCHEME_TOPK || cfg->scheme > DETO_SCHEME_RANDOM)
+        return DETO_ERR_BAD_CONFIG;
+    if (cfg->flags & ~(DETO_FLAG_SIGN | DETO_FLAG_DCT)) return DETO_ERR_BAD_CONFIG;
+    if (!std::isfinite(cfg->decay) || !std::isfinite(cfg->lr) || !std::isfinite(cfg->weight_decay))
+        return DETO_ERR_BAD_CONFIG;
+    return DETO_OK;
+}
+
+bool valid_dtype(int d) { return d == DETO_F32 || d == DETO_BF16; }
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+size_t elem_size(int dtype) { return dtype == DETO_BF16 ? 2 : 4; }
+
+KParams resolve(const deto_config* cfg, int R) {
+    KParams p;
+    p.s = cfg->chunk;
+    p.k = cfg->topk;
+    p.scheme = cfg->scheme;
+    p.use_dct = (cfg->scheme == DETO_SCHEME_TOPK || (cfg->flags & DETO_FLAG_DCT)) ? 1 : 0;
+    p.use_sign = (cfg->flags & DETO_FLAG_SIGN) ? 1 : 0;
+    p.R = R;
+    p.beta = cfg->decay;
+    p.lr = cfg->lr;
+    p.wd_scale = static_cast<float>(1.0 - static_cast<double>(cfg->lr) *
+                                              static_cast<double>(cfg->weight_decay));
+    p.alpha0 = static_cast<float>(std::sqrt(1.0 / cfg->chunk));
+    p.alpha = static_cast<float>(std::sqrt(2.0 / cfg->chunk));
+    p.inv_R = static_cast<float>(1.0 / R);
+    p.seed = cfg->seed;
+    p.step = cfg->step;
+    return p;
+}
+
+int64_t chunks_of(int64_t n, int s) { return (n + s - 1) / s; }
+
+unsigned grid_for(int64_t chunks) {
+    const int64_t cap = 256 * 32;  // 256 CUs, several single-wave workgroups each
+    return static_cast<unsigned>(chunks < cap ? chunks : cap);
+}
+
+int launched() { return hipGetLastError() == hipSuccess ? DETO_OK : DETO_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+int detonation_compress(const deto_config* cfg, int64_t n, const void* grad, int grad_dtype,
+                        float* momentum, int32_t* idx_out, float* val_out, float* coeff_dbg,
+                        void* stream) {
+    int rc = validate(cfg);
+    if (rc) return rc;
+    if (n < 0 || !valid_dtype(grad_dtype)) return DETO_ERR_BAD_CONFIG;
+    if (n == 0) return DETO_OK;
+    if (!grad || !momentum || !val_out) return DETO_ERR_NULL;
+    if (cfg->scheme == DETO_SCHEME_TOPK && !idx_out) return DETO_ERR_NULL;
+    if (!aligned(grad, elem_size(grad_dtype)) || !aligned(momentum, 4) || !aligned(val_out, 4) ||
+        !aligned(idx_out, 4) || !aligned(coeff_dbg, 4))
+        return DETO_ERR_ALIGN;
+
+    const KParams p = resolve(cfg, 1);
+    const int64_t C = chunks_of(n, p.s);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    const int64_t c0 = 0;
+    if (c0 < C) {
+        const unsigned grid = grid_for(C - c0);
+        if (grad_dtype == DETO_BF16)
+            deto::compress_generic<true><<<grid, deto::kWave, 0, st>>>(
+                p, n, c0, C, grad, momentum, idx_out, val_out, coeff_dbg);
+        else
+            deto::compress_generic<false><<<grid, deto::kWave, 0, st>>>(
+                p, n, c0, C, grad, momentum, idx_out, val_out, coeff_dbg);
+        rc = launched();
+    }
+    return rc;
+}
+
+int detonation_decompress_step(const deto_config* cfg, int64_t n, int32_t R, const int32_t* idx,
+                               int64_t idx_replica_stride, const float* val,
+                               int64_t val_replica_stride, void* params, int param_dtype,
+                               float* presign_dbg, void* stream) {
+    int rc = validate(cfg);
+    if (rc) return rc;
+    if (n < 0 || !valid_dtype(param_dtype) || R < 1 || R > 64) return DETO_ERR_BAD_CONFIG;
+    if (n == 0) return DETO_OK;
+    if (!val || !params) return DETO_ERR_NULL;
+    if (cfg->scheme == DETO_SCHEME_TOPK && !idx) return DETO_ERR_NULL;
+    if (!aligned(params, elem_size(param_dtype)) || !aligned(val, 4) || !aligned(idx, 4) ||
+        !aligned(presign_dbg, 4))
+        return DETO_ERR_ALIGN;
+
+    const KParams p = resolve(cfg, R);
+    const int64_t C = chunks_of(n, p.s);
+    const int64_t entries = C * p.k;
+    if (R > 1 && (val_replica_stride < entries || (idx && idx_replica_stride < entries)))
+        return DETO_ERR_BAD_CONFIG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    const int64_t c0 = 0;
+    if (c0 < C) {
+        const unsigned grid = grid_for(C - c0);
+        if (param_dtype == DETO_BF16)
+            deto::decompress_generic<true><<<grid, deto::kWave, 0, st>>>(
+                p, n, c0, C, idx, idx_replica_stride, val, val_replica_stride, params,
+                presign_dbg);
+        else
+            deto::decompress_generic<false><<<grid, deto::kWave, 0, st>>>(
+                p, n, c0, C, idx, idx_replica_stride, val, val_replica_stride, params,
+                presign_dbg);
+        rc = launched();
+    }
+    return rc;
+}
+
+int64_t detonation_payload_entries(const deto_config* cfg, int64_t n) {
+    if (validate(cfg) != DETO_OK || n < 0) return -1;
+    return chunks_of(n, cfg->chunk) * cfg->topk;
+}
+
+const char* detonation_status_string(int status) {
+    switch (status) {
+        case DETO_OK: return "ok";
+        case DETO_ERR_NULL: return "a required pointer is NULL";
+        case DETO_ERR_BAD_CONFIG: return "bad configuration or size";
+        case DETO_ERR_UNSUPPORTED: return "unsupported request";
+        case DETO_ERR_ALIGN: return "misaligned pointer";
+        case DETO_ERR_HIP: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+int detonation_version(void) { return 1000; }
+
+}  // extern "C"

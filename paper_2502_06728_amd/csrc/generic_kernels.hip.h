@@ -1,0 +1,230 @@
+// General kernels: any chunk size 1..256, any k, every scheme and dtype, ragged last chunk.
+// One 64-lane wavefront owns one chunk at a time (lane = element, element e + 64*r for
+// longer chunks) and walks the chunk range with a grid stride.  The DCT is the direct
+// O(s^2) sum over a cosine table held in LDS.  These kernels cover what the tiled
+// kernels do not (odd chunk sizes, the tail of a shard, unaligned buffers); they follow
+// Algorithm 1 of the paper step by step.
+#pragma once
+
+#include "deto_device.hip.h"
+
+namespace deto {
+
+// cos(pi*t/(2s)) for t in [0, 4s): every DCT-II matrix entry is alpha_j * tab[(2i+1)j mod 4s].
+__device__ __forceinline__ void build_cos_table(float* tab, int s, int lane) {
+    for (int t = lane; t < 4 * s; t += kWave)
+        tab[t] = static_cast<float>(cos(3.14159265358979323846 * static_cast<double>(t) /
+                                        (2.0 * static_cast<double>(s))));
+}
+
+// Striding / Random: flag[e] = 1 for the positions the scheme keeps in chunk `c`.
+// Random runs the first k steps of a Fisher-Yates shuffle on one lane.
+__device__ __forceinline__ void scheme_flags(const KParams& p, int64_t c, int lane, int* perm,
+                                             int* flag) {
+    const int s = p.s, k = p.k;
+    if (p.scheme == 1) {
+        const int stride = s / k;
+        const int off = static_cast<int>(p.step % static_cast<uint64_t>(stride));
+        for (int e = lane; e < s; e += kWave) {
+            const int d = e - off;
+            flag[e] = (d >= 0 && d % stride == 0 && d / stride < k) ? 1 : 0;
+        }
+    } else {
+        for (int e = lane; e < s; e += kWave) {
+            perm[e] = e;
+            flag[e] = 0;
+        }
+        __syncthreads();
+        if (lane == 0) {
+            const uint64_t key = chunk_key(p.seed, p.step, static_cast<uint64_t>(c));
+            for (int j = 0; j < k; ++j) {
+                const int t = j + static_cast<int>(bounded(draw(key, j), s - j));
+                const int tmp = perm[j];
+                perm[j] = perm[t];
+                perm[t] = tmp;
+            }
+            for (int j = 0; j < k; ++j) flag[perm[j]] = 1;
+        }
+    }
+    __syncthreads();
+}
+
+// Turn flags into the ascending list sidx[0..k) (and copy the matching values).
+__device__ __forceinline__ void compact_flags(int s, int lane, const int* flag, const float* cf,
+                                              int* sidx, float* sval) {
+    int before = 0;
+    for (int e0 = 0; e0 < s; e0 += kWave) {
+        const int e = e0 + lane;
+        const bool f = (e < s) && flag[e] != 0;
+        const uint64_t mask = __ballot(f);
+        const int pos = before + __popcll(mask & ((1ull << lane) - 1ull));
+        if (f) {
+            sidx[pos] = e;
+            if (cf) sval[pos] = cf[e];
+        }
+        before += __popcll(mask);
+    }
+    __syncthreads();
+}
+
+// Compress half for chunks [chunk_begin, chunk_end).
+template <bool GRAD_BF16>
+__global__ __launch_bounds__(kWave) void compress_generic(KParams p, int64_t n,
+                                                          int64_t chunk_begin, int64_t chunk_end,
+                                                          const void* __restrict__ grad,
+                                                          float* __restrict__ mom,
+                                                          int32_t* __restrict__ idx_out,
+                                                          float* __restrict__ val_out,
+                                                          float* __restrict__ coeff_dbg) {
+    __shared__ float tab[4 * kMaxChunk];
+    __shared__ float x[kMaxChunk];
+    __shared__ float cf[kMaxChunk];
+    __shared__ float sval[kMaxChunk];
+    __shared__ int flag[kMaxChunk];
+    __shared__ int sidx[kMaxChunk];
+    __shared__ int perm[kMaxChunk];
+
+    const int lane = threadIdx.x;
+    const int s = p.s, k = p.k;
+    if (p.use_dct) build_cos_table(tab, s, lane);
+    __syncthreads();
+
+    for (int64_t c = chunk_begin + blockIdx.x; c < chunk_end; c += gridDim.x) {
+        const int64_t base = c * s;
+        // m1 = beta*m + g, zero beyond the shard
+        for (int e = lane; e < s; e += kWave) {
+            const int64_t i = base + e;
+            float v = 0.0f;
+            if (i < n) {
+                const float g = GRAD_BF16 ? bf16_to_f32(static_cast<const uint16_t*>(grad)[i])
+                                          : static_cast<const float*>(grad)[i];
+                v = fmaf(p.beta, mom[i], g);
+            }
+            x[e] = v;
+        }
+        __syncthreads();
+        // coefficients
+        for (int e = lane; e < s; e += kWave) {
+            float acc;
+            if (p.use_dct) {
+                acc = 0.0f;
+                int ph = e;
+                for (int t = 0; t < s; ++t) {
+                    acc = fmaf(x[t], tab[ph], acc);
+                    ph += 2 * e;
+                    if (ph >= 4 * s) ph -= 4 * s;
+                }
+                acc *= (e == 0) ? p.alpha0 : p.alpha;
+            } else {
+                acc = x[e];
+            }
+            cf[e] = acc;
+            if (coeff_dbg) coeff_dbg[base + e] = acc;
+        }
+        __syncthreads();
+        // which entries are kept
+        if (p.scheme == 0) {
+            for (int e = lane; e < s; e += kWave) {
+                const uint32_t me = __float_as_uint(cf[e]) & 0x7FFFFFFFu;
+                int rank = 0;
+                for (int t = 0; t < s; ++t) {
+                    const uint32_t o = __float_as_uint(cf[t]) & 0x7FFFFFFFu;
+                    rank += (o > me || (o == me && t < e)) ? 1 : 0;
+                }
+                flag[e] = rank < k ? 1 : 0;
+            }
+            __syncthreads();
+        } else {
+            scheme_flags(p, c, lane, perm, flag);
+        }
+        compact_flags(s, lane, flag, cf, sidx, sval);
+        for (int j = lane; j < k; j += kWave) {
+            if (idx_out) idx_out[c * k + j] = sidx[j];
+            val_out[c * k + j] = sval[j];
+        }
+        // m <- m1 - q
+        for (int e = lane; e < s; e += kWave) {
+            const int64_t i = base + e;
+            if (i >= n) continue;
+            float q;
+            if (p.use_dct) {
+                q = 0.0f;
+                for (int j = 0; j < k; ++j) {
+                    const int r = sidx[j];
+                    const float a = (r == 0) ? p.alpha0 : p.alpha;
+                    q = fmaf(tab[((2 * e + 1) * r) % (4 * s)], a * sval[j], q);
+                }
+            } else {
+                q = flag[e] ? x[e] : 0.0f;
+            }
+            mom[i] = x[e] - q;
+        }
+        __syncthreads();
+    }
+}
+
+// Decompress-and-update half for chunks [chunk_begin, chunk_end).
+template <bool PARAM_BF16>
+__global__ __launch_bounds__(kWave) void decompress_generic(
+    KParams p, int64_t n, int64_t chunk_begin, int64_t chunk_end, const int32_t* __restrict__ idx,
+    int64_t idx_stride, const float* __restrict__ val, int64_t val_stride,
+    void* __restrict__ params, float* __restrict__ presign_dbg) {
+    __shared__ float tab[4 * kMaxChunk];
+    __shared__ float a[kMaxChunk];
+    __shared__ int flag[kMaxChunk];
+    __shared__ int sidx[kMaxChunk];
+    __shared__ int perm[kMaxChunk];
+
+    const int lane = threadIdx.x;
+    const int s = p.s, k = p.k;
+    if (p.use_dct) build_cos_table(tab, s, lane);
+    __syncthreads();
+
+    for (int64_t c = chunk_begin + blockIdx.x; c < chunk_end; c += gridDim.x) {
+        const int64_t base = c * s;
+        for (int e = lane; e < s; e += kWave) a[e] = 0.0f;
+        if (!idx) {
+            scheme_flags(p, c, lane, perm, flag);
+            compact_flags(s, lane, flag, nullptr, sidx, nullptr);
+        } else {
+            __syncthreads();
+        }
+        // scatter-add, one replica after the other so the order of additions is fixed
+        for (int r = 0; r < p.R; ++r) {
+            for (int j = lane; j < k; j += kWave) {
+                const int at = idx ? idx[r * idx_stride + c * k + j] : sidx[j];
+                if (at >= 0 && at < s) atomicAdd(&a[at], val[r * val_stride + c * k + j]);
+            }
+            __syncthreads();
+        }
+        for (int e = lane; e < s; e += kWave) {
+            const int64_t i = base + e;
+            if (i >= n) continue;
+            float y;
+            if (p.use_dct) {
+                y = 0.0f;
+                int ph = 0;
+                for (int j = 0; j < s; ++j) {
+                    const float al = (j == 0) ? p.alpha0 : p.alpha;
+                    y = fmaf(tab[ph], al * (a[j] * p.inv_R), y);
+                    ph += 2 * e + 1;
+                    if (ph >= 4 * s) ph -= 4 * s;
+                }
+            } else {
+                y = a[e] * p.inv_R;
+            }
+            if (presign_dbg) presign_dbg[i] = y;
+            const float q = sign_or_self(y, p.use_sign);
+            if (PARAM_BF16) {
+                uint16_t* th = static_cast<uint16_t*>(params);
+                th[i] = f32_to_bf16(fmaf(-p.lr, q, bf16_to_f32(th[i]) * p.wd_scale));
+            } else {
+                float* th = static_cast<float*>(params);
+                th[i] = fmaf(-p.lr, q, th[i] * p.wd_scale);
+            }
+        }
+        __syncthreads();
+    }
+}
+
+}  // namespace deto

@@ -1,0 +1,88 @@
+"""The C-ABI library loads, exports every symbol include/detonation.h declares, and its
+host-side validation answers without touching a GPU (these calls return before any launch)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2502_06728_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2502_06728_amd import build
+        build.build()
+    return binding.load()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "detonation.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(detonation_\w+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_version_and_status_strings(lib):
+    assert binding.version() == 1000
+    assert binding.status_string(0) == "ok"
+    assert len({binding.status_string(i) for i in range(6)}) == 6
+
+
+def test_config_struct_layout_matches_header():
+    assert ctypes.sizeof(binding.deto_config) == 48
+    assert binding.deto_config.seed.offset == 32 and binding.deto_config.step.offset == 40
+
+
+def test_payload_entries(lib):
+    cfg = binding.Config(chunk=32, topk=4)
+    assert binding.payload_entries(cfg, 10_820_957) == 338_155 * 4
+    assert binding.payload_entries(cfg, 0) == 0
+    assert binding.payload_entries(binding.Config(chunk=64, topk=65), 100) == -1
+
+
+def _compress(lib, cfg, n, grad=1024, mom=1024, idx=1024, val=1024, dtype=0):
+    vp = ctypes.c_void_p
+    return lib.detonation_compress(ctypes.byref(cfg.c()) if cfg else None, n, vp(grad), dtype,
+                                   vp(mom), vp(idx), vp(val), None, None)
+
+
+def test_host_side_validation(lib):
+    ok = binding.Config(chunk=64, topk=8)
+    assert _compress(lib, None, 10) == 1
+    assert _compress(lib, ok, 10, grad=None) == 1
+    assert _compress(lib, ok, 10, idx=None) == 1                      # top-k needs idx_out
+    assert _compress(lib, binding.Config(chunk=0, topk=1), 10) == 2
+    assert _compress(lib, binding.Config(chunk=257, topk=1), 10) == 2
+    assert _compress(lib, binding.Config(chunk=64, topk=0), 10) == 2
+    assert _compress(lib, binding.Config(chunk=64, topk=8, scheme=3), 10) == 2
+    assert _compress(lib, ok, -1) == 2
+    assert _compress(lib, ok, 10, dtype=9) == 2
+    assert _compress(lib, ok, 10, mom=1026) == 4                      # fp32 buffer off by 2 bytes
+    assert _compress(lib, ok, 0, grad=None, mom=None, idx=None, val=None) == 0   # n = 0: no-op
+    vp = ctypes.c_void_p
+    d = lib.detonation_decompress_step
+    c = ctypes.byref(ok.c())
+    assert d(c, 10, 0, vp(1024), 8, vp(1024), 8, vp(1024), 0, None, None) == 2   # R < 1
+    assert d(c, 10, 65, vp(1024), 8, vp(1024), 8, vp(1024), 0, None, None) == 2  # R too large
+    assert d(c, 10, 2, vp(1024), 4, vp(1024), 8, vp(1024), 0, None, None) == 2   # stride < C*k
+    assert d(c, 10, 1, None, 8, vp(1024), 8, vp(1024), 0, None, None) == 1       # top-k needs idx
+    assert d(c, 10, 1, vp(1024), 8, vp(1024), 8, vp(1025), 1, None, None) == 4   # bf16 off by 1
+    assert d(c, 0, 1, None, 0, None, 0, None, 0, None, None) == 0
+
+
+def test_binding_refuses_host_tensors(lib):
+    import torch
+    cfg = binding.Config()
+    t = torch.zeros(64)
+    with pytest.raises(ValueError):
+        binding.detonation_compress(cfg, t, t, t.int(), t)

@@ -1,0 +1,209 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the
+same seeded inputs (staged protocol of tests/parity.py)."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import Config, SCHEME_RANDOM, SCHEME_STRIDE, SCHEME_TOPK
+from paper_2502_06728_amd import synth
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H(gpu):
+    from tests import gpu_harness
+    from paper_2502_06728_amd import binding
+    binding.load()
+    return gpu_harness
+
+
+def make_inputs(n, seed=0, grad_bf16=False, params_bf16=False, outliers=0.0):
+    w = synth.Workload("t", n, grad_bf16=grad_bf16, params_bf16=params_bf16,
+                       outlier_frac=outliers, seed=seed)
+    return synth.shard(w)
+
+
+def full_step(H, cfg, n, R=1, seed=0, grad_bf16=False, params_bf16=False, outliers=0.0):
+    """One whole step on both sides.  Replica 0's payload is the shard's own; replicas
+    1..R-1 come from the oracle's compress on independently seeded shards."""
+    g, m, th = make_inputs(n, seed, grad_bf16, params_bf16, outliers)
+    send_idx = cfg.scheme == SCHEME_TOPK
+    m_gpu, idx_gpu, val_gpu, coeff_gpu = H.gpu_compress(cfg, g, m, want_idx=send_idx)
+    st_c = parity.check_compress(cfg, g, m, m_gpu, idx_gpu, val_gpu, coeff_gpu)
+    # payloads for the decompress half: all produced by the oracle
+    pays = []
+    for r in range(R):
+        gr, mr, _ = make_inputs(n, seed + 1000 * r, grad_bf16, params_bf16, outliers)
+        _, i_r, v_r = oracle.compress(cfg, gr, mr)
+        pays.append((i_r, v_r))
+    idx = np.stack([p[0] for p in pays]) if send_idx else None
+    val = np.stack([p[1] for p in pays])
+    th_gpu, y_gpu = H.gpu_decompress(cfg, idx, val, th)
+    st_d = parity.check_decompress(cfg, idx, val, th, th_gpu, y_gpu)
+    return st_c, st_d
+
+
+def test_config0_flat_1m(H):
+    cfg = Config(chunk=64, topk=8, decay=0.999, lr=1e-3, sign=True)
+    st_c, st_d = full_step(H, cfg, 1 << 20, R=1, seed=0)
+    assert st_c["chunks"] == 16384
+    print(st_c, st_d)
+
+
+@pytest.mark.parametrize("sign", [True, False])
+@pytest.mark.parametrize("s,k", [(32, 1), (32, 4), (32, 16), (64, 1), (64, 4), (64, 16), (64, 32),
+                                 (128, 1), (128, 4), (128, 16), (128, 64)])
+def test_vit_like_sweep_ragged(H, s, k, sign):
+    # the ViT-B/16 shard length is not a multiple of 32 (tail of 29): same raggedness, smaller n
+    n = 32 * 9000 + 29
+    cfg = Config(chunk=s, topk=k, sign=sign)
+    full_step(H, cfg, n, R=2, seed=s + k)
+
+
+@pytest.mark.parametrize("s,k", [(16, 2), (96, 6), (96, 96), (192, 12), (256, 16), (256, 256),
+                                 (1, 1), (2, 1), (3, 2), (65, 7), (200, 100)])
+def test_other_chunk_sizes(H, s, k):
+    cfg = Config(chunk=s, topk=k, sign=True)
+    full_step(H, cfg, s * 700 + (s // 3), R=3, seed=3)
+
+
+@pytest.mark.parametrize("grad_bf16,params_bf16", [(True, True), (True, False), (False, True)])
+def test_bf16_storage_with_outliers(H, grad_bf16, params_bf16):
+    cfg = Config(chunk=64, topk=32, sign=True)
+    full_step(H, cfg, 64 * 20000 + 5, R=4, seed=7, grad_bf16=grad_bf16, params_bf16=params_bf16,
+              outliers=0.01)
+
+
+@pytest.mark.parametrize("scheme", [SCHEME_STRIDE, SCHEME_RANDOM])
+@pytest.mark.parametrize("dct", [False, True])
+@pytest.mark.parametrize("step", [0, 1, 2, 3])
+def test_striding_and_random(H, scheme, dct, step):
+    cfg = Config(chunk=64, topk=32, scheme=scheme, dct=dct, seed=42, step=step, sign=True)
+    full_step(H, cfg, 64 * 6000 + 11, R=4, seed=step, grad_bf16=True, params_bf16=True)
+
+
+@pytest.mark.parametrize("scheme", [SCHEME_STRIDE, SCHEME_RANDOM])
+@pytest.mark.parametrize("s,k", [(32, 5), (128, 16), (96, 12), (256, 3)])
+def test_striding_and_random_other_shapes(H, scheme, s, k):
+    cfg = Config(chunk=s, topk=k, scheme=scheme, dct=(s == 128), seed=2**63 + 9, step=2**33 + 1,
+                 sign=False)
+    full_step(H, cfg, s * 900 + 1, R=2, seed=5)
+
+
+@pytest.mark.parametrize("n", [1, 5, 63, 64, 65, 64 * 64, 64 * 64 + 1, 64 * 129 - 1])
+def test_small_and_ragged_lengths(H, n):
+    cfg = Config(chunk=64, topk=8)
+    full_step(H, cfg, n, R=2, seed=n)
+
+
+def test_zero_inputs_select_lowest_indices(H):
+    # all magnitudes tie at zero: the rule keeps the k lowest indices; sign(0) = 0 moves nothing
+    n, s, k = 64 * 300 + 7, 64, 8
+    cfg = Config(chunk=s, topk=k)
+    g = np.zeros(n, np.float32)
+    m = np.zeros(n, np.float32)
+    th = synth.normal(1, synth.TAG_PARAMS, n, 0.02)
+    m_gpu, idx_gpu, val_gpu, coeff_gpu = H.gpu_compress(cfg, g, m)
+    assert np.array_equal(idx_gpu.reshape(-1, k), np.tile(np.arange(k, dtype=np.int32), (301, 1)))
+    assert not m_gpu.any() and not val_gpu.any()
+    th_gpu, y = H.gpu_decompress(cfg, idx_gpu[None], val_gpu[None], th)
+    assert np.array_equal(th_gpu, th)
+
+
+def test_hand_built_ties(H):
+    s, k = 64, 4
+    # a chunk that is one DCT basis vector has a single large coefficient and the rest near 0;
+    # an all-zero chunk ties everywhere and keeps the k lowest indices
+    cfg = Config(chunk=s, topk=k, decay=0.0)
+    D = oracle.dct_matrix(s)
+    g = np.concatenate([D[5], -D[9], D[0], np.zeros(s)]).astype(np.float32)
+    m = np.zeros_like(g)
+    m_gpu, idx_gpu, val_gpu, coeff_gpu = H.gpu_compress(cfg, g, m)
+    parity.check_compress(cfg, g, m, m_gpu, idx_gpu, val_gpu, coeff_gpu)
+    assert 5 in idx_gpu[:k] and 9 in idx_gpu[k:2 * k] and 0 in idx_gpu[2 * k:3 * k]
+    assert list(idx_gpu[3 * k:]) == [0, 1, 2, 3]
+
+
+def test_k_equals_s_is_lossless_and_reduces_to_sgd_momentum(H):
+    # nothing dropped, one replica, no sign: theta' = theta - eta*(beta*m + g)
+    s, n = 64, 64 * 500
+    cfg = Config(chunk=s, topk=s, sign=False, decay=0.9, lr=0.05)
+    g, m, th = make_inputs(n, 11)
+    m_gpu, idx_gpu, val_gpu, coeff_gpu = H.gpu_compress(cfg, g, m)
+    m1 = 0.9 * m.astype(np.float64) + g
+    assert np.abs(m_gpu).max() < 2e-6 * np.abs(m1).max()
+    th_gpu, _ = H.gpu_decompress(cfg, idx_gpu[None], val_gpu[None], th)
+    want = th.astype(np.float64) - np.float64(np.float32(0.05)) * (
+        np.float64(np.float32(0.9)) * m.astype(np.float64) + g.astype(np.float64))
+    assert np.abs(th_gpu - want).max() < 2e-6 * np.abs(want).max()
+
+
+@pytest.mark.parametrize("R", [1, 2, 4, 7])
+def test_replica_counts_weight_decay_and_strides(H, R):
+    import torch
+    from paper_2502_06728_amd import binding
+    s, k, n = 64, 16, 64 * 3000 + 3
+    cfg = Config(chunk=s, topk=k, sign=(R % 2 == 0), lr=1e-2, weight_decay=0.1)
+    full_step(H, cfg, n, R=R, seed=R)
+    # replica strides larger than the payload (an all_gather buffer with padding)
+    entries = -(-n // s) * k
+    stride = entries + 24
+    pays = [oracle.compress(cfg, *make_inputs(n, 50 + r)[:2])[1:] for r in range(R)]
+    idx = np.full((R, stride), 999, np.int32)
+    val = np.full((R, stride), np.nan, np.float32)
+    for r, (i_r, v_r) in enumerate(pays):
+        idx[r, :entries], val[r, :entries] = i_r, v_r
+    th = make_inputs(n, 77)[2]
+    p = H.to_dev(th)
+    y = torch.empty(n, dtype=torch.float32, device=H.DEV)
+    binding.detonation_decompress_step(H.bcfg(cfg), R, H.to_dev(idx), H.to_dev(val), p, y,
+                                       idx_replica_stride=stride, val_replica_stride=stride)
+    torch.cuda.synchronize()
+    parity.check_decompress(cfg, np.stack([q[0] for q in pays]), np.stack([q[1] for q in pays]),
+                            th, H.to_host(p), H.to_host(y))
+
+
+def test_duplicate_and_out_of_range_payload_indices(H):
+    s, k, n = 64, 4, 64 * 50
+    cfg = Config(chunk=s, topk=k, sign=False)
+    rng = np.random.default_rng(0)
+    idx = rng.integers(-3, s + 3, size=(2, 50 * k)).astype(np.int32)     # dups + out of range
+    idx[0, :8] = [5, 5, 5, 5, 64, -1, 7, 7]
+    val = rng.standard_normal((2, 50 * k)).astype(np.float32)
+    th = make_inputs(n, 3)[2]
+    th_gpu, y_gpu = H.gpu_decompress(cfg, idx, val, th)
+    parity.check_decompress(cfg, idx, val, th, th_gpu, y_gpu)
+
+
+def test_deterministic_and_debug_outputs_do_not_change_results(H):
+    cfg = Config(chunk=64, topk=32)
+    g, m, th = make_inputs(64 * 10000 + 17, 21, grad_bf16=True, params_bf16=True)
+    a = H.gpu_compress(cfg, g, m, want_coeff=True)
+    b = H.gpu_compress(cfg, g, m, want_coeff=False)
+    c = H.gpu_compress(cfg, g, m, want_coeff=False)
+    for x, y, z in zip(a[:3], b[:3], c[:3]):
+        assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
+        assert np.array_equal(y.view(np.uint32), z.view(np.uint32))
+    idx, val = np.stack([a[1]] * 3), np.stack([a[2]] * 3)
+    p1, _ = H.gpu_decompress(cfg, idx, val, th, want_presign=True)
+    p2, _ = H.gpu_decompress(cfg, idx, val, th, want_presign=False)
+    assert np.array_equal(p1, p2)
+
+
+def test_t5_base_shard_full_size(H):
+    # the T5-base-shaped 1/8 shard (27.9M parameters), chunk 64, top-k 32, R = 2
+    w = synth.workloads()["t5-base-1of8"]
+    assert w.n == 27_862_848
+    cfg = Config(chunk=w.chunk, topk=w.topk, decay=w.decay, lr=w.lr, sign=True)
+    st_c, st_d = full_step(H, cfg, w.n, R=2, seed=0)
+    print(st_c, st_d)
+    assert st_c["chunks"] == 435_357
+
+
+def test_vit_b16_shard_full_size(H):
+    w = synth.workloads()["vit-b16-1of8"]
+    assert w.n == 10_820_957 and w.n % 32 == 29
+    for s, k in [(32, 16), (128, 4)]:
+        full_step(H, Config(chunk=s, topk=k), w.n, R=2, seed=1)
