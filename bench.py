@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused optimizer step (compress + decompress-and-update) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload olmo-1b-1of8]
+
+A step is one pass of the whole hot path over the shard: detonation_compress (momentum
+accumulate, chunked DCT, selection, residual, payload) followed by
+detonation_decompress_step (scatter R payloads, average, inverse DCT, sign, parameter
+update).  All inputs are resident in HBM before the timed region; debug outputs are off.
+Prints ONE JSON line: throughput in parameters per second, the roofline of the slower
+kernel (algorithmic bytes / measured duration against the 8 TB/s HBM peak) and the CPU
+oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
+
+
+def algorithmic_bytes(n: int, s: int, k: int, R: int, grad_bytes: int, param_bytes: int,
+                      with_idx: bool) -> dict:
+    """Bytes the method itself must move per launch: compress reads g and m, writes m and
+    the payload; decompress reads R payloads, reads and writes the parameters."""
+    C = -(-n // s)
+    pay = C * k * (8 if with_idx else 4)
+    return {"compress": n * (grad_bytes + 8) + pay, "decompress": R * pay + 2 * n * param_bytes}
+
+
+def cpu_baseline(w, cfg_kwargs: dict, sample_params: int) -> dict:
+    """The oracle as it stands, on the host cores, on the leading `sample_params` of the shard."""
+    import numpy as np
+    import oracle
+    from paper_2502_06728_amd import synth
+    cfg = oracle.Config(**cfg_kwargs)
+    n = min(sample_params, w.n)
+    n -= n % cfg.chunk
+    g, m, th = synth.shard(w, stop=n)
+    C = n // cfg.chunk
+    R = w.replicas
+    idx = np.empty((R, C * cfg.topk), np.int32)
+    val = np.empty((R, C * cfg.topk), np.float32)
+    for r in range(1, R):   # replica payloads, untimed (as on the GPU side)
+        idx[r], val[r] = synth.structured_payload(w.seed + r, C, cfg.chunk, cfg.topk, w.momentum_std)
+    oracle.lib()
+    t0 = time.perf_counter()
+    m_new, idx0, val0 = oracle.compress(cfg, g, m)
+    idx[0], val[0] = idx0, val0
+    oracle.decompress_step(cfg, idx, val, th)
+    dt = time.perf_counter() - t0
+    return {"value": n / dt, "unit": "params/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"leading {n} of {w.n} parameters of the same shard, one full step "
+                      f"(compress + decompress, R={R}), {dt:.1f} s, gcc -O2 + OpenMP"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="olmo-1b-1of8")
+    ap.add_argument("--scheme", default="topk", choices=["topk", "stride", "random"])
+    ap.add_argument("--dct", action="store_true", help="coefficient domain for stride/random")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 28)
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures the one-GPU hot path only: the payload all_gather across the "
+              "replication group is not part of this build, so --gpus must be 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2502_06728_amd import binding, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    binding.load()
+    dev = torch.device("cuda:0")
+    w = synth.workloads()[args.workload]
+    scheme = {"topk": binding.SCHEME_TOPK, "stride": binding.SCHEME_STRIDE,
+              "random": binding.SCHEME_RANDOM}[args.scheme]
+    cfg_kwargs = dict(chunk=w.chunk, topk=w.topk, scheme=scheme, sign=w.sign, dct=args.dct,
+                      decay=w.decay, lr=w.lr, weight_decay=w.weight_decay, seed=w.seed, step=0)
+    cfg = binding.Config(**cfg_kwargs)
+    n, s, k, R = w.n, w.chunk, w.topk, w.replicas
+    entries = binding.payload_entries(cfg, n)
+    with_idx = scheme == binding.SCHEME_TOPK
+
+    # ---- resident inputs: the shard itself from the seeded recipe ...
+    g_np, m_np, th_np = synth.shard(w)
+
+    def up(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(a).to(dev)
+
+    grad, mom, params = up(g_np), up(m_np), up(th_np)
+    del g_np, m_np, th_np
+    idx = torch.zeros((R, entries), dtype=torch.int32, device=dev) if with_idx else None
+    val = torch.zeros((R, entries), dtype=torch.float32, device=dev)
+    # ... and R-1 other replicas' payloads: the library's compress run, untimed, on
+    # independently seeded shards of the same recipe (what an all_gather would deliver).
+    gen = torch.Generator(device=dev)
+    for r in range(1, R):
+        gen.manual_seed(w.seed + r)
+        gr = torch.randn(n, generator=gen, device=dev, dtype=torch.float32) * w.grad_std
+        if w.outlier_frac > 0:
+            u = torch.rand(n, generator=gen, device=dev)
+            gr = torch.where(u < w.outlier_frac, gr * w.outlier_scale, gr)
+        gr = gr.to(grad.dtype)
+        mr = torch.randn(n, generator=gen, device=dev, dtype=torch.float32) * w.momentum_std
+        binding.detonation_compress(cfg, gr, mr, None if idx is None else idx[r], val[r])
+        torch.cuda.synchronize()
+        del gr, mr
+    torch.cuda.empty_cache()
+
+    def step(ev=None):
+        cfg.step += 1
+        if ev:
+            ev[0].record()
+        binding.detonation_compress(cfg, grad, mom, None if idx is None else idx[0], val[0])
+        if ev:
+            ev[1].record()
+        binding.detonation_decompress_step(cfg, R, idx, val, params)
+        if ev:
+            ev[2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    t_c = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps   # ms per launch
+    t_d = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
+    ms_per_step = wall * 1e3 / args.steps
+    ab = algorithmic_bytes(n, s, k, R, grad.element_size(), params.element_size(), with_idx)
+    gbs_c = ab["compress"] / (t_c * 1e-3) / 1e9
+    gbs_d = ab["decompress"] / (t_d * 1e-3) / 1e9
+    dom = "compress" if t_c >= t_d else "decompress"
+    dom_gbs = gbs_c if dom == "compress" else gbs_d
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(f"{args.workload}:{args.scheme}", {}).get(dom)
+        except Exception:
+            traffic = None
+
+    out = {
+        "metric": "optimizer_step_params_per_sec", "value": n * args.steps / wall,
+        "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "params": n, "chunk": s, "topk": k, "replicas": R,
+                   "scheme": args.scheme, "dct_domain": bool(cfg.scheme == 0 or args.dct),
+                   "grad_dtype": str(grad.dtype).split(".")[-1],
+                   "param_dtype": str(params.dtype).split(".")[-1], "momentum_dtype": "float32",
+                   "sign": w.sign, "decay": w.decay, "lr": w.lr},
+        "step_hbm_gbs": (ab["compress"] + ab["decompress"]) / (ms_per_step * 1e-3) / 1e9,
+        "step_hbm_frac_of_peak": (ab["compress"] + ab["decompress"]) / (ms_per_step * 1e-3) / 1e9
+                                 / HBM_PEAK_GBS,
+        "kernels": {
+            "compress": {"ms": t_c, "algorithmic_bytes": ab["compress"], "gbs": gbs_c,
+                         "frac": gbs_c / HBM_PEAK_GBS},
+            "decompress": {"ms": t_d, "algorithmic_bytes": ab["decompress"], "gbs": gbs_d,
+                           "frac": gbs_d / HBM_PEAK_GBS}},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS, "traffic": traffic},
+    }
+    if not args.no_cpu:
+        del grad, mom, params, idx, val
+        out["cpu_baseline"] = cpu_baseline(w, cfg_kwargs, args.cpu_sample)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -8,6 +8,7 @@ import sys
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libdetonation.so")
+MEMBENCH = os.path.join(_HERE, "membench")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall",
@@ -32,6 +33,12 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError(f"hipcc failed:\n{res.stderr}")
     if verbose and err.strip():
         print(err, file=sys.stderr)
+    # the streaming micro-benchmark (HBM ceiling, counter calibration)
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-o", MEMBENCH,
+           os.path.join(CSRC, "membench.hip")]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError(f"hipcc failed:\n{res.stderr}")
     return LIB
 
 

@@ -1,0 +1,408 @@
+// Tiled kernels for power-of-two chunk sizes: the bandwidth path.
+//
+// Mapping.  A workgroup is ONE wavefront and owns a tile of 64 consecutive chunks.
+//   phase 1  all 64 lanes stream the tile from HBM with 16-byte accesses (fully
+//            coalesced), do the element-wise part there, and park the tile in LDS;
+//   phase 2  lane L picks up chunk L of the tile (one LDS row) into registers: the DCT,
+//            the selection and the inverse DCT of that chunk are private VALU work of one
+//            lane, with no cross-lane traffic and no divergence (fast_dct.hip.h);
+//   phase 3  results go back through LDS and leave with 16-byte coalesced stores.
+// LDS rows are padded by 16 bytes so both the coalesced phase (consecutive lanes ->
+// consecutive 16 B) and the row phase (lane L -> row L) are free of bank conflicts.
+//
+// Selection (top-k, ties to the lower index): the magnitudes' bit patterns are sorted as
+// two halves with a Batcher odd-even merge network in registers; the k-th largest
+// magnitude T follows from the two sorted halves as max_i min(A[i-1], B[k-i-1]); entries
+// with magnitude >= T are kept.  Only if some chunk of the wavefront has a tie AT the
+// threshold does the wavefront take the exact path that keeps the lowest indices.
+#pragma once
+
+#include "deto_device.hip.h"
+#include "fast_dct.hip.h"
+
+namespace deto {
+
+// ---- Batcher's odd-even merge sort as a compile-time list of compare-exchanges
+template <int N>
+struct SortNet {
+    static constexpr int kCap = N * 8;
+    int a[kCap];
+    int b[kCap];
+    int n;
+    constexpr SortNet() : a{}, b{}, n(0) { sort(0, N); }
+    constexpr void add(int i, int j) {
+        a[n] = i;
+        b[n] = j;
+        ++n;
+    }
+    constexpr void merge(int lo, int len, int r) {
+        const int m = r * 2;
+        if (m < len) {
+            merge(lo, len, m);
+            merge(lo + r, len, m);
+            for (int i = lo + r; i + r < lo + len; i += m) add(i, i + r);
+        } else {
+            add(lo, lo + r);
+        }
+    }
+    constexpr void sort(int lo, int len) {
+        if (len > 1) {
+            const int m = len / 2;
+            sort(lo, m);
+            sort(lo + m, m);
+            merge(lo, len, 1);
+        }
+    }
+};
+
+template <int N>
+struct SortNetHolder {
+    static constexpr SortNet<N> net{};
+};
+
+// sort descending, in registers
+template <int N>
+__device__ __forceinline__ void sort_desc(uint32_t (&k)[N]) {
+    constexpr int cnt = SortNetHolder<N>::net.n;
+    static_for<0, cnt>([&](auto I) {
+        constexpr int i = SortNetHolder<N>::net.a[I];
+        constexpr int j = SortNetHolder<N>::net.b[I];
+        const uint32_t hi = max(k[i], k[j]);
+        const uint32_t lo = min(k[i], k[j]);
+        k[i] = hi;
+        k[j] = lo;
+    });
+}
+
+// K-th largest of the union of two descending arrays of length H.
+template <int H, int K>
+__device__ __forceinline__ uint32_t kth_largest(const uint32_t (&A)[H], const uint32_t (&B)[H]) {
+    constexpr int lo = (K - H) > 0 ? (K - H) : 0;
+    constexpr int hi = K < H ? K : H;
+    uint32_t best = 0u;
+    static_for<lo, hi + 1>([&](auto I) {
+        constexpr int i = I;       // i entries from A, K - i from B
+        uint32_t term;
+        if constexpr (i == 0) term = B[K - 1];
+        else if constexpr (i == K) term = A[K - 1];
+        else term = min(A[i - 1], B[K - i - 1]);
+        best = max(best, term);
+    });
+    return best;
+}
+
+template <int S>
+struct TileGeom {
+    static constexpr int kRow = S + 4;           // floats per LDS row (16 B of padding)
+    static constexpr int kFloats = kWave * kRow;
+    static constexpr int kElems = kWave * S;     // elements per tile
+};
+
+// keep the `need` lowest set bits of `e` (per lane), wave-uniform loop
+__device__ __forceinline__ uint64_t lowest_bits(uint64_t e, int need) {
+    uint64_t keep = 0;
+    while (__any(need > 0)) {
+        if (need > 0) {
+            const uint64_t low = e & (0 - e);
+            keep |= low;
+            e ^= low;
+            --need;
+        }
+    }
+    return keep;
+}
+
+// Compress half on full tiles: chunks [0, 64*n_tiles), all complete.
+// SCHEME 0: top-k.  SCHEME 1/2: Striding / Random picking DCT coefficients
+// (`fixed_mask` carries the Striding pattern; Random regenerates per chunk).
+template <int S, int K, bool GRAD_BF16>
+__global__ __launch_bounds__(kWave, 2) void compress_tiled_topk(
+    KParams p, int64_t n_tiles, const void* __restrict__ grad, float* __restrict__ mom,
+    int32_t* __restrict__ idx_out, float* __restrict__ val_out, float* __restrict__ coeff_dbg) {
+    using G = TileGeom<S>;
+    constexpr int H = S / 2;
+    __shared__ __attribute__((aligned(16))) float tile[G::kFloats];
+    const int lane = threadIdx.x;
+
+    for (int64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        const int64_t ebase = t * G::kElems;
+        // ---- phase 1: m1 = beta*m + g, coalesced, into LDS
+#pragma unroll
+        for (int it = 0; it < S / 8; ++it) {
+            const int pe = it * 512 + lane * 8;
+            const float4 ma = *reinterpret_cast<const float4*>(mom + ebase + pe);
+            const float4 mb = *reinterpret_cast<const float4*>(mom + ebase + pe + 4);
+            float g[8];
+            if constexpr (GRAD_BF16) {
+                const uint4 raw = *reinterpret_cast<const uint4*>(
+                    static_cast<const uint16_t*>(grad) + ebase + pe);
+                g[0] = __uint_as_float(raw.x << 16);
+                g[1] = __uint_as_float(raw.x & 0xFFFF0000u);
+                g[2] = __uint_as_float(raw.y << 16);
+                g[3] = __uint_as_float(raw.y & 0xFFFF0000u);
+                g[4] = __uint_as_float(raw.z << 16);
+                g[5] = __uint_as_float(raw.z & 0xFFFF0000u);
+                g[6] = __uint_as_float(raw.w << 16);
+                g[7] = __uint_as_float(raw.w & 0xFFFF0000u);
+            } else {
+                const float4 ga =
+                    *reinterpret_cast<const float4*>(static_cast<const float*>(grad) + ebase + pe);
+                const float4 gb = *reinterpret_cast<const float4*>(static_cast<const float*>(grad) +
+                                                                   ebase + pe + 4);
+                g[0] = ga.x; g[1] = ga.y; g[2] = ga.z; g[3] = ga.w;
+                g[4] = gb.x; g[5] = gb.y; g[6] = gb.z; g[7] = gb.w;
+            }
+            float4 fa, fb;
+            fa.x = fmaf(p.beta, ma.x, g[0]);
+            fa.y = fmaf(p.beta, ma.y, g[1]);
+            fa.z = fmaf(p.beta, ma.z, g[2]);
+            fa.w = fmaf(p.beta, ma.w, g[3]);
+            fb.x = fmaf(p.beta, mb.x, g[4]);
+            fb.y = fmaf(p.beta, mb.y, g[5]);
+            fb.z = fmaf(p.beta, mb.z, g[6]);
+            fb.w = fmaf(p.beta, mb.w, g[7]);
+            float* dst = tile + (pe / S) * G::kRow + (pe % S);
+            *reinterpret_cast<float4*>(dst) = fa;
+            *reinterpret_cast<float4*>(dst + 4) = fb;
+        }
+        __syncthreads();
+
+        // ---- phase 2: lane = chunk
+        float* row = tile + lane * G::kRow;
+        float c[S];
+#pragma unroll
+        for (int j = 0; j < S / 4; ++j) {
+            const float4 v = *reinterpret_cast<const float4*>(row + 4 * j);
+            c[4 * j] = v.x; c[4 * j + 1] = v.y; c[4 * j + 2] = v.z; c[4 * j + 3] = v.w;
+        }
+        FastDct<S>::dct2(c);
+        c[0] *= p.alpha0;
+        static_for<1, S>([&](auto i) { c[i] *= p.alpha; });
+        if (coeff_dbg) {
+            float* dbg = coeff_dbg + ebase + static_cast<int64_t>(lane) * S;
+#pragma unroll
+            for (int j = 0; j < S / 4; ++j)
+                *reinterpret_cast<float4*>(dbg + 4 * j) =
+                    make_float4(c[4 * j], c[4 * j + 1], c[4 * j + 2], c[4 * j + 3]);
+        }
+
+        // threshold: K-th largest magnitude
+        uint32_t T;
+        {
+            uint32_t A[H], B[H];
+            static_for<0, H>([&](auto i) {
+                A[i] = __float_as_uint(c[i]) & 0x7FFFFFFFu;
+                B[i] = __float_as_uint(c[H + i]) & 0x7FFFFFFFu;
+            });
+            sort_desc<H>(A);
+            sort_desc<H>(B);
+            T = kth_largest<H, K>(A, B);
+        }
+        // keep magnitude >= T; the mask collects the decisions (bit i = element i)
+        float q[S];
+        uint32_t mlo = 0u, mhi = 0u;
+        static_for<0, S>([&](auto I) {
+            constexpr int i = S - 1 - I;   // descending so that shifting lands bit i at i
+            const bool keep = (__float_as_uint(c[i]) & 0x7FFFFFFFu) >= T;
+            q[i] = keep ? c[i] : 0.0f;
+            if constexpr (i >= 32) mhi = (mhi << 1) | (keep ? 1u : 0u);
+            else mlo = (mlo << 1) | (keep ? 1u : 0u);
+        });
+        if (__any(__popc(mlo) + __popc(mhi) != K)) {
+            // a tie at the threshold somewhere in this wavefront: exact rule
+            uint64_t gt = 0, eq = 0;
+            static_for<0, S>([&](auto i) {
+                const uint32_t key = __float_as_uint(c[i]) & 0x7FFFFFFFu;
+                gt |= static_cast<uint64_t>(key > T) << i;
+                eq |= static_cast<uint64_t>(key == T) << i;
+            });
+            const uint64_t m = gt | lowest_bits(eq, K - __popcll(gt));
+            mlo = static_cast<uint32_t>(m);
+            mhi = static_cast<uint32_t>(m >> 32);
+            static_for<0, S>([&](auto i) { q[i] = ((m >> i) & 1ull) ? c[i] : 0.0f; });
+        }
+
+        // q <- inverse transform of the kept coefficients; m' = m1 - q back into the row
+        {
+            float w[S];
+            w[0] = q[0] * p.alpha0;
+            static_for<1, S>([&](auto i) { w[i] = q[i] * p.alpha; });
+            FastDct<S>::dct3(w);
+#pragma unroll
+            for (int j = 0; j < S / 4; ++j) {
+                float4 v = *reinterpret_cast<const float4*>(row + 4 * j);
+                v.x -= w[4 * j]; v.y -= w[4 * j + 1]; v.z -= w[4 * j + 2]; v.w -= w[4 * j + 3];
+                *reinterpret_cast<float4*>(row + 4 * j) = v;
+            }
+        }
+        __syncthreads();
+
+        // ---- phase 3a: residual momentum out, coalesced
+#pragma unroll
+        for (int it = 0; it < S / 8; ++it) {
+            const int pe = it * 512 + lane * 8;
+            const float* src = tile + (pe / S) * G::kRow + (pe % S);
+            *reinterpret_cast<float4*>(mom + ebase + pe) = *reinterpret_cast<const float4*>(src);
+            *reinterpret_cast<float4*>(mom + ebase + pe + 4) =
+                *reinterpret_cast<const float4*>(src + 4);
+        }
+        __syncthreads();
+
+        // ---- phase 3b: compact the kept (index, value) pairs of each chunk, ascending.
+        // Every element is written at the running position, which only advances past kept
+        // ones, so a dropped element is overwritten by the next kept one.
+        constexpr int PR = K + 4;                       // staging row, one spare slot + pad
+        float* vrow = tile + lane * PR;
+        uint8_t* ibytes = reinterpret_cast<uint8_t*>(tile + kWave * PR);   // indices as bytes
+        uint8_t* irow = ibytes + lane * PR;
+        static_assert(kWave * PR * 5 <= G::kFloats * 4, "staging must fit in the tile");
+        {
+            int pos = 0;
+            static_for<0, S>([&](auto i) {
+                vrow[pos] = q[i];
+                irow[pos] = static_cast<uint8_t>(i);
+                const uint32_t bit = (i >= 32) ? ((mhi >> (i - 32)) & 1u) : ((mlo >> i) & 1u);
+                pos += static_cast<int>(bit);
+            });
+        }
+        __syncthreads();
+        const int64_t pbase = t * (kWave * K);
+        if constexpr (K % 4 == 0) {
+#pragma unroll
+            for (int it = 0; it < K / 4; ++it) {
+                const int e = it * 256 + lane * 4;
+                const int r = e / K, col = e % K;
+                *reinterpret_cast<float4*>(val_out + pbase + e) =
+                    *reinterpret_cast<const float4*>(tile + r * PR + col);
+                const uint32_t pk = *reinterpret_cast<const uint32_t*>(ibytes + r * PR + col);
+                *reinterpret_cast<int4*>(idx_out + pbase + e) =
+                    make_int4(pk & 0xFFu, (pk >> 8) & 0xFFu, (pk >> 16) & 0xFFu, pk >> 24);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                val_out[pbase + lane * K + j] = vrow[j];
+                idx_out[pbase + lane * K + j] = irow[j];
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// Decompress-and-update half on full tiles (transform domain, indices transmitted).
+template <int S, int K, bool PARAM_BF16>
+__global__ __launch_bounds__(kWave, 2) void decompress_tiled(
+    KParams p, int64_t n_tiles, const int32_t* __restrict__ idx, int64_t idx_stride,
+    const float* __restrict__ val, int64_t val_stride, void* __restrict__ params,
+    float* __restrict__ presign_dbg) {
+    using G = TileGeom<S>;
+    __shared__ __attribute__((aligned(16))) float tile[G::kFloats];
+    const int lane = threadIdx.x;
+
+    for (int64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        const int64_t ebase = t * G::kElems;
+        const int64_t pbase = t * (kWave * K);
+        // zero the accumulator tile
+#pragma unroll
+        for (int i = lane * 4; i < G::kFloats; i += kWave * 4)
+            *reinterpret_cast<float4*>(tile + i) = make_float4(0.f, 0.f, 0.f, 0.f);
+        __syncthreads();
+        // scatter-add the R payloads, replica after replica (fixed order of additions)
+        for (int r = 0; r < p.R; ++r) {
+            const int32_t* ir = idx + r * idx_stride + pbase;
+            const float* vr = val + r * val_stride + pbase;
+            if constexpr (K % 4 == 0) {
+#pragma unroll
+                for (int it = 0; it < K / 4; ++it) {
+                    const int e = it * 256 + lane * 4;
+                    const int4 i4 = *reinterpret_cast<const int4*>(ir + e);
+                    const float4 v4 = *reinterpret_cast<const float4*>(vr + e);
+                    float* arow = tile + (e / K) * G::kRow;
+                    if (static_cast<uint32_t>(i4.x) < S) atomicAdd(arow + i4.x, v4.x);
+                    if (static_cast<uint32_t>(i4.y) < S) atomicAdd(arow + i4.y, v4.y);
+                    if (static_cast<uint32_t>(i4.z) < S) atomicAdd(arow + i4.z, v4.z);
+                    if (static_cast<uint32_t>(i4.w) < S) atomicAdd(arow + i4.w, v4.w);
+                }
+            } else {
+                for (int e = lane; e < kWave * K; e += kWave) {
+                    const int at = ir[e];
+                    if (static_cast<uint32_t>(at) < S) atomicAdd(tile + (e / K) * G::kRow + at, vr[e]);
+                }
+            }
+            __syncthreads();
+        }
+        // lane = chunk: average, inverse transform, sign
+        float* row = tile + lane * G::kRow;
+        float y[S];
+#pragma unroll
+        for (int j = 0; j < S / 4; ++j) {
+            const float4 v = *reinterpret_cast<const float4*>(row + 4 * j);
+            y[4 * j] = v.x; y[4 * j + 1] = v.y; y[4 * j + 2] = v.z; y[4 * j + 3] = v.w;
+        }
+        y[0] *= p.alpha0 * p.inv_R;
+        {
+            const float ar = p.alpha * p.inv_R;
+            static_for<1, S>([&](auto i) { y[i] *= ar; });
+        }
+        FastDct<S>::dct3(y);
+        if (presign_dbg) {
+            float* dbg = presign_dbg + ebase + static_cast<int64_t>(lane) * S;
+#pragma unroll
+            for (int j = 0; j < S / 4; ++j)
+                *reinterpret_cast<float4*>(dbg + 4 * j) =
+                    make_float4(y[4 * j], y[4 * j + 1], y[4 * j + 2], y[4 * j + 3]);
+        }
+#pragma unroll
+        for (int j = 0; j < S / 4; ++j) {
+            float4 v;
+            v.x = sign_or_self(y[4 * j], p.use_sign);
+            v.y = sign_or_self(y[4 * j + 1], p.use_sign);
+            v.z = sign_or_self(y[4 * j + 2], p.use_sign);
+            v.w = sign_or_self(y[4 * j + 3], p.use_sign);
+            *reinterpret_cast<float4*>(row + 4 * j) = v;
+        }
+        __syncthreads();
+        // coalesced parameter update
+#pragma unroll
+        for (int it = 0; it < S / 8; ++it) {
+            const int pe = it * 512 + lane * 8;
+            const float* src = tile + (pe / S) * G::kRow + (pe % S);
+            const float4 qa = *reinterpret_cast<const float4*>(src);
+            const float4 qb = *reinterpret_cast<const float4*>(src + 4);
+            if constexpr (PARAM_BF16) {
+                uint16_t* th = static_cast<uint16_t*>(params) + ebase + pe;
+                const uint4 raw = *reinterpret_cast<const uint4*>(th);
+                auto upd = [&](uint32_t w, float q0, float q1) -> uint32_t {
+                    const float t0 = __uint_as_float(w << 16) * p.wd_scale;
+                    const float t1 = __uint_as_float(w & 0xFFFF0000u) * p.wd_scale;
+                    const uint32_t b0 = f32_to_bf16(fmaf(-p.lr, q0, t0));
+                    const uint32_t b1 = f32_to_bf16(fmaf(-p.lr, q1, t1));
+                    return b0 | (b1 << 16);
+                };
+                uint4 out;
+                out.x = upd(raw.x, qa.x, qa.y);
+                out.y = upd(raw.y, qa.z, qa.w);
+                out.z = upd(raw.z, qb.x, qb.y);
+                out.w = upd(raw.w, qb.z, qb.w);
+                *reinterpret_cast<uint4*>(th) = out;
+            } else {
+                float* th = static_cast<float*>(params) + ebase + pe;
+                float4 ta = *reinterpret_cast<const float4*>(th);
+                float4 tb = *reinterpret_cast<const float4*>(th + 4);
+                ta.x = fmaf(-p.lr, qa.x, ta.x * p.wd_scale);
+                ta.y = fmaf(-p.lr, qa.y, ta.y * p.wd_scale);
+                ta.z = fmaf(-p.lr, qa.z, ta.z * p.wd_scale);
+                ta.w = fmaf(-p.lr, qa.w, ta.w * p.wd_scale);
+                tb.x = fmaf(-p.lr, qb.x, tb.x * p.wd_scale);
+                tb.y = fmaf(-p.lr, qb.y, tb.y * p.wd_scale);
+                tb.z = fmaf(-p.lr, qb.z, tb.z * p.wd_scale);
+                tb.w = fmaf(-p.lr, qb.w, tb.w * p.wd_scale);
+                *reinterpret_cast<float4*>(th) = ta;
+                *reinterpret_cast<float4*>(th + 4) = tb;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+}  // namespace deto
