@@ -112,9 +112,7 @@ __device__ __forceinline__ uint64_t lowest_bits(uint64_t e, int need) {
     return keep;
 }
 
-// Compress half on full tiles: chunks [0, 64*n_tiles), all complete.
-// SCHEME 0: top-k.  SCHEME 1/2: Striding / Random picking DCT coefficients
-// (`fixed_mask` carries the Striding pattern; Random regenerates per chunk).
+// Compress half (top-k) on full tiles: chunks [0, 64*n_tiles), all complete.
 template <int S, int K, bool GRAD_BF16>
 __global__ __launch_bounds__(kWave, 2) void compress_tiled_topk(
     KParams p, int64_t n_tiles, const void* __restrict__ grad, float* __restrict__ mom,
@@ -289,7 +287,83 @@ __global__ __launch_bounds__(kWave, 2) void compress_tiled_topk(
     }
 }
 
+// One replica's payload entries of a tile, as each lane holds them after a coalesced load.
+template <int K>
+struct PayloadRegs {
+    static constexpr int kVec = (K % 4 == 0) ? K / 4 : 1;
+    int4 i[kVec];
+    float4 v[kVec];
+};
+
+template <int K>
+__device__ __forceinline__ void load_payload(PayloadRegs<K>& r, const int32_t* __restrict__ ir,
+                                             const float* __restrict__ vr, int lane) {
+    static_assert(K % 4 == 0, "vector path");
+#pragma unroll
+    for (int it = 0; it < K / 4; ++it) {
+        const int e = it * 256 + lane * 4;
+        r.i[it] = *reinterpret_cast<const int4*>(ir + e);
+        r.v[it] = *reinterpret_cast<const float4*>(vr + e);
+    }
+}
+
+// a[chunk][index] += value; an index outside [0,S) lands in the row's padding slot S.
+// LDS floating-point atomics take several cycles per lane on this hardware, so the common
+// case avoids them: when every chunk's indices are strictly ascending (what compress
+// emits) all additions of one replica go to distinct accumulators and a plain
+// read-all / add / write-all is exact.  Anything else (duplicates, disorder) takes the
+// atomic path, which adds duplicates like the scatter-add it is.
+template <int S, int K>
+__device__ __forceinline__ void scatter_payload(const PayloadRegs<K>& r, float* tile, int lane) {
+    constexpr int kRow = S + 4;
+    constexpr int kIt = K / 4;
+    constexpr uint32_t kS = static_cast<uint32_t>(S);
+    bool ok = true;
+    const bool first = (lane % kIt) == 0;       // first lane of its chunk (kIt lanes a chunk)
+#pragma unroll
+    for (int it = 0; it < kIt; ++it) {
+        const uint32_t x = r.i[it].x, y = r.i[it].y, z = r.i[it].z, w = r.i[it].w;
+        // previous lane's last index (row_shr:1; kIt divides the 16-lane DPP row)
+        const uint32_t pw = static_cast<uint32_t>(
+            __builtin_amdgcn_update_dpp(0, static_cast<int>(w), 0x111, 0xf, 0xf, false));
+        ok = ok && (x < y) && (y < z) && (z < w) && (first || pw < x);
+    }
+    if (!__any(!ok)) {
+        float old[kIt][4];
+        float* at[kIt][4];
+#pragma unroll
+        for (int it = 0; it < kIt; ++it) {
+            float* arow = tile + ((it * 256 + lane * 4) / K) * kRow;
+            at[it][0] = arow + min(static_cast<uint32_t>(r.i[it].x), kS);
+            at[it][1] = arow + min(static_cast<uint32_t>(r.i[it].y), kS);
+            at[it][2] = arow + min(static_cast<uint32_t>(r.i[it].z), kS);
+            at[it][3] = arow + min(static_cast<uint32_t>(r.i[it].w), kS);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) old[it][c] = *at[it][c];
+        }
+#pragma unroll
+        for (int it = 0; it < kIt; ++it) {
+            *at[it][0] = old[it][0] + r.v[it].x;
+            *at[it][1] = old[it][1] + r.v[it].y;
+            *at[it][2] = old[it][2] + r.v[it].z;
+            *at[it][3] = old[it][3] + r.v[it].w;
+        }
+    } else {
+#pragma unroll
+        for (int it = 0; it < kIt; ++it) {
+            float* arow = tile + ((it * 256 + lane * 4) / K) * kRow;
+            atomicAdd(arow + min(static_cast<uint32_t>(r.i[it].x), kS), r.v[it].x);
+            atomicAdd(arow + min(static_cast<uint32_t>(r.i[it].y), kS), r.v[it].y);
+            atomicAdd(arow + min(static_cast<uint32_t>(r.i[it].z), kS), r.v[it].z);
+            atomicAdd(arow + min(static_cast<uint32_t>(r.i[it].w), kS), r.v[it].w);
+        }
+    }
+}
+
 // Decompress-and-update half on full tiles (transform domain, indices transmitted).
+// The payload of replica r+1 is in flight while replica r is scattered into LDS; LDS
+// operations of one wavefront complete in order, so the additions into one accumulator
+// happen replica after replica and the result does not depend on timing.
 template <int S, int K, bool PARAM_BF16>
 __global__ __launch_bounds__(kWave, 2) void decompress_tiled(
     KParams p, int64_t n_tiles, const int32_t* __restrict__ idx, int64_t idx_stride,
@@ -304,33 +378,55 @@ __global__ __launch_bounds__(kWave, 2) void decompress_tiled(
         const int64_t pbase = t * (kWave * K);
         // zero the accumulator tile
 #pragma unroll
-        for (int i = lane * 4; i < G::kFloats; i += kWave * 4)
-            *reinterpret_cast<float4*>(tile + i) = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int i = 0; i < G::kFloats / (kWave * 4); ++i)
+            *reinterpret_cast<float4*>(tile + (i * kWave + lane) * 4) =
+                make_float4(0.f, 0.f, 0.f, 0.f);
         __syncthreads();
-        // scatter-add the R payloads, replica after replica (fixed order of additions)
-        for (int r = 0; r < p.R; ++r) {
-            const int32_t* ir = idx + r * idx_stride + pbase;
-            const float* vr = val + r * val_stride + pbase;
-            if constexpr (K % 4 == 0) {
-#pragma unroll
-                for (int it = 0; it < K / 4; ++it) {
-                    const int e = it * 256 + lane * 4;
-                    const int4 i4 = *reinterpret_cast<const int4*>(ir + e);
-                    const float4 v4 = *reinterpret_cast<const float4*>(vr + e);
-                    float* arow = tile + (e / K) * G::kRow;
-                    if (static_cast<uint32_t>(i4.x) < S) atomicAdd(arow + i4.x, v4.x);
-                    if (static_cast<uint32_t>(i4.y) < S) atomicAdd(arow + i4.y, v4.y);
-                    if (static_cast<uint32_t>(i4.z) < S) atomicAdd(arow + i4.z, v4.z);
-                    if (static_cast<uint32_t>(i4.w) < S) atomicAdd(arow + i4.w, v4.w);
-                }
-            } else {
-                for (int e = lane; e < kWave * K; e += kWave) {
-                    const int at = ir[e];
-                    if (static_cast<uint32_t>(at) < S) atomicAdd(tile + (e / K) * G::kRow + at, vr[e]);
-                }
+        if constexpr (K % 4 == 0) {
+            PayloadRegs<K> A, B;
+            load_payload<K>(A, idx + pbase, val + pbase, lane);
+            int r = 0;
+            while (true) {
+                if (r + 1 < p.R)
+                    load_payload<K>(B, idx + (r + 1) * idx_stride + pbase,
+                                    val + (r + 1) * val_stride + pbase, lane);
+                scatter_payload<S, K>(A, tile, lane);
+                if (++r >= p.R) break;
+                if (r + 1 < p.R)
+                    load_payload<K>(A, idx + (r + 1) * idx_stride + pbase,
+                                    val + (r + 1) * val_stride + pbase, lane);
+                scatter_payload<S, K>(B, tile, lane);
+                if (++r >= p.R) break;
             }
-            __syncthreads();
+        } else {
+            // K entries per chunk, lane = chunk
+            for (int r = 0; r < p.R; ++r) {
+                const int32_t* ir = idx + r * idx_stride + pbase + lane * K;
+                const float* vr = val + r * val_stride + pbase + lane * K;
+#pragma unroll
+                for (int j = 0; j < K; ++j)
+                    atomicAdd(tile + lane * G::kRow +
+                                  min(static_cast<uint32_t>(ir[j]), static_cast<uint32_t>(S)),
+                              vr[j]);
+            }
         }
+        // parameters of this tile: issue the loads now, they are needed after the transform
+        constexpr int kIt = S / 8;
+        uint4 thb[PARAM_BF16 ? kIt : 1];
+        float4 thf[PARAM_BF16 ? 1 : 2 * kIt];
+#pragma unroll
+        for (int it = 0; it < kIt; ++it) {
+            const int pe = it * 512 + lane * 8;
+            if constexpr (PARAM_BF16) {
+                thb[it] = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(params) +
+                                                          ebase + pe);
+            } else {
+                const float* th = static_cast<const float*>(params) + ebase + pe;
+                thf[2 * it] = *reinterpret_cast<const float4*>(th);
+                thf[2 * it + 1] = *reinterpret_cast<const float4*>(th + 4);
+            }
+        }
+        __syncthreads();
         // lane = chunk: average, inverse transform, sign
         float* row = tile + lane * G::kRow;
         float y[S];
@@ -364,14 +460,14 @@ __global__ __launch_bounds__(kWave, 2) void decompress_tiled(
         __syncthreads();
         // coalesced parameter update
 #pragma unroll
-        for (int it = 0; it < S / 8; ++it) {
+        for (int it = 0; it < kIt; ++it) {
             const int pe = it * 512 + lane * 8;
             const float* src = tile + (pe / S) * G::kRow + (pe % S);
             const float4 qa = *reinterpret_cast<const float4*>(src);
             const float4 qb = *reinterpret_cast<const float4*>(src + 4);
             if constexpr (PARAM_BF16) {
                 uint16_t* th = static_cast<uint16_t*>(params) + ebase + pe;
-                const uint4 raw = *reinterpret_cast<const uint4*>(th);
+                const uint4 raw = thb[it];
                 auto upd = [&](uint32_t w, float q0, float q1) -> uint32_t {
                     const float t0 = __uint_as_float(w << 16) * p.wd_scale;
                     const float t1 = __uint_as_float(w & 0xFFFF0000u) * p.wd_scale;
@@ -387,8 +483,8 @@ __global__ __launch_bounds__(kWave, 2) void decompress_tiled(
                 *reinterpret_cast<uint4*>(th) = out;
             } else {
                 float* th = static_cast<float*>(params) + ebase + pe;
-                float4 ta = *reinterpret_cast<const float4*>(th);
-                float4 tb = *reinterpret_cast<const float4*>(th + 4);
+                float4 ta = thf[2 * it];
+                float4 tb = thf[2 * it + 1];
                 ta.x = fmaf(-p.lr, qa.x, ta.x * p.wd_scale);
                 ta.y = fmaf(-p.lr, qa.y, ta.y * p.wd_scale);
                 ta.z = fmaf(-p.lr, qa.z, ta.z * p.wd_scale);
