@@ -65,10 +65,9 @@ int launched() { return hipGetLastError() == hipSuccess ? DETO_OK : DETO_ERR_HIP
 
 bool aligned16(const void* p) { return aligned(p, 16); }
 
-unsigned tile_grid(int64_t tiles) {
-    const int64_t cap = 1 << 20;
-    return static_cast<unsigned>(tiles < cap ? tiles : cap);
-}
+// tiled kernels take one 64-chunk tile per workgroup
+constexpr int64_t kMaxTiles = 0x7FFFFFFF;
+unsigned tile_grid(int64_t tiles) { return static_cast<unsigned>(tiles); }
 
 // ---- tiled top-k compress: chunk sizes and k values that have a compiled kernel
 template <int S, int K>
@@ -133,7 +132,7 @@ int detonation_compress(const deto_config* cfg, int64_t n, const void* grad, int
     if (p.scheme == DETO_SCHEME_TOPK && has_tiled(p.s, p.k) && aligned16(grad) &&
         aligned16(momentum) && aligned16(idx_out) && aligned16(val_out) && aligned16(coeff_dbg)) {
         const int64_t tiles = (n / p.s) / deto::kWave;
-        if (tiles > 0) {
+        if (tiles > 0 && tiles <= kMaxTiles) {
 #define X(S, K) if (p.s == S && p.k == K) \
         launch_compress_tiled<S, K>(p, tiles, grad, grad_dtype, momentum, idx_out, val_out, coeff_dbg, st);
             DETO_FOR_EACH_TILED(X)
@@ -182,7 +181,7 @@ int detonation_decompress_step(const deto_config* cfg, int64_t n, int32_t R, con
         aligned16(params) && aligned16(presign_dbg) &&
         (R == 1 || (idx_replica_stride % 4 == 0 && val_replica_stride % 4 == 0))) {
         const int64_t tiles = (n / p.s) / deto::kWave;
-        if (tiles > 0) {
+        if (tiles > 0 && tiles <= kMaxTiles) {
 #define X(S, K) if (p.s == S && p.k == K) \
         launch_decompress_tiled<S, K>(p, tiles, idx, idx_replica_stride, val, val_replica_stride, params, param_dtype, presign_dbg, st);
             DETO_FOR_EACH_TILED(X)

@@ -122,7 +122,10 @@ __global__ __launch_bounds__(kWave, 2) void compress_tiled_topk(
     __shared__ __attribute__((aligned(16))) float tile[G::kFloats];
     const int lane = threadIdx.x;
 
-    for (int64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+    // one tile per workgroup: the host launches exactly n_tiles workgroups
+    const int64_t t = blockIdx.x;
+    if (t >= n_tiles) return;
+    {
         const int64_t ebase = t * G::kElems;
         // ---- phase 1: m1 = beta*m + g, coalesced, into LDS
 #pragma unroll
@@ -196,13 +199,14 @@ __global__ __launch_bounds__(kWave, 2) void compress_tiled_topk(
             sort_desc<H>(B);
             T = kth_largest<H, K>(A, B);
         }
-        // keep magnitude >= T; the mask collects the decisions (bit i = element i)
-        float q[S];
+        // keep magnitude >= T: u holds what stays behind in the momentum (the dropped
+        // coefficients), the mask collects the decisions (bit i = element i kept)
+        float u[S];
         uint32_t mlo = 0u, mhi = 0u;
         static_for<0, S>([&](auto I) {
             constexpr int i = S - 1 - I;   // descending so that shifting lands bit i at i
             const bool keep = (__float_as_uint(c[i]) & 0x7FFFFFFFu) >= T;
-            q[i] = keep ? c[i] : 0.0f;
+            u[i] = keep ? 0.0f : c[i];
             if constexpr (i >= 32) mhi = (mhi << 1) | (keep ? 1u : 0u);
             else mlo = (mlo << 1) | (keep ? 1u : 0u);
         });
@@ -217,38 +221,13 @@ __global__ __launch_bounds__(kWave, 2) void compress_tiled_topk(
             const uint64_t m = gt | lowest_bits(eq, K - __popcll(gt));
             mlo = static_cast<uint32_t>(m);
             mhi = static_cast<uint32_t>(m >> 32);
-            static_for<0, S>([&](auto i) { q[i] = ((m >> i) & 1ull) ? c[i] : 0.0f; });
+            static_for<0, S>([&](auto i) { u[i] = ((m >> i) & 1ull) ? 0.0f : c[i]; });
         }
 
-        // q <- inverse transform of the kept coefficients; m' = m1 - q back into the row
-        {
-            float w[S];
-            w[0] = q[0] * p.alpha0;
-            static_for<1, S>([&](auto i) { w[i] = q[i] * p.alpha; });
-            FastDct<S>::dct3(w);
-#pragma unroll
-            for (int j = 0; j < S / 4; ++j) {
-                float4 v = *reinterpret_cast<const float4*>(row + 4 * j);
-                v.x -= w[4 * j]; v.y -= w[4 * j + 1]; v.z -= w[4 * j + 2]; v.w -= w[4 * j + 3];
-                *reinterpret_cast<float4*>(row + 4 * j) = v;
-            }
-        }
-        __syncthreads();
-
-        // ---- phase 3a: residual momentum out, coalesced
-#pragma unroll
-        for (int it = 0; it < S / 8; ++it) {
-            const int pe = it * 512 + lane * 8;
-            const float* src = tile + (pe / S) * G::kRow + (pe % S);
-            *reinterpret_cast<float4*>(mom + ebase + pe) = *reinterpret_cast<const float4*>(src);
-            *reinterpret_cast<float4*>(mom + ebase + pe + 4) =
-                *reinterpret_cast<const float4*>(src + 4);
-        }
-        __syncthreads();
-
-        // ---- phase 3b: compact the kept (index, value) pairs of each chunk, ascending.
-        // Every element is written at the running position, which only advances past kept
-        // ones, so a dropped element is overwritten by the next kept one.
+        // ---- phase 3a: compact the kept (index, value) pairs of each chunk, ascending.
+        // The tile is free again (every lane holds its row in registers).  Every element
+        // is written at the running position, which only advances past kept ones, so a
+        // dropped element is overwritten by the next kept one.
         constexpr int PR = K + 4;                       // staging row, one spare slot + pad
         float* vrow = tile + lane * PR;
         uint8_t* ibytes = reinterpret_cast<uint8_t*>(tile + kWave * PR);   // indices as bytes
@@ -257,7 +236,7 @@ __global__ __launch_bounds__(kWave, 2) void compress_tiled_topk(
         {
             int pos = 0;
             static_for<0, S>([&](auto i) {
-                vrow[pos] = q[i];
+                vrow[pos] = c[i];
                 irow[pos] = static_cast<uint8_t>(i);
                 const uint32_t bit = (i >= 32) ? ((mhi >> (i - 32)) & 1u) : ((mlo >> i) & 1u);
                 pos += static_cast<int>(bit);
@@ -282,6 +261,26 @@ __global__ __launch_bounds__(kWave, 2) void compress_tiled_topk(
                 val_out[pbase + lane * K + j] = vrow[j];
                 idx_out[pbase + lane * K + j] = irow[j];
             }
+        }
+        __syncthreads();
+
+        // ---- phase 3b: m <- m1 - q.  With q = D^T(kept coefficients) and m1 = D^T(all
+        // coefficients), the residual is the inverse transform of the dropped ones.
+        u[0] *= p.alpha0;
+        static_for<1, S>([&](auto i) { u[i] *= p.alpha; });
+        FastDct<S>::dct3(u);
+#pragma unroll
+        for (int j = 0; j < S / 4; ++j)
+            *reinterpret_cast<float4*>(row + 4 * j) =
+                make_float4(u[4 * j], u[4 * j + 1], u[4 * j + 2], u[4 * j + 3]);
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < S / 8; ++it) {
+            const int pe = it * 512 + lane * 8;
+            const float* src = tile + (pe / S) * G::kRow + (pe % S);
+            *reinterpret_cast<float4*>(mom + ebase + pe) = *reinterpret_cast<const float4*>(src);
+            *reinterpret_cast<float4*>(mom + ebase + pe + 4) =
+                *reinterpret_cast<const float4*>(src + 4);
         }
         __syncthreads();
     }
@@ -373,7 +372,10 @@ __global__ __launch_bounds__(kWave, 2) void decompress_tiled(
     __shared__ __attribute__((aligned(16))) float tile[G::kFloats];
     const int lane = threadIdx.x;
 
-    for (int64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+    // one tile per workgroup: the host launches exactly n_tiles workgroups
+    const int64_t t = blockIdx.x;
+    if (t >= n_tiles) return;
+    {
         const int64_t ebase = t * G::kElems;
         const int64_t pbase = t * (kWave * K);
         // zero the accumulator tile
