@@ -11,7 +11,8 @@ import os
 from dataclasses import dataclass
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libdetonation.so")
+# DETONATION_LIB points the binding at another build of the same library
+LIB_PATH = os.environ.get("DETONATION_LIB", os.path.join(_HERE, "libdetonation.so"))
 
 SCHEME_TOPK, SCHEME_STRIDE, SCHEME_RANDOM = 0, 1, 2
 F32, BF16 = 0, 1

@@ -23,7 +23,9 @@ def sources() -> list[str]:
 
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-o", LIB, *sources()]
+    extra = os.environ.get("DETO_EXTRA_FLAGS", "").split()
+    lib = os.environ.get("DETO_BUILD_OUT", LIB)
+    cmd = [hipcc, *HIPCC_FLAGS, *extra, "-o", lib, *sources()]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)

@@ -91,6 +91,17 @@ __device__ __forceinline__ uint32_t kth_largest(const uint32_t (&A)[H], const ui
     return best;
 }
 
+// Ordering point between the LDS phases of a single-wavefront workgroup.  The LDS queue of
+// one wavefront is processed in program order, so no hardware barrier is needed; this only
+// stops the compiler from moving LDS accesses across the phase boundary.  Unlike
+// __syncthreads() it does not wait for outstanding global loads and stores, so prefetched
+// data stays in flight and finished tiles retire without waiting for their stores.
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+}
+
 template <int S>
 struct TileGeom {
     static constexpr int kRow = S + 4;           // floats per LDS row (16 B of padding)
@@ -131,12 +142,11 @@ __global__ __launch_bounds__(kWave, 2) void compress_tiled_topk(
 #pragma unroll
         for (int it = 0; it < S / 8; ++it) {
             const int pe = it * 512 + lane * 8;
-            const float4 ma = *reinterpret_cast<const float4*>(mom + ebase + pe);
-            const float4 mb = *reinterpret_cast<const float4*>(mom + ebase + pe + 4);
+            const float4 ma = ld_f4<DETO_NT_COMPRESS_MOM>(mom + ebase + pe);
+            const float4 mb = ld_f4<DETO_NT_COMPRESS_MOM>(mom + ebase + pe + 4);
             float g[8];
             if constexpr (GRAD_BF16) {
-                const uint4 raw = *reinterpret_cast<const uint4*>(
-                    static_cast<const uint16_t*>(grad) + ebase + pe);
+                const uint4 raw = ld_u4<DETO_NT_COMPRESS_GRAD>(static_cast<const uint16_t*>(grad) + ebase + pe);
                 g[0] = __uint_as_float(raw.x << 16);
                 g[1] = __uint_as_float(raw.x & 0xFFFF0000u);
                 g[2] = __uint_as_float(raw.y << 16);
@@ -146,10 +156,8 @@ __global__ __launch_bounds__(kWave, 2) void compress_tiled_topk(
                 g[6] = __uint_as_float(raw.w << 16);
                 g[7] = __uint_as_float(raw.w & 0xFFFF0000u);
             } else {
-                const float4 ga =
-                    *reinterpret_cast<const float4*>(static_cast<const float*>(grad) + ebase + pe);
-                const float4 gb = *reinterpret_cast<const float4*>(static_cast<const float*>(grad) +
-                                                                   ebase + pe + 4);
+                const float4 ga = ld_f4<DETO_NT_COMPRESS_GRAD>(static_cast<const float*>(grad) + ebase + pe);
+                const float4 gb = ld_f4<DETO_NT_COMPRESS_GRAD>(static_cast<const float*>(grad) + ebase + pe + 4);
                 g[0] = ga.x; g[1] = ga.y; g[2] = ga.z; g[3] = ga.w;
                 g[4] = gb.x; g[5] = gb.y; g[6] = gb.z; g[7] = gb.w;
             }
@@ -166,7 +174,7 @@ __global__ __launch_bounds__(kWave, 2) void compress_tiled_topk(
             *reinterpret_cast<float4*>(dst) = fa;
             *reinterpret_cast<float4*>(dst + 4) = fb;
         }
-        __syncthreads();
+        wave_lds_sync();
 
         // ---- phase 2: lane = chunk
         float* row = tile + lane * G::kRow;
@@ -242,18 +250,18 @@ __global__ __launch_bounds__(kWave, 2) void compress_tiled_topk(
                 pos += static_cast<int>(bit);
             });
         }
-        __syncthreads();
+        wave_lds_sync();
         const int64_t pbase = t * (kWave * K);
         if constexpr (K % 4 == 0) {
 #pragma unroll
             for (int it = 0; it < K / 4; ++it) {
                 const int e = it * 256 + lane * 4;
                 const int r = e / K, col = e % K;
-                *reinterpret_cast<float4*>(val_out + pbase + e) =
-                    *reinterpret_cast<const float4*>(tile + r * PR + col);
+                st_f4<DETO_NT_COMPRESS_PAYLOAD>(val_out + pbase + e,
+                             *reinterpret_cast<const float4*>(tile + r * PR + col));
                 const uint32_t pk = *reinterpret_cast<const uint32_t*>(ibytes + r * PR + col);
-                *reinterpret_cast<int4*>(idx_out + pbase + e) =
-                    make_int4(pk & 0xFFu, (pk >> 8) & 0xFFu, (pk >> 16) & 0xFFu, pk >> 24);
+                st_u4<DETO_NT_COMPRESS_PAYLOAD>(idx_out + pbase + e,
+                             make_uint4(pk & 0xFFu, (pk >> 8) & 0xFFu, (pk >> 16) & 0xFFu, pk >> 24));
             }
         } else {
 #pragma unroll
@@ -262,7 +270,7 @@ __global__ __launch_bounds__(kWave, 2) void compress_tiled_topk(
                 idx_out[pbase + lane * K + j] = irow[j];
             }
         }
-        __syncthreads();
+        wave_lds_sync();
 
         // ---- phase 3b: m <- m1 - q.  With q = D^T(kept coefficients) and m1 = D^T(all
         // coefficients), the residual is the inverse transform of the dropped ones.
@@ -273,16 +281,15 @@ __global__ __launch_bounds__(kWave, 2) void compress_tiled_topk(
         for (int j = 0; j < S / 4; ++j)
             *reinterpret_cast<float4*>(row + 4 * j) =
                 make_float4(u[4 * j], u[4 * j + 1], u[4 * j + 2], u[4 * j + 3]);
-        __syncthreads();
+        wave_lds_sync();
 #pragma unroll
         for (int it = 0; it < S / 8; ++it) {
             const int pe = it * 512 + lane * 8;
             const float* src = tile + (pe / S) * G::kRow + (pe % S);
-            *reinterpret_cast<float4*>(mom + ebase + pe) = *reinterpret_cast<const float4*>(src);
-            *reinterpret_cast<float4*>(mom + ebase + pe + 4) =
-                *reinterpret_cast<const float4*>(src + 4);
+            st_f4<DETO_NT_COMPRESS_MOM_ST>(mom + ebase + pe, *reinterpret_cast<const float4*>(src));
+            st_f4<DETO_NT_COMPRESS_MOM_ST>(mom + ebase + pe + 4, *reinterpret_cast<const float4*>(src + 4));
         }
-        __syncthreads();
+        wave_lds_sync();
     }
 }
 
@@ -301,8 +308,9 @@ __device__ __forceinline__ void load_payload(PayloadRegs<K>& r, const int32_t* _
 #pragma unroll
     for (int it = 0; it < K / 4; ++it) {
         const int e = it * 256 + lane * 4;
-        r.i[it] = *reinterpret_cast<const int4*>(ir + e);
-        r.v[it] = *reinterpret_cast<const float4*>(vr + e);
+        const uint4 iv = ld_u4<DETO_NT_DECOMPRESS_LD>(ir + e);
+        r.i[it] = make_int4(iv.x, iv.y, iv.z, iv.w);
+        r.v[it] = ld_f4<DETO_NT_DECOMPRESS_LD>(vr + e);
     }
 }
 
@@ -328,24 +336,31 @@ __device__ __forceinline__ void scatter_payload(const PayloadRegs<K>& r, float* 
         ok = ok && (x < y) && (y < z) && (z < w) && (first || pw < x);
     }
     if (!__any(!ok)) {
-        float old[kIt][4];
-        float* at[kIt][4];
+        // groups of a few vectors: all reads of a group, then all its writes
+        constexpr int kGroup = kIt < 4 ? kIt : 4;
 #pragma unroll
-        for (int it = 0; it < kIt; ++it) {
-            float* arow = tile + ((it * 256 + lane * 4) / K) * kRow;
-            at[it][0] = arow + min(static_cast<uint32_t>(r.i[it].x), kS);
-            at[it][1] = arow + min(static_cast<uint32_t>(r.i[it].y), kS);
-            at[it][2] = arow + min(static_cast<uint32_t>(r.i[it].z), kS);
-            at[it][3] = arow + min(static_cast<uint32_t>(r.i[it].w), kS);
+        for (int g0 = 0; g0 < kIt; g0 += kGroup) {
+            float old[kGroup][4];
+            float* at[kGroup][4];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) old[it][c] = *at[it][c];
-        }
+            for (int g = 0; g < kGroup; ++g) {
+                const int it = g0 + g;
+                float* arow = tile + ((it * 256 + lane * 4) / K) * kRow;
+                at[g][0] = arow + min(static_cast<uint32_t>(r.i[it].x), kS);
+                at[g][1] = arow + min(static_cast<uint32_t>(r.i[it].y), kS);
+                at[g][2] = arow + min(static_cast<uint32_t>(r.i[it].z), kS);
+                at[g][3] = arow + min(static_cast<uint32_t>(r.i[it].w), kS);
 #pragma unroll
-        for (int it = 0; it < kIt; ++it) {
-            *at[it][0] = old[it][0] + r.v[it].x;
-            *at[it][1] = old[it][1] + r.v[it].y;
-            *at[it][2] = old[it][2] + r.v[it].z;
-            *at[it][3] = old[it][3] + r.v[it].w;
+                for (int c = 0; c < 4; ++c) old[g][c] = *at[g][c];
+            }
+#pragma unroll
+            for (int g = 0; g < kGroup; ++g) {
+                const int it = g0 + g;
+                *at[g][0] = old[g][0] + r.v[it].x;
+                *at[g][1] = old[g][1] + r.v[it].y;
+                *at[g][2] = old[g][2] + r.v[it].z;
+                *at[g][3] = old[g][3] + r.v[it].w;
+            }
         }
     } else {
 #pragma unroll
@@ -360,7 +375,7 @@ __device__ __forceinline__ void scatter_payload(const PayloadRegs<K>& r, float* 
 }
 
 // Decompress-and-update half on full tiles (transform domain, indices transmitted).
-// The payload of replica r+1 is in flight while replica r is scattered into LDS; LDS
+// Up to three replicas' payloads are in flight while one is scattered into LDS; LDS
 // operations of one wavefront complete in order, so the additions into one accumulator
 // happen replica after replica and the result does not depend on timing.
 template <int S, int K, bool PARAM_BF16>
@@ -383,21 +398,26 @@ __global__ __launch_bounds__(kWave, 2) void decompress_tiled(
         for (int i = 0; i < G::kFloats / (kWave * 4); ++i)
             *reinterpret_cast<float4*>(tile + (i * kWave + lane) * 4) =
                 make_float4(0.f, 0.f, 0.f, 0.f);
-        __syncthreads();
+        wave_lds_sync();
         if constexpr (K % 4 == 0) {
-            PayloadRegs<K> A, B;
-            load_payload<K>(A, idx + pbase, val + pbase, lane);
+            // three replicas' payloads in flight at a time
+            PayloadRegs<K> b0, b1, b2;
+            auto fetch = [&](PayloadRegs<K>& b, int r) {
+                load_payload<K>(b, idx + r * idx_stride + pbase, val + r * val_stride + pbase, lane);
+            };
+            fetch(b0, 0);
+            if (p.R > 1) fetch(b1, 1);
+            if (p.R > 2) fetch(b2, 2);
             int r = 0;
             while (true) {
-                if (r + 1 < p.R)
-                    load_payload<K>(B, idx + (r + 1) * idx_stride + pbase,
-                                    val + (r + 1) * val_stride + pbase, lane);
-                scatter_payload<S, K>(A, tile, lane);
+                scatter_payload<S, K>(b0, tile, lane);
+                if (r + 3 < p.R) fetch(b0, r + 3);
                 if (++r >= p.R) break;
-                if (r + 1 < p.R)
-                    load_payload<K>(A, idx + (r + 1) * idx_stride + pbase,
-                                    val + (r + 1) * val_stride + pbase, lane);
-                scatter_payload<S, K>(B, tile, lane);
+                scatter_payload<S, K>(b1, tile, lane);
+                if (r + 3 < p.R) fetch(b1, r + 3);
+                if (++r >= p.R) break;
+                scatter_payload<S, K>(b2, tile, lane);
+                if (r + 3 < p.R) fetch(b2, r + 3);
                 if (++r >= p.R) break;
             }
         } else {
@@ -420,15 +440,14 @@ __global__ __launch_bounds__(kWave, 2) void decompress_tiled(
         for (int it = 0; it < kIt; ++it) {
             const int pe = it * 512 + lane * 8;
             if constexpr (PARAM_BF16) {
-                thb[it] = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(params) +
-                                                          ebase + pe);
+                thb[it] = ld_u4<DETO_NT_DECOMPRESS_LD>(static_cast<const uint16_t*>(params) + ebase + pe);
             } else {
                 const float* th = static_cast<const float*>(params) + ebase + pe;
-                thf[2 * it] = *reinterpret_cast<const float4*>(th);
-                thf[2 * it + 1] = *reinterpret_cast<const float4*>(th + 4);
+                thf[2 * it] = ld_f4<DETO_NT_DECOMPRESS_LD>(th);
+                thf[2 * it + 1] = ld_f4<DETO_NT_DECOMPRESS_LD>(th + 4);
             }
         }
-        __syncthreads();
+        wave_lds_sync();
         // lane = chunk: average, inverse transform, sign
         float* row = tile + lane * G::kRow;
         float y[S];
@@ -459,7 +478,7 @@ __global__ __launch_bounds__(kWave, 2) void decompress_tiled(
             v.w = sign_or_self(y[4 * j + 3], p.use_sign);
             *reinterpret_cast<float4*>(row + 4 * j) = v;
         }
-        __syncthreads();
+        wave_lds_sync();
         // coalesced parameter update
 #pragma unroll
         for (int it = 0; it < kIt; ++it) {
@@ -482,7 +501,7 @@ __global__ __launch_bounds__(kWave, 2) void decompress_tiled(
                 out.y = upd(raw.y, qa.z, qa.w);
                 out.z = upd(raw.z, qb.x, qb.y);
                 out.w = upd(raw.w, qb.z, qb.w);
-                *reinterpret_cast<uint4*>(th) = out;
+                st_u4<DETO_NT_DECOMPRESS_ST>(th, out);
             } else {
                 float* th = static_cast<float*>(params) + ebase + pe;
                 float4 ta = thf[2 * it];
@@ -495,11 +514,11 @@ __global__ __launch_bounds__(kWave, 2) void decompress_tiled(
                 tb.y = fmaf(-p.lr, qb.y, tb.y * p.wd_scale);
                 tb.z = fmaf(-p.lr, qb.z, tb.z * p.wd_scale);
                 tb.w = fmaf(-p.lr, qb.w, tb.w * p.wd_scale);
-                *reinterpret_cast<float4*>(th) = ta;
-                *reinterpret_cast<float4*>(th + 4) = tb;
+                st_f4<DETO_NT_DECOMPRESS_ST>(th, ta);
+                st_f4<DETO_NT_DECOMPRESS_ST>(th + 4, tb);
             }
         }
-        __syncthreads();
+        wave_lds_sync();
     }
 }
 
