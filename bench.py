@@ -152,13 +152,15 @@ def main() -> int:
     dom = "compress" if t_c >= t_d else "decompress"
     dom_gbs = gbs_c if dom == "compress" else gbs_d
 
+    # HBM bytes per launch of the dominant kernel as rocprofv3's FETCH_SIZE + WRITE_SIZE counters
+    # measured them for this workload (recorded under profiles/, not re-measured here)
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{args.workload}_{args.scheme}.txt")
     if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get(f"{args.workload}:{args.scheme}", {}).get(dom)
-        except Exception:
-            traffic = None
+        for line in open(tpath):
+            f = line.split()
+            if len(f) == 2 and f[0] == dom:
+                traffic = float(f[1])
 
     out = {
         "metric": "optimizer_step_params_per_sec", "value": n * args.steps / wall,
