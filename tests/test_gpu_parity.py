@@ -207,3 +207,69 @@ def test_vit_b16_shard_full_size(H):
     assert w.n == 10_820_957 and w.n % 32 == 29
     for s, k in [(32, 16), (128, 4)]:
         full_step(H, Config(chunk=s, topk=k), w.n, R=2, seed=1)
+
+
+def _sample_runs(C, run=256, count=24, seed=5):
+    """Chunk ranges to check at full size: the first and last tiles, the ragged end, and
+    seeded random runs of `run` consecutive chunks."""
+    rng = np.random.default_rng(seed)
+    starts = [0, max(C - run, 0)] + [int(x) for x in rng.integers(0, max(C - run, 1), count)]
+    return sorted({(s0, min(s0 + run, C)) for s0 in starts})
+
+
+def _full_size_check(H, w, cfg, runs_count=24):
+    """Parity at a benchmark configuration's full size, in the launch configuration bench.py
+    times (debug outputs off), judged on sampled chunk runs the oracle computes one by one."""
+    import torch
+    from paper_2502_06728_amd import binding
+    s, k, R, n = cfg.chunk, cfg.topk, w.replicas, w.n
+    C = -(-n // s)
+    g, m, th = synth.shard(w)
+    send_idx = cfg.scheme == SCHEME_TOPK
+    # the timed configuration: no debug outputs
+    m_a, idx_a, val_a, _ = H.gpu_compress(cfg, g, m, want_idx=send_idx, want_coeff=False)
+    # same call with the coefficient export, which must not change any result
+    m_b, idx_b, val_b, coeff = H.gpu_compress(cfg, g, m, want_idx=send_idx, want_coeff=True)
+    assert np.array_equal(m_a.view(np.uint32), m_b.view(np.uint32))
+    assert np.array_equal(val_a.view(np.uint32), val_b.view(np.uint32))
+    if send_idx:
+        assert np.array_equal(idx_a, idx_b)
+        assert idx_a.min() >= 0 and idx_a.max() < s
+        assert (np.diff(idx_a.reshape(C, k), axis=1) > 0).all()        # holds at any size
+    worst = {"coeff": 0.0, "momentum": 0.0, "flips": 0}
+    for c0, c1 in _sample_runs(C, count=runs_count):
+        e0, e1 = c0 * s, min(c1 * s, n)
+        st = parity.check_compress(cfg, g[e0:e1], m[e0:e1], m_a[e0:e1],
+                                   idx_a[c0 * k:c1 * k] if send_idx else None,
+                                   val_a[c0 * k:c1 * k], coeff[c0 * s:c1 * s], chunk0=c0)
+        worst["coeff"] = max(worst["coeff"], st["coeff"])
+        worst["momentum"] = max(worst["momentum"], st["momentum"])
+        worst["flips"] += st["flips"]
+    del m_a, m_b, val_b, idx_b, coeff
+    # decompress: R structurally valid payloads from the generator (not from either compress)
+    idx = np.empty((R, C * k), np.int32)
+    val = np.empty((R, C * k), np.float32)
+    for r in range(R):
+        idx[r], val[r] = synth.structured_payload(w.seed + 10 + r, C, s, k, w.momentum_std)
+    th_a, _ = H.gpu_decompress(cfg, idx if send_idx else None, val, th, want_presign=False)
+    th_b, y = H.gpu_decompress(cfg, idx if send_idx else None, val, th, want_presign=True)
+    assert np.array_equal(th_a, th_b)
+    worst["presign"] = 0.0
+    for c0, c1 in _sample_runs(C, count=runs_count, seed=6):
+        e0, e1 = c0 * s, min(c1 * s, n)
+        if not send_idx:
+            continue   # regenerated indices are keyed by the global chunk number: covered at small n
+        st = parity.check_decompress(cfg, idx[:, c0 * k:c1 * k], val[:, c0 * k:c1 * k], th[e0:e1],
+                                     th_a[e0:e1], y[e0:e1])
+        worst["presign"] = max(worst["presign"], st["presign"])
+    return worst
+
+
+def test_olmo_1b_shard_full_size_bench_configuration(H):
+    # the benchmark's workload: 147,095,552 parameters, bf16 grads/params with outliers,
+    # chunk 64, top-k 32, R = 4
+    w = synth.workloads()["olmo-1b-1of8"]
+    assert w.n == 147_095_552
+    cfg = Config(chunk=w.chunk, topk=w.topk, decay=w.decay, lr=w.lr, sign=w.sign)
+    worst = _full_size_check(H, w, cfg)
+    print("olmo-1b full size:", worst)
