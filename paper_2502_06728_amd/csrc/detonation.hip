@@ -10,7 +10,7 @@
 
 #include "deto_device.hip.h"
 #include "generic_kernels.hip.h"
-#include "tiled_kernels.hip.h"
+#include "tiled_launch.h"
 
 namespace {
 
@@ -67,47 +67,15 @@ bool aligned16(const void* p) { return aligned(p, 16); }
 
 // tiled kernels take one 64-chunk tile per workgroup
 constexpr int64_t kMaxTiles = 0x7FFFFFFF;
-unsigned tile_grid(int64_t tiles) { return static_cast<unsigned>(tiles); }
 
-// ---- tiled top-k compress: chunk sizes and k values that have a compiled kernel
-template <int S, int K>
-void launch_compress_tiled(const KParams& p, int64_t tiles, const void* grad, int grad_dtype,
-                           float* mom, int32_t* idx, float* val, float* dbg, hipStream_t st) {
-    const unsigned grid = tile_grid(tiles);
-    if (grad_dtype == DETO_BF16)
-        deto::compress_tiled_topk<S, K, true><<<grid, deto::kWave, 0, st>>>(p, tiles, grad, mom, idx,
-                                                                            val, dbg);
-    else
-        deto::compress_tiled_topk<S, K, false><<<grid, deto::kWave, 0, st>>>(p, tiles, grad, mom,
-                                                                             idx, val, dbg);
-}
-
-template <int S, int K>
-void launch_decompress_tiled(const KParams& p, int64_t tiles, const int32_t* idx, int64_t is,
-                             const float* val, int64_t vs, void* params, int param_dtype,
-                             float* dbg, hipStream_t st) {
-    const unsigned grid = tile_grid(tiles);
-    if (param_dtype == DETO_BF16)
-        deto::decompress_tiled<S, K, true><<<grid, deto::kWave, 0, st>>>(p, tiles, idx, is, val, vs,
-                                                                         params, dbg);
-    else
-        deto::decompress_tiled<S, K, false><<<grid, deto::kWave, 0, st>>>(p, tiles, idx, is, val,
-                                                                          vs, params, dbg);
-}
-
-#ifdef DETO_TILED_ONLY_64_32   // development builds: one instantiation, seconds to compile
-#define DETO_FOR_EACH_TILED(X) X(64, 32)
-#else
-#define DETO_FOR_EACH_TILED(X) \
-    X(64, 1) X(64, 2) X(64, 4) X(64, 8) X(64, 16) X(64, 32) \
-    X(32, 1) X(32, 2) X(32, 4) X(32, 8) X(32, 16)
-#endif
-
-bool has_tiled(int s, int k) {
-#define X(S, K) if (s == S && k == K) return true;
-    DETO_FOR_EACH_TILED(X)
-#undef X
-    return false;
+// Striding: the positions o + j*floor(s/k) as a bit pattern (chunk sizes up to 64)
+uint64_t stride_pattern(const KParams& p) {
+    if (p.s > 64) return 0;
+    const int stride = p.s / p.k;
+    const int off = static_cast<int>(p.step % static_cast<uint64_t>(stride));
+    uint64_t m = 0;
+    for (int j = 0; j < p.k; ++j) m |= 1ull << (off + j * stride);
+    return m;
 }
 
 }  // namespace
@@ -131,16 +99,18 @@ int detonation_compress(const deto_config* cfg, int64_t n, const void* grad, int
     const int64_t C = chunks_of(n, p.s);
     hipStream_t st = static_cast<hipStream_t>(stream);
 
-    // full 64-chunk tiles go to the tiled kernel, whatever is left to the general one
+    // full 64-chunk tiles go to a tiled kernel if one exists, whatever is left to the
+    // general one
     int64_t c0 = 0;
-    if (p.scheme == DETO_SCHEME_TOPK && has_tiled(p.s, p.k) && aligned16(grad) &&
-        aligned16(momentum) && aligned16(idx_out) && aligned16(val_out) && aligned16(coeff_dbg)) {
-        const int64_t tiles = (n / p.s) / deto::kWave;
-        if (tiles > 0 && tiles <= kMaxTiles) {
-#define X(S, K) if (p.s == S && p.k == K) \
-        launch_compress_tiled<S, K>(p, tiles, grad, grad_dtype, momentum, idx_out, val_out, coeff_dbg, st);
-            DETO_FOR_EACH_TILED(X)
-#undef X
+    const int64_t tiles = (n / p.s) / deto::kWave;
+    if (tiles > 0 && tiles <= kMaxTiles && aligned16(grad) && aligned16(momentum) &&
+        aligned16(idx_out) && aligned16(val_out) && aligned16(coeff_dbg)) {
+        const deto::CompressLaunch a{p, tiles, grad, grad_dtype == DETO_BF16, momentum, idx_out,
+                                     val_out, coeff_dbg, stride_pattern(p), st};
+        const bool done = (p.scheme == DETO_SCHEME_TOPK)
+                              ? (deto::launch_compress_topk_s64(a) || deto::launch_compress_topk_s32(a))
+                              : deto::launch_compress_scheme(a);
+        if (done) {
             rc = launched();
             if (rc) return rc;
             c0 = tiles * deto::kWave;
@@ -181,15 +151,16 @@ int detonation_decompress_step(const deto_config* cfg, int64_t n, int32_t R, con
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     int64_t c0 = 0;
-    if (idx && p.use_dct && has_tiled(p.s, p.k) && aligned16(idx) && aligned16(val) &&
-        aligned16(params) && aligned16(presign_dbg) &&
-        (R == 1 || (idx_replica_stride % 4 == 0 && val_replica_stride % 4 == 0))) {
-        const int64_t tiles = (n / p.s) / deto::kWave;
-        if (tiles > 0 && tiles <= kMaxTiles) {
-#define X(S, K) if (p.s == S && p.k == K) \
-        launch_decompress_tiled<S, K>(p, tiles, idx, idx_replica_stride, val, val_replica_stride, params, param_dtype, presign_dbg, st);
-            DETO_FOR_EACH_TILED(X)
-#undef X
+    const int64_t tiles = (n / p.s) / deto::kWave;
+    if (tiles > 0 && tiles <= kMaxTiles && aligned16(idx) && aligned16(val) && aligned16(params) &&
+        aligned16(presign_dbg) &&
+        (R == 1 || ((!idx || idx_replica_stride % 4 == 0) && val_replica_stride % 4 == 0))) {
+        const deto::DecompressLaunch a{p, tiles, idx, idx_replica_stride, val, val_replica_stride,
+                                       params, param_dtype == DETO_BF16, presign_dbg,
+                                       stride_pattern(p), st};
+        const bool done = idx ? (deto::launch_decompress_idx_s64(a) || deto::launch_decompress_idx_s32(a))
+                              : deto::launch_decompress_scheme(a);
+        if (done) {
             rc = launched();
             if (rc) return rc;
             c0 = tiles * deto::kWave;

@@ -15,6 +15,8 @@
 // magnitude T follows from the two sorted halves as max_i min(A[i-1], B[k-i-1]); entries
 // with magnitude >= T are kept.  Only if some chunk of the wavefront has a tie AT the
 // threshold does the wavefront take the exact path that keeps the lowest indices.
+// Striding keeps a fixed bit pattern, Random builds each chunk's pattern with a
+// Fisher-Yates shuffle private to the chunk's lane.
 #pragma once
 
 #include "deto_device.hip.h"
@@ -107,6 +109,7 @@ struct TileGeom {
     static constexpr int kRow = S + 4;           // floats per LDS row (16 B of padding)
     static constexpr int kFloats = kWave * kRow;
     static constexpr int kElems = kWave * S;     // elements per tile
+    static constexpr int kPermStride = S + 4;    // bytes per lane of Fisher-Yates scratch
 };
 
 // keep the `need` lowest set bits of `e` (per lane), wave-uniform loop
@@ -123,6 +126,168 @@ __device__ __forceinline__ uint64_t lowest_bits(uint64_t e, int need) {
     return keep;
 }
 
+__device__ __forceinline__ uint32_t mask_bit(uint32_t mlo, uint32_t mhi, int i) {
+    return (i >= 32) ? ((mhi >> (i - 32)) & 1u) : ((mlo >> i) & 1u);
+}
+
+// ---- phase 1 of compress: m1 = beta*m + g, coalesced, into the LDS tile
+template <int S, bool GRAD_BF16>
+__device__ __forceinline__ void fold_tile_to_lds(const KParams& p, const void* __restrict__ grad,
+                                                 const float* __restrict__ mom, int64_t ebase,
+                                                 float* tile, int lane) {
+    using G = TileGeom<S>;
+#pragma unroll
+    for (int it = 0; it < S / 8; ++it) {
+        const int pe = it * 512 + lane * 8;
+        const float4 ma = ld_f4<DETO_NT_COMPRESS_MOM>(mom + ebase + pe);
+        const float4 mb = ld_f4<DETO_NT_COMPRESS_MOM>(mom + ebase + pe + 4);
+        float g[8];
+        if constexpr (GRAD_BF16) {
+            const uint4 raw =
+                ld_u4<DETO_NT_COMPRESS_GRAD>(static_cast<const uint16_t*>(grad) + ebase + pe);
+            g[0] = __uint_as_float(raw.x << 16);
+            g[1] = __uint_as_float(raw.x & 0xFFFF0000u);
+            g[2] = __uint_as_float(raw.y << 16);
+            g[3] = __uint_as_float(raw.y & 0xFFFF0000u);
+            g[4] = __uint_as_float(raw.z << 16);
+            g[5] = __uint_as_float(raw.z & 0xFFFF0000u);
+            g[6] = __uint_as_float(raw.w << 16);
+            g[7] = __uint_as_float(raw.w & 0xFFFF0000u);
+        } else {
+            const float4 ga =
+                ld_f4<DETO_NT_COMPRESS_GRAD>(static_cast<const float*>(grad) + ebase + pe);
+            const float4 gb =
+                ld_f4<DETO_NT_COMPRESS_GRAD>(static_cast<const float*>(grad) + ebase + pe + 4);
+            g[0] = ga.x; g[1] = ga.y; g[2] = ga.z; g[3] = ga.w;
+            g[4] = gb.x; g[5] = gb.y; g[6] = gb.z; g[7] = gb.w;
+        }
+        float4 fa, fb;
+        fa.x = fmaf(p.beta, ma.x, g[0]);
+        fa.y = fmaf(p.beta, ma.y, g[1]);
+        fa.z = fmaf(p.beta, ma.z, g[2]);
+        fa.w = fmaf(p.beta, ma.w, g[3]);
+        fb.x = fmaf(p.beta, mb.x, g[4]);
+        fb.y = fmaf(p.beta, mb.y, g[5]);
+        fb.z = fmaf(p.beta, mb.z, g[6]);
+        fb.w = fmaf(p.beta, mb.w, g[7]);
+        float* dst = tile + (pe / S) * G::kRow + (pe % S);
+        *reinterpret_cast<float4*>(dst) = fa;
+        *reinterpret_cast<float4*>(dst + 4) = fb;
+    }
+}
+
+template <int S>
+__device__ __forceinline__ void row_to_regs(const float* row, float (&x)[S]) {
+#pragma unroll
+    for (int j = 0; j < S / 4; ++j) {
+        const float4 v = *reinterpret_cast<const float4*>(row + 4 * j);
+        x[4 * j] = v.x; x[4 * j + 1] = v.y; x[4 * j + 2] = v.z; x[4 * j + 3] = v.w;
+    }
+}
+
+template <int S>
+__device__ __forceinline__ void regs_to_row(float* row, const float (&x)[S]) {
+#pragma unroll
+    for (int j = 0; j < S / 4; ++j)
+        *reinterpret_cast<float4*>(row + 4 * j) =
+            make_float4(x[4 * j], x[4 * j + 1], x[4 * j + 2], x[4 * j + 3]);
+}
+
+// debug export of one chunk's S values straight from the lane that owns the chunk
+template <int S>
+__device__ __forceinline__ void regs_to_global(float* dst, const float (&x)[S]) {
+#pragma unroll
+    for (int j = 0; j < S / 4; ++j)
+        *reinterpret_cast<float4*>(dst + 4 * j) =
+            make_float4(x[4 * j], x[4 * j + 1], x[4 * j + 2], x[4 * j + 3]);
+}
+
+// ---- phase 3a of compress: compact the kept (index, value) pairs of each chunk, ascending,
+// and store the tile's payload coalesced.  The tile must be free (every lane holds its row
+// in registers).  Every element is written at the running position, which only advances
+// past kept ones, so a dropped element is overwritten by the next kept one.
+template <int S, int K>
+__device__ __forceinline__ void compact_and_store_payload(const float (&c)[S], uint32_t mlo,
+                                                          uint32_t mhi, float* tile, int lane,
+                                                          int32_t* __restrict__ idx_out,
+                                                          float* __restrict__ val_out,
+                                                          int64_t pbase) {
+    using G = TileGeom<S>;
+    constexpr int PR = K + 4;                       // staging row, one spare slot + pad
+    float* vrow = tile + lane * PR;
+    uint8_t* ibytes = reinterpret_cast<uint8_t*>(tile + kWave * PR);   // indices as bytes
+    uint8_t* irow = ibytes + lane * PR;
+    static_assert(kWave * PR * 5 <= G::kFloats * 4, "staging must fit in the tile");
+    {
+        int pos = 0;
+        static_for<0, S>([&](auto i) {
+            vrow[pos] = c[i];
+            irow[pos] = static_cast<uint8_t>(i);
+            pos += static_cast<int>(mask_bit(mlo, mhi, i));
+        });
+    }
+    wave_lds_sync();
+    if constexpr (K % 4 == 0) {
+#pragma unroll
+        for (int it = 0; it < K / 4; ++it) {
+            const int e = it * 256 + lane * 4;
+            const int r = e / K, col = e % K;
+            st_f4<DETO_NT_COMPRESS_PAYLOAD>(val_out + pbase + e,
+                                            *reinterpret_cast<const float4*>(tile + r * PR + col));
+            if (idx_out) {
+                const uint32_t pk = *reinterpret_cast<const uint32_t*>(ibytes + r * PR + col);
+                st_u4<DETO_NT_COMPRESS_PAYLOAD>(
+                    idx_out + pbase + e,
+                    make_uint4(pk & 0xFFu, (pk >> 8) & 0xFFu, (pk >> 16) & 0xFFu, pk >> 24));
+            }
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+            val_out[pbase + lane * K + j] = vrow[j];
+            if (idx_out) idx_out[pbase + lane * K + j] = irow[j];
+        }
+    }
+    wave_lds_sync();
+}
+
+// ---- phase 3b of compress: the tile (rows = residual momentum) out, coalesced
+template <int S>
+__device__ __forceinline__ void store_tile_momentum(const float* tile, float* __restrict__ mom,
+                                                    int64_t ebase, int lane) {
+    using G = TileGeom<S>;
+#pragma unroll
+    for (int it = 0; it < S / 8; ++it) {
+        const int pe = it * 512 + lane * 8;
+        const float* src = tile + (pe / S) * G::kRow + (pe % S);
+        st_f4<DETO_NT_COMPRESS_MOM_ST>(mom + ebase + pe, *reinterpret_cast<const float4*>(src));
+        st_f4<DETO_NT_COMPRESS_MOM_ST>(mom + ebase + pe + 4,
+                                       *reinterpret_cast<const float4*>(src + 4));
+    }
+}
+
+// Random scheme: the kept positions of one chunk as a bit mask.  `perm` is S bytes of LDS
+// private to the calling lane.  Only perm[t] needs writing back: place j is never read
+// again once step j has taken its value.
+template <int S, int K>
+__device__ __forceinline__ uint64_t random_mask(uint64_t seed, uint64_t step, uint64_t chunk,
+                                                uint8_t* perm) {
+#pragma unroll
+    for (int w = 0; w < S / 4; ++w)
+        reinterpret_cast<uint32_t*>(perm)[w] = 0x03020100u + 0x04040404u * w;
+    const uint64_t key = chunk_key(seed, step, chunk);
+    uint64_t mask = 0;
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+        const int t = j + static_cast<int>(bounded(draw(key, j), S - j));
+        const uint8_t pj = perm[j];
+        const uint8_t pt = perm[t];
+        perm[t] = pj;
+        mask |= 1ull << pt;
+    }
+    return mask;
+}
+
 // Compress half (top-k) on full tiles: chunks [0, 64*n_tiles), all complete.
 template <int S, int K, bool GRAD_BF16>
 __global__ __launch_bounds__(kWave, 2) void compress_tiled_topk(
@@ -132,165 +297,120 @@ __global__ __launch_bounds__(kWave, 2) void compress_tiled_topk(
     constexpr int H = S / 2;
     __shared__ __attribute__((aligned(16))) float tile[G::kFloats];
     const int lane = threadIdx.x;
-
     // one tile per workgroup: the host launches exactly n_tiles workgroups
     const int64_t t = blockIdx.x;
     if (t >= n_tiles) return;
-    {
-        const int64_t ebase = t * G::kElems;
-        // ---- phase 1: m1 = beta*m + g, coalesced, into LDS
-#pragma unroll
-        for (int it = 0; it < S / 8; ++it) {
-            const int pe = it * 512 + lane * 8;
-            const float4 ma = ld_f4<DETO_NT_COMPRESS_MOM>(mom + ebase + pe);
-            const float4 mb = ld_f4<DETO_NT_COMPRESS_MOM>(mom + ebase + pe + 4);
-            float g[8];
-            if constexpr (GRAD_BF16) {
-                const uint4 raw = ld_u4<DETO_NT_COMPRESS_GRAD>(static_cast<const uint16_t*>(grad) + ebase + pe);
-                g[0] = __uint_as_float(raw.x << 16);
-                g[1] = __uint_as_float(raw.x & 0xFFFF0000u);
-                g[2] = __uint_as_float(raw.y << 16);
-                g[3] = __uint_as_float(raw.y & 0xFFFF0000u);
-                g[4] = __uint_as_float(raw.z << 16);
-                g[5] = __uint_as_float(raw.z & 0xFFFF0000u);
-                g[6] = __uint_as_float(raw.w << 16);
-                g[7] = __uint_as_float(raw.w & 0xFFFF0000u);
-            } else {
-                const float4 ga = ld_f4<DETO_NT_COMPRESS_GRAD>(static_cast<const float*>(grad) + ebase + pe);
-                const float4 gb = ld_f4<DETO_NT_COMPRESS_GRAD>(static_cast<const float*>(grad) + ebase + pe + 4);
-                g[0] = ga.x; g[1] = ga.y; g[2] = ga.z; g[3] = ga.w;
-                g[4] = gb.x; g[5] = gb.y; g[6] = gb.z; g[7] = gb.w;
-            }
-            float4 fa, fb;
-            fa.x = fmaf(p.beta, ma.x, g[0]);
-            fa.y = fmaf(p.beta, ma.y, g[1]);
-            fa.z = fmaf(p.beta, ma.z, g[2]);
-            fa.w = fmaf(p.beta, ma.w, g[3]);
-            fb.x = fmaf(p.beta, mb.x, g[4]);
-            fb.y = fmaf(p.beta, mb.y, g[5]);
-            fb.z = fmaf(p.beta, mb.z, g[6]);
-            fb.w = fmaf(p.beta, mb.w, g[7]);
-            float* dst = tile + (pe / S) * G::kRow + (pe % S);
-            *reinterpret_cast<float4*>(dst) = fa;
-            *reinterpret_cast<float4*>(dst + 4) = fb;
-        }
-        wave_lds_sync();
+    const int64_t ebase = t * G::kElems;
 
-        // ---- phase 2: lane = chunk
-        float* row = tile + lane * G::kRow;
-        float c[S];
-#pragma unroll
-        for (int j = 0; j < S / 4; ++j) {
-            const float4 v = *reinterpret_cast<const float4*>(row + 4 * j);
-            c[4 * j] = v.x; c[4 * j + 1] = v.y; c[4 * j + 2] = v.z; c[4 * j + 3] = v.w;
-        }
+    fold_tile_to_lds<S, GRAD_BF16>(p, grad, mom, ebase, tile, lane);
+    wave_lds_sync();
+
+    // ---- phase 2: lane = chunk
+    float* row = tile + lane * G::kRow;
+    float c[S];
+    row_to_regs<S>(row, c);
+    FastDct<S>::dct2(c);
+    c[0] *= p.alpha0;
+    static_for<1, S>([&](auto i) { c[i] *= p.alpha; });
+    if (coeff_dbg) regs_to_global<S>(coeff_dbg + ebase + static_cast<int64_t>(lane) * S, c);
+
+    // threshold: K-th largest magnitude
+    uint32_t T;
+    {
+        uint32_t A[H], B[H];
+        static_for<0, H>([&](auto i) {
+            A[i] = __float_as_uint(c[i]) & 0x7FFFFFFFu;
+            B[i] = __float_as_uint(c[H + i]) & 0x7FFFFFFFu;
+        });
+        sort_desc<H>(A);
+        sort_desc<H>(B);
+        T = kth_largest<H, K>(A, B);
+    }
+    // keep magnitude >= T: u holds what stays behind in the momentum (the dropped
+    // coefficients), the mask collects the decisions (bit i = element i kept)
+    float u[S];
+    uint32_t mlo = 0u, mhi = 0u;
+    static_for<0, S>([&](auto I) {
+        constexpr int i = S - 1 - I;   // descending so that shifting lands bit i at i
+        const bool keep = (__float_as_uint(c[i]) & 0x7FFFFFFFu) >= T;
+        u[i] = keep ? 0.0f : c[i];
+        if constexpr (i >= 32) mhi = (mhi << 1) | (keep ? 1u : 0u);
+        else mlo = (mlo << 1) | (keep ? 1u : 0u);
+    });
+    if (__any(__popc(mlo) + __popc(mhi) != K)) {
+        // a tie at the threshold somewhere in this wavefront: exact rule
+        uint64_t gt = 0, eq = 0;
+        static_for<0, S>([&](auto i) {
+            const uint32_t key = __float_as_uint(c[i]) & 0x7FFFFFFFu;
+            gt |= static_cast<uint64_t>(key > T) << i;
+            eq |= static_cast<uint64_t>(key == T) << i;
+        });
+        const uint64_t m = gt | lowest_bits(eq, K - __popcll(gt));
+        mlo = static_cast<uint32_t>(m);
+        mhi = static_cast<uint32_t>(m >> 32);
+        static_for<0, S>([&](auto i) { u[i] = ((m >> i) & 1ull) ? 0.0f : c[i]; });
+    }
+
+    compact_and_store_payload<S, K>(c, mlo, mhi, tile, lane, idx_out, val_out, t * (kWave * K));
+
+    // ---- m <- m1 - q.  With q = D^T(kept coefficients) and m1 = D^T(all coefficients), the
+    // residual is the inverse transform of the dropped ones.
+    u[0] *= p.alpha0;
+    static_for<1, S>([&](auto i) { u[i] *= p.alpha; });
+    FastDct<S>::dct3(u);
+    regs_to_row<S>(row, u);
+    wave_lds_sync();
+    store_tile_momentum<S>(tile, mom, ebase, lane);
+}
+
+// Compress half for Striding and Random on full tiles, in the raw-momentum domain or (with
+// p.use_dct) on DCT coefficients.  Same three phases; the kept set is a bit pattern that does
+// not depend on the data: `stride_mask` for Striding, a per-chunk shuffle for Random.
+template <int S, int K, bool GRAD_BF16>
+__global__ __launch_bounds__(kWave, 2) void compress_tiled_scheme(
+    KParams p, uint64_t stride_mask, int64_t n_tiles, const void* __restrict__ grad,
+    float* __restrict__ mom, int32_t* __restrict__ idx_out, float* __restrict__ val_out,
+    float* __restrict__ coeff_dbg) {
+    using G = TileGeom<S>;
+    __shared__ __attribute__((aligned(16))) float tile[G::kFloats];
+    const int lane = threadIdx.x;
+    const int64_t t = blockIdx.x;
+    if (t >= n_tiles) return;
+    const int64_t ebase = t * G::kElems;
+
+    fold_tile_to_lds<S, GRAD_BF16>(p, grad, mom, ebase, tile, lane);
+    wave_lds_sync();
+
+    float* row = tile + lane * G::kRow;
+    float c[S];
+    row_to_regs<S>(row, c);
+    if (p.use_dct) {
         FastDct<S>::dct2(c);
         c[0] *= p.alpha0;
         static_for<1, S>([&](auto i) { c[i] *= p.alpha; });
-        if (coeff_dbg) {
-            float* dbg = coeff_dbg + ebase + static_cast<int64_t>(lane) * S;
-#pragma unroll
-            for (int j = 0; j < S / 4; ++j)
-                *reinterpret_cast<float4*>(dbg + 4 * j) =
-                    make_float4(c[4 * j], c[4 * j + 1], c[4 * j + 2], c[4 * j + 3]);
-        }
+    }
+    if (coeff_dbg) regs_to_global<S>(coeff_dbg + ebase + static_cast<int64_t>(lane) * S, c);
 
-        // threshold: K-th largest magnitude
-        uint32_t T;
-        {
-            uint32_t A[H], B[H];
-            static_for<0, H>([&](auto i) {
-                A[i] = __float_as_uint(c[i]) & 0x7FFFFFFFu;
-                B[i] = __float_as_uint(c[H + i]) & 0x7FFFFFFFu;
-            });
-            sort_desc<H>(A);
-            sort_desc<H>(B);
-            T = kth_largest<H, K>(A, B);
-        }
-        // keep magnitude >= T: u holds what stays behind in the momentum (the dropped
-        // coefficients), the mask collects the decisions (bit i = element i kept)
-        float u[S];
-        uint32_t mlo = 0u, mhi = 0u;
-        static_for<0, S>([&](auto I) {
-            constexpr int i = S - 1 - I;   // descending so that shifting lands bit i at i
-            const bool keep = (__float_as_uint(c[i]) & 0x7FFFFFFFu) >= T;
-            u[i] = keep ? 0.0f : c[i];
-            if constexpr (i >= 32) mhi = (mhi << 1) | (keep ? 1u : 0u);
-            else mlo = (mlo << 1) | (keep ? 1u : 0u);
-        });
-        if (__any(__popc(mlo) + __popc(mhi) != K)) {
-            // a tie at the threshold somewhere in this wavefront: exact rule
-            uint64_t gt = 0, eq = 0;
-            static_for<0, S>([&](auto i) {
-                const uint32_t key = __float_as_uint(c[i]) & 0x7FFFFFFFu;
-                gt |= static_cast<uint64_t>(key > T) << i;
-                eq |= static_cast<uint64_t>(key == T) << i;
-            });
-            const uint64_t m = gt | lowest_bits(eq, K - __popcll(gt));
-            mlo = static_cast<uint32_t>(m);
-            mhi = static_cast<uint32_t>(m >> 32);
-            static_for<0, S>([&](auto i) { u[i] = ((m >> i) & 1ull) ? 0.0f : c[i]; });
-        }
-
-        // ---- phase 3a: compact the kept (index, value) pairs of each chunk, ascending.
-        // The tile is free again (every lane holds its row in registers).  Every element
-        // is written at the running position, which only advances past kept ones, so a
-        // dropped element is overwritten by the next kept one.
-        constexpr int PR = K + 4;                       // staging row, one spare slot + pad
-        float* vrow = tile + lane * PR;
-        uint8_t* ibytes = reinterpret_cast<uint8_t*>(tile + kWave * PR);   // indices as bytes
-        uint8_t* irow = ibytes + lane * PR;
-        static_assert(kWave * PR * 5 <= G::kFloats * 4, "staging must fit in the tile");
-        {
-            int pos = 0;
-            static_for<0, S>([&](auto i) {
-                vrow[pos] = c[i];
-                irow[pos] = static_cast<uint8_t>(i);
-                const uint32_t bit = (i >= 32) ? ((mhi >> (i - 32)) & 1u) : ((mlo >> i) & 1u);
-                pos += static_cast<int>(bit);
-            });
-        }
-        wave_lds_sync();
-        const int64_t pbase = t * (kWave * K);
-        if constexpr (K % 4 == 0) {
-#pragma unroll
-            for (int it = 0; it < K / 4; ++it) {
-                const int e = it * 256 + lane * 4;
-                const int r = e / K, col = e % K;
-                st_f4<DETO_NT_COMPRESS_PAYLOAD>(val_out + pbase + e,
-                             *reinterpret_cast<const float4*>(tile + r * PR + col));
-                const uint32_t pk = *reinterpret_cast<const uint32_t*>(ibytes + r * PR + col);
-                st_u4<DETO_NT_COMPRESS_PAYLOAD>(idx_out + pbase + e,
-                             make_uint4(pk & 0xFFu, (pk >> 8) & 0xFFu, (pk >> 16) & 0xFFu, pk >> 24));
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < K; ++j) {
-                val_out[pbase + lane * K + j] = vrow[j];
-                idx_out[pbase + lane * K + j] = irow[j];
-            }
-        }
-        wave_lds_sync();
-
-        // ---- phase 3b: m <- m1 - q.  With q = D^T(kept coefficients) and m1 = D^T(all
-        // coefficients), the residual is the inverse transform of the dropped ones.
-        u[0] *= p.alpha0;
-        static_for<1, S>([&](auto i) { u[i] *= p.alpha; });
-        FastDct<S>::dct3(u);
-#pragma unroll
-        for (int j = 0; j < S / 4; ++j)
-            *reinterpret_cast<float4*>(row + 4 * j) =
-                make_float4(u[4 * j], u[4 * j + 1], u[4 * j + 2], u[4 * j + 3]);
-        wave_lds_sync();
-#pragma unroll
-        for (int it = 0; it < S / 8; ++it) {
-            const int pe = it * 512 + lane * 8;
-            const float* src = tile + (pe / S) * G::kRow + (pe % S);
-            st_f4<DETO_NT_COMPRESS_MOM_ST>(mom + ebase + pe, *reinterpret_cast<const float4*>(src));
-            st_f4<DETO_NT_COMPRESS_MOM_ST>(mom + ebase + pe + 4, *reinterpret_cast<const float4*>(src + 4));
-        }
+    uint64_t m = stride_mask;
+    if (p.scheme == 2) {
+        wave_lds_sync();   // rows are in registers: the tile doubles as shuffle scratch
+        m = random_mask<S, K>(p.seed, p.step, static_cast<uint64_t>(t) * kWave + lane,
+                              reinterpret_cast<uint8_t*>(tile) + lane * G::kPermStride);
         wave_lds_sync();
     }
+    const uint32_t mlo = static_cast<uint32_t>(m), mhi = static_cast<uint32_t>(m >> 32);
+
+    compact_and_store_payload<S, K>(c, mlo, mhi, tile, lane, idx_out, val_out, t * (kWave * K));
+
+    static_for<0, S>([&](auto i) { c[i] = mask_bit(mlo, mhi, i) ? 0.0f : c[i]; });
+    if (p.use_dct) {
+        c[0] *= p.alpha0;
+        static_for<1, S>([&](auto i) { c[i] *= p.alpha; });
+        FastDct<S>::dct3(c);
+    }
+    regs_to_row<S>(row, c);
+    wave_lds_sync();
+    store_tile_momentum<S>(tile, mom, ebase, lane);
 }
 
 // One replica's payload entries of a tile, as each lane holds them after a coalesced load.
@@ -374,10 +494,103 @@ __device__ __forceinline__ void scatter_payload(const PayloadRegs<K>& r, float* 
     }
 }
 
-// Decompress-and-update half on full tiles (transform domain, indices transmitted).
-// Up to three replicas' payloads are in flight while one is scattered into LDS; LDS
-// operations of one wavefront complete in order, so the additions into one accumulator
-// happen replica after replica and the result does not depend on timing.
+// The tile's parameters, loaded early (needed only after the transform).
+template <int S, bool PARAM_BF16>
+struct ParamRegs {
+    static constexpr int kIt = S / 8;
+    uint4 b[PARAM_BF16 ? kIt : 1];
+    float4 f[PARAM_BF16 ? 1 : 2 * kIt];
+};
+
+template <int S, bool PARAM_BF16>
+__device__ __forceinline__ void load_params(ParamRegs<S, PARAM_BF16>& th,
+                                            const void* __restrict__ params, int64_t ebase,
+                                            int lane) {
+#pragma unroll
+    for (int it = 0; it < S / 8; ++it) {
+        const int pe = it * 512 + lane * 8;
+        if constexpr (PARAM_BF16) {
+            th.b[it] =
+                ld_u4<DETO_NT_DECOMPRESS_LD>(static_cast<const uint16_t*>(params) + ebase + pe);
+        } else {
+            const float* src = static_cast<const float*>(params) + ebase + pe;
+            th.f[2 * it] = ld_f4<DETO_NT_DECOMPRESS_LD>(src);
+            th.f[2 * it + 1] = ld_f4<DETO_NT_DECOMPRESS_LD>(src + 4);
+        }
+    }
+}
+
+// Last phase of decompress: the tile rows hold Q; theta <- theta*(1-eta*lambda) - eta*Q,
+// coalesced, rounded to the parameter dtype.
+template <int S, bool PARAM_BF16>
+__device__ __forceinline__ void update_params_from_tile(const KParams& p, const float* tile,
+                                                        const ParamRegs<S, PARAM_BF16>& th,
+                                                        void* __restrict__ params, int64_t ebase,
+                                                        int lane) {
+    using G = TileGeom<S>;
+#pragma unroll
+    for (int it = 0; it < S / 8; ++it) {
+        const int pe = it * 512 + lane * 8;
+        const float* src = tile + (pe / S) * G::kRow + (pe % S);
+        const float4 qa = *reinterpret_cast<const float4*>(src);
+        const float4 qb = *reinterpret_cast<const float4*>(src + 4);
+        if constexpr (PARAM_BF16) {
+            uint16_t* dst = static_cast<uint16_t*>(params) + ebase + pe;
+            const uint4 raw = th.b[it];
+            auto upd = [&](uint32_t w, float q0, float q1) -> uint32_t {
+                const float t0 = __uint_as_float(w << 16) * p.wd_scale;
+                const float t1 = __uint_as_float(w & 0xFFFF0000u) * p.wd_scale;
+                const uint32_t b0 = f32_to_bf16(fmaf(-p.lr, q0, t0));
+                const uint32_t b1 = f32_to_bf16(fmaf(-p.lr, q1, t1));
+                return b0 | (b1 << 16);
+            };
+            uint4 out;
+            out.x = upd(raw.x, qa.x, qa.y);
+            out.y = upd(raw.y, qa.z, qa.w);
+            out.z = upd(raw.z, qb.x, qb.y);
+            out.w = upd(raw.w, qb.z, qb.w);
+            st_u4<DETO_NT_DECOMPRESS_ST>(dst, out);
+        } else {
+            float* dst = static_cast<float*>(params) + ebase + pe;
+            float4 ta = th.f[2 * it];
+            float4 tb = th.f[2 * it + 1];
+            ta.x = fmaf(-p.lr, qa.x, ta.x * p.wd_scale);
+            ta.y = fmaf(-p.lr, qa.y, ta.y * p.wd_scale);
+            ta.z = fmaf(-p.lr, qa.z, ta.z * p.wd_scale);
+            ta.w = fmaf(-p.lr, qa.w, ta.w * p.wd_scale);
+            tb.x = fmaf(-p.lr, qb.x, tb.x * p.wd_scale);
+            tb.y = fmaf(-p.lr, qb.y, tb.y * p.wd_scale);
+            tb.z = fmaf(-p.lr, qb.z, tb.z * p.wd_scale);
+            tb.w = fmaf(-p.lr, qb.w, tb.w * p.wd_scale);
+            st_f4<DETO_NT_DECOMPRESS_ST>(dst, ta);
+            st_f4<DETO_NT_DECOMPRESS_ST>(dst + 4, tb);
+        }
+    }
+}
+
+// lane = chunk: scale the accumulated coefficients, inverse transform (if in the transform
+// domain), optional export, sign, back into the lane's LDS row.
+template <int S>
+__device__ __forceinline__ void finish_chunk(const KParams& p, float (&y)[S], float* row,
+                                             float* __restrict__ presign_dbg, int64_t ebase,
+                                             int lane) {
+    if (p.use_dct) {
+        y[0] *= p.alpha0 * p.inv_R;
+        const float ar = p.alpha * p.inv_R;
+        static_for<1, S>([&](auto i) { y[i] *= ar; });
+        FastDct<S>::dct3(y);
+    } else {
+        static_for<0, S>([&](auto i) { y[i] *= p.inv_R; });
+    }
+    if (presign_dbg) regs_to_global<S>(presign_dbg + ebase + static_cast<int64_t>(lane) * S, y);
+    static_for<0, S>([&](auto i) { y[i] = sign_or_self(y[i], p.use_sign); });
+    regs_to_row<S>(row, y);
+}
+
+// Decompress-and-update half on full tiles, indices transmitted (top-k, or any scheme whose
+// caller passes indices).  Up to three replicas' payloads are in flight while one is
+// scattered into LDS; LDS operations of one wavefront complete in order, so the additions
+// into one accumulator happen replica after replica and the result does not depend on timing.
 template <int S, int K, bool PARAM_BF16>
 __global__ __launch_bounds__(kWave, 2) void decompress_tiled(
     KParams p, int64_t n_tiles, const int32_t* __restrict__ idx, int64_t idx_stride,
@@ -386,140 +599,138 @@ __global__ __launch_bounds__(kWave, 2) void decompress_tiled(
     using G = TileGeom<S>;
     __shared__ __attribute__((aligned(16))) float tile[G::kFloats];
     const int lane = threadIdx.x;
-
-    // one tile per workgroup: the host launches exactly n_tiles workgroups
     const int64_t t = blockIdx.x;
     if (t >= n_tiles) return;
-    {
-        const int64_t ebase = t * G::kElems;
-        const int64_t pbase = t * (kWave * K);
-        // zero the accumulator tile
+    const int64_t ebase = t * G::kElems;
+    const int64_t pbase = t * (kWave * K);
+
+    // zero the accumulator tile
 #pragma unroll
-        for (int i = 0; i < G::kFloats / (kWave * 4); ++i)
-            *reinterpret_cast<float4*>(tile + (i * kWave + lane) * 4) =
-                make_float4(0.f, 0.f, 0.f, 0.f);
-        wave_lds_sync();
-        if constexpr (K % 4 == 0) {
-            // three replicas' payloads in flight at a time
-            PayloadRegs<K> b0, b1, b2;
-            auto fetch = [&](PayloadRegs<K>& b, int r) {
-                load_payload<K>(b, idx + r * idx_stride + pbase, val + r * val_stride + pbase, lane);
-            };
-            fetch(b0, 0);
-            if (p.R > 1) fetch(b1, 1);
-            if (p.R > 2) fetch(b2, 2);
-            int r = 0;
-            while (true) {
-                scatter_payload<S, K>(b0, tile, lane);
-                if (r + 3 < p.R) fetch(b0, r + 3);
-                if (++r >= p.R) break;
-                scatter_payload<S, K>(b1, tile, lane);
-                if (r + 3 < p.R) fetch(b1, r + 3);
-                if (++r >= p.R) break;
-                scatter_payload<S, K>(b2, tile, lane);
-                if (r + 3 < p.R) fetch(b2, r + 3);
-                if (++r >= p.R) break;
-            }
-        } else {
-            // K entries per chunk, lane = chunk
-            for (int r = 0; r < p.R; ++r) {
-                const int32_t* ir = idx + r * idx_stride + pbase + lane * K;
-                const float* vr = val + r * val_stride + pbase + lane * K;
+    for (int i = 0; i < G::kFloats / (kWave * 4); ++i)
+        *reinterpret_cast<float4*>(tile + (i * kWave + lane) * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+    wave_lds_sync();
+    if constexpr (K % 4 == 0) {
+        PayloadRegs<K> b0, b1, b2;
+        auto fetch = [&](PayloadRegs<K>& b, int r) {
+            load_payload<K>(b, idx + r * idx_stride + pbase, val + r * val_stride + pbase, lane);
+        };
+        fetch(b0, 0);
+        if (p.R > 1) fetch(b1, 1);
+        if (p.R > 2) fetch(b2, 2);
+        int r = 0;
+        while (true) {
+            scatter_payload<S, K>(b0, tile, lane);
+            if (r + 3 < p.R) fetch(b0, r + 3);
+            if (++r >= p.R) break;
+            scatter_payload<S, K>(b1, tile, lane);
+            if (r + 3 < p.R) fetch(b1, r + 3);
+            if (++r >= p.R) break;
+            scatter_payload<S, K>(b2, tile, lane);
+            if (r + 3 < p.R) fetch(b2, r + 3);
+            if (++r >= p.R) break;
+        }
+    } else {
+        // K entries per chunk, lane = chunk: the lane owns its row, plain sequential adds
+        for (int r = 0; r < p.R; ++r) {
+            const int32_t* ir = idx + r * idx_stride + pbase + lane * K;
+            const float* vr = val + r * val_stride + pbase + lane * K;
+            float* arow = tile + lane * G::kRow;
 #pragma unroll
-                for (int j = 0; j < K; ++j)
-                    atomicAdd(tile + lane * G::kRow +
-                                  min(static_cast<uint32_t>(ir[j]), static_cast<uint32_t>(S)),
-                              vr[j]);
+            for (int j = 0; j < K; ++j) {
+                const uint32_t at = min(static_cast<uint32_t>(ir[j]), static_cast<uint32_t>(S));
+                arow[at] += vr[j];
             }
         }
-        // parameters of this tile: issue the loads now, they are needed after the transform
-        constexpr int kIt = S / 8;
-        uint4 thb[PARAM_BF16 ? kIt : 1];
-        float4 thf[PARAM_BF16 ? 1 : 2 * kIt];
-#pragma unroll
-        for (int it = 0; it < kIt; ++it) {
-            const int pe = it * 512 + lane * 8;
-            if constexpr (PARAM_BF16) {
-                thb[it] = ld_u4<DETO_NT_DECOMPRESS_LD>(static_cast<const uint16_t*>(params) + ebase + pe);
-            } else {
-                const float* th = static_cast<const float*>(params) + ebase + pe;
-                thf[2 * it] = ld_f4<DETO_NT_DECOMPRESS_LD>(th);
-                thf[2 * it + 1] = ld_f4<DETO_NT_DECOMPRESS_LD>(th + 4);
-            }
-        }
-        wave_lds_sync();
-        // lane = chunk: average, inverse transform, sign
-        float* row = tile + lane * G::kRow;
-        float y[S];
-#pragma unroll
-        for (int j = 0; j < S / 4; ++j) {
-            const float4 v = *reinterpret_cast<const float4*>(row + 4 * j);
-            y[4 * j] = v.x; y[4 * j + 1] = v.y; y[4 * j + 2] = v.z; y[4 * j + 3] = v.w;
-        }
-        y[0] *= p.alpha0 * p.inv_R;
-        {
-            const float ar = p.alpha * p.inv_R;
-            static_for<1, S>([&](auto i) { y[i] *= ar; });
-        }
-        FastDct<S>::dct3(y);
-        if (presign_dbg) {
-            float* dbg = presign_dbg + ebase + static_cast<int64_t>(lane) * S;
-#pragma unroll
-            for (int j = 0; j < S / 4; ++j)
-                *reinterpret_cast<float4*>(dbg + 4 * j) =
-                    make_float4(y[4 * j], y[4 * j + 1], y[4 * j + 2], y[4 * j + 3]);
-        }
-#pragma unroll
-        for (int j = 0; j < S / 4; ++j) {
-            float4 v;
-            v.x = sign_or_self(y[4 * j], p.use_sign);
-            v.y = sign_or_self(y[4 * j + 1], p.use_sign);
-            v.z = sign_or_self(y[4 * j + 2], p.use_sign);
-            v.w = sign_or_self(y[4 * j + 3], p.use_sign);
-            *reinterpret_cast<float4*>(row + 4 * j) = v;
-        }
-        wave_lds_sync();
-        // coalesced parameter update
-#pragma unroll
-        for (int it = 0; it < kIt; ++it) {
-            const int pe = it * 512 + lane * 8;
-            const float* src = tile + (pe / S) * G::kRow + (pe % S);
-            const float4 qa = *reinterpret_cast<const float4*>(src);
-            const float4 qb = *reinterpret_cast<const float4*>(src + 4);
-            if constexpr (PARAM_BF16) {
-                uint16_t* th = static_cast<uint16_t*>(params) + ebase + pe;
-                const uint4 raw = thb[it];
-                auto upd = [&](uint32_t w, float q0, float q1) -> uint32_t {
-                    const float t0 = __uint_as_float(w << 16) * p.wd_scale;
-                    const float t1 = __uint_as_float(w & 0xFFFF0000u) * p.wd_scale;
-                    const uint32_t b0 = f32_to_bf16(fmaf(-p.lr, q0, t0));
-                    const uint32_t b1 = f32_to_bf16(fmaf(-p.lr, q1, t1));
-                    return b0 | (b1 << 16);
-                };
-                uint4 out;
-                out.x = upd(raw.x, qa.x, qa.y);
-                out.y = upd(raw.y, qa.z, qa.w);
-                out.z = upd(raw.z, qb.x, qb.y);
-                out.w = upd(raw.w, qb.z, qb.w);
-                st_u4<DETO_NT_DECOMPRESS_ST>(th, out);
-            } else {
-                float* th = static_cast<float*>(params) + ebase + pe;
-                float4 ta = thf[2 * it];
-                float4 tb = thf[2 * it + 1];
-                ta.x = fmaf(-p.lr, qa.x, ta.x * p.wd_scale);
-                ta.y = fmaf(-p.lr, qa.y, ta.y * p.wd_scale);
-                ta.z = fmaf(-p.lr, qa.z, ta.z * p.wd_scale);
-                ta.w = fmaf(-p.lr, qa.w, ta.w * p.wd_scale);
-                tb.x = fmaf(-p.lr, qb.x, tb.x * p.wd_scale);
-                tb.y = fmaf(-p.lr, qb.y, tb.y * p.wd_scale);
-                tb.z = fmaf(-p.lr, qb.z, tb.z * p.wd_scale);
-                tb.w = fmaf(-p.lr, qb.w, tb.w * p.wd_scale);
-                st_f4<DETO_NT_DECOMPRESS_ST>(th, ta);
-                st_f4<DETO_NT_DECOMPRESS_ST>(th + 4, tb);
-            }
-        }
-        wave_lds_sync();
     }
+    ParamRegs<S, PARAM_BF16> th;
+    load_params<S, PARAM_BF16>(th, params, ebase, lane);
+    wave_lds_sync();
+
+    float* row = tile + lane * G::kRow;
+    float y[S];
+    row_to_regs<S>(row, y);
+    finish_chunk<S>(p, y, row, presign_dbg, ebase, lane);
+    wave_lds_sync();
+    update_params_from_tile<S, PARAM_BF16>(p, tile, th, params, ebase, lane);
+}
+
+// Decompress-and-update half for Striding and Random without transmitted indices: every
+// replica kept the same positions, so the R value arrays are summed entry by entry while
+// they stream in, and each chunk's lane spreads the k sums over the positions of its bit
+// pattern.
+template <int S, int K, bool PARAM_BF16>
+__global__ __launch_bounds__(kWave, 2) void decompress_tiled_scheme(
+    KParams p, uint64_t stride_mask, int64_t n_tiles, const float* __restrict__ val,
+    int64_t val_stride, void* __restrict__ params, float* __restrict__ presign_dbg) {
+    using G = TileGeom<S>;
+    __shared__ __attribute__((aligned(16))) float tile[G::kFloats];
+    const int lane = threadIdx.x;
+    const int64_t t = blockIdx.x;
+    if (t >= n_tiles) return;
+    const int64_t ebase = t * G::kElems;
+    const int64_t pbase = t * (kWave * K);
+    constexpr int PR = K + 4;
+    static_assert(kWave * PR * 4 + kWave * G::kPermStride <= G::kFloats * 4, "LDS layout");
+
+    ParamRegs<S, PARAM_BF16> th;
+    load_params<S, PARAM_BF16>(th, params, ebase, lane);
+
+    // sum over replicas, coalesced; staged as [chunk][k]
+    if constexpr (K % 4 == 0) {
+        float4 acc[K / 4];
+#pragma unroll
+        for (int it = 0; it < K / 4; ++it)
+            acc[it] = ld_f4<DETO_NT_DECOMPRESS_LD>(val + pbase + it * 256 + lane * 4);
+        for (int r = 1; r < p.R; ++r) {
+            float4 nxt[K / 4];
+#pragma unroll
+            for (int it = 0; it < K / 4; ++it)
+                nxt[it] = ld_f4<DETO_NT_DECOMPRESS_LD>(val + r * val_stride + pbase + it * 256 +
+                                                       lane * 4);
+#pragma unroll
+            for (int it = 0; it < K / 4; ++it) {
+                acc[it].x += nxt[it].x; acc[it].y += nxt[it].y;
+                acc[it].z += nxt[it].z; acc[it].w += nxt[it].w;
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < K / 4; ++it) {
+            const int e = it * 256 + lane * 4;
+            *reinterpret_cast<float4*>(tile + (e / K) * PR + (e % K)) = acc[it];
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+            float a = 0.0f;
+            for (int r = 0; r < p.R; ++r) a += val[r * val_stride + pbase + lane * K + j];
+            tile[lane * PR + j] = a;
+        }
+    }
+    uint64_t m = stride_mask;
+    if (p.scheme == 2)
+        m = random_mask<S, K>(p.seed, p.step, static_cast<uint64_t>(t) * kWave + lane,
+                              reinterpret_cast<uint8_t*>(tile + kWave * PR) +
+                                  lane * G::kPermStride);
+    const uint32_t mlo = static_cast<uint32_t>(m), mhi = static_cast<uint32_t>(m >> 32);
+    wave_lds_sync();
+
+    // lane = chunk: y[i] = kept ? sum[rank of i among the kept] : 0
+    float y[S];
+    {
+        const float* vrow = tile + lane * PR;
+        int pos = 0;
+        static_for<0, S>([&](auto i) {
+            const uint32_t bit = mask_bit(mlo, mhi, i);
+            const float v = vrow[pos];
+            y[i] = bit ? v : 0.0f;
+            pos += static_cast<int>(bit);
+        });
+    }
+    wave_lds_sync();
+    float* row = tile + lane * G::kRow;
+    finish_chunk<S>(p, y, row, presign_dbg, ebase, lane);
+    wave_lds_sync();
+    update_params_from_tile<S, PARAM_BF16>(p, tile, th, params, ebase, lane);
 }
 
 }  // namespace deto

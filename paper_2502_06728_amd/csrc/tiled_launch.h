@@ -1,0 +1,47 @@
+// Host-side launchers of the tiled kernels.  Each translation unit tiled_*.hip instantiates
+// one family of kernels and defines its launcher, so the families compile in parallel.
+// A launcher returns true if it has a kernel for (p.s, p.k) and has enqueued it.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "deto_device.hip.h"
+
+namespace deto {
+
+struct CompressLaunch {
+    KParams p;
+    int64_t tiles;          // full 64-chunk tiles, one workgroup each
+    const void* grad;
+    bool grad_bf16;
+    float* mom;
+    int32_t* idx;           // may be null for Striding/Random
+    float* val;
+    float* coeff_dbg;
+    uint64_t stride_mask;   // Striding: kept positions of every chunk
+    hipStream_t stream;
+};
+
+struct DecompressLaunch {
+    KParams p;
+    int64_t tiles;
+    const int32_t* idx;     // null: indices regenerated from the scheme
+    int64_t idx_stride;
+    const float* val;
+    int64_t val_stride;
+    void* params;
+    bool param_bf16;
+    float* presign_dbg;
+    uint64_t stride_mask;
+    hipStream_t stream;
+};
+
+bool launch_compress_topk_s64(const CompressLaunch& a);
+bool launch_compress_topk_s32(const CompressLaunch& a);
+bool launch_decompress_idx_s64(const DecompressLaunch& a);
+bool launch_decompress_idx_s32(const DecompressLaunch& a);
+bool launch_compress_scheme(const CompressLaunch& a);
+bool launch_decompress_scheme(const DecompressLaunch& a);
+
+}  // namespace deto

@@ -1,0 +1,49 @@
+// Tiled Striding / Random kernels (raw-momentum or coefficient domain): compress, and
+// decompress without transmitted indices.
+#include "tiled_kernels.hip.h"
+#include "tiled_launch.h"
+
+#ifdef DETO_TILED_ONLY_64_32
+#define DETO_SCHEME_LIST(X) X(64, 32)
+#else
+#define DETO_SCHEME_LIST(X) X(64, 32) X(64, 16) X(64, 8) X(32, 16) X(32, 8)
+#endif
+
+namespace deto {
+
+bool launch_compress_scheme(const CompressLaunch& a) {
+    const unsigned grid = static_cast<unsigned>(a.tiles);
+#define X(S, K)                                                                                 \
+    if (a.p.s == S && a.p.k == K) {                                                             \
+        if (a.grad_bf16)                                                                        \
+            compress_tiled_scheme<S, K, true><<<grid, kWave, 0, a.stream>>>(                    \
+                a.p, a.stride_mask, a.tiles, a.grad, a.mom, a.idx, a.val, a.coeff_dbg);         \
+        else                                                                                    \
+            compress_tiled_scheme<S, K, false><<<grid, kWave, 0, a.stream>>>(                   \
+                a.p, a.stride_mask, a.tiles, a.grad, a.mom, a.idx, a.val, a.coeff_dbg);         \
+        return true;                                                                            \
+    }
+    DETO_SCHEME_LIST(X)
+#undef X
+    return false;
+}
+
+bool launch_decompress_scheme(const DecompressLaunch& a) {
+    if (a.idx) return false;
+    const unsigned grid = static_cast<unsigned>(a.tiles);
+#define X(S, K)                                                                                 \
+    if (a.p.s == S && a.p.k == K) {                                                             \
+        if (a.param_bf16)                                                                       \
+            decompress_tiled_scheme<S, K, true><<<grid, kWave, 0, a.stream>>>(                  \
+                a.p, a.stride_mask, a.tiles, a.val, a.val_stride, a.params, a.presign_dbg);     \
+        else                                                                                    \
+            decompress_tiled_scheme<S, K, false><<<grid, kWave, 0, a.stream>>>(                 \
+                a.p, a.stride_mask, a.tiles, a.val, a.val_stride, a.params, a.presign_dbg);     \
+        return true;                                                                            \
+    }
+    DETO_SCHEME_LIST(X)
+#undef X
+    return false;
+}
+
+}  // namespace deto

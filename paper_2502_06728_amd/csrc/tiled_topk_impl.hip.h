@@ -1,0 +1,47 @@
+// Shared body of tiled_topk_s64.hip / tiled_topk_s32.hip: instantiates the top-k compress
+// kernel and the indexed decompress kernel for chunk size DETO_S and the k values in
+// DETO_K_LIST(X), and defines the two launchers named by DETO_COMPRESS_FN / DETO_DECOMPRESS_FN.
+#include "tiled_kernels.hip.h"
+#include "tiled_launch.h"
+
+namespace deto {
+
+bool DETO_COMPRESS_FN(const CompressLaunch& a) {
+    if (a.p.s != DETO_S) return false;
+    const unsigned grid = static_cast<unsigned>(a.tiles);
+#define X(K)                                                                                    \
+    if (a.p.k == K) {                                                                           \
+        if (a.grad_bf16)                                                                        \
+            compress_tiled_topk<DETO_S, K, true><<<grid, kWave, 0, a.stream>>>(                 \
+                a.p, a.tiles, a.grad, a.mom, a.idx, a.val, a.coeff_dbg);                        \
+        else                                                                                    \
+            compress_tiled_topk<DETO_S, K, false><<<grid, kWave, 0, a.stream>>>(                \
+                a.p, a.tiles, a.grad, a.mom, a.idx, a.val, a.coeff_dbg);                        \
+        return true;                                                                            \
+    }
+    DETO_K_LIST(X)
+#undef X
+    return false;
+}
+
+bool DETO_DECOMPRESS_FN(const DecompressLaunch& a) {
+    if (a.p.s != DETO_S || !a.idx) return false;
+    const unsigned grid = static_cast<unsigned>(a.tiles);
+#define X(K)                                                                                    \
+    if (a.p.k == K) {                                                                           \
+        if (a.param_bf16)                                                                       \
+            decompress_tiled<DETO_S, K, true><<<grid, kWave, 0, a.stream>>>(                    \
+                a.p, a.tiles, a.idx, a.idx_stride, a.val, a.val_stride, a.params,               \
+                a.presign_dbg);                                                                 \
+        else                                                                                    \
+            decompress_tiled<DETO_S, K, false><<<grid, kWave, 0, a.stream>>>(                   \
+                a.p, a.tiles, a.idx, a.idx_stride, a.val, a.val_stride, a.params,               \
+                a.presign_dbg);                                                                 \
+        return true;                                                                            \
+    }
+    DETO_K_LIST(X)
+#undef X
+    return false;
+}
+
+}  // namespace deto
