@@ -273,3 +273,110 @@ def test_olmo_1b_shard_full_size_bench_configuration(H):
     cfg = Config(chunk=w.chunk, topk=w.topk, decay=w.decay, lr=w.lr, sign=w.sign)
     worst = _full_size_check(H, w, cfg)
     print("olmo-1b full size:", worst)
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("scheme,dct", [(SCHEME_TOPK, False), (SCHEME_STRIDE, False),
+                                        (SCHEME_RANDOM, False), (SCHEME_RANDOM, True)])
+def test_olmo_7b_shard_full_size(H, scheme, dct):
+    """The OLMo-7B-shaped 1/8 shard (861,011,968 parameters; chunk 64, k = 32, R = 4), top-k
+    against Striding and Random.  At this size the inputs are drawn on the device with
+    torch's seeded generator (same recipe: N(0,1e-3) grads and momentum, N(0,0.02) parameters,
+    bf16 storage); the sampled chunk runs are copied to the host for the oracle."""
+    import torch
+    from paper_2502_06728_amd import binding
+    w = synth.workloads()["olmo-7b-1of8"]
+    assert w.n == 861_011_968
+    n, s, k, R = w.n, w.chunk, w.topk, w.replicas
+    C = n // s
+    cfg = Config(chunk=s, topk=k, scheme=scheme, dct=dct, seed=2024, step=3, decay=w.decay,
+                 lr=w.lr, sign=True)
+    dev = H.DEV
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(7)
+    g = (torch.randn(n, generator=gen, device=dev) * w.grad_std).to(torch.bfloat16)
+    m = torch.randn(n, generator=gen, device=dev) * w.momentum_std
+    th = (torch.randn(n, generator=gen, device=dev) * w.params_std).to(torch.bfloat16)
+    m0 = m.clone()
+    th0 = th.clone()
+    send_idx = scheme == SCHEME_TOPK
+    idx = torch.empty(C * k, dtype=torch.int32, device=dev) if send_idx else None
+    val = torch.empty(C * k, dtype=torch.float32, device=dev)
+    coeff = torch.empty(C * s, dtype=torch.float32, device=dev)
+    binding.detonation_compress(H.bcfg(cfg), g, m, idx, val, coeff)
+    torch.cuda.synchronize()
+    for c0, c1 in _sample_runs(C, count=10):
+        e0, e1 = c0 * s, c1 * s
+        parity.check_compress(cfg, H.to_host(g[e0:e1]), H.to_host(m0[e0:e1]), H.to_host(m[e0:e1]),
+                              H.to_host(idx[c0 * k:c1 * k]) if send_idx else None,
+                              H.to_host(val[c0 * k:c1 * k]), H.to_host(coeff[e0:e1]), chunk0=c0)
+    del coeff, m0
+    # R payloads of valid structure: one position drawn from each of k groups of s/k, ascending
+    pv = torch.randn((R, C * k), generator=gen, device=dev) * w.momentum_std
+    pi = None
+    if send_idx:
+        grp = s // k
+        pi = torch.randint(0, grp, (R, C * k), generator=gen, device=dev, dtype=torch.int32)
+        pi += (torch.arange(C * k, device=dev, dtype=torch.int32) % k) * grp
+    y = torch.empty(n, dtype=torch.float32, device=dev)
+    binding.detonation_decompress_step(H.bcfg(cfg), R, pi, pv, th, y)
+    torch.cuda.synchronize()
+    if send_idx:    # regenerated indices are keyed by the global chunk number: covered at small n
+        for c0, c1 in _sample_runs(C, count=10, seed=8):
+            e0, e1 = c0 * s, c1 * s
+            parity.check_decompress(cfg, H.to_host(pi[:, c0 * k:c1 * k].contiguous()),
+                                    H.to_host(pv[:, c0 * k:c1 * k].contiguous()),
+                                    H.to_host(th0[e0:e1]), H.to_host(th[e0:e1]),
+                                    H.to_host(y[e0:e1]))
+
+
+@pytest.mark.parametrize("scheme", [SCHEME_TOPK, SCHEME_STRIDE, SCHEME_RANDOM])
+def test_multi_step_trajectory(H, scheme):
+    """Algorithm 1 is iterative: T steps of compress -> (exchange) -> decompress with evolving
+    momentum and parameters, the Striding offset and the Random stream advancing with the
+    step.  Every step is checked from the GPU's own state (staged protocol), the energy of
+    the momentum is book-kept, and a free-running oracle trajectory measures the drift."""
+    n, s, k, T, R = 64 * 1500 + 21, 64, 16, 6, 2
+    rng = np.random.default_rng(11)
+    m_gpu = synth.normal(3, synth.TAG_MOMENTUM, n, 1e-3)
+    th_gpu = synth.normal(3, synth.TAG_PARAMS, n, 0.02)
+    m_free, th_free = m_gpu.copy(), th_gpu.copy()         # oracle running on its own
+    m_other = synth.normal(4, synth.TAG_MOMENTUM, n, 1e-3)  # the other replica's momentum
+    send_idx = scheme == SCHEME_TOPK
+    seen = np.zeros(s, dtype=int)
+    for step in range(T):
+        cfg = Config(chunk=s, topk=k, scheme=scheme, seed=5, step=step, decay=0.9, lr=1e-3,
+                     sign=True)
+        g = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+        g_other = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+        # the other replica lives in the oracle
+        m_other, idx_o, val_o = oracle.compress(cfg, g_other, m_other)
+        # this replica on the GPU, judged from its own state
+        m_new, idx_g, val_g, coeff_g = H.gpu_compress(cfg, g, m_gpu, want_idx=send_idx)
+        parity.check_compress(cfg, g, m_gpu, m_new, idx_g, val_g, coeff_g)
+        # energy over the complete chunks (the ragged last chunk sheds what falls on its pad)
+        nf, cf = (n // s) * s, n // s
+        m1 = oracle.fold(cfg, g, m_gpu).astype(np.float64)[:nf]
+        e_in = (m1 ** 2).sum()
+        e_out = ((m_new[:nf].astype(np.float64) ** 2).sum() +
+                 (val_g[:cf * k].astype(np.float64) ** 2).sum())
+        assert abs(e_in - e_out) < 1e-5 * e_in                  # nothing lost, nothing made up
+        if scheme == SCHEME_STRIDE:
+            own_idx = oracle.select(cfg, None, 1)
+            seen[own_idx] += 1
+        # exchange: [own payload, other replica's payload]
+        val = np.stack([val_g, val_o])
+        idx = np.stack([idx_g, idx_o]) if send_idx else None
+        th_new, y = H.gpu_decompress(cfg, idx, val, th_gpu)
+        parity.check_decompress(cfg, idx, val, th_gpu, th_new, y)
+        # free-running oracle with the same gradients and the same other replica
+        m_free, idx_f, val_f = oracle.compress(cfg, g, m_free)
+        th_free = oracle.decompress_step(cfg, np.stack([idx_f, idx_o]) if send_idx else None,
+                                         np.stack([val_f, val_o]), th_free)
+        m_gpu, th_gpu = m_new, th_new
+    if scheme == SCHEME_STRIDE:
+        assert seen.sum() == T * k and seen.max() - seen.min() <= 1   # offset rotates evenly
+    # drift of the free-running oracle from the GPU trajectory: a flipped near-tie or sign
+    # moves single elements by a coefficient or 2*eta, so compare in the mean
+    assert np.abs(th_free - th_gpu).mean() < 1e-3 * 1e-3
+    assert np.abs(m_free - m_gpu).mean() < 1e-3 * np.abs(m_free).mean()
