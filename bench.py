@@ -68,6 +68,8 @@ def main() -> int:
     ap.add_argument("--workload", default="olmo-1b-1of8")
     ap.add_argument("--scheme", default="topk", choices=["topk", "stride", "random"])
     ap.add_argument("--dct", action="store_true", help="coefficient domain for stride/random")
+    ap.add_argument("--chunk", type=int, default=0, help="override the workload's chunk size")
+    ap.add_argument("--topk", type=int, default=0, help="override the workload's k")
     ap.add_argument("--cpu-sample", type=int, default=1 << 28)
     ap.add_argument("--no-cpu", action="store_true")
     args = ap.parse_args()
@@ -84,6 +86,9 @@ def main() -> int:
     binding.load()
     dev = torch.device("cuda:0")
     w = synth.workloads()[args.workload]
+    if args.chunk or args.topk:
+        import dataclasses
+        w = dataclasses.replace(w, chunk=args.chunk or w.chunk, topk=args.topk or w.topk)
     scheme = {"topk": binding.SCHEME_TOPK, "stride": binding.SCHEME_STRIDE,
               "random": binding.SCHEME_RANDOM}[args.scheme]
     cfg_kwargs = dict(chunk=w.chunk, topk=w.topk, scheme=scheme, sign=w.sign, dct=args.dct,

@@ -68,14 +68,16 @@ bool aligned16(const void* p) { return aligned(p, 16); }
 // tiled kernels take one 64-chunk tile per workgroup
 constexpr int64_t kMaxTiles = 0x7FFFFFFF;
 
-// Striding: the positions o + j*floor(s/k) as a bit pattern (chunk sizes up to 64)
-uint64_t stride_pattern(const KParams& p) {
-    if (p.s > 64) return 0;
+// Striding: the positions o + j*floor(s/k) as a bit pattern (chunk sizes up to 128)
+void stride_pattern(const KParams& p, uint32_t (&w)[4]) {
+    w[0] = w[1] = w[2] = w[3] = 0u;
+    if (p.s > 128) return;
     const int stride = p.s / p.k;
     const int off = static_cast<int>(p.step % static_cast<uint64_t>(stride));
-    uint64_t m = 0;
-    for (int j = 0; j < p.k; ++j) m |= 1ull << (off + j * stride);
-    return m;
+    for (int j = 0; j < p.k; ++j) {
+        const int at = off + j * stride;
+        w[at / 32] |= 1u << (at % 32);
+    }
 }
 
 }  // namespace
@@ -105,10 +107,14 @@ int detonation_compress(const deto_config* cfg, int64_t n, const void* grad, int
     const int64_t tiles = (n / p.s) / deto::kWave;
     if (tiles > 0 && tiles <= kMaxTiles && aligned16(grad) && aligned16(momentum) &&
         aligned16(idx_out) && aligned16(val_out) && aligned16(coeff_dbg)) {
-        const deto::CompressLaunch a{p, tiles, grad, grad_dtype == DETO_BF16, momentum, idx_out,
-                                     val_out, coeff_dbg, stride_pattern(p), st};
+        deto::CompressLaunch a{p, tiles, grad, grad_dtype == DETO_BF16, momentum, idx_out,
+                               val_out, coeff_dbg, {0, 0, 0, 0}, st};
+        stride_pattern(p, a.stride_mask);
         const bool done = (p.scheme == DETO_SCHEME_TOPK)
-                              ? (deto::launch_compress_topk_s64(a) || deto::launch_compress_topk_s32(a))
+                              ? (deto::launch_compress_topk_s64(a) ||
+                                 deto::launch_compress_topk_s32(a) ||
+                                 deto::launch_compress_topk_s128_k4(a) ||
+                                 deto::launch_compress_topk_s128_k16(a))
                               : deto::launch_compress_scheme(a);
         if (done) {
             rc = launched();
@@ -155,10 +161,13 @@ int detonation_decompress_step(const deto_config* cfg, int64_t n, int32_t R, con
     if (tiles > 0 && tiles <= kMaxTiles && aligned16(idx) && aligned16(val) && aligned16(params) &&
         aligned16(presign_dbg) &&
         (R == 1 || ((!idx || idx_replica_stride % 4 == 0) && val_replica_stride % 4 == 0))) {
-        const deto::DecompressLaunch a{p, tiles, idx, idx_replica_stride, val, val_replica_stride,
-                                       params, param_dtype == DETO_BF16, presign_dbg,
-                                       stride_pattern(p), st};
-        const bool done = idx ? (deto::launch_decompress_idx_s64(a) || deto::launch_decompress_idx_s32(a))
+        deto::DecompressLaunch a{p, tiles, idx, idx_replica_stride, val, val_replica_stride,
+                                 params, param_dtype == DETO_BF16, presign_dbg, {0, 0, 0, 0}, st};
+        stride_pattern(p, a.stride_mask);
+        const bool done = idx ? (deto::launch_decompress_idx_s64(a) ||
+                                 deto::launch_decompress_idx_s32(a) ||
+                                 deto::launch_decompress_idx_s128_k4(a) ||
+                                 deto::launch_decompress_idx_s128_k16(a))
                               : deto::launch_decompress_scheme(a);
         if (done) {
             rc = launched();

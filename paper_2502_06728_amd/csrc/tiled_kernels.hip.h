@@ -27,7 +27,7 @@ namespace deto {
 // ---- Batcher's odd-even merge sort as a compile-time list of compare-exchanges
 template <int N>
 struct SortNet {
-    static constexpr int kCap = N * 8;
+    static constexpr int kCap = N * 12;   // N log^2 N / 4 compare-exchanges fit up to N = 128
     int a[kCap];
     int b[kCap];
     int n;
@@ -110,24 +110,35 @@ struct TileGeom {
     static constexpr int kFloats = kWave * kRow;
     static constexpr int kElems = kWave * S;     // elements per tile
     static constexpr int kPermStride = S + 4;    // bytes per lane of Fisher-Yates scratch
+    // a chunk lives in S VGPRs of its lane: 2 wavefronts per SIMD up to S = 64, 1 beyond
+    static constexpr int kWavesPerSimd = S <= 64 ? 2 : 1;
 };
 
-// keep the `need` lowest set bits of `e` (per lane), wave-uniform loop
-__device__ __forceinline__ uint64_t lowest_bits(uint64_t e, int need) {
-    uint64_t keep = 0;
-    while (__any(need > 0)) {
-        if (need > 0) {
-            const uint64_t low = e & (0 - e);
-            keep |= low;
-            e ^= low;
-            --need;
-        }
+// A chunk's kept positions as a bit pattern: bit i%32 of word i/32 = element i is kept.
+template <int S>
+struct ChunkMask {
+    static constexpr int kWords = (S + 31) / 32;
+    uint32_t w[kWords];
+    __device__ __forceinline__ uint32_t bit(int i) const { return (w[i / 32] >> (i % 32)) & 1u; }
+    __device__ __forceinline__ int count() const {
+        int c = 0;
+#pragma unroll
+        for (int j = 0; j < kWords; ++j) c += __popc(w[j]);
+        return c;
     }
-    return keep;
-}
+};
 
-__device__ __forceinline__ uint32_t mask_bit(uint32_t mlo, uint32_t mhi, int i) {
-    return (i >= 32) ? ((mhi >> (i - 32)) & 1u) : ((mlo >> i) & 1u);
+// Striding's pattern is the same for every chunk: computed on the host, passed by value.
+struct MaskWords {
+    uint32_t w[4];
+};
+
+template <int S>
+__device__ __forceinline__ ChunkMask<S> mask_from_words(const MaskWords& m) {
+    ChunkMask<S> r;
+#pragma unroll
+    for (int j = 0; j < ChunkMask<S>::kWords; ++j) r.w[j] = m.w[j];
+    return r;
 }
 
 // ---- phase 1 of compress: m1 = beta*m + g, coalesced, into the LDS tile
@@ -207,8 +218,9 @@ __device__ __forceinline__ void regs_to_global(float* dst, const float (&x)[S]) 
 // in registers).  Every element is written at the running position, which only advances
 // past kept ones, so a dropped element is overwritten by the next kept one.
 template <int S, int K>
-__device__ __forceinline__ void compact_and_store_payload(const float (&c)[S], uint32_t mlo,
-                                                          uint32_t mhi, float* tile, int lane,
+__device__ __forceinline__ void compact_and_store_payload(const float (&c)[S],
+                                                          const ChunkMask<S>& mk, float* tile,
+                                                          int lane,
                                                           int32_t* __restrict__ idx_out,
                                                           float* __restrict__ val_out,
                                                           int64_t pbase) {
@@ -223,7 +235,7 @@ __device__ __forceinline__ void compact_and_store_payload(const float (&c)[S], u
         static_for<0, S>([&](auto i) {
             vrow[pos] = c[i];
             irow[pos] = static_cast<uint8_t>(i);
-            pos += static_cast<int>(mask_bit(mlo, mhi, i));
+            pos += static_cast<int>(mk.bit(i));
         });
     }
     wave_lds_sync();
@@ -270,27 +282,31 @@ __device__ __forceinline__ void store_tile_momentum(const float* tile, float* __
 // private to the calling lane.  Only perm[t] needs writing back: place j is never read
 // again once step j has taken its value.
 template <int S, int K>
-__device__ __forceinline__ uint64_t random_mask(uint64_t seed, uint64_t step, uint64_t chunk,
-                                                uint8_t* perm) {
+__device__ __forceinline__ ChunkMask<S> random_mask(uint64_t seed, uint64_t step, uint64_t chunk,
+                                                    uint8_t* perm) {
 #pragma unroll
     for (int w = 0; w < S / 4; ++w)
         reinterpret_cast<uint32_t*>(perm)[w] = 0x03020100u + 0x04040404u * w;
     const uint64_t key = chunk_key(seed, step, chunk);
-    uint64_t mask = 0;
+    ChunkMask<S> mask;
+#pragma unroll
+    for (int w = 0; w < ChunkMask<S>::kWords; ++w) mask.w[w] = 0u;
 #pragma unroll
     for (int j = 0; j < K; ++j) {
         const int t = j + static_cast<int>(bounded(draw(key, j), S - j));
         const uint8_t pj = perm[j];
         const uint8_t pt = perm[t];
         perm[t] = pj;
-        mask |= 1ull << pt;
+        const uint32_t b = 1u << (pt & 31u);
+#pragma unroll
+        for (int w = 0; w < ChunkMask<S>::kWords; ++w) mask.w[w] |= ((pt >> 5) == w) ? b : 0u;
     }
     return mask;
 }
 
 // Compress half (top-k) on full tiles: chunks [0, 64*n_tiles), all complete.
 template <int S, int K, bool GRAD_BF16>
-__global__ __launch_bounds__(kWave, 2) void compress_tiled_topk(
+__global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void compress_tiled_topk(
     KParams p, int64_t n_tiles, const void* __restrict__ grad, float* __restrict__ mom,
     int32_t* __restrict__ idx_out, float* __restrict__ val_out, float* __restrict__ coeff_dbg) {
     using G = TileGeom<S>;
@@ -314,7 +330,9 @@ __global__ __launch_bounds__(kWave, 2) void compress_tiled_topk(
     static_for<1, S>([&](auto i) { c[i] *= p.alpha; });
     if (coeff_dbg) regs_to_global<S>(coeff_dbg + ebase + static_cast<int64_t>(lane) * S, c);
 
-    // threshold: K-th largest magnitude
+    // threshold: K-th largest magnitude.  Beyond S = 64 the coefficients wait in the lane's
+    // LDS row (free by now) while their magnitudes are sorted, to stay within the registers.
+    constexpr bool kLean = S > 64;
     uint32_t T;
     {
         uint32_t A[H], B[H];
@@ -322,43 +340,68 @@ __global__ __launch_bounds__(kWave, 2) void compress_tiled_topk(
             A[i] = __float_as_uint(c[i]) & 0x7FFFFFFFu;
             B[i] = __float_as_uint(c[H + i]) & 0x7FFFFFFFu;
         });
+        if constexpr (kLean) {
+            regs_to_row<S>(row, c);
+            wave_lds_sync();
+        }
         sort_desc<H>(A);
         sort_desc<H>(B);
         T = kth_largest<H, K>(A, B);
+        if constexpr (kLean) {
+            wave_lds_sync();
+            row_to_regs<S>(row, c);
+            wave_lds_sync();
+        }
     }
-    // keep magnitude >= T: u holds what stays behind in the momentum (the dropped
-    // coefficients), the mask collects the decisions (bit i = element i kept)
-    float u[S];
-    uint32_t mlo = 0u, mhi = 0u;
+    // keep magnitude >= T: the mask collects the decisions (bit i = element i kept).  Up to
+    // S = 64 a second register array u receives, in the same pass, what stays behind in the
+    // momentum (the dropped coefficients); beyond that registers are short and the kept
+    // entries of c are cleared after the payload has been written instead.
+    float u[kLean ? 1 : S];
+    ChunkMask<S> mk;
+#pragma unroll
+    for (int w = 0; w < ChunkMask<S>::kWords; ++w) mk.w[w] = 0u;
     static_for<0, S>([&](auto I) {
         constexpr int i = S - 1 - I;   // descending so that shifting lands bit i at i
         const bool keep = (__float_as_uint(c[i]) & 0x7FFFFFFFu) >= T;
-        u[i] = keep ? 0.0f : c[i];
-        if constexpr (i >= 32) mhi = (mhi << 1) | (keep ? 1u : 0u);
-        else mlo = (mlo << 1) | (keep ? 1u : 0u);
+        if constexpr (!kLean) u[i] = keep ? 0.0f : c[i];
+        mk.w[i / 32] = (mk.w[i / 32] << 1) | (keep ? 1u : 0u);
     });
-    if (__any(__popc(mlo) + __popc(mhi) != K)) {
-        // a tie at the threshold somewhere in this wavefront: exact rule
-        uint64_t gt = 0, eq = 0;
+    if (__any(mk.count() != K)) {
+        // a tie at the threshold somewhere in this wavefront: exact rule, everything above
+        // T plus the lowest-index entries equal to T
+        int need = K;
+        static_for<0, S>([&](auto i) {
+            need -= ((__float_as_uint(c[i]) & 0x7FFFFFFFu) > T) ? 1 : 0;
+        });
+#pragma unroll
+        for (int w = 0; w < ChunkMask<S>::kWords; ++w) mk.w[w] = 0u;
         static_for<0, S>([&](auto i) {
             const uint32_t key = __float_as_uint(c[i]) & 0x7FFFFFFFu;
-            gt |= static_cast<uint64_t>(key > T) << i;
-            eq |= static_cast<uint64_t>(key == T) << i;
+            const bool take = (key == T) && (need > 0);
+            need -= take ? 1 : 0;
+            const bool keep = (key > T) || take;
+            mk.w[i / 32] |= (keep ? 1u : 0u) << (i % 32);
+            if constexpr (!kLean) u[i] = keep ? 0.0f : c[i];
         });
-        const uint64_t m = gt | lowest_bits(eq, K - __popcll(gt));
-        mlo = static_cast<uint32_t>(m);
-        mhi = static_cast<uint32_t>(m >> 32);
-        static_for<0, S>([&](auto i) { u[i] = ((m >> i) & 1ull) ? 0.0f : c[i]; });
     }
 
-    compact_and_store_payload<S, K>(c, mlo, mhi, tile, lane, idx_out, val_out, t * (kWave * K));
+    compact_and_store_payload<S, K>(c, mk, tile, lane, idx_out, val_out, t * (kWave * K));
 
     // ---- m <- m1 - q.  With q = D^T(kept coefficients) and m1 = D^T(all coefficients), the
     // residual is the inverse transform of the dropped ones.
-    u[0] *= p.alpha0;
-    static_for<1, S>([&](auto i) { u[i] *= p.alpha; });
-    FastDct<S>::dct3(u);
-    regs_to_row<S>(row, u);
+    if constexpr (kLean) {
+        static_for<0, S>([&](auto i) { c[i] = mk.bit(i) ? 0.0f : c[i]; });
+        c[0] *= p.alpha0;
+        static_for<1, S>([&](auto i) { c[i] *= p.alpha; });
+        FastDct<S>::dct3(c);
+        regs_to_row<S>(row, c);
+    } else {
+        u[0] *= p.alpha0;
+        static_for<1, S>([&](auto i) { u[i] *= p.alpha; });
+        FastDct<S>::dct3(u);
+        regs_to_row<S>(row, u);
+    }
     wave_lds_sync();
     store_tile_momentum<S>(tile, mom, ebase, lane);
 }
@@ -367,8 +410,8 @@ __global__ __launch_bounds__(kWave, 2) void compress_tiled_topk(
 // p.use_dct) on DCT coefficients.  Same three phases; the kept set is a bit pattern that does
 // not depend on the data: `stride_mask` for Striding, a per-chunk shuffle for Random.
 template <int S, int K, bool GRAD_BF16>
-__global__ __launch_bounds__(kWave, 2) void compress_tiled_scheme(
-    KParams p, uint64_t stride_mask, int64_t n_tiles, const void* __restrict__ grad,
+__global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void compress_tiled_scheme(
+    KParams p, MaskWords stride_mask, int64_t n_tiles, const void* __restrict__ grad,
     float* __restrict__ mom, int32_t* __restrict__ idx_out, float* __restrict__ val_out,
     float* __restrict__ coeff_dbg) {
     using G = TileGeom<S>;
@@ -391,18 +434,17 @@ __global__ __launch_bounds__(kWave, 2) void compress_tiled_scheme(
     }
     if (coeff_dbg) regs_to_global<S>(coeff_dbg + ebase + static_cast<int64_t>(lane) * S, c);
 
-    uint64_t m = stride_mask;
+    ChunkMask<S> mk = mask_from_words<S>(stride_mask);
     if (p.scheme == 2) {
         wave_lds_sync();   // rows are in registers: the tile doubles as shuffle scratch
-        m = random_mask<S, K>(p.seed, p.step, static_cast<uint64_t>(t) * kWave + lane,
-                              reinterpret_cast<uint8_t*>(tile) + lane * G::kPermStride);
+        mk = random_mask<S, K>(p.seed, p.step, static_cast<uint64_t>(t) * kWave + lane,
+                               reinterpret_cast<uint8_t*>(tile) + lane * G::kPermStride);
         wave_lds_sync();
     }
-    const uint32_t mlo = static_cast<uint32_t>(m), mhi = static_cast<uint32_t>(m >> 32);
 
-    compact_and_store_payload<S, K>(c, mlo, mhi, tile, lane, idx_out, val_out, t * (kWave * K));
+    compact_and_store_payload<S, K>(c, mk, tile, lane, idx_out, val_out, t * (kWave * K));
 
-    static_for<0, S>([&](auto i) { c[i] = mask_bit(mlo, mhi, i) ? 0.0f : c[i]; });
+    static_for<0, S>([&](auto i) { c[i] = mk.bit(i) ? 0.0f : c[i]; });
     if (p.use_dct) {
         c[0] *= p.alpha0;
         static_for<1, S>([&](auto i) { c[i] *= p.alpha; });
@@ -592,7 +634,7 @@ __device__ __forceinline__ void finish_chunk(const KParams& p, float (&y)[S], fl
 // scattered into LDS; LDS operations of one wavefront complete in order, so the additions
 // into one accumulator happen replica after replica and the result does not depend on timing.
 template <int S, int K, bool PARAM_BF16>
-__global__ __launch_bounds__(kWave, 2) void decompress_tiled(
+__global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_tiled(
     KParams p, int64_t n_tiles, const int32_t* __restrict__ idx, int64_t idx_stride,
     const float* __restrict__ val, int64_t val_stride, void* __restrict__ params,
     float* __restrict__ presign_dbg) {
@@ -609,7 +651,24 @@ __global__ __launch_bounds__(kWave, 2) void decompress_tiled(
     for (int i = 0; i < G::kFloats / (kWave * 4); ++i)
         *reinterpret_cast<float4*>(tile + (i * kWave + lane) * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
     wave_lds_sync();
-    if constexpr (K % 4 == 0) {
+    if constexpr (K % 4 == 0 && K > 32) {
+        // large k: two replicas in flight
+        PayloadRegs<K> b0, b1;
+        auto fetch = [&](PayloadRegs<K>& b, int r) {
+            load_payload<K>(b, idx + r * idx_stride + pbase, val + r * val_stride + pbase, lane);
+        };
+        fetch(b0, 0);
+        if (p.R > 1) fetch(b1, 1);
+        int r = 0;
+        while (true) {
+            scatter_payload<S, K>(b0, tile, lane);
+            if (r + 2 < p.R) fetch(b0, r + 2);
+            if (++r >= p.R) break;
+            scatter_payload<S, K>(b1, tile, lane);
+            if (r + 2 < p.R) fetch(b1, r + 2);
+            if (++r >= p.R) break;
+        }
+    } else if constexpr (K % 4 == 0) {
         PayloadRegs<K> b0, b1, b2;
         auto fetch = [&](PayloadRegs<K>& b, int r) {
             load_payload<K>(b, idx + r * idx_stride + pbase, val + r * val_stride + pbase, lane);
@@ -659,8 +718,8 @@ __global__ __launch_bounds__(kWave, 2) void decompress_tiled(
 // they stream in, and each chunk's lane spreads the k sums over the positions of its bit
 // pattern.
 template <int S, int K, bool PARAM_BF16>
-__global__ __launch_bounds__(kWave, 2) void decompress_tiled_scheme(
-    KParams p, uint64_t stride_mask, int64_t n_tiles, const float* __restrict__ val,
+__global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_tiled_scheme(
+    KParams p, MaskWords stride_mask, int64_t n_tiles, const float* __restrict__ val,
     int64_t val_stride, void* __restrict__ params, float* __restrict__ presign_dbg) {
     using G = TileGeom<S>;
     __shared__ __attribute__((aligned(16))) float tile[G::kFloats];
@@ -706,12 +765,11 @@ __global__ __launch_bounds__(kWave, 2) void decompress_tiled_scheme(
             tile[lane * PR + j] = a;
         }
     }
-    uint64_t m = stride_mask;
+    ChunkMask<S> mk = mask_from_words<S>(stride_mask);
     if (p.scheme == 2)
-        m = random_mask<S, K>(p.seed, p.step, static_cast<uint64_t>(t) * kWave + lane,
-                              reinterpret_cast<uint8_t*>(tile + kWave * PR) +
-                                  lane * G::kPermStride);
-    const uint32_t mlo = static_cast<uint32_t>(m), mhi = static_cast<uint32_t>(m >> 32);
+        mk = random_mask<S, K>(p.seed, p.step, static_cast<uint64_t>(t) * kWave + lane,
+                               reinterpret_cast<uint8_t*>(tile + kWave * PR) +
+                                   lane * G::kPermStride);
     wave_lds_sync();
 
     // lane = chunk: y[i] = kept ? sum[rank of i among the kept] : 0
@@ -720,7 +778,7 @@ __global__ __launch_bounds__(kWave, 2) void decompress_tiled_scheme(
         const float* vrow = tile + lane * PR;
         int pos = 0;
         static_for<0, S>([&](auto i) {
-            const uint32_t bit = mask_bit(mlo, mhi, i);
+            const uint32_t bit = mk.bit(i);
             const float v = vrow[pos];
             y[i] = bit ? v : 0.0f;
             pos += static_cast<int>(bit);

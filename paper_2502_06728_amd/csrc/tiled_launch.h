@@ -19,7 +19,7 @@ struct CompressLaunch {
     int32_t* idx;           // may be null for Striding/Random
     float* val;
     float* coeff_dbg;
-    uint64_t stride_mask;   // Striding: kept positions of every chunk
+    uint32_t stride_mask[4];  // Striding: kept positions of every chunk (bit i%32 of word i/32)
     hipStream_t stream;
 };
 
@@ -33,7 +33,7 @@ struct DecompressLaunch {
     void* params;
     bool param_bf16;
     float* presign_dbg;
-    uint64_t stride_mask;
+    uint32_t stride_mask[4];
     hipStream_t stream;
 };
 
@@ -41,6 +41,10 @@ bool launch_compress_topk_s64(const CompressLaunch& a);
 bool launch_compress_topk_s32(const CompressLaunch& a);
 bool launch_decompress_idx_s64(const DecompressLaunch& a);
 bool launch_decompress_idx_s32(const DecompressLaunch& a);
+bool launch_compress_topk_s128_k4(const CompressLaunch& a);
+bool launch_compress_topk_s128_k16(const CompressLaunch& a);
+bool launch_decompress_idx_s128_k4(const DecompressLaunch& a);
+bool launch_decompress_idx_s128_k16(const DecompressLaunch& a);
 bool launch_compress_scheme(const CompressLaunch& a);
 bool launch_decompress_scheme(const DecompressLaunch& a);
 
