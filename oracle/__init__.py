@@ -19,7 +19,7 @@ _SRC = os.path.join(_HERE, "detonation_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
 
 SCHEME_TOPK, SCHEME_STRIDE, SCHEME_RANDOM = 0, 1, 2
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 FLAG_SIGN, FLAG_DCT = 1, 2
 
 
@@ -73,6 +73,10 @@ def lib() -> ctypes.CDLL:
         _lib.orc_threads.restype = ctypes.c_int
         _lib.orc_double_to_bf16.restype = ctypes.c_uint16
         _lib.orc_double_to_bf16.argtypes = [ctypes.c_double]
+        _lib.orc_float_to_f16.restype = ctypes.c_uint16
+        _lib.orc_float_to_f16.argtypes = [ctypes.c_float]
+        _lib.orc_f16_to_float.restype = ctypes.c_float
+        _lib.orc_f16_to_float.argtypes = [ctypes.c_uint16]
     return _lib
 
 
@@ -114,6 +118,14 @@ def n_chunks(cfg: Config, n: int) -> int:
 
 def double_to_bf16(v: float) -> int:
     return int(lib().orc_double_to_bf16(float(v)))
+
+
+def float_to_f16(v: float) -> int:
+    return int(lib().orc_float_to_f16(float(v)))
+
+
+def f16_to_float(bits: int) -> float:
+    return float(lib().orc_f16_to_float(int(bits)))
 
 
 def dct_matrix(s: int) -> np.ndarray:
@@ -160,6 +172,42 @@ def extract(cfg: Config, m1: np.ndarray, coeff: np.ndarray, idx: np.ndarray):
     _chk(lib().orc_extract(ctypes.byref(cfg.c()), ctypes.c_int64(m1.size), _p(m1), _p(coeff),
                            _p(idx), _p(val), _p(m_new)))
     return val, m_new
+
+
+def extract_q(cfg: Config, m1: np.ndarray, coeff: np.ndarray, idx: np.ndarray, val_dtype: int):
+    """Payload values in a 16-bit transfer dtype (uint16 bit patterns) and the residual momentum
+    that removes exactly what the receivers decode."""
+    m1 = _c(m1, np.float32)
+    coeff = _c(coeff, np.float32)
+    idx = _c(idx, np.int32)
+    val = np.empty(idx.size, dtype=np.uint16)
+    m_new = np.empty_like(m1)
+    _chk(lib().orc_extract_q(ctypes.byref(cfg.c()), ctypes.c_int64(m1.size), _p(m1), _p(coeff),
+                             _p(idx), ctypes.c_int(val_dtype), _p(val), _p(m_new)))
+    return val, m_new
+
+
+def compress_q(cfg: Config, grad: np.ndarray, momentum: np.ndarray, val_dtype: int):
+    """Compress half with 16-bit payload values: the steps in order.  Returns (m_new, idx, val_bits)."""
+    m1 = fold(cfg, grad, momentum)
+    coeff = transform(cfg, m1)
+    idx = select(cfg, coeff)
+    val, m_new = extract_q(cfg, m1, coeff, idx, val_dtype)
+    return m_new, idx, val
+
+
+def presign_q(cfg: Config, n: int, idx, val_bits: np.ndarray, val_dtype: int) -> np.ndarray:
+    val_bits = _c(val_bits, np.uint16)
+    if val_bits.ndim == 1:
+        val_bits = val_bits[None, :]
+    R = val_bits.shape[0]
+    if idx is not None:
+        idx = _c(idx, np.int32).reshape(R, -1)
+    y = np.empty(n, dtype=np.float32)
+    _chk(lib().orc_presign_q(ctypes.byref(cfg.c()), ctypes.c_int64(n), ctypes.c_int32(R), _p(idx),
+                             ctypes.c_int64(0 if idx is None else idx.shape[1]), _p(val_bits),
+                             ctypes.c_int(val_dtype), ctypes.c_int64(val_bits.shape[1]), _p(y)))
+    return y
 
 
 def compress(cfg: Config, grad: np.ndarray, momentum: np.ndarray, want_coeff: bool = False):

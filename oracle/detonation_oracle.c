@@ -52,7 +52,7 @@ static const double ORC_PI = 3.14159265358979323846264338327950288;
 
 enum { ORC_OK = 0, ORC_ERR_NULL = 1, ORC_ERR_BAD_CONFIG = 2 };
 enum { ORC_SCHEME_TOPK = 0, ORC_SCHEME_STRIDE = 1, ORC_SCHEME_RANDOM = 2 };
-enum { ORC_F32 = 0, ORC_BF16 = 1 };
+enum { ORC_F32 = 0, ORC_BF16 = 1, ORC_F16 = 2 };
 #define ORC_FLAG_SIGN 1u
 #define ORC_FLAG_DCT 2u
 
@@ -136,6 +136,51 @@ static double load_elem(const void *p, int dtype, int64_t i)
 {
     if (dtype == ORC_BF16) return (double)bf16_bits_to_float(((const uint16_t *)p)[i]);
     return (double)((const float *)p)[i];
+}
+
+/* ---------------------------------------------- 16-bit transfer formats */
+
+/* fp32 -> IEEE half, round to nearest even, subnormals kept, overflow to infinity. */
+uint16_t orc_float_to_f16(float f)
+{
+    uint32_t x;
+    memcpy(&x, &f, 4);
+    const uint16_t sign = (uint16_t)((x >> 16) & 0x8000u);
+    const uint32_t ax = x & 0x7FFFFFFFu;
+    if (ax >= 0x7F800000u) return (uint16_t)(sign | 0x7C00u | ((ax > 0x7F800000u) ? 0x200u : 0u));
+    if (ax >= 0x477FF000u) return (uint16_t)(sign | 0x7C00u);   /* >= 65520 rounds to infinity */
+    if (ax < 0x38800000u) {
+        /* below 2^-14: the result is a multiple of 2^-24; rint() rounds to nearest even */
+        const double units = rint((double)fabsf(f) * 16777216.0);
+        return (uint16_t)(sign | (uint16_t)units);               /* 1024 is the smallest normal */
+    }
+    const uint32_t mant = ax & 0x7FFFFFu;
+    uint32_t half = (((ax >> 23) - 127u + 15u) << 10) | (mant >> 13);
+    const uint32_t rem = mant & 0x1FFFu;
+    if (rem > 0x1000u || (rem == 0x1000u && (half & 1u))) ++half;  /* a carry moves the exponent */
+    return (uint16_t)(sign | half);
+}
+
+float orc_f16_to_float(uint16_t h)
+{
+    const int e = (h >> 10) & 0x1F, m = h & 0x3FF;
+    double v;
+    if (e == 0) v = ldexp((double)m, -24);
+    else if (e == 31) v = m ? NAN : INFINITY;
+    else v = ldexp(1.0 + (double)m / 1024.0, e - 15);
+    return (float)((h & 0x8000u) ? -v : v);
+}
+
+/* Transfer-dtype round trip of one payload value: what the receiver decodes.
+ * (Appendix B, "Communication Floating Point Data Type": fp32 or a 16-bit format.) */
+static float transfer_decode(int val_dtype, uint16_t bits)
+{
+    return val_dtype == ORC_F16 ? orc_f16_to_float(bits) : bf16_bits_to_float(bits);
+}
+
+static uint16_t transfer_encode(int val_dtype, float v)
+{
+    return val_dtype == ORC_F16 ? orc_float_to_f16(v) : orc_double_to_bf16((double)v);
 }
 
 /* ------------------------------------------------------- DCT-II matrix (S1) */
@@ -353,6 +398,55 @@ int orc_extract(const orc_config *cfg, int64_t n, const float *m1, const float *
     }
     free(D);
     return ORC_OK;
+}
+
+/* Payload values in a 16-bit transfer dtype (val_bits), and the residual that removes from
+ * the momentum exactly what the receivers will decode:
+ * val_bits[c*k+j] = encode(coeff[c*s + idx]);  m_new = fl32( m1 - D^T decode(val_bits) ). */
+int orc_extract_q(const orc_config *cfg, int64_t n, const float *m1, const float *coeff,
+                  const int32_t *idx, int val_dtype, uint16_t *val_bits, float *m_new)
+{
+    int rc = orc_check(cfg);
+    if (rc) return rc;
+    if (val_dtype != ORC_BF16 && val_dtype != ORC_F16) return ORC_ERR_BAD_CONFIG;
+    if (n > 0 && (!m1 || !coeff || !idx || !val_bits || !m_new)) return ORC_ERR_NULL;
+    const int k = cfg->topk, s = cfg->chunk;
+    const int64_t C = (n + s - 1) / s;
+    float *decoded = (float *)malloc(sizeof(float) * (size_t)(C * k));
+    float *shadow = (float *)malloc(sizeof(float) * (size_t)(C * s));
+    memcpy(shadow, coeff, sizeof(float) * (size_t)(C * s));
+    for (int64_t e = 0; e < C * k; ++e) {
+        const int64_t at = (e / k) * s + idx[e];
+        val_bits[e] = transfer_encode(val_dtype, coeff[at]);
+        shadow[at] = transfer_decode(val_dtype, val_bits[e]);
+    }
+    /* orc_extract reads the kept values from the coefficient array it is given: hand it the
+     * array with the kept entries replaced by their decoded transfer values */
+    rc = orc_extract(cfg, n, m1, shadow, idx, decoded, m_new);
+    free(shadow);
+    free(decoded);
+    return rc;
+}
+
+/* Averaged update before sign from payloads whose values are in a 16-bit transfer dtype. */
+int orc_presign_q(const orc_config *cfg, int64_t n, int32_t R, const int32_t *idx,
+                  int64_t idx_replica_stride, const uint16_t *val_bits, int val_dtype,
+                  int64_t val_replica_stride, float *y)
+{
+    int rc = orc_check(cfg);
+    if (rc) return rc;
+    if (val_dtype != ORC_BF16 && val_dtype != ORC_F16) return ORC_ERR_BAD_CONFIG;
+    if (R < 1) return ORC_ERR_BAD_CONFIG;
+    if (n == 0) return ORC_OK;
+    if (!val_bits || !y) return ORC_ERR_NULL;
+    const int64_t entries = ((n + cfg->chunk - 1) / cfg->chunk) * cfg->topk;
+    float *val = (float *)malloc(sizeof(float) * (size_t)(R * entries));
+    for (int r = 0; r < R; ++r)
+        for (int64_t e = 0; e < entries; ++e)
+            val[r * entries + e] = transfer_decode(val_dtype, val_bits[r * val_replica_stride + e]);
+    rc = orc_presign(cfg, n, R, idx, idx_replica_stride, val, entries, y);
+    free(val);
+    return rc;
 }
 
 /* The whole compress half: fold, transform, select, extract.

@@ -418,3 +418,60 @@ def test_golden_regression_small_case():
     assert now.keys() == gold.keys()
     for key in gold:
         assert now[key] == gold[key], key
+
+
+# ------------------------------------------- 16-bit transfer dtypes (Appendix B, "dtype")
+
+def test_f16_conversion_exhaustive_and_against_numpy():
+    bits = np.arange(1 << 16, dtype=np.uint16)
+    ref = bits.view(np.float16).astype(np.float32)
+    for b in range(0, 1 << 16, 1):
+        e = (b >> 10) & 0x1F
+        v = oracle.f16_to_float(b)
+        if e == 31:
+            assert np.isnan(v) == bool(b & 0x3FF) and (np.isinf(v) or np.isnan(v))
+            continue
+        assert v == ref[b]                                   # decode: library pin (numpy)
+        assert oracle.float_to_f16(v) == b or (v == 0.0)     # round trip of every finite half
+    # encode against numpy's fp32 -> fp16 (round to nearest even), incl. subnormals and overflow
+    rng = np.random.default_rng(0)
+    x = np.concatenate([rng.standard_normal(20000).astype(np.float32) * s
+                        for s in (1e-8, 1e-6, 1e-4, 1e-2, 1.0, 1e3, 1e5)])
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float16).view(np.uint16)
+    got = np.array([oracle.float_to_f16(float(v)) for v in x], dtype=np.uint16)
+    assert np.array_equal(got, want)
+    # exact midpoints between neighbouring halves go to the even one
+    for b in [0x3C00, 0x3C01, 0x0001, 0x0002, 0x03FF, 0x0400, 0x7BFE]:
+        lo, hi = float(ref[b]), float(ref[b + 1])
+        mid = np.float32((lo + hi) / 2)
+        assert float(mid) == (lo + hi) / 2                   # representable in fp32
+        assert oracle.float_to_f16(float(mid)) == (b if b % 2 == 0 else b + 1)
+    assert oracle.float_to_f16(65519.9) == 0x7BFF and oracle.float_to_f16(65520.0) == 0x7C00
+    assert oracle.float_to_f16(2.0 ** -25) == 0 and oracle.float_to_f16(2.0 ** -25 * 1.001) == 1
+
+
+@pytest.mark.parametrize("val_dtype", [oracle.BF16, oracle.F16])
+def test_16bit_payload_residual_removes_what_is_decoded(val_dtype):
+    s, k, n = 64, 16, 64 * 40 + 9
+    cfg = Config(chunk=s, topk=k, sign=False)
+    g, m = rnd(200, n, 1e-3), rnd(201, n, 1e-3)
+    m1 = oracle.fold(cfg, g, m)
+    m_new, idx, vbits = oracle.compress_q(cfg, g, m, val_dtype)
+    m_ref, idx_ref, val_ref = oracle.compress(cfg, g, m)
+    assert np.array_equal(idx, idx_ref)                       # selection is unchanged
+    dec = (synth.from_bf16_bits(vbits) if val_dtype == oracle.BF16
+           else vbits.view(np.float16).astype(np.float32))
+    # the payload is the fp32 payload rounded to the transfer dtype (library conversions)
+    want_bits = (synth.to_bf16_bits(val_ref) if val_dtype == oracle.BF16
+                 else val_ref.astype(np.float16).view(np.uint16))
+    assert np.array_equal(vbits, want_bits)
+    # what is subtracted from the momentum is what the receiver decodes: m1 = m' + IDCT(decoded)
+    y = oracle.presign_q(cfg, n, idx, vbits, val_dtype)
+    assert np.abs((m_new.astype(np.float64) + y) - m1).max() < 3e-7 * np.abs(m1).max()
+    # and decoding then averaging equals the fp32 path on the decoded values
+    y32 = oracle.presign(cfg, n, idx, dec)
+    assert np.array_equal(y, y32)
+    # the rounding error of the transfer stays in the momentum instead of being lost
+    rel = 2.0 ** -8 if val_dtype == oracle.BF16 else 2.0 ** -11
+    assert np.abs(m_new - m_ref).max() <= 1.01 * rel * np.abs(val_ref).max() * np.sqrt(2 * k / s)
