@@ -26,11 +26,11 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 
 
 def algorithmic_bytes(n: int, s: int, k: int, R: int, grad_bytes: int, param_bytes: int,
-                      with_idx: bool) -> dict:
+                      with_idx: bool, val_bytes: int = 4, idx_bytes: int = 4) -> dict:
     """Bytes the method itself must move per launch: compress reads g and m, writes m and
     the payload; decompress reads R payloads, reads and writes the parameters."""
     C = -(-n // s)
-    pay = C * k * (8 if with_idx else 4)
+    pay = C * k * (val_bytes + (idx_bytes if with_idx else 0))
     return {"compress": n * (grad_bytes + 8) + pay, "decompress": R * pay + 2 * n * param_bytes}
 
 
@@ -68,6 +68,8 @@ def main() -> int:
     ap.add_argument("--workload", default="olmo-1b-1of8")
     ap.add_argument("--scheme", default="topk", choices=["topk", "stride", "random"])
     ap.add_argument("--dct", action="store_true", help="coefficient domain for stride/random")
+    ap.add_argument("--payload", default="f32i32", choices=["f32i32", "bf16u8", "f16u8"],
+                    help="payload format: value dtype + index width (top-k)")
     ap.add_argument("--chunk", type=int, default=0, help="override the workload's chunk size")
     ap.add_argument("--topk", type=int, default=0, help="override the workload's k")
     ap.add_argument("--cpu-sample", type=int, default=1 << 28)
@@ -108,8 +110,14 @@ def main() -> int:
 
     grad, mom, params = up(g_np), up(m_np), up(th_np)
     del g_np, m_np, th_np
-    idx = torch.zeros((R, entries), dtype=torch.int32, device=dev) if with_idx else None
-    val = torch.zeros((R, entries), dtype=torch.float32, device=dev)
+    packed = args.payload != "f32i32"
+    val_t = {"f32i32": torch.float32, "bf16u8": torch.bfloat16, "f16u8": torch.float16}[args.payload]
+    idx_t = torch.uint8 if packed else torch.int32
+    idx = torch.zeros((R, entries), dtype=idx_t, device=dev) if with_idx else None
+    val = torch.zeros((R, entries), dtype=val_t, device=dev)
+    compress = binding.detonation_compress_packed if packed else binding.detonation_compress
+    decompress = (binding.detonation_decompress_step_packed if packed
+                  else binding.detonation_decompress_step)
     # ... and R-1 other replicas' payloads: the library's compress run, untimed, on
     # independently seeded shards of the same recipe (what an all_gather would deliver).
     gen = torch.Generator(device=dev)
@@ -121,7 +129,7 @@ def main() -> int:
             gr = torch.where(u < w.outlier_frac, gr * w.outlier_scale, gr)
         gr = gr.to(grad.dtype)
         mr = torch.randn(n, generator=gen, device=dev, dtype=torch.float32) * w.momentum_std
-        binding.detonation_compress(cfg, gr, mr, None if idx is None else idx[r], val[r])
+        compress(cfg, gr, mr, None if idx is None else idx[r], val[r])
         torch.cuda.synchronize()
         del gr, mr
     torch.cuda.empty_cache()
@@ -130,10 +138,10 @@ def main() -> int:
         cfg.step += 1
         if ev:
             ev[0].record()
-        binding.detonation_compress(cfg, grad, mom, None if idx is None else idx[0], val[0])
+        compress(cfg, grad, mom, None if idx is None else idx[0], val[0])
         if ev:
             ev[1].record()
-        binding.detonation_decompress_step(cfg, R, idx, val, params)
+        decompress(cfg, R, idx, val, params)
         if ev:
             ev[2].record()
 
@@ -151,7 +159,8 @@ def main() -> int:
     t_c = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps   # ms per launch
     t_d = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
     ms_per_step = wall * 1e3 / args.steps
-    ab = algorithmic_bytes(n, s, k, R, grad.element_size(), params.element_size(), with_idx)
+    ab = algorithmic_bytes(n, s, k, R, grad.element_size(), params.element_size(), with_idx,
+                           val.element_size(), idx.element_size() if with_idx else 0)
     gbs_c = ab["compress"] / (t_c * 1e-3) / 1e9
     gbs_d = ab["decompress"] / (t_d * 1e-3) / 1e9
     dom = "compress" if t_c >= t_d else "decompress"
@@ -161,7 +170,7 @@ def main() -> int:
     # measured them for this workload (recorded under profiles/, not re-measured here)
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"traffic_{args.workload}_{args.scheme}.txt")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and not packed and not (args.chunk or args.topk or args.dct):
         for line in open(tpath):
             f = line.split()
             if len(f) == 2 and f[0] == dom:
@@ -173,7 +182,7 @@ def main() -> int:
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "params": n, "chunk": s, "topk": k, "replicas": R,
-                   "scheme": args.scheme, "dct_domain": bool(cfg.scheme == 0 or args.dct),
+                   "scheme": args.scheme, "payload": args.payload, "dct_domain": bool(cfg.scheme == 0 or args.dct),
                    "grad_dtype": str(grad.dtype).split(".")[-1],
                    "param_dtype": str(params.dtype).split(".")[-1], "momentum_dtype": "float32",
                    "sign": w.sign, "decay": w.decay, "lr": w.lr},

@@ -56,7 +56,12 @@ typedef enum {
  *            so every replica regenerates them.  Indices are not transmitted. */
 typedef enum { DETO_SCHEME_TOPK = 0, DETO_SCHEME_STRIDE = 1, DETO_SCHEME_RANDOM = 2 } deto_scheme;
 
-typedef enum { DETO_F32 = 0, DETO_BF16 = 1 } deto_dtype;
+/* Element types.  Gradients and parameters are F32 or BF16; payload values may also be F16
+ * (IEEE half). */
+typedef enum { DETO_F32 = 0, DETO_BF16 = 1, DETO_F16 = 2 } deto_dtype;
+
+/* Payload index width: chunk-local indices always fit a byte (s <= 256). */
+typedef enum { DETO_IDX_I32 = 0, DETO_IDX_U8 = 1 } deto_idx_dtype;
 
 enum {
     DETO_FLAG_SIGN = 1u, /* apply sign() (sign(0)=0) to the averaged update before the
@@ -130,6 +135,33 @@ int detonation_decompress_step(const deto_config* cfg, int64_t n, int32_t R,
                                float* presign_dbg,
                                void* stream);
 
+/*
+ * The same two halves with a narrower payload (paper, Appendix B "Communication Floating Point
+ * Data Type": values sent as fp16 instead of fp32; "Replicator bandwidth usage": the indices
+ * are half of DeMo's traffic).  Values travel as val_dtype (DETO_F32, DETO_BF16 or DETO_F16,
+ * rounded to nearest even), indices as idx_dtype (DETO_IDX_I32 or DETO_IDX_U8).  The
+ * momentum gives up exactly what the receivers will decode:
+ *     momentum = m1 - D^T * decode(encode(c restricted to I)),
+ * so the rounding error of the transfer stays in the local momentum.  Everything else, the
+ * argument rules and the error codes are those of detonation_compress and
+ * detonation_decompress_step, which are these calls with DETO_IDX_I32 and DETO_F32; replica
+ * strides are in elements of the respective dtype.
+ */
+int detonation_compress_packed(const deto_config* cfg, int64_t n,
+                               const void* grad, int grad_dtype,
+                               float* momentum,
+                               void* idx_out, int idx_dtype,
+                               void* val_out, int val_dtype,
+                               float* coeff_dbg,
+                               void* stream);
+
+int detonation_decompress_step_packed(const deto_config* cfg, int64_t n, int32_t R,
+                                      const void* idx, int idx_dtype, int64_t idx_replica_stride,
+                                      const void* val, int val_dtype, int64_t val_replica_stride,
+                                      void* params, int param_dtype,
+                                      float* presign_dbg,
+                                      void* stream);
+
 /* Payload entries per replica, ceil(n/s)*k (the paper's compression rate k/s times the
  * padded shard length); -1 if cfg is invalid. */
 int64_t detonation_payload_entries(const deto_config* cfg, int64_t n);
@@ -137,7 +169,7 @@ int64_t detonation_payload_entries(const deto_config* cfg, int64_t n);
 /* Static, human-readable name of a deto_status. */
 const char* detonation_status_string(int status);
 
-/* ABI version of this header: major*1000 + minor. */
+/* ABI version of this header: major*1000 + minor (1001: the *_packed entry points). */
 int detonation_version(void);
 
 #ifdef __cplusplus

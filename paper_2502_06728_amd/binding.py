@@ -15,10 +15,12 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("DETONATION_LIB", os.path.join(_HERE, "libdetonation.so"))
 
 SCHEME_TOPK, SCHEME_STRIDE, SCHEME_RANDOM = 0, 1, 2
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
+IDX_I32, IDX_U8 = 0, 1
 FLAG_SIGN, FLAG_DCT = 1, 2
 
-EXPORTS = ("detonation_compress", "detonation_decompress_step", "detonation_payload_entries",
+EXPORTS = ("detonation_compress", "detonation_decompress_step", "detonation_compress_packed",
+           "detonation_decompress_step_packed", "detonation_payload_entries",
            "detonation_status_string", "detonation_version")
 
 
@@ -72,6 +74,12 @@ def load() -> ctypes.CDLL:
         lib.detonation_decompress_step.argtypes = [cfgp, i64, i32, vp, i64, vp, i64, vp,
                                                    ctypes.c_int, vp, vp]
         lib.detonation_decompress_step.restype = ctypes.c_int
+        lib.detonation_compress_packed.argtypes = [cfgp, i64, vp, ctypes.c_int, vp, vp, ctypes.c_int,
+                                                   vp, ctypes.c_int, vp, vp]
+        lib.detonation_compress_packed.restype = ctypes.c_int
+        lib.detonation_decompress_step_packed.argtypes = [cfgp, i64, i32, vp, ctypes.c_int, i64, vp,
+                                                          ctypes.c_int, i64, vp, ctypes.c_int, vp, vp]
+        lib.detonation_decompress_step_packed.restype = ctypes.c_int
         lib.detonation_payload_entries.argtypes = [cfgp, i64]
         lib.detonation_payload_entries.restype = i64
         lib.detonation_status_string.argtypes = [ctypes.c_int]
@@ -103,7 +111,18 @@ def _dtype(t) -> int:
         return F32
     if t.dtype == torch.bfloat16:
         return BF16
+    if t.dtype == torch.float16:
+        return F16
     raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _idx_dtype(t) -> int:
+    import torch
+    if t is None or t.dtype == torch.int32:
+        return IDX_I32
+    if t.dtype == torch.uint8:
+        return IDX_U8
+    raise TypeError(f"unsupported index dtype {t.dtype}")
 
 
 def _stream(stream):
@@ -147,5 +166,37 @@ def detonation_decompress_step(cfg: Config, R: int, idx, val, params, presign_db
     rc = load().detonation_decompress_step(ctypes.byref(cfg.c()), n, R, _ptr(idx), istr, _ptr(val),
                                            vs, _ptr(params), _dtype(params), _ptr(presign_dbg),
                                            _stream(stream))
+    if rc != 0:
+        raise DetonationError(rc)
+
+
+def detonation_compress_packed(cfg: Config, grad, momentum, idx_out, val_out, coeff_dbg=None,
+                               stream=None, n: int | None = None) -> None:
+    """Compress half with the payload format given by the output tensors' dtypes: indices
+    int32 or uint8, values float32, bfloat16 or float16."""
+    _check(grad, momentum, idx_out, val_out, coeff_dbg)
+    n = momentum.numel() if n is None else n
+    rc = load().detonation_compress_packed(ctypes.byref(cfg.c()), n, _ptr(grad), _dtype(grad),
+                                           _ptr(momentum), _ptr(idx_out), _idx_dtype(idx_out),
+                                           _ptr(val_out), _dtype(val_out), _ptr(coeff_dbg),
+                                           _stream(stream))
+    if rc != 0:
+        raise DetonationError(rc)
+
+
+def detonation_decompress_step_packed(cfg: Config, R: int, idx, val, params, presign_dbg=None,
+                                      stream=None, n: int | None = None,
+                                      idx_replica_stride: int | None = None,
+                                      val_replica_stride: int | None = None) -> None:
+    """Decompress-and-update half for payloads in the format given by the tensors' dtypes."""
+    _check(idx, val, params, presign_dbg)
+    n = params.numel() if n is None else n
+    entries = payload_entries(cfg, n)
+    vs = entries if val_replica_stride is None else val_replica_stride
+    istr = entries if idx_replica_stride is None else idx_replica_stride
+    rc = load().detonation_decompress_step_packed(ctypes.byref(cfg.c()), n, R, _ptr(idx),
+                                                  _idx_dtype(idx), istr, _ptr(val), _dtype(val), vs,
+                                                  _ptr(params), _dtype(params), _ptr(presign_dbg),
+                                                  _stream(stream))
     if rc != 0:
         raise DetonationError(rc)

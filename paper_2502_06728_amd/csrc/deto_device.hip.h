@@ -18,6 +18,8 @@ struct KParams {
     int use_dct;        // transform domain (always for TOPK)
     int use_sign;       // DETO_FLAG_SIGN
     int R;              // replicas (decompress)
+    int val_dtype;      // payload values: 0 fp32, 1 bf16, 2 fp16
+    int idx_u8;         // payload indices as bytes instead of int32
     float beta;         // momentum decay
     float lr;           // eta
     float wd_scale;     // 1 - eta*lambda
@@ -76,6 +78,24 @@ __device__ __forceinline__ uint4 ld_u4(const void* p) {
     }
 }
 
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+
+template <bool NT>
+__device__ __forceinline__ uint2 ld_u2(const void* p) {
+    if constexpr (NT) {
+        const u32x2_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t*>(p));
+        return make_uint2(t.x, t.y);
+    } else {
+        return *reinterpret_cast<const uint2*>(p);
+    }
+}
+
+template <bool NT>
+__device__ __forceinline__ uint32_t ld_u1(const void* p) {
+    if constexpr (NT) return __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(p));
+    else return *reinterpret_cast<const uint32_t*>(p);
+}
+
 template <bool NT>
 __device__ __forceinline__ void st_f4(float* p, float4 v) {
     if constexpr (NT) {
@@ -105,6 +125,30 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
     uint32_t u = __float_as_uint(f);
     u += 0x7FFFu + ((u >> 16) & 1u);
     return static_cast<uint16_t>(u >> 16);
+}
+
+// IEEE half <-> fp32 (round to nearest even; half subnormals are kept on gfx950)
+__device__ __forceinline__ uint16_t f32_to_f16(float f) {
+    return __builtin_bit_cast(uint16_t, static_cast<_Float16>(f));
+}
+
+__device__ __forceinline__ float f16_to_f32(uint16_t b) {
+    return static_cast<float>(__builtin_bit_cast(_Float16, b));
+}
+
+// payload value formats: 0 fp32, 1 bf16, 2 fp16
+template <int VAL>
+__device__ __forceinline__ uint16_t encode16(float v) {
+    static_assert(VAL == 1 || VAL == 2, "16-bit transfer dtype");
+    if constexpr (VAL == 1) return f32_to_bf16(v);
+    else return f32_to_f16(v);
+}
+
+template <int VAL>
+__device__ __forceinline__ float decode16(uint16_t b) {
+    static_assert(VAL == 1 || VAL == 2, "16-bit transfer dtype");
+    if constexpr (VAL == 1) return bf16_to_f32(b);
+    else return f16_to_f32(b);
 }
 
 __device__ __forceinline__ float sign_or_self(float y, int use_sign) {

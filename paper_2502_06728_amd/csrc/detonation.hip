@@ -30,12 +30,22 @@ int validate(const deto_config* cfg) {
 
 bool valid_dtype(int d) { return d == DETO_F32 || d == DETO_BF16; }
 
+bool valid_val_dtype(int d) { return d == DETO_F32 || d == DETO_BF16 || d == DETO_F16; }
+
+bool valid_idx_dtype(int d) { return d == DETO_IDX_I32 || d == DETO_IDX_U8; }
+
+size_t idx_size(int d) { return d == DETO_IDX_U8 ? 1 : 4; }
+
+size_t val_size(int d) { return d == DETO_F32 ? 4 : 2; }
+
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 size_t elem_size(int dtype) { return dtype == DETO_BF16 ? 2 : 4; }
 
-KParams resolve(const deto_config* cfg, int R) {
+KParams resolve(const deto_config* cfg, int R, int val_dtype, int idx_dtype) {
     KParams p;
+    p.val_dtype = val_dtype;
+    p.idx_u8 = idx_dtype == DETO_IDX_U8 ? 1 : 0;
     p.s = cfg->chunk;
     p.k = cfg->topk;
     p.scheme = cfg->scheme;
@@ -84,20 +94,23 @@ void stride_pattern(const KParams& p, uint32_t (&w)[4]) {
 
 extern "C" {
 
-int detonation_compress(const deto_config* cfg, int64_t n, const void* grad, int grad_dtype,
-                        float* momentum, int32_t* idx_out, float* val_out, float* coeff_dbg,
-                        void* stream) {
+int detonation_compress_packed(const deto_config* cfg, int64_t n, const void* grad,
+                               int grad_dtype, float* momentum, void* idx_out, int idx_dtype,
+                               void* val_out, int val_dtype, float* coeff_dbg, void* stream) {
     int rc = validate(cfg);
     if (rc) return rc;
-    if (n < 0 || !valid_dtype(grad_dtype)) return DETO_ERR_BAD_CONFIG;
+    if (n < 0 || !valid_dtype(grad_dtype) || !valid_val_dtype(val_dtype) ||
+        !valid_idx_dtype(idx_dtype))
+        return DETO_ERR_BAD_CONFIG;
     if (n == 0) return DETO_OK;
     if (!grad || !momentum || !val_out) return DETO_ERR_NULL;
     if (cfg->scheme == DETO_SCHEME_TOPK && !idx_out) return DETO_ERR_NULL;
-    if (!aligned(grad, elem_size(grad_dtype)) || !aligned(momentum, 4) || !aligned(val_out, 4) ||
-        !aligned(idx_out, 4) || !aligned(coeff_dbg, 4))
+    if (!aligned(grad, elem_size(grad_dtype)) || !aligned(momentum, 4) ||
+        !aligned(val_out, val_size(val_dtype)) || !aligned(idx_out, idx_size(idx_dtype)) ||
+        !aligned(coeff_dbg, 4))
         return DETO_ERR_ALIGN;
 
-    const KParams p = resolve(cfg, 1);
+    const KParams p = resolve(cfg, 1, val_dtype, idx_dtype);
     const int64_t C = chunks_of(n, p.s);
     hipStream_t st = static_cast<hipStream_t>(stream);
 
@@ -114,7 +127,8 @@ int detonation_compress(const deto_config* cfg, int64_t n, const void* grad, int
                               ? (deto::launch_compress_topk_s64(a) ||
                                  deto::launch_compress_topk_s32(a) ||
                                  deto::launch_compress_topk_s128_k4(a) ||
-                                 deto::launch_compress_topk_s128_k16(a))
+                                 deto::launch_compress_topk_s128_k16(a) ||
+                                 deto::launch_compress_topk_packed(a))
                               : deto::launch_compress_scheme(a);
         if (done) {
             rc = launched();
@@ -135,21 +149,31 @@ int detonation_compress(const deto_config* cfg, int64_t n, const void* grad, int
     return rc;
 }
 
-int detonation_decompress_step(const deto_config* cfg, int64_t n, int32_t R, const int32_t* idx,
-                               int64_t idx_replica_stride, const float* val,
-                               int64_t val_replica_stride, void* params, int param_dtype,
-                               float* presign_dbg, void* stream) {
+int detonation_compress(const deto_config* cfg, int64_t n, const void* grad, int grad_dtype,
+                        float* momentum, int32_t* idx_out, float* val_out, float* coeff_dbg,
+                        void* stream) {
+    return detonation_compress_packed(cfg, n, grad, grad_dtype, momentum, idx_out, DETO_IDX_I32,
+                                      val_out, DETO_F32, coeff_dbg, stream);
+}
+
+int detonation_decompress_step_packed(const deto_config* cfg, int64_t n, int32_t R,
+                                      const void* idx, int idx_dtype, int64_t idx_replica_stride,
+                                      const void* val, int val_dtype, int64_t val_replica_stride,
+                                      void* params, int param_dtype, float* presign_dbg,
+                                      void* stream) {
     int rc = validate(cfg);
     if (rc) return rc;
-    if (n < 0 || !valid_dtype(param_dtype) || R < 1 || R > 64) return DETO_ERR_BAD_CONFIG;
+    if (n < 0 || !valid_dtype(param_dtype) || R < 1 || R > 64 || !valid_val_dtype(val_dtype) ||
+        !valid_idx_dtype(idx_dtype))
+        return DETO_ERR_BAD_CONFIG;
     if (n == 0) return DETO_OK;
     if (!val || !params) return DETO_ERR_NULL;
     if (cfg->scheme == DETO_SCHEME_TOPK && !idx) return DETO_ERR_NULL;
-    if (!aligned(params, elem_size(param_dtype)) || !aligned(val, 4) || !aligned(idx, 4) ||
-        !aligned(presign_dbg, 4))
+    if (!aligned(params, elem_size(param_dtype)) || !aligned(val, val_size(val_dtype)) ||
+        !aligned(idx, idx_size(idx_dtype)) || !aligned(presign_dbg, 4))
         return DETO_ERR_ALIGN;
 
-    const KParams p = resolve(cfg, R);
+    const KParams p = resolve(cfg, R, val_dtype, idx_dtype);
     const int64_t C = chunks_of(n, p.s);
     const int64_t entries = C * p.k;
     if (R > 1 && (val_replica_stride < entries || (idx && idx_replica_stride < entries)))
@@ -158,16 +182,21 @@ int detonation_decompress_step(const deto_config* cfg, int64_t n, int32_t R, con
 
     int64_t c0 = 0;
     const int64_t tiles = (n / p.s) / deto::kWave;
+    // the tiled kernels read 16 bytes (or 4 entries) per lane: every replica's base must keep
+    // the alignment of the first
+    const bool strides_ok =
+        R == 1 || ((!idx || (idx_replica_stride * static_cast<int64_t>(idx_size(idx_dtype))) % 16 == 0) &&
+                   (val_replica_stride * static_cast<int64_t>(val_size(val_dtype))) % 16 == 0);
     if (tiles > 0 && tiles <= kMaxTiles && aligned16(idx) && aligned16(val) && aligned16(params) &&
-        aligned16(presign_dbg) &&
-        (R == 1 || ((!idx || idx_replica_stride % 4 == 0) && val_replica_stride % 4 == 0))) {
+        aligned16(presign_dbg) && strides_ok) {
         deto::DecompressLaunch a{p, tiles, idx, idx_replica_stride, val, val_replica_stride,
                                  params, param_dtype == DETO_BF16, presign_dbg, {0, 0, 0, 0}, st};
         stride_pattern(p, a.stride_mask);
         const bool done = idx ? (deto::launch_decompress_idx_s64(a) ||
                                  deto::launch_decompress_idx_s32(a) ||
                                  deto::launch_decompress_idx_s128_k4(a) ||
-                                 deto::launch_decompress_idx_s128_k16(a))
+                                 deto::launch_decompress_idx_s128_k16(a) ||
+                                 deto::launch_decompress_idx_packed(a))
                               : deto::launch_decompress_scheme(a);
         if (done) {
             rc = launched();
@@ -190,6 +219,15 @@ int detonation_decompress_step(const deto_config* cfg, int64_t n, int32_t R, con
     return rc;
 }
 
+int detonation_decompress_step(const deto_config* cfg, int64_t n, int32_t R, const int32_t* idx,
+                               int64_t idx_replica_stride, const float* val,
+                               int64_t val_replica_stride, void* params, int param_dtype,
+                               float* presign_dbg, void* stream) {
+    return detonation_decompress_step_packed(cfg, n, R, idx, DETO_IDX_I32, idx_replica_stride, val,
+                                             DETO_F32, val_replica_stride, params, param_dtype,
+                                             presign_dbg, stream);
+}
+
 int64_t detonation_payload_entries(const deto_config* cfg, int64_t n) {
     if (validate(cfg) != DETO_OK || n < 0) return -1;
     return chunks_of(n, cfg->chunk) * cfg->topk;
@@ -207,6 +245,6 @@ const char* detonation_status_string(int status) {
     }
 }
 
-int detonation_version(void) { return 1000; }
+int detonation_version(void) { return 1001; }
 
 }  // extern "C"

@@ -67,14 +67,43 @@ __device__ __forceinline__ void compact_flags(int s, int lane, const int* flag, 
     __syncthreads();
 }
 
+// Payload access in whatever format the caller chose (runtime switch: these kernels are the
+// general path).
+__device__ __forceinline__ float payload_roundtrip(int val_dtype, float v) {
+    if (val_dtype == 1) return decode16<1>(encode16<1>(v));
+    if (val_dtype == 2) return decode16<2>(encode16<2>(v));
+    return v;
+}
+
+__device__ __forceinline__ void store_payload_value(void* base, int64_t e, int val_dtype, float v) {
+    if (val_dtype == 0) static_cast<float*>(base)[e] = v;
+    else static_cast<uint16_t*>(base)[e] = (val_dtype == 1) ? encode16<1>(v) : encode16<2>(v);
+}
+
+__device__ __forceinline__ float load_payload_value(const void* base, int64_t e, int val_dtype) {
+    if (val_dtype == 0) return static_cast<const float*>(base)[e];
+    const uint16_t b = static_cast<const uint16_t*>(base)[e];
+    return (val_dtype == 1) ? decode16<1>(b) : decode16<2>(b);
+}
+
+__device__ __forceinline__ void store_payload_index(void* base, int64_t e, int idx_u8, int at) {
+    if (idx_u8) static_cast<uint8_t*>(base)[e] = static_cast<uint8_t>(at);
+    else static_cast<int32_t*>(base)[e] = at;
+}
+
+__device__ __forceinline__ int load_payload_index(const void* base, int64_t e, int idx_u8) {
+    return idx_u8 ? static_cast<int>(static_cast<const uint8_t*>(base)[e])
+                  : static_cast<const int32_t*>(base)[e];
+}
+
 // Compress half for chunks [chunk_begin, chunk_end).
 template <bool GRAD_BF16>
 __global__ __launch_bounds__(kWave) void compress_generic(KParams p, int64_t n,
                                                           int64_t chunk_begin, int64_t chunk_end,
                                                           const void* __restrict__ grad,
                                                           float* __restrict__ mom,
-                                                          int32_t* __restrict__ idx_out,
-                                                          float* __restrict__ val_out,
+                                                          void* __restrict__ idx_out,
+                                                          void* __restrict__ val_out,
                                                           float* __restrict__ coeff_dbg) {
     __shared__ float tab[4 * kMaxChunk];
     __shared__ float x[kMaxChunk];
@@ -138,10 +167,14 @@ __global__ __launch_bounds__(kWave) void compress_generic(KParams p, int64_t n,
             scheme_flags(p, c, lane, perm, flag);
         }
         compact_flags(s, lane, flag, cf, sidx, sval);
+        // what travels is the value in the transfer dtype; the residual below removes exactly
+        // what the receivers will decode
         for (int j = lane; j < k; j += kWave) {
-            if (idx_out) idx_out[c * k + j] = sidx[j];
-            val_out[c * k + j] = sval[j];
+            if (idx_out) store_payload_index(idx_out, c * k + j, p.idx_u8, sidx[j]);
+            store_payload_value(val_out, c * k + j, p.val_dtype, sval[j]);
+            sval[j] = payload_roundtrip(p.val_dtype, sval[j]);
         }
+        __syncthreads();
         // m <- m1 - q
         for (int e = lane; e < s; e += kWave) {
             const int64_t i = base + e;
@@ -155,7 +188,7 @@ __global__ __launch_bounds__(kWave) void compress_generic(KParams p, int64_t n,
                     q = fmaf(tab[((2 * e + 1) * r) % (4 * s)], a * sval[j], q);
                 }
             } else {
-                q = flag[e] ? x[e] : 0.0f;
+                q = flag[e] ? payload_roundtrip(p.val_dtype, x[e]) : 0.0f;
             }
             mom[i] = x[e] - q;
         }
@@ -166,8 +199,8 @@ __global__ __launch_bounds__(kWave) void compress_generic(KParams p, int64_t n,
 // Decompress-and-update half for chunks [chunk_begin, chunk_end).
 template <bool PARAM_BF16>
 __global__ __launch_bounds__(kWave) void decompress_generic(
-    KParams p, int64_t n, int64_t chunk_begin, int64_t chunk_end, const int32_t* __restrict__ idx,
-    int64_t idx_stride, const float* __restrict__ val, int64_t val_stride,
+    KParams p, int64_t n, int64_t chunk_begin, int64_t chunk_end, const void* __restrict__ idx,
+    int64_t idx_stride, const void* __restrict__ val, int64_t val_stride,
     void* __restrict__ params, float* __restrict__ presign_dbg) {
     __shared__ float tab[4 * kMaxChunk];
     __shared__ float a[kMaxChunk];
@@ -192,8 +225,11 @@ __global__ __launch_bounds__(kWave) void decompress_generic(
         // scatter-add, one replica after the other so the order of additions is fixed
         for (int r = 0; r < p.R; ++r) {
             for (int j = lane; j < k; j += kWave) {
-                const int at = idx ? idx[r * idx_stride + c * k + j] : sidx[j];
-                if (at >= 0 && at < s) atomicAdd(&a[at], val[r * val_stride + c * k + j]);
+                const int at =
+                    idx ? load_payload_index(idx, r * idx_stride + c * k + j, p.idx_u8) : sidx[j];
+                if (at >= 0 && at < s)
+                    atomicAdd(&a[at],
+                              load_payload_value(val, r * val_stride + c * k + j, p.val_dtype));
             }
             __syncthreads();
         }

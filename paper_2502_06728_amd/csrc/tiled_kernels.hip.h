@@ -217,12 +217,14 @@ __device__ __forceinline__ void regs_to_global(float* dst, const float (&x)[S]) 
 // and store the tile's payload coalesced.  The tile must be free (every lane holds its row
 // in registers).  Every element is written at the running position, which only advances
 // past kept ones, so a dropped element is overwritten by the next kept one.
-template <int S, int K>
+// VAL selects the payload format: 0 = fp32 values + int32 indices; 1 (bf16) / 2 (fp16) =
+// 16-bit values + byte indices (the values in c are then already rounded to that format).
+template <int S, int K, int VAL = 0>
 __device__ __forceinline__ void compact_and_store_payload(const float (&c)[S],
                                                           const ChunkMask<S>& mk, float* tile,
                                                           int lane,
-                                                          int32_t* __restrict__ idx_out,
-                                                          float* __restrict__ val_out,
+                                                          void* __restrict__ idx_out_v,
+                                                          void* __restrict__ val_out_v,
                                                           int64_t pbase) {
     using G = TileGeom<S>;
     constexpr int PR = K + 4;                       // staging row, one spare slot + pad
@@ -239,6 +241,28 @@ __device__ __forceinline__ void compact_and_store_payload(const float (&c)[S],
         });
     }
     wave_lds_sync();
+    if constexpr (VAL != 0) {
+        static_assert(K % 4 == 0, "16-bit payloads are stored four entries at a time");
+        uint16_t* val16 = static_cast<uint16_t*>(val_out_v);
+        uint8_t* idx8 = static_cast<uint8_t*>(idx_out_v);
+#pragma unroll
+        for (int it = 0; it < K / 4; ++it) {
+            const int e = it * 256 + lane * 4;
+            const int r = e / K, col = e % K;
+            const float4 v = *reinterpret_cast<const float4*>(tile + r * PR + col);
+            uint2 packed;
+            packed.x = encode16<VAL>(v.x) | (static_cast<uint32_t>(encode16<VAL>(v.y)) << 16);
+            packed.y = encode16<VAL>(v.z) | (static_cast<uint32_t>(encode16<VAL>(v.w)) << 16);
+            *reinterpret_cast<uint2*>(val16 + pbase + e) = packed;
+            if (idx8)
+                *reinterpret_cast<uint32_t*>(idx8 + pbase + e) =
+                    *reinterpret_cast<const uint32_t*>(ibytes + r * PR + col);
+        }
+        wave_lds_sync();
+        return;
+    }
+    int32_t* idx_out = static_cast<int32_t*>(idx_out_v);
+    float* val_out = static_cast<float*>(val_out_v);
     if constexpr (K % 4 == 0) {
 #pragma unroll
         for (int it = 0; it < K / 4; ++it) {
@@ -305,10 +329,10 @@ __device__ __forceinline__ ChunkMask<S> random_mask(uint64_t seed, uint64_t step
 }
 
 // Compress half (top-k) on full tiles: chunks [0, 64*n_tiles), all complete.
-template <int S, int K, bool GRAD_BF16>
+template <int S, int K, bool GRAD_BF16, int VAL = 0>
 __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void compress_tiled_topk(
     KParams p, int64_t n_tiles, const void* __restrict__ grad, float* __restrict__ mom,
-    int32_t* __restrict__ idx_out, float* __restrict__ val_out, float* __restrict__ coeff_dbg) {
+    void* __restrict__ idx_out, void* __restrict__ val_out, float* __restrict__ coeff_dbg) {
     using G = TileGeom<S>;
     constexpr int H = S / 2;
     __shared__ __attribute__((aligned(16))) float tile[G::kFloats];
@@ -386,7 +410,17 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void compress_ti
         });
     }
 
-    compact_and_store_payload<S, K>(c, mk, tile, lane, idx_out, val_out, t * (kWave * K));
+    if constexpr (VAL != 0) {
+        // 16-bit transfer: the payload carries the rounded coefficient, and the rounding
+        // error of a kept coefficient stays behind in the momentum with the dropped ones
+        static_assert(!kLean, "16-bit payloads are built for chunk sizes up to 64");
+        static_for<0, S>([&](auto i) {
+            const float r = decode16<VAL>(encode16<VAL>(c[i]));
+            u[i] = mk.bit(i) ? (c[i] - r) : c[i];
+            c[i] = r;
+        });
+    }
+    compact_and_store_payload<S, K, VAL>(c, mk, tile, lane, idx_out, val_out, t * (kWave * K));
 
     // ---- m <- m1 - q.  With q = D^T(kept coefficients) and m1 = D^T(all coefficients), the
     // residual is the inverse transform of the dropped ones.
@@ -455,25 +489,58 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void compress_ti
     store_tile_momentum<S>(tile, mom, ebase, lane);
 }
 
-// One replica's payload entries of a tile, as each lane holds them after a coalesced load.
+// One replica's payload entries of a tile, as each lane holds them after a coalesced load:
+// K/4 vectors of four consecutive entries.  VAL = 0: int32 indices + fp32 values;
+// VAL = 1/2: byte indices + bf16/fp16 values, kept packed (3 registers per four entries).
+template <int K, int VAL>
+struct PayloadRegs;
+
 template <int K>
-struct PayloadRegs {
+struct PayloadRegs<K, 0> {
     static constexpr int kVec = (K % 4 == 0) ? K / 4 : 1;
     int4 i[kVec];
     float4 v[kVec];
+    __device__ __forceinline__ void load(int it, const void* ir, const void* vr, int e) {
+        const uint4 iv = ld_u4<DETO_NT_DECOMPRESS_LD>(static_cast<const int32_t*>(ir) + e);
+        i[it] = make_int4(iv.x, iv.y, iv.z, iv.w);
+        v[it] = ld_f4<DETO_NT_DECOMPRESS_LD>(static_cast<const float*>(vr) + e);
+    }
+    template <int C>
+    __device__ __forceinline__ uint32_t idx(int it) const {
+        return static_cast<uint32_t>(C == 0 ? i[it].x : C == 1 ? i[it].y : C == 2 ? i[it].z : i[it].w);
+    }
+    template <int C>
+    __device__ __forceinline__ float val(int it) const {
+        return C == 0 ? v[it].x : C == 1 ? v[it].y : C == 2 ? v[it].z : v[it].w;
+    }
 };
 
-template <int K>
-__device__ __forceinline__ void load_payload(PayloadRegs<K>& r, const int32_t* __restrict__ ir,
-                                             const float* __restrict__ vr, int lane) {
+template <int K, int VAL>
+struct PayloadRegs {
+    static constexpr int kVec = (K % 4 == 0) ? K / 4 : 1;
+    uint32_t i[kVec];
+    uint2 v[kVec];
+    __device__ __forceinline__ void load(int it, const void* ir, const void* vr, int e) {
+        i[it] = ld_u1<DETO_NT_DECOMPRESS_LD>(static_cast<const uint8_t*>(ir) + e);
+        v[it] = ld_u2<DETO_NT_DECOMPRESS_LD>(static_cast<const uint16_t*>(vr) + e);
+    }
+    template <int C>
+    __device__ __forceinline__ uint32_t idx(int it) const {
+        return (i[it] >> (8 * C)) & 0xFFu;
+    }
+    template <int C>
+    __device__ __forceinline__ float val(int it) const {
+        const uint32_t w = (C < 2) ? v[it].x : v[it].y;
+        return decode16<VAL>(static_cast<uint16_t>((C & 1) ? (w >> 16) : (w & 0xFFFFu)));
+    }
+};
+
+template <int K, int VAL>
+__device__ __forceinline__ void load_payload(PayloadRegs<K, VAL>& r, const void* __restrict__ ir,
+                                             const void* __restrict__ vr, int lane) {
     static_assert(K % 4 == 0, "vector path");
 #pragma unroll
-    for (int it = 0; it < K / 4; ++it) {
-        const int e = it * 256 + lane * 4;
-        const uint4 iv = ld_u4<DETO_NT_DECOMPRESS_LD>(ir + e);
-        r.i[it] = make_int4(iv.x, iv.y, iv.z, iv.w);
-        r.v[it] = ld_f4<DETO_NT_DECOMPRESS_LD>(vr + e);
-    }
+    for (int it = 0; it < K / 4; ++it) r.load(it, ir, vr, it * 256 + lane * 4);
 }
 
 // a[chunk][index] += value; an index outside [0,S) lands in the row's padding slot S.
@@ -482,8 +549,9 @@ __device__ __forceinline__ void load_payload(PayloadRegs<K>& r, const int32_t* _
 // emits) all additions of one replica go to distinct accumulators and a plain
 // read-all / add / write-all is exact.  Anything else (duplicates, disorder) takes the
 // atomic path, which adds duplicates like the scatter-add it is.
-template <int S, int K>
-__device__ __forceinline__ void scatter_payload(const PayloadRegs<K>& r, float* tile, int lane) {
+template <int S, int K, int VAL>
+__device__ __forceinline__ void scatter_payload(const PayloadRegs<K, VAL>& r, float* tile,
+                                                int lane) {
     constexpr int kRow = S + 4;
     constexpr int kIt = K / 4;
     constexpr uint32_t kS = static_cast<uint32_t>(S);
@@ -491,7 +559,8 @@ __device__ __forceinline__ void scatter_payload(const PayloadRegs<K>& r, float* 
     const bool first = (lane % kIt) == 0;       // first lane of its chunk (kIt lanes a chunk)
 #pragma unroll
     for (int it = 0; it < kIt; ++it) {
-        const uint32_t x = r.i[it].x, y = r.i[it].y, z = r.i[it].z, w = r.i[it].w;
+        const uint32_t x = r.template idx<0>(it), y = r.template idx<1>(it),
+                       z = r.template idx<2>(it), w = r.template idx<3>(it);
         // previous lane's last index (row_shr:1; kIt divides the 16-lane DPP row)
         const uint32_t pw = static_cast<uint32_t>(
             __builtin_amdgcn_update_dpp(0, static_cast<int>(w), 0x111, 0xf, 0xf, false));
@@ -508,30 +577,30 @@ __device__ __forceinline__ void scatter_payload(const PayloadRegs<K>& r, float* 
             for (int g = 0; g < kGroup; ++g) {
                 const int it = g0 + g;
                 float* arow = tile + ((it * 256 + lane * 4) / K) * kRow;
-                at[g][0] = arow + min(static_cast<uint32_t>(r.i[it].x), kS);
-                at[g][1] = arow + min(static_cast<uint32_t>(r.i[it].y), kS);
-                at[g][2] = arow + min(static_cast<uint32_t>(r.i[it].z), kS);
-                at[g][3] = arow + min(static_cast<uint32_t>(r.i[it].w), kS);
+                at[g][0] = arow + min(r.template idx<0>(it), kS);
+                at[g][1] = arow + min(r.template idx<1>(it), kS);
+                at[g][2] = arow + min(r.template idx<2>(it), kS);
+                at[g][3] = arow + min(r.template idx<3>(it), kS);
 #pragma unroll
                 for (int c = 0; c < 4; ++c) old[g][c] = *at[g][c];
             }
 #pragma unroll
             for (int g = 0; g < kGroup; ++g) {
                 const int it = g0 + g;
-                *at[g][0] = old[g][0] + r.v[it].x;
-                *at[g][1] = old[g][1] + r.v[it].y;
-                *at[g][2] = old[g][2] + r.v[it].z;
-                *at[g][3] = old[g][3] + r.v[it].w;
+                *at[g][0] = old[g][0] + r.template val<0>(it);
+                *at[g][1] = old[g][1] + r.template val<1>(it);
+                *at[g][2] = old[g][2] + r.template val<2>(it);
+                *at[g][3] = old[g][3] + r.template val<3>(it);
             }
         }
     } else {
 #pragma unroll
         for (int it = 0; it < kIt; ++it) {
             float* arow = tile + ((it * 256 + lane * 4) / K) * kRow;
-            atomicAdd(arow + min(static_cast<uint32_t>(r.i[it].x), kS), r.v[it].x);
-            atomicAdd(arow + min(static_cast<uint32_t>(r.i[it].y), kS), r.v[it].y);
-            atomicAdd(arow + min(static_cast<uint32_t>(r.i[it].z), kS), r.v[it].z);
-            atomicAdd(arow + min(static_cast<uint32_t>(r.i[it].w), kS), r.v[it].w);
+            atomicAdd(arow + min(r.template idx<0>(it), kS), r.template val<0>(it));
+            atomicAdd(arow + min(r.template idx<1>(it), kS), r.template val<1>(it));
+            atomicAdd(arow + min(r.template idx<2>(it), kS), r.template val<2>(it));
+            atomicAdd(arow + min(r.template idx<3>(it), kS), r.template val<3>(it));
         }
     }
 }
@@ -633,10 +702,10 @@ __device__ __forceinline__ void finish_chunk(const KParams& p, float (&y)[S], fl
 // caller passes indices).  Up to three replicas' payloads are in flight while one is
 // scattered into LDS; LDS operations of one wavefront complete in order, so the additions
 // into one accumulator happen replica after replica and the result does not depend on timing.
-template <int S, int K, bool PARAM_BF16>
+template <int S, int K, bool PARAM_BF16, int VAL = 0>
 __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_tiled(
-    KParams p, int64_t n_tiles, const int32_t* __restrict__ idx, int64_t idx_stride,
-    const float* __restrict__ val, int64_t val_stride, void* __restrict__ params,
+    KParams p, int64_t n_tiles, const void* __restrict__ idx_v, int64_t idx_stride,
+    const void* __restrict__ val_v, int64_t val_stride, void* __restrict__ params,
     float* __restrict__ presign_dbg) {
     using G = TileGeom<S>;
     __shared__ __attribute__((aligned(16))) float tile[G::kFloats];
@@ -645,6 +714,11 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_
     if (t >= n_tiles) return;
     const int64_t ebase = t * G::kElems;
     const int64_t pbase = t * (kWave * K);
+    // replica r's entries of this tile, in bytes from the array bases
+    constexpr int kIdxBytes = VAL ? 1 : 4, kValBytes = VAL ? 2 : 4;
+    const char* idx = static_cast<const char*>(idx_v) + pbase * kIdxBytes;
+    const char* val = static_cast<const char*>(val_v) + pbase * kValBytes;
+    const int64_t idx_step = idx_stride * kIdxBytes, val_step = val_stride * kValBytes;
 
     // zero the accumulator tile
 #pragma unroll
@@ -653,46 +727,47 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_
     wave_lds_sync();
     if constexpr (K % 4 == 0 && K > 32) {
         // large k: two replicas in flight
-        PayloadRegs<K> b0, b1;
-        auto fetch = [&](PayloadRegs<K>& b, int r) {
-            load_payload<K>(b, idx + r * idx_stride + pbase, val + r * val_stride + pbase, lane);
+        PayloadRegs<K, VAL> b0, b1;
+        auto fetch = [&](PayloadRegs<K, VAL>& b, int r) {
+            load_payload<K, VAL>(b, idx + r * idx_step, val + r * val_step, lane);
         };
         fetch(b0, 0);
         if (p.R > 1) fetch(b1, 1);
         int r = 0;
         while (true) {
-            scatter_payload<S, K>(b0, tile, lane);
+            scatter_payload<S, K, VAL>(b0, tile, lane);
             if (r + 2 < p.R) fetch(b0, r + 2);
             if (++r >= p.R) break;
-            scatter_payload<S, K>(b1, tile, lane);
+            scatter_payload<S, K, VAL>(b1, tile, lane);
             if (r + 2 < p.R) fetch(b1, r + 2);
             if (++r >= p.R) break;
         }
     } else if constexpr (K % 4 == 0) {
-        PayloadRegs<K> b0, b1, b2;
-        auto fetch = [&](PayloadRegs<K>& b, int r) {
-            load_payload<K>(b, idx + r * idx_stride + pbase, val + r * val_stride + pbase, lane);
+        PayloadRegs<K, VAL> b0, b1, b2;
+        auto fetch = [&](PayloadRegs<K, VAL>& b, int r) {
+            load_payload<K, VAL>(b, idx + r * idx_step, val + r * val_step, lane);
         };
         fetch(b0, 0);
         if (p.R > 1) fetch(b1, 1);
         if (p.R > 2) fetch(b2, 2);
         int r = 0;
         while (true) {
-            scatter_payload<S, K>(b0, tile, lane);
+            scatter_payload<S, K, VAL>(b0, tile, lane);
             if (r + 3 < p.R) fetch(b0, r + 3);
             if (++r >= p.R) break;
-            scatter_payload<S, K>(b1, tile, lane);
+            scatter_payload<S, K, VAL>(b1, tile, lane);
             if (r + 3 < p.R) fetch(b1, r + 3);
             if (++r >= p.R) break;
-            scatter_payload<S, K>(b2, tile, lane);
+            scatter_payload<S, K, VAL>(b2, tile, lane);
             if (r + 3 < p.R) fetch(b2, r + 3);
             if (++r >= p.R) break;
         }
     } else {
         // K entries per chunk, lane = chunk: the lane owns its row, plain sequential adds
+        static_assert(VAL == 0 || K % 4 == 0, "16-bit payloads use the vector path");
         for (int r = 0; r < p.R; ++r) {
-            const int32_t* ir = idx + r * idx_stride + pbase + lane * K;
-            const float* vr = val + r * val_stride + pbase + lane * K;
+            const int32_t* ir = reinterpret_cast<const int32_t*>(idx + r * idx_step) + lane * K;
+            const float* vr = reinterpret_cast<const float*>(val + r * val_step) + lane * K;
             float* arow = tile + lane * G::kRow;
 #pragma unroll
             for (int j = 0; j < K; ++j) {

@@ -16,8 +16,8 @@ struct CompressLaunch {
     const void* grad;
     bool grad_bf16;
     float* mom;
-    int32_t* idx;           // may be null for Striding/Random
-    float* val;
+    void* idx;              // may be null for Striding/Random; dtype per p.idx_u8
+    void* val;              // dtype per p.val_dtype
     float* coeff_dbg;
     uint32_t stride_mask[4];  // Striding: kept positions of every chunk (bit i%32 of word i/32)
     hipStream_t stream;
@@ -26,9 +26,9 @@ struct CompressLaunch {
 struct DecompressLaunch {
     KParams p;
     int64_t tiles;
-    const int32_t* idx;     // null: indices regenerated from the scheme
-    int64_t idx_stride;
-    const float* val;
+    const void* idx;        // null: indices regenerated from the scheme
+    int64_t idx_stride;     // replica strides in elements
+    const void* val;
     int64_t val_stride;
     void* params;
     bool param_bf16;
@@ -45,6 +45,8 @@ bool launch_compress_topk_s128_k4(const CompressLaunch& a);
 bool launch_compress_topk_s128_k16(const CompressLaunch& a);
 bool launch_decompress_idx_s128_k4(const DecompressLaunch& a);
 bool launch_decompress_idx_s128_k16(const DecompressLaunch& a);
+bool launch_compress_topk_packed(const CompressLaunch& a);     // byte indices + 16-bit values
+bool launch_decompress_idx_packed(const DecompressLaunch& a);
 bool launch_compress_scheme(const CompressLaunch& a);
 bool launch_decompress_scheme(const DecompressLaunch& a);
 

@@ -7,7 +7,7 @@
 namespace deto {
 
 bool DETO_COMPRESS_FN(const CompressLaunch& a) {
-    if (a.p.s != DETO_S) return false;
+    if (a.p.s != DETO_S || a.p.val_dtype != 0 || a.p.idx_u8) return false;
     const unsigned grid = static_cast<unsigned>(a.tiles);
 #define X(K)                                                                                    \
     if (a.p.k == K) {                                                                           \
@@ -25,7 +25,7 @@ bool DETO_COMPRESS_FN(const CompressLaunch& a) {
 }
 
 bool DETO_DECOMPRESS_FN(const DecompressLaunch& a) {
-    if (a.p.s != DETO_S || !a.idx) return false;
+    if (a.p.s != DETO_S || !a.idx || a.p.val_dtype != 0 || a.p.idx_u8) return false;
     const unsigned grid = static_cast<unsigned>(a.tiles);
 #define X(K)                                                                                    \
     if (a.p.k == K) {                                                                           \

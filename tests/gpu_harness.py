@@ -60,3 +60,41 @@ def gpu_decompress(cfg: oracle.Config, idx, val: np.ndarray, params: np.ndarray,
     binding.detonation_decompress_step(bcfg(cfg), R, i, v, p, y)
     torch.cuda.synchronize()
     return to_host(p), None if y is None else to_host(y)
+
+
+VAL_TORCH = {oracle.F32: torch.float32, oracle.BF16: torch.bfloat16, oracle.F16: torch.float16}
+
+
+def bits16_to_dev(bits: np.ndarray, val_dtype: int):
+    """uint16 bit patterns -> device tensor of the 16-bit transfer dtype."""
+    t = torch.from_numpy(bits.view(np.int16).copy()).to(DEV)
+    return t.view(VAL_TORCH[val_dtype])
+
+
+def gpu_compress_packed(cfg: oracle.Config, grad: np.ndarray, mom: np.ndarray, val_dtype: int,
+                        idx_u8: bool):
+    """Returns (momentum, idx as int32, value bit patterns as uint16, coefficients)."""
+    n = mom.size
+    C = -(-n // cfg.chunk)
+    g, m = to_dev(grad), to_dev(mom)
+    idx = torch.full((C * cfg.topk,), 251 if idx_u8 else -7,
+                     dtype=torch.uint8 if idx_u8 else torch.int32, device=DEV)
+    val = torch.zeros((C * cfg.topk,), dtype=VAL_TORCH[val_dtype], device=DEV)
+    coeff = torch.full((C * cfg.chunk,), float("nan"), dtype=torch.float32, device=DEV)
+    binding.detonation_compress_packed(bcfg(cfg), g, m, idx, val, coeff)
+    torch.cuda.synchronize()
+    vbits = val.view(torch.int16).cpu().numpy().view(np.uint16)
+    return to_host(m), idx.cpu().numpy().astype(np.int32), vbits, to_host(coeff)
+
+
+def gpu_decompress_packed(cfg: oracle.Config, idx: np.ndarray, val_bits: np.ndarray,
+                          params: np.ndarray, val_dtype: int, idx_u8: bool):
+    R = val_bits.shape[0]
+    n = params.size
+    i = torch.from_numpy(np.ascontiguousarray(idx.astype(np.uint8 if idx_u8 else np.int32))).to(DEV)
+    v = bits16_to_dev(np.ascontiguousarray(val_bits), val_dtype)
+    p = to_dev(params)
+    y = torch.full((n,), float("nan"), dtype=torch.float32, device=DEV)
+    binding.detonation_decompress_step_packed(bcfg(cfg), R, i, v, p, y)
+    torch.cuda.synchronize()
+    return to_host(p), to_host(y)

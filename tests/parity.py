@@ -125,3 +125,46 @@ def check_decompress(cfg: oracle.Config, idx, val: np.ndarray, params_in: np.nda
     sign_flips = int((np.sign(presign_gpu) != np.sign(y_o)).sum())
     return {"presign": e_y, "params_max_err": float(err.max()) if n else 0.0,
             "params_bit_exact_frac": exact, "sign_flips_vs_oracle": sign_flips}
+
+
+def check_compress_packed(cfg: oracle.Config, grad, mom_in, mom_gpu, idx_gpu, val_bits_gpu,
+                          coeff_gpu, val_dtype: int, tol: float = TOL_F32) -> dict:
+    """Staged check of the compress half with 16-bit payload values: coefficients, the oracle's
+    selection on the GPU's coefficients, bit-exact encoded values, and the residual that removes
+    what the receivers decode."""
+    s = cfg.chunk
+    m1 = oracle.fold(cfg, grad, mom_in)
+    coeff_o = oracle.transform(cfg, m1)
+    e_coeff = rel_chunk_err(coeff_gpu, coeff_o, s)
+    assert e_coeff <= tol, f"coefficients differ: {e_coeff:.3e}"
+    idx_stage = oracle.select(cfg, coeff_gpu)
+    assert np.array_equal(idx_gpu, idx_stage), "selected indices differ from the oracle's rule"
+    val_stage, m_stage = oracle.extract_q(cfg, m1, coeff_gpu, idx_stage, val_dtype)
+    assert np.array_equal(val_bits_gpu, val_stage), "encoded payload values"
+    e_mom = rel_chunk_err(mom_gpu, m_stage, s, scale=m1)
+    assert e_mom <= tol, f"residual momentum differs: {e_mom:.3e}"
+    return {"coeff": e_coeff, "momentum": e_mom}
+
+
+def check_decompress_packed(cfg: oracle.Config, idx, val_bits, val_dtype, params_in, params_gpu,
+                            presign_gpu, tol: float = TOL_F32) -> dict:
+    s, k = cfg.chunk, cfg.topk
+    n = params_in.size
+    C = -(-n // s)
+    y_o = oracle.presign_q(cfg, n, idx, val_bits, val_dtype)
+    dec = ((val_bits.astype(np.uint32) << 16).view(np.float32) if val_dtype == oracle.BF16
+           else val_bits.view(np.float16).astype(np.float32))
+    vmax = np.abs(dec.astype(np.float64).reshape(-1, C, k)).max(axis=(0, 2))
+    scale = np.maximum(np.repeat(vmax, s)[:n], parity_chunk_max(y_o, s))
+    e_y = rel_chunk_err(presign_gpu, y_o, s, scale=scale)
+    assert e_y <= tol, f"pre-sign update differs: {e_y:.3e}"
+    p_stage = oracle.update(cfg, presign_gpu, params_in)
+    if params_in.dtype == np.uint16:
+        got = (params_gpu.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+        want = (p_stage.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+        ptol = TOL_BF16
+    else:
+        got, want, ptol = params_gpu.astype(np.float64), p_stage.astype(np.float64), tol
+    err = np.abs(got - want)
+    assert (err <= ptol * np.abs(want) + ptol * abs(cfg.lr)).all(), f"parameters differ: {err.max():.3e}"
+    return {"presign": e_y}

@@ -380,3 +380,49 @@ def test_multi_step_trajectory(H, scheme):
     # moves single elements by a coefficient or 2*eta, so compare in the mean
     assert np.abs(th_free - th_gpu).mean() < 1e-3 * 1e-3
     assert np.abs(m_free - m_gpu).mean() < 1e-3 * np.abs(m_free).mean()
+
+
+@pytest.mark.parametrize("val_dtype", [oracle.BF16, oracle.F16])
+@pytest.mark.parametrize("idx_u8", [True, False])
+@pytest.mark.parametrize("s,k,n", [(64, 32, 64 * 3000 + 13), (64, 8, 64 * 2000), (32, 4, 32 * 777 + 5),
+                                   (96, 12, 96 * 300 + 1)])
+def test_packed_payload_formats(H, val_dtype, idx_u8, s, k, n):
+    """16-bit transfer values (Appendix B, communication dtype) and byte indices: the payload is
+    the fp32 payload rounded to the transfer dtype, and the momentum keeps the rounding error."""
+    cfg = Config(chunk=s, topk=k, sign=True, decay=0.999, lr=1e-3)
+    g, m, th = make_inputs(n, seed=s + k, grad_bf16=True, params_bf16=True, outliers=0.01)
+    m_gpu, idx_gpu, vbits_gpu, coeff_gpu = H.gpu_compress_packed(cfg, g, m, val_dtype, idx_u8)
+    parity.check_compress_packed(cfg, g, m, m_gpu, idx_gpu, vbits_gpu, coeff_gpu, val_dtype)
+    R = 3
+    pays = [oracle.compress_q(cfg, *make_inputs(n, seed=900 + r, grad_bf16=True, outliers=0.01)[:2],
+                              val_dtype)[1:] for r in range(R)]
+    idx = np.stack([p[0] for p in pays])
+    vbits = np.stack([p[1] for p in pays])
+    th_gpu, y_gpu = H.gpu_decompress_packed(cfg, idx, vbits, th, val_dtype, idx_u8)
+    parity.check_decompress_packed(cfg, idx, vbits, val_dtype, th, th_gpu, y_gpu)
+
+
+def test_packed_striding_random_values_only(H):
+    # Striding / Random ship values only; with a 16-bit transfer dtype they run on the general kernels
+    import torch
+    from paper_2502_06728_amd import binding
+    n, s, k = 64 * 500 + 3, 64, 16
+    for scheme in (SCHEME_STRIDE, SCHEME_RANDOM):
+        cfg = Config(chunk=s, topk=k, scheme=scheme, seed=9, step=2, sign=False)
+        g, m, th = make_inputs(n, seed=31)
+        m1 = oracle.fold(cfg, g, m)
+        coeff = oracle.transform(cfg, m1)
+        idx_o = oracle.select(cfg, None, -(-n // s))
+        vb_o, m_o = oracle.extract_q(cfg, m1, coeff, idx_o, oracle.F16)
+        gm, gg = H.to_dev(m), H.to_dev(g)
+        val = torch.zeros(idx_o.size, dtype=torch.float16, device=H.DEV)
+        binding.detonation_compress_packed(H.bcfg(cfg), gg, gm, None, val)
+        torch.cuda.synchronize()
+        assert np.array_equal(val.view(torch.int16).cpu().numpy().view(np.uint16), vb_o)
+        assert np.array_equal(H.to_host(gm), m_o)            # raw domain: exact arithmetic
+        p = H.to_dev(th)
+        y = torch.empty(n, dtype=torch.float32, device=H.DEV)
+        binding.detonation_decompress_step_packed(H.bcfg(cfg), 2, None, torch.stack([val, val]), p, y)
+        torch.cuda.synchronize()
+        y_o = oracle.presign_q(cfg, n, np.stack([idx_o, idx_o]), np.stack([vb_o, vb_o]), oracle.F16)
+        assert np.array_equal(H.to_host(y), y_o)
