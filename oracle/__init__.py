@@ -63,6 +63,24 @@ class Config:
         return self.scheme == SCHEME_TOPK or self.dct
 
 
+class _AdamW(ctypes.Structure):
+    _fields_ = [("beta1", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float),
+                ("amsgrad", ctypes.c_int32), ("step", ctypes.c_uint64)]
+
+
+@dataclass
+class AdamW:
+    """Decoupled AdamW hyper-parameters (moments are local, never synchronised)."""
+    beta1: float = 0.9
+    beta2: float = 0.999
+    eps: float = 1e-8
+    amsgrad: bool = False
+    step: int = 1
+
+    def c(self) -> _AdamW:
+        return _AdamW(self.beta1, self.beta2, self.eps, int(self.amsgrad), self.step)
+
+
 _lib = None
 
 
@@ -263,3 +281,17 @@ def decompress_step(cfg: Config, idx, val: np.ndarray, params: np.ndarray,
                                    _p(val), ctypes.c_int64(val.shape[1]), _p(p),
                                    ctypes.c_int(_dtype_of(p)), _p(y)))
     return (p, y) if want_presign else p
+
+
+def adamw_update(cfg: Config, opt: AdamW, y: np.ndarray, params: np.ndarray, exp_avg: np.ndarray,
+                 exp_avg_sq: np.ndarray, max_exp_avg_sq=None):
+    """One Decoupled-AdamW parameter step driven by the averaged update y.  Returns new
+    (params, exp_avg, exp_avg_sq, max_exp_avg_sq); inputs are not modified."""
+    y = _c(y, np.float32)
+    p = np.ascontiguousarray(params).copy()
+    m = _c(exp_avg, np.float32).copy()
+    v = _c(exp_avg_sq, np.float32).copy()
+    vm = None if max_exp_avg_sq is None else _c(max_exp_avg_sq, np.float32).copy()
+    _chk(lib().orc_adamw_update(ctypes.byref(cfg.c()), ctypes.byref(opt.c()), ctypes.c_int64(y.size),
+                                _p(y), _p(p), ctypes.c_int(_dtype_of(p)), _p(m), _p(v), _p(vm)))
+    return p, m, v, vm

@@ -553,6 +553,60 @@ int orc_update(const orc_config *cfg, int64_t n, const float *y, void *params,
     return ORC_OK;
 }
 
+/* ------------------------------------------------- Decoupled AdamW variant */
+
+/* Section "Decoupled AdamW": AdamW whose first and second moments (and, with amsgrad, the
+ * running maximum of the second moment) stay local and are never synchronised; only Q is
+ * shared.  The averaged update Q takes the place of the gradient in the textbook AdamW
+ * step (Loshchilov & Hutter; Kingma & Ba), t counted from 1:
+ *   m <- b1 m + (1-b1) Q,   v <- b2 v + (1-b2) Q^2,   vmax <- max(vmax, v)  (amsgrad)
+ *   theta <- theta (1 - eta lambda) - eta/(1-b1^t) * m / ( sqrt(v or vmax)/sqrt(1-b2^t) + eps )
+ * The moments are stored in fp32 and the stored values are the ones used for theta. */
+typedef struct {
+    float beta1;
+    float beta2;
+    float eps;
+    int32_t amsgrad;
+    uint64_t step;   /* t >= 1 */
+} orc_adamw;
+
+int orc_adamw_update(const orc_config *cfg, const orc_adamw *opt, int64_t n, const float *y,
+                     void *params, int param_dtype, float *exp_avg, float *exp_avg_sq,
+                     float *max_exp_avg_sq)
+{
+    int rc = orc_check(cfg);
+    if (rc) return rc;
+    if (!opt) return ORC_ERR_NULL;
+    if (opt->step < 1) return ORC_ERR_BAD_CONFIG;
+    if (n > 0 && (!y || !params || !exp_avg || !exp_avg_sq)) return ORC_ERR_NULL;
+    if (n > 0 && opt->amsgrad && !max_exp_avg_sq) return ORC_ERR_NULL;
+    const double eta = (double)cfg->lr, lambda = (double)cfg->weight_decay;
+    const double b1 = (double)opt->beta1, b2 = (double)opt->beta2, eps = (double)opt->eps;
+    const double bc1 = 1.0 - pow(b1, (double)opt->step);
+    const double bc2 = 1.0 - pow(b2, (double)opt->step);
+    const int use_sign = (cfg->flags & ORC_FLAG_SIGN) != 0;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        double q = (double)y[i];
+        if (use_sign) q = (q > 0.0) ? 1.0 : ((q < 0.0) ? -1.0 : 0.0);
+        exp_avg[i] = (float)(b1 * (double)exp_avg[i] + (1.0 - b1) * q);
+        exp_avg_sq[i] = (float)(b2 * (double)exp_avg_sq[i] + (1.0 - b2) * q * q);
+        double vhat = (double)exp_avg_sq[i];
+        if (opt->amsgrad) {
+            if (vhat > (double)max_exp_avg_sq[i]) max_exp_avg_sq[i] = exp_avg_sq[i];
+            vhat = (double)max_exp_avg_sq[i];
+        }
+        const double denom = sqrt(vhat) / sqrt(bc2) + eps;
+        const double th = load_elem(params, param_dtype, i);
+        const double nw = th * (1.0 - eta * lambda) - (eta / bc1) * (double)exp_avg[i] / denom;
+        if (param_dtype == ORC_BF16)
+            ((uint16_t *)params)[i] = orc_double_to_bf16(nw);
+        else
+            ((float *)params)[i] = (float)nw;
+    }
+    return ORC_OK;
+}
+
 /* The whole decompress half.  presign_out may be NULL. */
 int orc_decompress_step(const orc_config *cfg, int64_t n, int32_t R, const int32_t *idx,
                         int64_t idx_replica_stride, const float *val,

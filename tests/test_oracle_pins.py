@@ -475,3 +475,55 @@ def test_16bit_payload_residual_removes_what_is_decoded(val_dtype):
     # the rounding error of the transfer stays in the momentum instead of being lost
     rel = 2.0 ** -8 if val_dtype == oracle.BF16 else 2.0 ** -11
     assert np.abs(m_new - m_ref).max() <= 1.01 * rel * np.abs(val_ref).max() * np.sqrt(2 * k / s)
+
+
+# ------------------------------------------------------- Decoupled AdamW ("Decoupled AdamW")
+
+@pytest.mark.parametrize("amsgrad", [False, True])
+@pytest.mark.parametrize("wd", [0.0, 0.1])
+def test_adamw_update_matches_torch_adamw(amsgrad, wd):
+    # library pin: PyTorch's AdamW on the CPU, fed the same "gradients" (the averaged update Q)
+    import torch
+    n, T = 4000, 6
+    rng = np.random.default_rng(5)
+    th0 = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    qs = [(rng.standard_normal(n) * 10 ** rng.uniform(-4, 0)).astype(np.float32) for _ in range(T)]
+    cfg = Config(sign=False, lr=3e-3, weight_decay=wd)
+    p = torch.nn.Parameter(torch.from_numpy(th0.copy()).double())
+    opt = torch.optim.AdamW([p], lr=float(np.float32(3e-3)), betas=(float(np.float32(0.9)),
+                            float(np.float32(0.95))), eps=float(np.float32(1e-8)),
+                            weight_decay=float(np.float32(wd)), amsgrad=amsgrad)
+    th, m, v = th0.copy(), np.zeros(n, np.float32), np.zeros(n, np.float32)
+    vm = np.zeros(n, np.float32) if amsgrad else None
+    for t, q in enumerate(qs, start=1):
+        p.grad = torch.from_numpy(q).double()
+        opt.step()
+        th, m, v, vm = oracle.adamw_update(cfg, oracle.AdamW(0.9, 0.95, 1e-8, amsgrad, t), q, th, m, v, vm)
+        ref = p.detach().numpy()
+        assert np.abs(th - ref).max() < 2e-6 * np.abs(ref).max() + 2e-7 * t
+        st = opt.state[p]
+        assert np.abs(m - st["exp_avg"].numpy()).max() < 1e-6 * np.abs(m).max()
+        assert np.abs(v - st["exp_avg_sq"].numpy()).max() < 1e-6 * np.abs(v).max()
+        if amsgrad:
+            assert np.abs(vm - st["max_exp_avg_sq"].numpy()).max() < 1e-6 * np.abs(vm).max()
+    assert np.abs(th - th0).max() > 1e-3     # it moved
+
+
+def test_adamw_first_step_with_sign_is_a_unit_step():
+    # t = 1, zero moments: m/(1-b1) = Q and sqrt(v/(1-b2)) = |Q|, so theta moves by eta*sign(Q)
+    n = 1000
+    y = rnd(300, n, 1e-3)
+    y[:10] = 0.0
+    th = rnd(301, n, 0.02)
+    cfg = Config(sign=True, lr=1e-3)
+    z = np.zeros(n, np.float32)
+    th1, m, v, _ = oracle.adamw_update(cfg, oracle.AdamW(0.9, 0.999, 1e-12, False, 1), y, th, z, z)
+    want = th.astype(np.float64) - np.float64(np.float32(1e-3)) * np.sign(y)
+    assert np.abs(th1 - want).max() < 4e-9          # one fp32 rounding of theta
+    assert np.array_equal(th1[:10], th[:10]) and not m[:10].any() and not v[:10].any()
+    # bf16 parameters are rounded once, from the exact result
+    thb = synth.to_bf16_bits(th)
+    th1b, _, _, _ = oracle.adamw_update(cfg, oracle.AdamW(0.9, 0.999, 1e-12, False, 1), y, thb, z, z)
+    exact = synth.from_bf16_bits(thb).astype(np.float64) - np.float64(np.float32(1e-3)) * np.sign(y)
+    got = synth.from_bf16_bits(th1b).astype(np.float64)
+    assert (np.abs(got - exact) <= np.abs(exact) * 2.0 ** -8 + 1e-30).all()
