@@ -70,6 +70,8 @@ def main() -> int:
     ap.add_argument("--dct", action="store_true", help="coefficient domain for stride/random")
     ap.add_argument("--payload", default="f32i32", choices=["f32i32", "bf16u8", "f16u8"],
                     help="payload format: value dtype + index width (top-k)")
+    ap.add_argument("--optimizer", default="sgd", choices=["sgd", "adamw"],
+                    help="underlying optimizer of the update: DeMo-SGD or Decoupled AdamW")
     ap.add_argument("--chunk", type=int, default=0, help="override the workload's chunk size")
     ap.add_argument("--topk", type=int, default=0, help="override the workload's k")
     ap.add_argument("--cpu-sample", type=int, default=1 << 28)
@@ -134,6 +136,13 @@ def main() -> int:
         del gr, mr
     torch.cuda.empty_cache()
 
+    adamw = args.optimizer == "adamw"
+    if adamw:
+        assert not packed, "the AdamW update takes fp32 values and int32 indices"
+        exp_avg = torch.zeros(n, dtype=torch.float32, device=dev)
+        exp_avg_sq = torch.zeros(n, dtype=torch.float32, device=dev)
+        opt = binding.AdamW(0.9, 0.95, 1e-8, False, 0)
+
     def step(ev=None):
         cfg.step += 1
         if ev:
@@ -141,7 +150,12 @@ def main() -> int:
         compress(cfg, grad, mom, None if idx is None else idx[0], val[0])
         if ev:
             ev[1].record()
-        decompress(cfg, R, idx, val, params)
+        if adamw:
+            opt.step += 1
+            binding.detonation_decompress_adamw_step(cfg, opt, R, idx, val, params, exp_avg,
+                                                     exp_avg_sq)
+        else:
+            decompress(cfg, R, idx, val, params)
         if ev:
             ev[2].record()
 
@@ -161,6 +175,8 @@ def main() -> int:
     ms_per_step = wall * 1e3 / args.steps
     ab = algorithmic_bytes(n, s, k, R, grad.element_size(), params.element_size(), with_idx,
                            val.element_size(), idx.element_size() if with_idx else 0)
+    if adamw:
+        ab["decompress"] += 16 * n          # exp_avg and exp_avg_sq, fp32, read and written
     gbs_c = ab["compress"] / (t_c * 1e-3) / 1e9
     gbs_d = ab["decompress"] / (t_d * 1e-3) / 1e9
     dom = "compress" if t_c >= t_d else "decompress"
@@ -170,7 +186,7 @@ def main() -> int:
     # measured them for this workload (recorded under profiles/, not re-measured here)
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"traffic_{args.workload}_{args.scheme}.txt")
-    if os.path.exists(tpath) and not packed and not (args.chunk or args.topk or args.dct):
+    if os.path.exists(tpath) and not packed and not adamw and not (args.chunk or args.topk or args.dct):
         for line in open(tpath):
             f = line.split()
             if len(f) == 2 and f[0] == dom:
@@ -182,7 +198,8 @@ def main() -> int:
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "params": n, "chunk": s, "topk": k, "replicas": R,
-                   "scheme": args.scheme, "payload": args.payload, "dct_domain": bool(cfg.scheme == 0 or args.dct),
+                   "scheme": args.scheme, "payload": args.payload,
+                   "optimizer": args.optimizer, "dct_domain": bool(cfg.scheme == 0 or args.dct),
                    "grad_dtype": str(grad.dtype).split(".")[-1],
                    "param_dtype": str(params.dtype).split(".")[-1], "momentum_dtype": "float32",
                    "sign": w.sign, "decay": w.decay, "lr": w.lr},
@@ -199,6 +216,7 @@ def main() -> int:
     }
     if not args.no_cpu:
         del grad, mom, params, idx, val
+        torch.cuda.empty_cache()
         out["cpu_baseline"] = cpu_baseline(w, cfg_kwargs, args.cpu_sample)
     print(json.dumps(out))
     return 0

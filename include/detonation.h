@@ -162,6 +162,40 @@ int detonation_decompress_step_packed(const deto_config* cfg, int64_t n, int32_t
                                       float* presign_dbg,
                                       void* stream);
 
+/* Decoupled AdamW (paper, section "Decoupled AdamW"): AdamW whose first and second moments
+ * (and, with amsgrad, the running maximum of the second moment) are local to the rank and
+ * never synchronised.  The averaged update Q takes the place of the gradient:
+ *   m <- b1 m + (1-b1) Q,  v <- b2 v + (1-b2) Q^2,  vmax <- max(vmax, v)   (amsgrad)
+ *   params <- params (1 - eta lambda) - eta/(1-b1^t) * m / ( sqrt(v or vmax)/sqrt(1-b2^t) + eps ) */
+typedef struct {
+    float beta1;
+    float beta2;
+    float eps;
+    int32_t amsgrad;   /* 0 or 1 */
+    uint64_t step;     /* t, counted from 1 (bias correction) */
+} deto_adamw;
+
+/*
+ * detonation_decompress_step with Decoupled AdamW as the underlying optimizer: Q is computed
+ * exactly as there (scatter R payloads, average, inverse DCT, optional sign) and then drives
+ * the AdamW step above instead of the plain SGD update.
+ *
+ *   exp_avg, exp_avg_sq   device, [n] fp32, updated in place
+ *   max_exp_avg_sq        device, [n] fp32, updated in place; required iff opt->amsgrad
+ *   everything else       as for detonation_decompress_step (fp32 values, int32 indices)
+ *
+ * Errors as there, plus DETO_ERR_NULL for a missing state array and DETO_ERR_BAD_CONFIG for
+ * opt->step == 0 or betas outside [0,1).
+ */
+int detonation_decompress_adamw_step(const deto_config* cfg, const deto_adamw* opt, int64_t n,
+                                     int32_t R,
+                                     const int32_t* idx, int64_t idx_replica_stride,
+                                     const float* val, int64_t val_replica_stride,
+                                     void* params, int param_dtype,
+                                     float* exp_avg, float* exp_avg_sq, float* max_exp_avg_sq,
+                                     float* presign_dbg,
+                                     void* stream);
+
 /* Payload entries per replica, ceil(n/s)*k (the paper's compression rate k/s times the
  * padded shard length); -1 if cfg is invalid. */
 int64_t detonation_payload_entries(const deto_config* cfg, int64_t n);
@@ -169,7 +203,7 @@ int64_t detonation_payload_entries(const deto_config* cfg, int64_t n);
 /* Static, human-readable name of a deto_status. */
 const char* detonation_status_string(int status);
 
-/* ABI version of this header: major*1000 + minor (1001: the *_packed entry points). */
+/* ABI version of this header: major*1000 + minor (1001: the *_packed entry points; 1002: Decoupled AdamW). */
 int detonation_version(void);
 
 #ifdef __cplusplus

@@ -20,7 +20,8 @@ IDX_I32, IDX_U8 = 0, 1
 FLAG_SIGN, FLAG_DCT = 1, 2
 
 EXPORTS = ("detonation_compress", "detonation_decompress_step", "detonation_compress_packed",
-           "detonation_decompress_step_packed", "detonation_payload_entries",
+           "detonation_decompress_step_packed", "detonation_decompress_adamw_step",
+           "detonation_payload_entries",
            "detonation_status_string", "detonation_version")
 
 
@@ -29,6 +30,24 @@ class deto_config(ctypes.Structure):
                 ("flags", ctypes.c_uint32), ("decay", ctypes.c_float), ("lr", ctypes.c_float),
                 ("weight_decay", ctypes.c_float), ("seed", ctypes.c_uint64),
                 ("step", ctypes.c_uint64)]
+
+
+class deto_adamw(ctypes.Structure):
+    _fields_ = [("beta1", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float),
+                ("amsgrad", ctypes.c_int32), ("step", ctypes.c_uint64)]
+
+
+@dataclass
+class AdamW:
+    """Host-side mirror of deto_adamw (Decoupled AdamW: local, never synchronised moments)."""
+    beta1: float = 0.9
+    beta2: float = 0.999
+    eps: float = 1e-8
+    amsgrad: bool = False
+    step: int = 1
+
+    def c(self) -> deto_adamw:
+        return deto_adamw(self.beta1, self.beta2, self.eps, int(self.amsgrad), self.step)
 
 
 @dataclass
@@ -80,6 +99,10 @@ def load() -> ctypes.CDLL:
         lib.detonation_decompress_step_packed.argtypes = [cfgp, i64, i32, vp, ctypes.c_int, i64, vp,
                                                           ctypes.c_int, i64, vp, ctypes.c_int, vp, vp]
         lib.detonation_decompress_step_packed.restype = ctypes.c_int
+        lib.detonation_decompress_adamw_step.argtypes = [cfgp, ctypes.POINTER(deto_adamw), i64, i32,
+                                                         vp, i64, vp, i64, vp, ctypes.c_int, vp,
+                                                         vp, vp, vp, vp]
+        lib.detonation_decompress_adamw_step.restype = ctypes.c_int
         lib.detonation_payload_entries.argtypes = [cfgp, i64]
         lib.detonation_payload_entries.restype = i64
         lib.detonation_status_string.argtypes = [ctypes.c_int]
@@ -198,5 +221,26 @@ def detonation_decompress_step_packed(cfg: Config, R: int, idx, val, params, pre
                                                   _idx_dtype(idx), istr, _ptr(val), _dtype(val), vs,
                                                   _ptr(params), _dtype(params), _ptr(presign_dbg),
                                                   _stream(stream))
+    if rc != 0:
+        raise DetonationError(rc)
+
+
+def detonation_decompress_adamw_step(cfg: Config, opt: AdamW, R: int, idx, val, params, exp_avg,
+                                     exp_avg_sq, max_exp_avg_sq=None, presign_dbg=None,
+                                     stream=None, n: int | None = None,
+                                     idx_replica_stride: int | None = None,
+                                     val_replica_stride: int | None = None) -> None:
+    """Decompress half with Decoupled AdamW as the underlying optimizer; params and the moment
+    tensors are updated in place."""
+    _check(idx, val, params, exp_avg, exp_avg_sq, max_exp_avg_sq, presign_dbg)
+    n = params.numel() if n is None else n
+    entries = payload_entries(cfg, n)
+    vs = entries if val_replica_stride is None else val_replica_stride
+    istr = entries if idx_replica_stride is None else idx_replica_stride
+    rc = load().detonation_decompress_adamw_step(ctypes.byref(cfg.c()), ctypes.byref(opt.c()), n, R,
+                                                 _ptr(idx), istr, _ptr(val), vs, _ptr(params),
+                                                 _dtype(params), _ptr(exp_avg), _ptr(exp_avg_sq),
+                                                 _ptr(max_exp_avg_sq), _ptr(presign_dbg),
+                                                 _stream(stream))
     if rc != 0:
         raise DetonationError(rc)

@@ -28,6 +28,21 @@ struct KParams {
     float inv_R;        // 1/R
     uint64_t seed;
     uint64_t step;
+    // Decoupled AdamW as the underlying optimizer (adam != 0)
+    int adam;
+    int amsgrad;
+    float b1, b2;       // betas
+    float omb1, omb2;   // 1 - beta
+    float eps;
+    float step_size;    // eta / (1 - beta1^t)
+    float inv_sqrt_bc2; // 1 / sqrt(1 - beta2^t)
+};
+
+// AdamW moment arrays (device pointers; vmax only with amsgrad)
+struct AdamPtrs {
+    float* m;
+    float* v;
+    float* vmax;
 };
 
 // ---- 16-byte global accesses with an optional non-temporal hint.  Every tensor on this
@@ -154,6 +169,21 @@ __device__ __forceinline__ float decode16(uint16_t b) {
 __device__ __forceinline__ float sign_or_self(float y, int use_sign) {
     if (!use_sign) return y;
     return (y > 0.0f) ? 1.0f : ((y < 0.0f) ? -1.0f : 0.0f);
+}
+
+// One Decoupled-AdamW step for one element: moments updated in place, returns the new
+// parameter value in fp32 (section "Decoupled AdamW"; q is the averaged update).
+__device__ __forceinline__ float adamw_step(const KParams& p, float theta, float q, float& m,
+                                            float& v, float& vmax) {
+    m = fmaf(p.b1, m, p.omb1 * q);
+    v = fmaf(p.b2, v, p.omb2 * q * q);
+    float vh = v;
+    if (p.amsgrad) {
+        vmax = fmaxf(vmax, v);
+        vh = vmax;
+    }
+    const float denom = fmaf(sqrtf(vh), p.inv_sqrt_bc2, p.eps);
+    return fmaf(-p.step_size, m / denom, theta * p.wd_scale);
 }
 
 // ---- Random scheme generator (paper, "Replication Schemes": indices are reproduced on

@@ -43,7 +43,7 @@ bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 size_t elem_size(int dtype) { return dtype == DETO_BF16 ? 2 : 4; }
 
 KParams resolve(const deto_config* cfg, int R, int val_dtype, int idx_dtype) {
-    KParams p;
+    KParams p = {};
     p.val_dtype = val_dtype;
     p.idx_u8 = idx_dtype == DETO_IDX_U8 ? 1 : 0;
     p.s = cfg->chunk;
@@ -156,24 +156,51 @@ int detonation_compress(const deto_config* cfg, int64_t n, const void* grad, int
                                       val_out, DETO_F32, coeff_dbg, stream);
 }
 
-int detonation_decompress_step_packed(const deto_config* cfg, int64_t n, int32_t R,
-                                      const void* idx, int idx_dtype, int64_t idx_replica_stride,
-                                      const void* val, int val_dtype, int64_t val_replica_stride,
-                                      void* params, int param_dtype, float* presign_dbg,
-                                      void* stream) {
+}  // extern "C"
+
+namespace {
+
+// Both decompress entry points: `opt` is null for the plain SGD update.
+int decompress_impl(const deto_config* cfg, const deto_adamw* opt, int64_t n, int32_t R,
+                    const void* idx, int idx_dtype, int64_t idx_replica_stride, const void* val,
+                    int val_dtype, int64_t val_replica_stride, void* params, int param_dtype,
+                    deto::AdamPtrs adam, float* presign_dbg, void* stream) {
     int rc = validate(cfg);
     if (rc) return rc;
+    if (opt) {
+        if (opt->step < 1 || !(opt->beta1 >= 0.0f && opt->beta1 < 1.0f) ||
+            !(opt->beta2 >= 0.0f && opt->beta2 < 1.0f) || !std::isfinite(opt->eps) ||
+            (opt->amsgrad != 0 && opt->amsgrad != 1))
+            return DETO_ERR_BAD_CONFIG;
+    }
     if (n < 0 || !valid_dtype(param_dtype) || R < 1 || R > 64 || !valid_val_dtype(val_dtype) ||
         !valid_idx_dtype(idx_dtype))
         return DETO_ERR_BAD_CONFIG;
     if (n == 0) return DETO_OK;
     if (!val || !params) return DETO_ERR_NULL;
     if (cfg->scheme == DETO_SCHEME_TOPK && !idx) return DETO_ERR_NULL;
+    if (opt && (!adam.m || !adam.v || (opt->amsgrad && !adam.vmax))) return DETO_ERR_NULL;
     if (!aligned(params, elem_size(param_dtype)) || !aligned(val, val_size(val_dtype)) ||
-        !aligned(idx, idx_size(idx_dtype)) || !aligned(presign_dbg, 4))
+        !aligned(idx, idx_size(idx_dtype)) || !aligned(presign_dbg, 4) || !aligned(adam.m, 4) ||
+        !aligned(adam.v, 4) || !aligned(adam.vmax, 4))
         return DETO_ERR_ALIGN;
 
-    const KParams p = resolve(cfg, R, val_dtype, idx_dtype);
+    KParams p = resolve(cfg, R, val_dtype, idx_dtype);
+    if (opt) {
+        const double bc1 = 1.0 - std::pow(static_cast<double>(opt->beta1),
+                                          static_cast<double>(opt->step));
+        const double bc2 = 1.0 - std::pow(static_cast<double>(opt->beta2),
+                                          static_cast<double>(opt->step));
+        p.adam = 1;
+        p.amsgrad = opt->amsgrad;
+        p.b1 = opt->beta1;
+        p.b2 = opt->beta2;
+        p.omb1 = static_cast<float>(1.0 - static_cast<double>(opt->beta1));
+        p.omb2 = static_cast<float>(1.0 - static_cast<double>(opt->beta2));
+        p.eps = opt->eps;
+        p.step_size = static_cast<float>(static_cast<double>(cfg->lr) / bc1);
+        p.inv_sqrt_bc2 = static_cast<float>(1.0 / std::sqrt(bc2));
+    }
     const int64_t C = chunks_of(n, p.s);
     const int64_t entries = C * p.k;
     if (R > 1 && (val_replica_stride < entries || (idx && idx_replica_stride < entries)))
@@ -188,11 +215,14 @@ int detonation_decompress_step_packed(const deto_config* cfg, int64_t n, int32_t
         R == 1 || ((!idx || (idx_replica_stride * static_cast<int64_t>(idx_size(idx_dtype))) % 16 == 0) &&
                    (val_replica_stride * static_cast<int64_t>(val_size(val_dtype))) % 16 == 0);
     if (tiles > 0 && tiles <= kMaxTiles && aligned16(idx) && aligned16(val) && aligned16(params) &&
-        aligned16(presign_dbg) && strides_ok) {
+        aligned16(presign_dbg) && aligned16(adam.m) && aligned16(adam.v) && aligned16(adam.vmax) &&
+        strides_ok) {
         deto::DecompressLaunch a{p, tiles, idx, idx_replica_stride, val, val_replica_stride,
-                                 params, param_dtype == DETO_BF16, presign_dbg, {0, 0, 0, 0}, st};
+                                 params, param_dtype == DETO_BF16, presign_dbg, {0, 0, 0, 0}, st,
+                                 adam};
         stride_pattern(p, a.stride_mask);
-        const bool done = idx ? (deto::launch_decompress_idx_s64(a) ||
+        const bool done = idx ? (deto::launch_decompress_adamw(a) ||
+                                 deto::launch_decompress_idx_s64(a) ||
                                  deto::launch_decompress_idx_s32(a) ||
                                  deto::launch_decompress_idx_s128_k4(a) ||
                                  deto::launch_decompress_idx_s128_k16(a) ||
@@ -208,15 +238,40 @@ int detonation_decompress_step_packed(const deto_config* cfg, int64_t n, int32_t
         const unsigned grid = grid_for(C - c0);
         if (param_dtype == DETO_BF16)
             deto::decompress_generic<true><<<grid, deto::kWave, 0, st>>>(
-                p, n, c0, C, idx, idx_replica_stride, val, val_replica_stride, params,
+                p, n, c0, C, idx, idx_replica_stride, val, val_replica_stride, params, adam,
                 presign_dbg);
         else
             deto::decompress_generic<false><<<grid, deto::kWave, 0, st>>>(
-                p, n, c0, C, idx, idx_replica_stride, val, val_replica_stride, params,
+                p, n, c0, C, idx, idx_replica_stride, val, val_replica_stride, params, adam,
                 presign_dbg);
         rc = launched();
     }
     return rc;
+}
+
+}  // namespace
+
+extern "C" {
+
+int detonation_decompress_step_packed(const deto_config* cfg, int64_t n, int32_t R,
+                                      const void* idx, int idx_dtype, int64_t idx_replica_stride,
+                                      const void* val, int val_dtype, int64_t val_replica_stride,
+                                      void* params, int param_dtype, float* presign_dbg,
+                                      void* stream) {
+    return decompress_impl(cfg, nullptr, n, R, idx, idx_dtype, idx_replica_stride, val, val_dtype,
+                           val_replica_stride, params, param_dtype,
+                           deto::AdamPtrs{nullptr, nullptr, nullptr}, presign_dbg, stream);
+}
+
+int detonation_decompress_adamw_step(const deto_config* cfg, const deto_adamw* opt, int64_t n,
+                                     int32_t R, const int32_t* idx, int64_t idx_replica_stride,
+                                     const float* val, int64_t val_replica_stride, void* params,
+                                     int param_dtype, float* exp_avg, float* exp_avg_sq,
+                                     float* max_exp_avg_sq, float* presign_dbg, void* stream) {
+    if (!opt) return DETO_ERR_NULL;
+    return decompress_impl(cfg, opt, n, R, idx, DETO_IDX_I32, idx_replica_stride, val, DETO_F32,
+                           val_replica_stride, params, param_dtype,
+                           deto::AdamPtrs{exp_avg, exp_avg_sq, max_exp_avg_sq}, presign_dbg, stream);
 }
 
 int detonation_decompress_step(const deto_config* cfg, int64_t n, int32_t R, const int32_t* idx,
@@ -245,6 +300,6 @@ const char* detonation_status_string(int status) {
     }
 }
 
-int detonation_version(void) { return 1001; }
+int detonation_version(void) { return 1002; }
 
 }  // extern "C"

@@ -201,7 +201,7 @@ template <bool PARAM_BF16>
 __global__ __launch_bounds__(kWave) void decompress_generic(
     KParams p, int64_t n, int64_t chunk_begin, int64_t chunk_end, const void* __restrict__ idx,
     int64_t idx_stride, const void* __restrict__ val, int64_t val_stride,
-    void* __restrict__ params, float* __restrict__ presign_dbg) {
+    void* __restrict__ params, AdamPtrs ad, float* __restrict__ presign_dbg) {
     __shared__ float tab[4 * kMaxChunk];
     __shared__ float a[kMaxChunk];
     __shared__ int flag[kMaxChunk];
@@ -251,13 +251,20 @@ __global__ __launch_bounds__(kWave) void decompress_generic(
             }
             if (presign_dbg) presign_dbg[i] = y;
             const float q = sign_or_self(y, p.use_sign);
-            if (PARAM_BF16) {
-                uint16_t* th = static_cast<uint16_t*>(params);
-                th[i] = f32_to_bf16(fmaf(-p.lr, q, bf16_to_f32(th[i]) * p.wd_scale));
+            const float old = PARAM_BF16 ? bf16_to_f32(static_cast<uint16_t*>(params)[i])
+                                         : static_cast<float*>(params)[i];
+            float nw;
+            if (p.adam) {
+                float m = ad.m[i], v = ad.v[i], vm = p.amsgrad ? ad.vmax[i] : 0.0f;
+                nw = adamw_step(p, old, q, m, v, vm);
+                ad.m[i] = m;
+                ad.v[i] = v;
+                if (p.amsgrad) ad.vmax[i] = vm;
             } else {
-                float* th = static_cast<float*>(params);
-                th[i] = fmaf(-p.lr, q, th[i] * p.wd_scale);
+                nw = fmaf(-p.lr, q, old * p.wd_scale);
             }
+            if (PARAM_BF16) static_cast<uint16_t*>(params)[i] = f32_to_bf16(nw);
+            else static_cast<float*>(params)[i] = nw;
         }
         __syncthreads();
     }

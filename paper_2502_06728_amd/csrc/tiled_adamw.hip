@@ -1,0 +1,33 @@
+// Tiled indexed decompress with Decoupled AdamW as the underlying optimizer (chunk size 64).
+#include "tiled_kernels.hip.h"
+#include "tiled_launch.h"
+
+#ifdef DETO_TILED_ONLY_64_32
+#define DETO_ADAMW_LIST(X) X(64, 32)
+#else
+#define DETO_ADAMW_LIST(X) X(64, 32) X(64, 16) X(64, 8)
+#endif
+
+namespace deto {
+
+bool launch_decompress_adamw(const DecompressLaunch& a) {
+    if (!a.p.adam || !a.idx || a.p.val_dtype != 0 || a.p.idx_u8) return false;
+    const unsigned grid = static_cast<unsigned>(a.tiles);
+#define X(S, K)                                                                                 \
+    if (a.p.s == S && a.p.k == K) {                                                             \
+        if (a.param_bf16)                                                                       \
+            decompress_tiled<S, K, true, 0, true><<<grid, kWave, 0, a.stream>>>(                \
+                a.p, a.tiles, a.idx, a.idx_stride, a.val, a.val_stride, a.params, a.adam,       \
+                a.presign_dbg);                                                                 \
+        else                                                                                    \
+            decompress_tiled<S, K, false, 0, true><<<grid, kWave, 0, a.stream>>>(               \
+                a.p, a.tiles, a.idx, a.idx_stride, a.val, a.val_stride, a.params, a.adam,       \
+                a.presign_dbg);                                                                 \
+        return true;                                                                            \
+    }
+    DETO_ADAMW_LIST(X)
+#undef X
+    return false;
+}
+
+}  // namespace deto

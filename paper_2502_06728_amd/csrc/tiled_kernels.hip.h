@@ -679,6 +679,68 @@ __device__ __forceinline__ void update_params_from_tile(const KParams& p, const 
     }
 }
 
+// Last phase of decompress with Decoupled AdamW: the tile rows hold Q; the moments stream
+// through (read, update, write) together with the parameters.
+template <int S, bool PARAM_BF16>
+__device__ __forceinline__ void update_params_adamw_from_tile(const KParams& p, const float* tile,
+                                                              const ParamRegs<S, PARAM_BF16>& th,
+                                                              void* __restrict__ params,
+                                                              const AdamPtrs& ad, int64_t ebase,
+                                                              int lane) {
+    using G = TileGeom<S>;
+#pragma unroll
+    for (int it = 0; it < S / 8; ++it) {
+        const int pe = it * 512 + lane * 8;
+        const float* src = tile + (pe / S) * G::kRow + (pe % S);
+        const float4 qa = *reinterpret_cast<const float4*>(src);
+        const float4 qb = *reinterpret_cast<const float4*>(src + 4);
+        const float q[8] = {qa.x, qa.y, qa.z, qa.w, qb.x, qb.y, qb.z, qb.w};
+        float m[8], v[8], vm[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, old[8], nw[8];
+        auto load8 = [&](const float* base, float (&x)[8]) {
+            const float4 a = ld_f4<DETO_NT_DECOMPRESS_LD>(base + ebase + pe);
+            const float4 b = ld_f4<DETO_NT_DECOMPRESS_LD>(base + ebase + pe + 4);
+            x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
+            x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+        };
+        auto store8 = [&](float* base, const float (&x)[8]) {
+            st_f4<DETO_NT_DECOMPRESS_ST>(base + ebase + pe, make_float4(x[0], x[1], x[2], x[3]));
+            st_f4<DETO_NT_DECOMPRESS_ST>(base + ebase + pe + 4,
+                                         make_float4(x[4], x[5], x[6], x[7]));
+        };
+        load8(ad.m, m);
+        load8(ad.v, v);
+        if (p.amsgrad) load8(ad.vmax, vm);
+        if constexpr (PARAM_BF16) {
+            const uint4 raw = th.b[it];
+            const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                old[2 * j] = __uint_as_float(w[j] << 16);
+                old[2 * j + 1] = __uint_as_float(w[j] & 0xFFFF0000u);
+            }
+        } else {
+            const float4 a = th.f[2 * it], b = th.f[2 * it + 1];
+            old[0] = a.x; old[1] = a.y; old[2] = a.z; old[3] = a.w;
+            old[4] = b.x; old[5] = b.y; old[6] = b.z; old[7] = b.w;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) nw[j] = adamw_step(p, old[j], q[j], m[j], v[j], vm[j]);
+        store8(ad.m, m);
+        store8(ad.v, v);
+        if (p.amsgrad) store8(ad.vmax, vm);
+        if constexpr (PARAM_BF16) {
+            uint4 out;
+            out.x = f32_to_bf16(nw[0]) | (static_cast<uint32_t>(f32_to_bf16(nw[1])) << 16);
+            out.y = f32_to_bf16(nw[2]) | (static_cast<uint32_t>(f32_to_bf16(nw[3])) << 16);
+            out.z = f32_to_bf16(nw[4]) | (static_cast<uint32_t>(f32_to_bf16(nw[5])) << 16);
+            out.w = f32_to_bf16(nw[6]) | (static_cast<uint32_t>(f32_to_bf16(nw[7])) << 16);
+            st_u4<DETO_NT_DECOMPRESS_ST>(static_cast<uint16_t*>(params) + ebase + pe, out);
+        } else {
+            store8(static_cast<float*>(params), nw);
+        }
+    }
+}
+
 // lane = chunk: scale the accumulated coefficients, inverse transform (if in the transform
 // domain), optional export, sign, back into the lane's LDS row.
 template <int S>
@@ -702,10 +764,10 @@ __device__ __forceinline__ void finish_chunk(const KParams& p, float (&y)[S], fl
 // caller passes indices).  Up to three replicas' payloads are in flight while one is
 // scattered into LDS; LDS operations of one wavefront complete in order, so the additions
 // into one accumulator happen replica after replica and the result does not depend on timing.
-template <int S, int K, bool PARAM_BF16, int VAL = 0>
+template <int S, int K, bool PARAM_BF16, int VAL = 0, bool ADAM = false>
 __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_tiled(
     KParams p, int64_t n_tiles, const void* __restrict__ idx_v, int64_t idx_stride,
-    const void* __restrict__ val_v, int64_t val_stride, void* __restrict__ params,
+    const void* __restrict__ val_v, int64_t val_stride, void* __restrict__ params, AdamPtrs ad,
     float* __restrict__ presign_dbg) {
     using G = TileGeom<S>;
     __shared__ __attribute__((aligned(16))) float tile[G::kFloats];
@@ -785,7 +847,8 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_
     row_to_regs<S>(row, y);
     finish_chunk<S>(p, y, row, presign_dbg, ebase, lane);
     wave_lds_sync();
-    update_params_from_tile<S, PARAM_BF16>(p, tile, th, params, ebase, lane);
+    if constexpr (ADAM) update_params_adamw_from_tile<S, PARAM_BF16>(p, tile, th, params, ad, ebase, lane);
+    else update_params_from_tile<S, PARAM_BF16>(p, tile, th, params, ebase, lane);
 }
 
 // Decompress-and-update half for Striding and Random without transmitted indices: every

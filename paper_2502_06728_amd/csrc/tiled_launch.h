@@ -35,6 +35,7 @@ struct DecompressLaunch {
     float* presign_dbg;
     uint32_t stride_mask[4];
     hipStream_t stream;
+    AdamPtrs adam;          // moment arrays when p.adam
 };
 
 bool launch_compress_topk_s64(const CompressLaunch& a);
@@ -47,6 +48,7 @@ bool launch_decompress_idx_s128_k4(const DecompressLaunch& a);
 bool launch_decompress_idx_s128_k16(const DecompressLaunch& a);
 bool launch_compress_topk_packed(const CompressLaunch& a);     // byte indices + 16-bit values
 bool launch_decompress_idx_packed(const DecompressLaunch& a);
+bool launch_decompress_adamw(const DecompressLaunch& a);       // Decoupled AdamW update
 bool launch_compress_scheme(const CompressLaunch& a);
 bool launch_decompress_scheme(const DecompressLaunch& a);
 

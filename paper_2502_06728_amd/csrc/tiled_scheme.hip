@@ -36,7 +36,7 @@ bool launch_compress_scheme(const CompressLaunch& a) {
 }
 
 bool launch_decompress_scheme(const DecompressLaunch& a) {
-    if (a.idx || a.p.val_dtype != 0) return false;
+    if (a.idx || a.p.val_dtype != 0 || a.p.adam) return false;
     const unsigned grid = static_cast<unsigned>(a.tiles);
 #define X(S, K)                                                                                 \
     if (a.p.s == S && a.p.k == K) {                                                             \

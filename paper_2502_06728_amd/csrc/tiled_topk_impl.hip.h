@@ -25,18 +25,18 @@ bool DETO_COMPRESS_FN(const CompressLaunch& a) {
 }
 
 bool DETO_DECOMPRESS_FN(const DecompressLaunch& a) {
-    if (a.p.s != DETO_S || !a.idx || a.p.val_dtype != 0 || a.p.idx_u8) return false;
+    if (a.p.s != DETO_S || !a.idx || a.p.val_dtype != 0 || a.p.idx_u8 || a.p.adam) return false;
     const unsigned grid = static_cast<unsigned>(a.tiles);
 #define X(K)                                                                                    \
     if (a.p.k == K) {                                                                           \
         if (a.param_bf16)                                                                       \
             decompress_tiled<DETO_S, K, true><<<grid, kWave, 0, a.stream>>>(                    \
                 a.p, a.tiles, a.idx, a.idx_stride, a.val, a.val_stride, a.params,               \
-                a.presign_dbg);                                                                 \
+                AdamPtrs{nullptr, nullptr, nullptr}, a.presign_dbg);                                                                 \
         else                                                                                    \
             decompress_tiled<DETO_S, K, false><<<grid, kWave, 0, a.stream>>>(                   \
                 a.p, a.tiles, a.idx, a.idx_stride, a.val, a.val_stride, a.params,               \
-                a.presign_dbg);                                                                 \
+                AdamPtrs{nullptr, nullptr, nullptr}, a.presign_dbg);                                                                 \
         return true;                                                                            \
     }
     DETO_K_LIST(X)

@@ -33,11 +33,12 @@ bool launch_compress_topk_packed(const CompressLaunch& a) {
 }
 
 bool launch_decompress_idx_packed(const DecompressLaunch& a) {
-    if (a.p.val_dtype == 0 || !a.p.idx_u8 || !a.idx) return false;
+    if (a.p.val_dtype == 0 || !a.p.idx_u8 || !a.idx || a.p.adam) return false;
     const unsigned grid = static_cast<unsigned>(a.tiles);
 #define LAUNCH(S, K, B, V)                                                                      \
     decompress_tiled<S, K, B, V><<<grid, kWave, 0, a.stream>>>(                                 \
-        a.p, a.tiles, a.idx, a.idx_stride, a.val, a.val_stride, a.params, a.presign_dbg)
+        a.p, a.tiles, a.idx, a.idx_stride, a.val, a.val_stride, a.params,                       \
+        AdamPtrs{nullptr, nullptr, nullptr}, a.presign_dbg)
 #define X(S, K)                                                                                 \
     if (a.p.s == S && a.p.k == K) {                                                             \
         if (a.p.val_dtype == 1) {                                                               \

@@ -33,7 +33,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_version_and_status_strings(lib):
-    assert binding.version() == 1001
+    assert binding.version() == 1002
     assert binding.status_string(0) == "ok"
     assert len({binding.status_string(i) for i in range(6)}) == 6
 
@@ -99,3 +99,22 @@ def test_packed_entry_points_validate_formats(lib):
     d = lib.detonation_decompress_step_packed
     assert d(ok, 10, 1, vp(1024), 2, 8, vp(1024), 0, 8, vp(1024), 0, None, None) == 2
     assert d(ok, 0, 1, None, 1, 0, None, 2, 0, None, 0, None, None) == 0
+
+
+def test_adamw_entry_point_validation(lib):
+    vp = ctypes.c_void_p
+    ok = ctypes.byref(binding.Config(chunk=64, topk=8).c())
+    f = lib.detonation_decompress_adamw_step
+    good = ctypes.byref(binding.AdamW(step=1).c())
+
+    def call(opt, m=1024, v=1024, vm=None, n=10):
+        return f(ok, opt, n, 1, vp(1024), 8, vp(1024), 8, vp(1024), 0, vp(m) if m else None,
+                 vp(v) if v else None, vp(vm) if vm else None, None, None)
+    assert call(None) == 1
+    assert call(ctypes.byref(binding.AdamW(step=0).c())) == 2
+    assert call(ctypes.byref(binding.AdamW(beta1=1.0).c())) == 2
+    assert call(good, m=None) == 1
+    assert call(ctypes.byref(binding.AdamW(amsgrad=True).c())) == 1       # needs max_exp_avg_sq
+    assert call(good, m=1026) == 4
+    assert call(good, n=0) == 0
+    assert ctypes.sizeof(binding.deto_adamw) == 24
