@@ -472,3 +472,65 @@ def test_decoupled_adamw_steps(H, amsgrad, s, k, n, params_bf16):
         else:
             got, want, tol = got.astype(np.float64), th_o.astype(np.float64), parity.TOL_F32
         assert (np.abs(got - want) <= tol * np.abs(want) + tol * cfg.lr).all()
+
+
+def test_maximum_replicas_and_chunk(H):
+    # R = 64 (the most the library accepts) and s = k = 256 (the largest chunk, nothing dropped)
+    cfg = Config(chunk=64, topk=4, sign=False)
+    full_step(H, cfg, 64 * 200 + 9, R=64, seed=2)
+    cfg = Config(chunk=256, topk=256, sign=True)
+    full_step(H, cfg, 256 * 40 + 100, R=2, seed=3)
+
+
+def test_step_inside_a_hip_graph(H):
+    """Both calls only enqueue kernels on the caller's stream and allocate nothing, so a whole
+    step can be captured into a HIP graph.  The graph is replayed several times with eager work
+    and synchronisations in between; every replay must equal the eager result bit for bit."""
+    import torch
+    from paper_2502_06728_amd import binding
+    n, s, k, R = 64 * 4096 + 64 * 7 + 3, 64, 32, 3
+    cfg = Config(chunk=s, topk=k, sign=True)
+    g, m0, th0 = make_inputs(n, 17, grad_bf16=True, params_bf16=True)
+    entries = -(-n // s) * k
+    pays = [oracle.compress(cfg, *make_inputs(n, 40 + r, grad_bf16=True)[:2])[1:] for r in range(R)]
+    idx_np = np.stack([q[0] for q in pays])
+    val_np = np.stack([q[1] for q in pays])
+    gd = H.to_dev(g)
+    bc = H.bcfg(cfg)
+
+    def fresh():
+        return (H.to_dev(m0), H.to_dev(th0), H.to_dev(idx_np.copy()), H.to_dev(val_np.copy()))
+
+    # eager reference: compress writes replica 0's slot, decompress consumes all R
+    m_e, th_e, idx_e, val_e = fresh()
+    binding.detonation_compress(bc, gd, m_e, idx_e[0], val_e[0])
+    binding.detonation_decompress_step(bc, R, idx_e, val_e, th_e)
+    torch.cuda.synchronize()
+    want = [H.to_host(t) for t in (m_e, th_e, idx_e, val_e)]
+
+    m_g, th_g, idx_g, val_g = fresh()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):     # warm-up on the capture stream
+        binding.detonation_compress(bc, gd, m_g, idx_g[0], val_g[0])
+        binding.detonation_decompress_step(bc, R, idx_g, val_g, th_g)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        binding.detonation_compress(bc, gd, m_g, idx_g[0], val_g[0])
+        binding.detonation_decompress_step(bc, R, idx_g, val_g, th_g)
+    for replay in range(3):
+        # reset the in-place state with eager copies, do unrelated eager work, then replay
+        m_g.copy_(H.to_dev(m0))
+        th_g.copy_(H.to_dev(th0))
+        idx_g.copy_(H.to_dev(idx_np))
+        val_g.copy_(H.to_dev(val_np))
+        junk = torch.randn(1 << 20, device=H.DEV).sum().item()
+        assert np.isfinite(junk)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [H.to_host(t) for t in (m_g, th_g, idx_g, val_g)]
+        for a, b in zip(got, want):
+            assert np.array_equal(a.view(np.uint8), b.view(np.uint8)), f"replay {replay}"
