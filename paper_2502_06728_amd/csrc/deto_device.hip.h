@@ -166,9 +166,23 @@ __device__ __forceinline__ float decode16(uint16_t b) {
     else return f16_to_f32(b);
 }
 
+// two fp32 -> packed bf16 (lo in bits 0..15), round to nearest even: one v_cvt_pk_bf16_f32
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
+// sign(y) in {-1, 0, +1} without compares: scaling by 2^192 (two exact multiplications by
+// 2^96, enough to lift the smallest fp32 subnormal above 1) and clamping to [-1, 1] maps
+// every non-zero finite y to +-1 and keeps +-0.
+__device__ __forceinline__ float sign3(float y) {
+    return __builtin_amdgcn_fmed3f(y * 0x1p96f * 0x1p96f, -1.0f, 1.0f);
+}
+
 __device__ __forceinline__ float sign_or_self(float y, int use_sign) {
-    if (!use_sign) return y;
-    return (y > 0.0f) ? 1.0f : ((y < 0.0f) ? -1.0f : 0.0f);
+    return use_sign ? sign3(y) : y;
 }
 
 // One Decoupled-AdamW step for one element: moments updated in place, returns the new

@@ -251,8 +251,13 @@ __device__ __forceinline__ void compact_and_store_payload(const float (&c)[S],
             const int r = e / K, col = e % K;
             const float4 v = *reinterpret_cast<const float4*>(tile + r * PR + col);
             uint2 packed;
-            packed.x = encode16<VAL>(v.x) | (static_cast<uint32_t>(encode16<VAL>(v.y)) << 16);
-            packed.y = encode16<VAL>(v.z) | (static_cast<uint32_t>(encode16<VAL>(v.w)) << 16);
+            if constexpr (VAL == 1) {
+                packed.x = pack_bf16x2(v.x, v.y);
+                packed.y = pack_bf16x2(v.z, v.w);
+            } else {
+                packed.x = encode16<VAL>(v.x) | (static_cast<uint32_t>(encode16<VAL>(v.y)) << 16);
+                packed.y = encode16<VAL>(v.z) | (static_cast<uint32_t>(encode16<VAL>(v.w)) << 16);
+            }
             *reinterpret_cast<uint2*>(val16 + pbase + e) = packed;
             if (idx8)
                 *reinterpret_cast<uint32_t*>(idx8 + pbase + e) =
@@ -651,9 +656,7 @@ __device__ __forceinline__ void update_params_from_tile(const KParams& p, const 
             auto upd = [&](uint32_t w, float q0, float q1) -> uint32_t {
                 const float t0 = __uint_as_float(w << 16) * p.wd_scale;
                 const float t1 = __uint_as_float(w & 0xFFFF0000u) * p.wd_scale;
-                const uint32_t b0 = f32_to_bf16(fmaf(-p.lr, q0, t0));
-                const uint32_t b1 = f32_to_bf16(fmaf(-p.lr, q1, t1));
-                return b0 | (b1 << 16);
+                return pack_bf16x2(fmaf(-p.lr, q0, t0), fmaf(-p.lr, q1, t1));
             };
             uint4 out;
             out.x = upd(raw.x, qa.x, qa.y);
@@ -730,10 +733,10 @@ __device__ __forceinline__ void update_params_adamw_from_tile(const KParams& p, 
         if (p.amsgrad) store8(ad.vmax, vm);
         if constexpr (PARAM_BF16) {
             uint4 out;
-            out.x = f32_to_bf16(nw[0]) | (static_cast<uint32_t>(f32_to_bf16(nw[1])) << 16);
-            out.y = f32_to_bf16(nw[2]) | (static_cast<uint32_t>(f32_to_bf16(nw[3])) << 16);
-            out.z = f32_to_bf16(nw[4]) | (static_cast<uint32_t>(f32_to_bf16(nw[5])) << 16);
-            out.w = f32_to_bf16(nw[6]) | (static_cast<uint32_t>(f32_to_bf16(nw[7])) << 16);
+            out.x = pack_bf16x2(nw[0], nw[1]);
+            out.y = pack_bf16x2(nw[2], nw[3]);
+            out.z = pack_bf16x2(nw[4], nw[5]);
+            out.w = pack_bf16x2(nw[6], nw[7]);
             st_u4<DETO_NT_DECOMPRESS_ST>(static_cast<uint16_t*>(params) + ebase + pe, out);
         } else {
             store8(static_cast<float*>(params), nw);

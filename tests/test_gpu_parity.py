@@ -534,3 +534,22 @@ def test_step_inside_a_hip_graph(H):
         got = [H.to_host(t) for t in (m_g, th_g, idx_g, val_g)]
         for a, b in zip(got, want):
             assert np.array_equal(a.view(np.uint8), b.view(np.uint8)), f"replay {replay}"
+
+
+def test_sign_of_subnormal_and_huge_updates(H):
+    # sign() must be exact for every non-zero finite value, including fp32 subnormals and
+    # values near overflow; zero (of either sign) leaves the parameter alone
+    s, k, n = 64, 32, 64 * 130
+    cfg = Config(chunk=s, topk=k, scheme=SCHEME_STRIDE, sign=True, lr=1e-3)   # raw domain: y = val
+    C = n // s
+    special = np.array([1e-45, -1e-45, 1e-40, -3e-39, 1.1754942e-38, 3e38, -3e38, 0.0, -0.0, 1e-30],
+                       dtype=np.float32)
+    val = np.tile(special, C * k // special.size + 1)[:C * k].copy()
+    th = make_inputs(n, 9)[2]
+    th_gpu, y_gpu = H.gpu_decompress(cfg, None, val[None, :], th)
+    parity.check_decompress(cfg, None, val[None, :], th, th_gpu, y_gpu)
+    idx = oracle.select(cfg, None, C).reshape(C, k)
+    flat = (np.arange(C)[:, None] * s + idx).ravel()
+    moved = (th_gpu - th)[flat]
+    want = -np.float32(1e-3) * np.sign(val)
+    assert np.abs(moved - want).max() < 1e-8
