@@ -114,13 +114,13 @@ int detonation_compress_packed(const deto_config* cfg, int64_t n, const void* gr
     const int64_t C = chunks_of(n, p.s);
     hipStream_t st = static_cast<hipStream_t>(stream);
 
-    // full 64-chunk tiles go to a tiled kernel if one exists, whatever is left to the
-    // general one
+    // a tiled kernel if one exists (full 64-chunk tiles plus, in the same launch, the tail
+    // chunks on the general code), else the general kernel for everything
     int64_t c0 = 0;
     const int64_t tiles = (n / p.s) / deto::kWave;
     if (tiles > 0 && tiles <= kMaxTiles && aligned16(grad) && aligned16(momentum) &&
         aligned16(idx_out) && aligned16(val_out) && aligned16(coeff_dbg)) {
-        deto::CompressLaunch a{p, tiles, grad, grad_dtype == DETO_BF16, momentum, idx_out,
+        deto::CompressLaunch a{p, tiles, n, C, grad, grad_dtype == DETO_BF16, momentum, idx_out,
                                val_out, coeff_dbg, {0, 0, 0, 0}, st};
         stride_pattern(p, a.stride_mask);
         const bool done = (p.scheme == DETO_SCHEME_TOPK)
@@ -133,7 +133,7 @@ int detonation_compress_packed(const deto_config* cfg, int64_t n, const void* gr
         if (done) {
             rc = launched();
             if (rc) return rc;
-            c0 = tiles * deto::kWave;
+            c0 = C;   // the tail chunks rode along in the same launch
         }
     }
     if (c0 < C) {
@@ -217,9 +217,9 @@ int decompress_impl(const deto_config* cfg, const deto_adamw* opt, int64_t n, in
     if (tiles > 0 && tiles <= kMaxTiles && aligned16(idx) && aligned16(val) && aligned16(params) &&
         aligned16(presign_dbg) && aligned16(adam.m) && aligned16(adam.v) && aligned16(adam.vmax) &&
         strides_ok) {
-        deto::DecompressLaunch a{p, tiles, idx, idx_replica_stride, val, val_replica_stride,
-                                 params, param_dtype == DETO_BF16, presign_dbg, {0, 0, 0, 0}, st,
-                                 adam};
+        deto::DecompressLaunch a{p, tiles, n, C, idx, idx_replica_stride, val,
+                                 val_replica_stride, params, param_dtype == DETO_BF16, presign_dbg,
+                                 {0, 0, 0, 0}, st, adam};
         stride_pattern(p, a.stride_mask);
         const bool done = idx ? (deto::launch_decompress_adamw(a) ||
                                  deto::launch_decompress_idx_s64(a) ||
@@ -231,7 +231,7 @@ int decompress_impl(const deto_config* cfg, const deto_adamw* opt, int64_t n, in
         if (done) {
             rc = launched();
             if (rc) return rc;
-            c0 = tiles * deto::kWave;
+            c0 = C;   // the tail chunks rode along in the same launch
         }
     }
     if (c0 < C) {

@@ -96,29 +96,47 @@ __device__ __forceinline__ int load_payload_index(const void* base, int64_t e, i
                   : static_cast<const int32_t*>(base)[e];
 }
 
-// Compress half for chunks [chunk_begin, chunk_end).
+// LDS working set of one wavefront of the general compress / decompress code.
+struct GenericCompressSmem {
+    float tab[4 * kMaxChunk];
+    float x[kMaxChunk];
+    float cf[kMaxChunk];
+    float sval[kMaxChunk];
+    int flag[kMaxChunk];
+    int sidx[kMaxChunk];
+    int perm[kMaxChunk];
+};
+
+struct GenericDecompressSmem {
+    float tab[4 * kMaxChunk];
+    float a[kMaxChunk];
+    int flag[kMaxChunk];
+    int sidx[kMaxChunk];
+    int perm[kMaxChunk];
+};
+
+// Compress half for the chunks first, first+stride, ... below chunk_end, one chunk at a time
+// on the calling wavefront.  Also the tail path of the tiled kernels (the chunks that do not
+// fill a tile), which call it from their surplus workgroups.
 template <bool GRAD_BF16>
-__global__ __launch_bounds__(kWave) void compress_generic(KParams p, int64_t n,
-                                                          int64_t chunk_begin, int64_t chunk_end,
-                                                          const void* __restrict__ grad,
-                                                          float* __restrict__ mom,
-                                                          void* __restrict__ idx_out,
-                                                          void* __restrict__ val_out,
-                                                          float* __restrict__ coeff_dbg) {
-    __shared__ float tab[4 * kMaxChunk];
-    __shared__ float x[kMaxChunk];
-    __shared__ float cf[kMaxChunk];
-    __shared__ float sval[kMaxChunk];
-    __shared__ int flag[kMaxChunk];
-    __shared__ int sidx[kMaxChunk];
-    __shared__ int perm[kMaxChunk];
+__device__ __forceinline__ void compress_generic_chunks(
+    const KParams& p, int64_t n, int64_t first, int64_t chunk_end, int64_t stride,
+    GenericCompressSmem& sm, const void* __restrict__ grad, float* __restrict__ mom,
+    void* __restrict__ idx_out, void* __restrict__ val_out, float* __restrict__ coeff_dbg) {
+    float* tab = sm.tab;
+    float* x = sm.x;
+    float* cf = sm.cf;
+    float* sval = sm.sval;
+    int* flag = sm.flag;
+    int* sidx = sm.sidx;
+    int* perm = sm.perm;
 
     const int lane = threadIdx.x;
     const int s = p.s, k = p.k;
     if (p.use_dct) build_cos_table(tab, s, lane);
     __syncthreads();
 
-    for (int64_t c = chunk_begin + blockIdx.x; c < chunk_end; c += gridDim.x) {
+    for (int64_t c = first; c < chunk_end; c += stride) {
         const int64_t base = c * s;
         // m1 = beta*m + g, zero beyond the shard
         for (int e = lane; e < s; e += kWave) {
@@ -196,24 +214,38 @@ __global__ __launch_bounds__(kWave) void compress_generic(KParams p, int64_t n,
     }
 }
 
-// Decompress-and-update half for chunks [chunk_begin, chunk_end).
+template <bool GRAD_BF16>
+__global__ __launch_bounds__(kWave) void compress_generic(KParams p, int64_t n,
+                                                          int64_t chunk_begin, int64_t chunk_end,
+                                                          const void* __restrict__ grad,
+                                                          float* __restrict__ mom,
+                                                          void* __restrict__ idx_out,
+                                                          void* __restrict__ val_out,
+                                                          float* __restrict__ coeff_dbg) {
+    __shared__ GenericCompressSmem sm;
+    compress_generic_chunks<GRAD_BF16>(p, n, chunk_begin + blockIdx.x, chunk_end, gridDim.x, sm,
+                                       grad, mom, idx_out, val_out, coeff_dbg);
+}
+
+// Decompress-and-update half for the chunks first, first+stride, ... below chunk_end.
 template <bool PARAM_BF16>
-__global__ __launch_bounds__(kWave) void decompress_generic(
-    KParams p, int64_t n, int64_t chunk_begin, int64_t chunk_end, const void* __restrict__ idx,
-    int64_t idx_stride, const void* __restrict__ val, int64_t val_stride,
-    void* __restrict__ params, AdamPtrs ad, float* __restrict__ presign_dbg) {
-    __shared__ float tab[4 * kMaxChunk];
-    __shared__ float a[kMaxChunk];
-    __shared__ int flag[kMaxChunk];
-    __shared__ int sidx[kMaxChunk];
-    __shared__ int perm[kMaxChunk];
+__device__ __forceinline__ void decompress_generic_chunks(
+    const KParams& p, int64_t n, int64_t first, int64_t chunk_end, int64_t stride,
+    GenericDecompressSmem& sm, const void* __restrict__ idx, int64_t idx_stride,
+    const void* __restrict__ val, int64_t val_stride, void* __restrict__ params,
+    const AdamPtrs& ad, float* __restrict__ presign_dbg) {
+    float* tab = sm.tab;
+    float* a = sm.a;
+    int* flag = sm.flag;
+    int* sidx = sm.sidx;
+    int* perm = sm.perm;
 
     const int lane = threadIdx.x;
     const int s = p.s, k = p.k;
     if (p.use_dct) build_cos_table(tab, s, lane);
     __syncthreads();
 
-    for (int64_t c = chunk_begin + blockIdx.x; c < chunk_end; c += gridDim.x) {
+    for (int64_t c = first; c < chunk_end; c += stride) {
         const int64_t base = c * s;
         for (int e = lane; e < s; e += kWave) a[e] = 0.0f;
         if (!idx) {
@@ -268,6 +300,17 @@ __global__ __launch_bounds__(kWave) void decompress_generic(
         }
         __syncthreads();
     }
+}
+
+template <bool PARAM_BF16>
+__global__ __launch_bounds__(kWave) void decompress_generic(
+    KParams p, int64_t n, int64_t chunk_begin, int64_t chunk_end, const void* __restrict__ idx,
+    int64_t idx_stride, const void* __restrict__ val, int64_t val_stride,
+    void* __restrict__ params, AdamPtrs ad, float* __restrict__ presign_dbg) {
+    __shared__ GenericDecompressSmem sm;
+    decompress_generic_chunks<PARAM_BF16>(p, n, chunk_begin + blockIdx.x, chunk_end, gridDim.x, sm,
+                                          idx, idx_stride, val, val_stride, params, ad,
+                                          presign_dbg);
 }
 
 }  // namespace deto

@@ -12,16 +12,17 @@ namespace deto {
 
 bool launch_decompress_adamw(const DecompressLaunch& a) {
     if (!a.p.adam || !a.idx || a.p.val_dtype != 0 || a.p.idx_u8) return false;
-    const unsigned grid = static_cast<unsigned>(a.tiles);
+    const unsigned grid = tiled_grid(a.tiles, a.n_chunks);
+    const TailRange tail{a.n, a.n_chunks};
 #define X(S, K)                                                                                 \
     if (a.p.s == S && a.p.k == K) {                                                             \
         if (a.param_bf16)                                                                       \
             decompress_tiled<S, K, true, 0, true><<<grid, kWave, 0, a.stream>>>(                \
-                a.p, a.tiles, a.idx, a.idx_stride, a.val, a.val_stride, a.params, a.adam,       \
+                a.p, a.tiles, tail, a.idx, a.idx_stride, a.val, a.val_stride, a.params, a.adam,       \
                 a.presign_dbg);                                                                 \
         else                                                                                    \
             decompress_tiled<S, K, false, 0, true><<<grid, kWave, 0, a.stream>>>(               \
-                a.p, a.tiles, a.idx, a.idx_stride, a.val, a.val_stride, a.params, a.adam,       \
+                a.p, a.tiles, tail, a.idx, a.idx_stride, a.val, a.val_stride, a.params, a.adam,       \
                 a.presign_dbg);                                                                 \
         return true;                                                                            \
     }

@@ -17,10 +17,15 @@
 // threshold does the wavefront take the exact path that keeps the lowest indices.
 // Striding keeps a fixed bit pattern, Random builds each chunk's pattern with a
 // Fisher-Yates shuffle private to the chunk's lane.
+//
+// Tail.  The chunks that do not fill a last tile (and a ragged last chunk) are handled in the
+// same launch: the grid has one surplus workgroup per tail chunk, and those run the general
+// per-chunk code (generic_kernels.hip.h) side by side with the tiles.
 #pragma once
 
 #include "deto_device.hip.h"
 #include "fast_dct.hip.h"
+#include "generic_kernels.hip.h"
 
 namespace deto {
 
@@ -112,6 +117,19 @@ struct TileGeom {
     static constexpr int kPermStride = S + 4;    // bytes per lane of Fisher-Yates scratch
     // a chunk lives in S VGPRs of its lane: 2 wavefronts per SIMD up to S = 64, 1 beyond
     static constexpr int kWavesPerSimd = S <= 64 ? 2 : 1;
+    // LDS of a workgroup: the tile, or the general code's working set in a tail workgroup
+    static constexpr size_t kTileBytes = sizeof(float) * kFloats;
+    static constexpr size_t kCompressBytes =
+        kTileBytes > sizeof(GenericCompressSmem) ? kTileBytes : sizeof(GenericCompressSmem);
+    static constexpr size_t kDecompressBytes =
+        kTileBytes > sizeof(GenericDecompressSmem) ? kTileBytes : sizeof(GenericDecompressSmem);
+};
+
+// Where a launch's tail lives: tiles [0, n_tiles) are full; chunks [64*n_tiles, n_chunks) go
+// one per surplus workgroup to the general code.
+struct TailRange {
+    int64_t n;          // shard length
+    int64_t n_chunks;   // ceil(n / s)
 };
 
 // A chunk's kept positions as a bit pattern: bit i%32 of word i/32 = element i is kept.
@@ -336,15 +354,23 @@ __device__ __forceinline__ ChunkMask<S> random_mask(uint64_t seed, uint64_t step
 // Compress half (top-k) on full tiles: chunks [0, 64*n_tiles), all complete.
 template <int S, int K, bool GRAD_BF16, int VAL = 0>
 __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void compress_tiled_topk(
-    KParams p, int64_t n_tiles, const void* __restrict__ grad, float* __restrict__ mom,
-    void* __restrict__ idx_out, void* __restrict__ val_out, float* __restrict__ coeff_dbg) {
+    KParams p, int64_t n_tiles, TailRange tail, const void* __restrict__ grad,
+    float* __restrict__ mom, void* __restrict__ idx_out, void* __restrict__ val_out,
+    float* __restrict__ coeff_dbg) {
     using G = TileGeom<S>;
     constexpr int H = S / 2;
-    __shared__ __attribute__((aligned(16))) float tile[G::kFloats];
+    __shared__ __attribute__((aligned(16))) char smem[G::kCompressBytes];
+    float* tile = reinterpret_cast<float*>(smem);
     const int lane = threadIdx.x;
-    // one tile per workgroup: the host launches exactly n_tiles workgroups
+    // one tile per workgroup, then one tail chunk per surplus workgroup
     const int64_t t = blockIdx.x;
-    if (t >= n_tiles) return;
+    if (t >= n_tiles) {
+        compress_generic_chunks<GRAD_BF16>(p, tail.n, n_tiles * kWave + (t - n_tiles),
+                                           tail.n_chunks, gridDim.x - n_tiles,
+                                           *reinterpret_cast<GenericCompressSmem*>(smem), grad, mom,
+                                           idx_out, val_out, coeff_dbg);
+        return;
+    }
     const int64_t ebase = t * G::kElems;
 
     fold_tile_to_lds<S, GRAD_BF16>(p, grad, mom, ebase, tile, lane);
@@ -450,14 +476,21 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void compress_ti
 // not depend on the data: `stride_mask` for Striding, a per-chunk shuffle for Random.
 template <int S, int K, bool GRAD_BF16>
 __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void compress_tiled_scheme(
-    KParams p, MaskWords stride_mask, int64_t n_tiles, const void* __restrict__ grad,
-    float* __restrict__ mom, int32_t* __restrict__ idx_out, float* __restrict__ val_out,
-    float* __restrict__ coeff_dbg) {
+    KParams p, MaskWords stride_mask, int64_t n_tiles, TailRange tail,
+    const void* __restrict__ grad, float* __restrict__ mom, int32_t* __restrict__ idx_out,
+    float* __restrict__ val_out, float* __restrict__ coeff_dbg) {
     using G = TileGeom<S>;
-    __shared__ __attribute__((aligned(16))) float tile[G::kFloats];
+    __shared__ __attribute__((aligned(16))) char smem[G::kCompressBytes];
+    float* tile = reinterpret_cast<float*>(smem);
     const int lane = threadIdx.x;
     const int64_t t = blockIdx.x;
-    if (t >= n_tiles) return;
+    if (t >= n_tiles) {
+        compress_generic_chunks<GRAD_BF16>(p, tail.n, n_tiles * kWave + (t - n_tiles),
+                                           tail.n_chunks, gridDim.x - n_tiles,
+                                           *reinterpret_cast<GenericCompressSmem*>(smem), grad, mom,
+                                           idx_out, val_out, coeff_dbg);
+        return;
+    }
     const int64_t ebase = t * G::kElems;
 
     fold_tile_to_lds<S, GRAD_BF16>(p, grad, mom, ebase, tile, lane);
@@ -769,14 +802,22 @@ __device__ __forceinline__ void finish_chunk(const KParams& p, float (&y)[S], fl
 // into one accumulator happen replica after replica and the result does not depend on timing.
 template <int S, int K, bool PARAM_BF16, int VAL = 0, bool ADAM = false>
 __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_tiled(
-    KParams p, int64_t n_tiles, const void* __restrict__ idx_v, int64_t idx_stride,
-    const void* __restrict__ val_v, int64_t val_stride, void* __restrict__ params, AdamPtrs ad,
-    float* __restrict__ presign_dbg) {
+    KParams p, int64_t n_tiles, TailRange tail, const void* __restrict__ idx_v,
+    int64_t idx_stride, const void* __restrict__ val_v, int64_t val_stride,
+    void* __restrict__ params, AdamPtrs ad, float* __restrict__ presign_dbg) {
     using G = TileGeom<S>;
-    __shared__ __attribute__((aligned(16))) float tile[G::kFloats];
+    __shared__ __attribute__((aligned(16))) char smem[G::kDecompressBytes];
+    float* tile = reinterpret_cast<float*>(smem);
     const int lane = threadIdx.x;
     const int64_t t = blockIdx.x;
-    if (t >= n_tiles) return;
+    if (t >= n_tiles) {
+        decompress_generic_chunks<PARAM_BF16>(p, tail.n, n_tiles * kWave + (t - n_tiles),
+                                              tail.n_chunks, gridDim.x - n_tiles,
+                                              *reinterpret_cast<GenericDecompressSmem*>(smem),
+                                              idx_v, idx_stride, val_v, val_stride, params, ad,
+                                              presign_dbg);
+        return;
+    }
     const int64_t ebase = t * G::kElems;
     const int64_t pbase = t * (kWave * K);
     // replica r's entries of this tile, in bytes from the array bases
@@ -860,13 +901,22 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_
 // pattern.
 template <int S, int K, bool PARAM_BF16>
 __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_tiled_scheme(
-    KParams p, MaskWords stride_mask, int64_t n_tiles, const float* __restrict__ val,
-    int64_t val_stride, void* __restrict__ params, float* __restrict__ presign_dbg) {
+    KParams p, MaskWords stride_mask, int64_t n_tiles, TailRange tail,
+    const float* __restrict__ val, int64_t val_stride, void* __restrict__ params,
+    float* __restrict__ presign_dbg) {
     using G = TileGeom<S>;
-    __shared__ __attribute__((aligned(16))) float tile[G::kFloats];
+    __shared__ __attribute__((aligned(16))) char smem[G::kDecompressBytes];
+    float* tile = reinterpret_cast<float*>(smem);
     const int lane = threadIdx.x;
     const int64_t t = blockIdx.x;
-    if (t >= n_tiles) return;
+    if (t >= n_tiles) {
+        decompress_generic_chunks<PARAM_BF16>(p, tail.n, n_tiles * kWave + (t - n_tiles),
+                                              tail.n_chunks, gridDim.x - n_tiles,
+                                              *reinterpret_cast<GenericDecompressSmem*>(smem),
+                                              nullptr, 0, val, val_stride, params,
+                                              AdamPtrs{nullptr, nullptr, nullptr}, presign_dbg);
+        return;
+    }
     const int64_t ebase = t * G::kElems;
     const int64_t pbase = t * (kWave * K);
     constexpr int PR = K + 4;

@@ -13,6 +13,8 @@ namespace deto {
 struct CompressLaunch {
     KParams p;
     int64_t tiles;          // full 64-chunk tiles, one workgroup each
+    int64_t n;              // shard length
+    int64_t n_chunks;       // ceil(n / s): the chunks past the last full tile ride along
     const void* grad;
     bool grad_bf16;
     float* mom;
@@ -26,6 +28,8 @@ struct CompressLaunch {
 struct DecompressLaunch {
     KParams p;
     int64_t tiles;
+    int64_t n;
+    int64_t n_chunks;
     const void* idx;        // null: indices regenerated from the scheme
     int64_t idx_stride;     // replica strides in elements
     const void* val;
@@ -37,6 +41,11 @@ struct DecompressLaunch {
     hipStream_t stream;
     AdamPtrs adam;          // moment arrays when p.adam
 };
+
+// grid of a launch: one workgroup per tile plus one per tail chunk
+inline unsigned tiled_grid(int64_t tiles, int64_t n_chunks) {
+    return static_cast<unsigned>(tiles + (n_chunks - tiles * kWave));
+}
 
 bool launch_compress_topk_s64(const CompressLaunch& a);
 bool launch_compress_topk_s32(const CompressLaunch& a);

@@ -17,16 +17,17 @@ MaskWords words(const uint32_t (&w)[4]) { return MaskWords{{w[0], w[1], w[2], w[
 
 bool launch_compress_scheme(const CompressLaunch& a) {
     if (a.p.val_dtype != 0 || a.p.idx_u8) return false;   // fp32 values, int32 indices only
-    const unsigned grid = static_cast<unsigned>(a.tiles);
+    const unsigned grid = tiled_grid(a.tiles, a.n_chunks);
+    const TailRange tail{a.n, a.n_chunks};
 #define X(S, K)                                                                                 \
     if (a.p.s == S && a.p.k == K) {                                                             \
         if (a.grad_bf16)                                                                        \
             compress_tiled_scheme<S, K, true><<<grid, kWave, 0, a.stream>>>(                    \
-                a.p, words(a.stride_mask), a.tiles, a.grad, a.mom, static_cast<int32_t*>(a.idx),        \
+                a.p, words(a.stride_mask), a.tiles, tail, a.grad, a.mom, static_cast<int32_t*>(a.idx),        \
                 static_cast<float*>(a.val), a.coeff_dbg);         \
         else                                                                                    \
             compress_tiled_scheme<S, K, false><<<grid, kWave, 0, a.stream>>>(                   \
-                a.p, words(a.stride_mask), a.tiles, a.grad, a.mom, static_cast<int32_t*>(a.idx),        \
+                a.p, words(a.stride_mask), a.tiles, tail, a.grad, a.mom, static_cast<int32_t*>(a.idx),        \
                 static_cast<float*>(a.val), a.coeff_dbg);         \
         return true;                                                                            \
     }
@@ -37,16 +38,17 @@ bool launch_compress_scheme(const CompressLaunch& a) {
 
 bool launch_decompress_scheme(const DecompressLaunch& a) {
     if (a.idx || a.p.val_dtype != 0 || a.p.adam) return false;
-    const unsigned grid = static_cast<unsigned>(a.tiles);
+    const unsigned grid = tiled_grid(a.tiles, a.n_chunks);
+    const TailRange tail{a.n, a.n_chunks};
 #define X(S, K)                                                                                 \
     if (a.p.s == S && a.p.k == K) {                                                             \
         if (a.param_bf16)                                                                       \
             decompress_tiled_scheme<S, K, true><<<grid, kWave, 0, a.stream>>>(                  \
-                a.p, words(a.stride_mask), a.tiles, static_cast<const float*>(a.val), a.val_stride,     \
+                a.p, words(a.stride_mask), a.tiles, tail, static_cast<const float*>(a.val), a.val_stride,     \
                 a.params, a.presign_dbg);     \
         else                                                                                    \
             decompress_tiled_scheme<S, K, false><<<grid, kWave, 0, a.stream>>>(                 \
-                a.p, words(a.stride_mask), a.tiles, static_cast<const float*>(a.val), a.val_stride,     \
+                a.p, words(a.stride_mask), a.tiles, tail, static_cast<const float*>(a.val), a.val_stride,     \
                 a.params, a.presign_dbg);     \
         return true;                                                                            \
     }

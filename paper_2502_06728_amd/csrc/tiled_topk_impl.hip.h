@@ -8,15 +8,16 @@ namespace deto {
 
 bool DETO_COMPRESS_FN(const CompressLaunch& a) {
     if (a.p.s != DETO_S || a.p.val_dtype != 0 || a.p.idx_u8) return false;
-    const unsigned grid = static_cast<unsigned>(a.tiles);
+    const unsigned grid = tiled_grid(a.tiles, a.n_chunks);
+    const TailRange tail{a.n, a.n_chunks};
 #define X(K)                                                                                    \
     if (a.p.k == K) {                                                                           \
         if (a.grad_bf16)                                                                        \
             compress_tiled_topk<DETO_S, K, true><<<grid, kWave, 0, a.stream>>>(                 \
-                a.p, a.tiles, a.grad, a.mom, a.idx, a.val, a.coeff_dbg);                        \
+                a.p, a.tiles, tail, a.grad, a.mom, a.idx, a.val, a.coeff_dbg);                        \
         else                                                                                    \
             compress_tiled_topk<DETO_S, K, false><<<grid, kWave, 0, a.stream>>>(                \
-                a.p, a.tiles, a.grad, a.mom, a.idx, a.val, a.coeff_dbg);                        \
+                a.p, a.tiles, tail, a.grad, a.mom, a.idx, a.val, a.coeff_dbg);                        \
         return true;                                                                            \
     }
     DETO_K_LIST(X)
@@ -26,16 +27,17 @@ bool DETO_COMPRESS_FN(const CompressLaunch& a) {
 
 bool DETO_DECOMPRESS_FN(const DecompressLaunch& a) {
     if (a.p.s != DETO_S || !a.idx || a.p.val_dtype != 0 || a.p.idx_u8 || a.p.adam) return false;
-    const unsigned grid = static_cast<unsigned>(a.tiles);
+    const unsigned grid = tiled_grid(a.tiles, a.n_chunks);
+    const TailRange tail{a.n, a.n_chunks};
 #define X(K)                                                                                    \
     if (a.p.k == K) {                                                                           \
         if (a.param_bf16)                                                                       \
             decompress_tiled<DETO_S, K, true><<<grid, kWave, 0, a.stream>>>(                    \
-                a.p, a.tiles, a.idx, a.idx_stride, a.val, a.val_stride, a.params,               \
+                a.p, a.tiles, tail, a.idx, a.idx_stride, a.val, a.val_stride, a.params,               \
                 AdamPtrs{nullptr, nullptr, nullptr}, a.presign_dbg);                                                                 \
         else                                                                                    \
             decompress_tiled<DETO_S, K, false><<<grid, kWave, 0, a.stream>>>(                   \
-                a.p, a.tiles, a.idx, a.idx_stride, a.val, a.val_stride, a.params,               \
+                a.p, a.tiles, tail, a.idx, a.idx_stride, a.val, a.val_stride, a.params,               \
                 AdamPtrs{nullptr, nullptr, nullptr}, a.presign_dbg);                                                                 \
         return true;                                                                            \
     }

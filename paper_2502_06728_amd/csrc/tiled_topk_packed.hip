@@ -13,9 +13,10 @@ namespace deto {
 
 bool launch_compress_topk_packed(const CompressLaunch& a) {
     if (a.p.val_dtype == 0 || !a.p.idx_u8 || a.p.scheme != 0) return false;
-    const unsigned grid = static_cast<unsigned>(a.tiles);
+    const unsigned grid = tiled_grid(a.tiles, a.n_chunks);
+    const TailRange tail{a.n, a.n_chunks};
 #define LAUNCH(S, K, G, V)                                                                      \
-    compress_tiled_topk<S, K, G, V><<<grid, kWave, 0, a.stream>>>(a.p, a.tiles, a.grad, a.mom,   \
+    compress_tiled_topk<S, K, G, V><<<grid, kWave, 0, a.stream>>>(a.p, a.tiles, tail, a.grad, a.mom,   \
                                                                   a.idx, a.val, a.coeff_dbg)
 #define X(S, K)                                                                                 \
     if (a.p.s == S && a.p.k == K) {                                                             \
@@ -34,10 +35,11 @@ bool launch_compress_topk_packed(const CompressLaunch& a) {
 
 bool launch_decompress_idx_packed(const DecompressLaunch& a) {
     if (a.p.val_dtype == 0 || !a.p.idx_u8 || !a.idx || a.p.adam) return false;
-    const unsigned grid = static_cast<unsigned>(a.tiles);
+    const unsigned grid = tiled_grid(a.tiles, a.n_chunks);
+    const TailRange tail{a.n, a.n_chunks};
 #define LAUNCH(S, K, B, V)                                                                      \
     decompress_tiled<S, K, B, V><<<grid, kWave, 0, a.stream>>>(                                 \
-        a.p, a.tiles, a.idx, a.idx_stride, a.val, a.val_stride, a.params,                       \
+        a.p, a.tiles, tail, a.idx, a.idx_stride, a.val, a.val_stride, a.params,                       \
         AdamPtrs{nullptr, nullptr, nullptr}, a.presign_dbg)
 #define X(S, K)                                                                                 \
     if (a.p.s == S && a.p.k == K) {                                                             \
