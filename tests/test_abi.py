@@ -118,3 +118,16 @@ def test_adamw_entry_point_validation(lib):
     assert call(good, m=1026) == 4
     assert call(good, n=0) == 0
     assert ctypes.sizeof(binding.deto_adamw) == 24
+
+
+def test_header_is_plain_c(tmp_path):
+    # the boundary is a C ABI: the header must compile as C99 with no C++ or HIP types
+    import subprocess
+    src = tmp_path / "use.c"
+    src.write_text('#include "detonation.h"\n'
+                   'int use(void) { deto_config c = {64, 8, DETO_SCHEME_TOPK, DETO_FLAG_SIGN, 0.9f, '
+                   '1e-3f, 0.0f, 0u, 0u}; deto_adamw a = {0.9f, 0.999f, 1e-8f, 0, 1u};\n'
+                   '  (void)a; return (int)detonation_payload_entries(&c, 128) + '
+                   'detonation_compress(&c, 0, 0, DETO_F32, 0, 0, 0, 0, 0); }\n')
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
+                    "-I", os.path.join(ROOT, "include"), str(src)], check=True)
