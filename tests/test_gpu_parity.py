@@ -553,3 +553,31 @@ def test_sign_of_subnormal_and_huge_updates(H):
     moved = (th_gpu - th)[flat]
     want = -np.float32(1e-3) * np.sign(val)
     assert np.abs(moved - want).max() < 1e-8
+
+
+def test_byte_indices_with_fp32_values(H):
+    # index width and value dtype are independent: fp32 values + byte indices go through the
+    # same staged check as the plain format (these run on the general kernels)
+    import torch
+    from paper_2502_06728_amd import binding
+    n, s, k, R = 64 * 700 + 11, 64, 16, 2
+    cfg = Config(chunk=s, topk=k, sign=True)
+    g, m, th = make_inputs(n, 23)
+    entries = -(-n // s) * k
+    gm = H.to_dev(m)
+    idx8 = torch.zeros(entries, dtype=torch.uint8, device=H.DEV)
+    val = torch.zeros(entries, dtype=torch.float32, device=H.DEV)
+    coeff = torch.zeros(-(-n // s) * s, dtype=torch.float32, device=H.DEV)
+    binding.detonation_compress_packed(H.bcfg(cfg), H.to_dev(g), gm, idx8, val, coeff)
+    torch.cuda.synchronize()
+    parity.check_compress(cfg, g, m, H.to_host(gm), idx8.cpu().numpy().astype(np.int32),
+                          H.to_host(val), H.to_host(coeff))
+    pays = [oracle.compress(cfg, *make_inputs(n, 60 + r)[:2])[1:] for r in range(R)]
+    idx = np.stack([q[0] for q in pays])
+    vals = np.stack([q[1] for q in pays])
+    p = H.to_dev(th)
+    y = torch.empty(n, dtype=torch.float32, device=H.DEV)
+    binding.detonation_decompress_step_packed(
+        H.bcfg(cfg), R, torch.from_numpy(idx.astype(np.uint8)).to(H.DEV), H.to_dev(vals), p, y)
+    torch.cuda.synchronize()
+    parity.check_decompress(cfg, idx, vals, th, H.to_host(p), H.to_host(y))
