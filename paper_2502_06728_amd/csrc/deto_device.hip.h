@@ -131,6 +131,17 @@ __device__ __forceinline__ void st_u4(void* p, uint4 v) {
     }
 }
 
+// Ordering point between the LDS phases of a single-wavefront workgroup.  The LDS queue of
+// one wavefront is processed in program order, so no hardware barrier is needed; this only
+// stops the compiler from moving LDS accesses across the phase boundary.  Unlike
+// __syncthreads() it does not wait for outstanding global loads and stores, so prefetched
+// data stays in flight and finished tiles retire without waiting for their stores.
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+}
+
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) {
     return __uint_as_float(static_cast<uint32_t>(b) << 16);
 }

@@ -118,12 +118,13 @@ int detonation_compress_packed(const deto_config* cfg, int64_t n, const void* gr
     // chunks on the general code), else the general kernel for everything
     int64_t c0 = 0;
     const int64_t tiles = (n / p.s) / deto::kWave;
-    if (tiles > 0 && tiles <= kMaxTiles && aligned16(grad) && aligned16(momentum) &&
-        aligned16(idx_out) && aligned16(val_out) && aligned16(coeff_dbg)) {
+    if (tiles <= kMaxTiles && aligned16(grad) && aligned16(momentum) && aligned16(idx_out) &&
+        aligned16(val_out) && aligned16(coeff_dbg)) {
         deto::CompressLaunch a{p, tiles, n, C, grad, grad_dtype == DETO_BF16, momentum, idx_out,
                                val_out, coeff_dbg, {0, 0, 0, 0}, st};
         stride_pattern(p, a.stride_mask);
-        const bool done = (p.scheme == DETO_SCHEME_TOPK)
+        const bool done = tiles == 0 ? false
+                          : (p.scheme == DETO_SCHEME_TOPK)
                               ? (deto::launch_compress_topk_s64(a) ||
                                  deto::launch_compress_topk_s32(a) ||
                                  deto::launch_compress_topk_s128_k4(a) ||
@@ -134,6 +135,14 @@ int detonation_compress_packed(const deto_config* cfg, int64_t n, const void* gr
             rc = launched();
             if (rc) return rc;
             c0 = C;   // the tail chunks rode along in the same launch
+        } else {
+            // no lane-per-chunk kernel for this (s, k): the matrix-core kernel takes the
+            // leading multiple of 32 chunks
+            c0 = deto::launch_compress_mfma(a);
+            if (c0 > 0) {
+                rc = launched();
+                if (rc) return rc;
+            }
         }
     }
     if (c0 < C) {
@@ -214,14 +223,15 @@ int decompress_impl(const deto_config* cfg, const deto_adamw* opt, int64_t n, in
     const bool strides_ok =
         R == 1 || ((!idx || (idx_replica_stride * static_cast<int64_t>(idx_size(idx_dtype))) % 16 == 0) &&
                    (val_replica_stride * static_cast<int64_t>(val_size(val_dtype))) % 16 == 0);
-    if (tiles > 0 && tiles <= kMaxTiles && aligned16(idx) && aligned16(val) && aligned16(params) &&
+    if (tiles <= kMaxTiles && aligned16(idx) && aligned16(val) && aligned16(params) &&
         aligned16(presign_dbg) && aligned16(adam.m) && aligned16(adam.v) && aligned16(adam.vmax) &&
         strides_ok) {
         deto::DecompressLaunch a{p, tiles, n, C, idx, idx_replica_stride, val,
                                  val_replica_stride, params, param_dtype == DETO_BF16, presign_dbg,
                                  {0, 0, 0, 0}, st, adam};
         stride_pattern(p, a.stride_mask);
-        const bool done = idx ? (deto::launch_decompress_adamw(a) ||
+        const bool done = tiles == 0 ? false
+                          : idx ? (deto::launch_decompress_adamw(a) ||
                                  deto::launch_decompress_idx_s64(a) ||
                                  deto::launch_decompress_idx_s32(a) ||
                                  deto::launch_decompress_idx_s128_k4(a) ||
@@ -232,6 +242,12 @@ int decompress_impl(const deto_config* cfg, const deto_adamw* opt, int64_t n, in
             rc = launched();
             if (rc) return rc;
             c0 = C;   // the tail chunks rode along in the same launch
+        } else {
+            c0 = deto::launch_decompress_mfma(a);
+            if (c0 > 0) {
+                rc = launched();
+                if (rc) return rc;
+            }
         }
     }
     if (c0 < C) {

@@ -1,0 +1,31 @@
+// Matrix-core decompress-and-update kernels (chunk sizes 32, 64, ..., 256; any k; transmitted
+// indices; plain SGD update or Decoupled AdamW).
+#include "mfma_kernels.hip.h"
+#include "tiled_launch.h"
+
+namespace deto {
+
+int64_t launch_decompress_mfma(const DecompressLaunch& a) {
+    const KParams& p = a.p;
+    if (!a.idx || !p.use_dct || p.s % 32 != 0 || p.s > 256) return 0;
+    const int64_t tiles = (a.n / p.s) / kMfmaChunks;
+    if (tiles <= 0) return 0;
+#define X(NB)                                                                                   \
+    if (p.s == 32 * NB) {                                                                       \
+        const unsigned grid = mfma_grid(tiles, MfmaGeom<NB>::kSmemBytes);                       \
+        if (a.param_bf16)                                                                       \
+            decompress_mfma<NB, true><<<grid, kWave, 0, a.stream>>>(                            \
+                p, tiles, a.idx, a.idx_stride, a.val, a.val_stride, a.params, a.adam,           \
+                a.presign_dbg);                                                                 \
+        else                                                                                    \
+            decompress_mfma<NB, false><<<grid, kWave, 0, a.stream>>>(                           \
+                p, tiles, a.idx, a.idx_stride, a.val, a.val_stride, a.params, a.adam,           \
+                a.presign_dbg);                                                                 \
+        return tiles * kMfmaChunks;                                                             \
+    }
+    DETO_MFMA_NB_LIST(X)
+#undef X
+    return 0;
+}
+
+}  // namespace deto

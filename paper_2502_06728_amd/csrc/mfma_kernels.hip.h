@@ -1,0 +1,439 @@
+// Matrix-core kernels for the chunk sizes the lane-per-chunk tiled kernels do not cover
+// (any multiple of 32 up to 256, any k, top-k selection): the DCT of Algorithm 1 as the dense
+// product it is defined as, on v_mfma_f32_32x32x2f32.
+//
+// One wavefront (= one workgroup) owns a tile of 32 complete chunks, held as a 32 x S matrix
+// in LDS (row = chunk).  With X the tile and D the S x S DCT-II matrix:
+//     coefficients^T = D   * X^T      (A operand: D rows,     B operand: X rows)
+//     output^T       = D^T * A_in^T   (A operand: D columns,  B operand: coefficient rows)
+// so both directions read their B operand from the LDS rows with the same 16-byte reads
+// (contraction index 8q + 4h + i for half-wave h at MFMA step 4q + i) and differ only in how
+// the A operand walks the cosine table  tab[t] = cos(pi t / (2S)), t in [0, 4S):
+//     D[j][n] = alpha_j * tab[(2n+1) j mod 4S].
+// The scale alpha_j is applied outside the product.  Selection is a bitwise binary search
+// for the k-th largest magnitude of each chunk (two lanes per chunk, half a row each),
+// followed by one pass over the chunks with the whole wavefront that emits the payload in
+// ascending index order and leaves alpha_j * (what the receivers will not get) in LDS for
+// the inverse product: the new momentum is the inverse transform of that remainder.
+#pragma once
+
+#include "deto_device.hip.h"
+#include "generic_kernels.hip.h"
+
+namespace deto {
+
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+constexpr int kMfmaChunks = 32;   // chunks per tile = N of the 32x32 MFMA
+
+template <int NB>
+struct MfmaGeom {
+    static constexpr int S = 32 * NB;          // chunk size
+    static constexpr int kRow = S + 4;         // floats per LDS row (16 B of padding)
+    static constexpr int kTab = 4 * S;         // cosine table entries
+    static constexpr int kVecIters = S / 8;    // 16-byte pieces per lane in a linear pass
+    static constexpr size_t kSmemBytes = sizeof(float) * (kMfmaChunks * kRow + kTab);
+};
+
+// tab[t] = cos(pi t / (2S)) for t in [0, 4S), from the first quarter period by symmetry
+template <int S>
+__device__ __forceinline__ void build_cos_table_quarter(float* tab, int lane) {
+    for (int t = lane; t <= S; t += kWave) {
+        float c = static_cast<float>(cos(3.14159265358979323846 * static_cast<double>(t) /
+                                         (2.0 * static_cast<double>(S))));
+        if (t == S) c = 0.0f;
+        tab[t] = c;
+        tab[2 * S - t] = -c;
+        tab[2 * S + t] = -c;
+        if (t > 0) tab[4 * S - t] = c;
+    }
+}
+
+// acc[b] += A_b * B over the whole contraction length S.  B: the calling lane's LDS row
+// (`row` points at column 4h of row t).  A for output block b: tab[cur[b]], where cur[b]
+// advances by inc[b] (mod 4S) per contraction index; inc5[b] = 5 inc[b] mod 4S bridges the
+// gap between the lane's groups of four consecutive indices.
+template <int NB>
+__device__ __forceinline__ void cos_product(const float* __restrict__ row,
+                                            const float* __restrict__ tab, int (&cur)[NB],
+                                            const int (&inc)[NB], const int (&inc5)[NB],
+                                            f32x16_t (&acc)[NB]) {
+    constexpr int S = 32 * NB, W = 4 * S;
+#pragma unroll 1
+    for (int q = 0; q < S / 8; ++q) {
+        const float4 x = *reinterpret_cast<const float4*>(row + 8 * q);
+        const float xv[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const float a = tab[cur[b]];
+                acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, xv[i], acc[b], 0, 0, 0);
+                const int nx = cur[b] + (i < 3 ? inc[b] : inc5[b]);
+                cur[b] = nx >= W ? nx - W : nx;
+            }
+        }
+    }
+}
+
+__device__ __forceinline__ int lanes_below(uint64_t mask, int lane) {
+    return __popcll(mask & ((1ull << lane) - 1ull));
+}
+
+// Compress half on full tiles of 32 chunks (top-k selection, DCT domain).
+template <int NB, bool GRAD_BF16>
+__global__ __launch_bounds__(kWave) void compress_mfma(KParams p, int64_t tiles,
+                                                       const void* __restrict__ grad,
+                                                       float* __restrict__ mom,
+                                                       void* __restrict__ idx_out,
+                                                       void* __restrict__ val_out,
+                                                       float* __restrict__ coeff_dbg) {
+    using G = MfmaGeom<NB>;
+    constexpr int S = G::S, kRow = G::kRow, W = G::kTab;
+    __shared__ __attribute__((aligned(16))) float buf[kMfmaChunks * kRow];
+    __shared__ float tab[W];
+
+    const int lane = threadIdx.x;
+    const int t = lane & 31, h = lane >> 5;
+    const int k = p.k;
+    build_cos_table_quarter<S>(tab, lane);
+    wave_lds_sync();
+
+    for (int64_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+        const int64_t base = tile * static_cast<int64_t>(kMfmaChunks * S);
+        const int64_t chunk0 = tile * kMfmaChunks;
+
+        // ---- m1 = beta*m + g, coalesced, into the LDS rows
+#pragma unroll 4
+        for (int it = 0; it < G::kVecIters; ++it) {
+            const int e4 = 4 * (lane + kWave * it);
+            const int row = e4 / S, col = e4 - row * S;
+            const float4 m = ld_f4<false>(mom + base + e4);
+            float4 g;
+            if constexpr (GRAD_BF16) {
+                const uint2 gb = ld_u2<false>(static_cast<const uint16_t*>(grad) + base + e4);
+                g = make_float4(__uint_as_float(gb.x << 16), __uint_as_float(gb.x & 0xFFFF0000u),
+                                __uint_as_float(gb.y << 16), __uint_as_float(gb.y & 0xFFFF0000u));
+            } else {
+                g = ld_f4<false>(static_cast<const float*>(grad) + base + e4);
+            }
+            const float4 x = make_float4(fmaf(p.beta, m.x, g.x), fmaf(p.beta, m.y, g.y),
+                                         fmaf(p.beta, m.z, g.z), fmaf(p.beta, m.w, g.w));
+            *reinterpret_cast<float4*>(&buf[row * kRow + col]) = x;
+        }
+        wave_lds_sync();
+
+        // ---- coefficients^T = D * X^T: lane's A rows are j = 32b + t
+        f32x16_t acc[NB];
+        int cur[NB], inc[NB], inc5[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int j = 32 * b + t;
+            cur[b] = ((8 * h + 1) * j) % W;     // contraction index n = 4h first
+            inc[b] = 2 * j;
+            inc5[b] = (10 * j) % W;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[b][r] = 0.0f;
+        }
+        cos_product<NB>(&buf[t * kRow + 4 * h], tab, cur, inc, inc5, acc);
+        wave_lds_sync();
+        // acc[b][r] is coefficient j = 32b + 8(r/4) + 4h + r%4 of chunk t.  Stored with the
+        // sign bit rotated to the bottom, so unsigned order = magnitude order.
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const int j0 = 32 * b + 8 * g4 + 4 * h;
+                float c[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) c[i] = acc[b][4 * g4 + i] * p.alpha;
+                if (b == 0 && g4 == 0 && h == 0) c[0] = acc[0][0] * p.alpha0;
+                float4 o;
+                o.x = __uint_as_float(__builtin_rotateleft32(__float_as_uint(c[0]), 1));
+                o.y = __uint_as_float(__builtin_rotateleft32(__float_as_uint(c[1]), 1));
+                o.z = __uint_as_float(__builtin_rotateleft32(__float_as_uint(c[2]), 1));
+                o.w = __uint_as_float(__builtin_rotateleft32(__float_as_uint(c[3]), 1));
+                *reinterpret_cast<float4*>(&buf[t * kRow + j0]) = o;
+            }
+        }
+        wave_lds_sync();
+
+        // ---- k-th largest magnitude of chunk t: lanes t and t+32 count half a row each.
+        // thr_gt: everything at or above it is kept; thr_eq: of the entries equal to it the
+        // first `need` (lowest indices) are kept as well.
+        const float* half = &buf[t * kRow + h * (S / 2)];
+        uint32_t T = 0u, thr_gt = 0u;
+        bool done = false;
+        for (int bit = 30; bit >= 0; --bit) {
+            const uint32_t cand = T | (1u << bit);
+            const uint32_t c2 = cand << 1;
+            int cnt = 0;
+#pragma unroll 4
+            for (int v = 0; v < S / 8; ++v) {
+                const float4 f = *reinterpret_cast<const float4*>(half + 4 * v);
+                cnt += (__float_as_uint(f.x) >= c2) ? 1 : 0;
+                cnt += (__float_as_uint(f.y) >= c2) ? 1 : 0;
+                cnt += (__float_as_uint(f.z) >= c2) ? 1 : 0;
+                cnt += (__float_as_uint(f.w) >= c2) ? 1 : 0;
+            }
+            cnt += __shfl_xor(cnt, 32);
+            if (!done && cnt >= k) {
+                T = cand;
+                if (cnt == k) {   // exactly k entries at or above cand: the selection is settled
+                    done = true;
+                    thr_gt = cand;
+                }
+            }
+            if (__all(done)) break;
+        }
+        uint32_t thr_eq = 0xFFFFFFFFu;
+        int need = 0;
+        {
+            // lanes still open: T is the k-th largest magnitude itself
+            const bool open = !done;
+            const uint32_t gt = T + 1u;                       // <= 0x80000000
+            const uint32_t c2 = (gt > 0x7FFFFFFFu) ? 0xFFFFFFFFu : (gt << 1);
+            int cg = 0;
+#pragma unroll 4
+            for (int v = 0; v < S / 8; ++v) {
+                const float4 f = *reinterpret_cast<const float4*>(half + 4 * v);
+                cg += (__float_as_uint(f.x) >= c2) ? 1 : 0;
+                cg += (__float_as_uint(f.y) >= c2) ? 1 : 0;
+                cg += (__float_as_uint(f.z) >= c2) ? 1 : 0;
+                cg += (__float_as_uint(f.w) >= c2) ? 1 : 0;
+            }
+            cg += __shfl_xor(cg, 32);
+            if (open) {
+                thr_gt = gt;
+                thr_eq = T;
+                need = k - cg;
+            }
+        }
+
+        // ---- one chunk at a time with the whole wavefront: payload out, remainder in
+        for (int tt = 0; tt < kMfmaChunks; ++tt) {
+            const uint32_t c_gt = __builtin_amdgcn_readlane(thr_gt, tt);
+            const uint32_t c_eq = __builtin_amdgcn_readlane(thr_eq, tt);
+            const int c_need = __builtin_amdgcn_readlane(need, tt);
+            const int64_t chunk = chunk0 + tt;
+            int kept_before = 0, eq_before = 0;
+#pragma unroll
+            for (int e0 = 0; e0 < S; e0 += kWave) {
+                const int e = e0 + lane;
+                const bool in = (S % kWave == 0) || e < S;
+                const uint32_t u = in ? __float_as_uint(buf[tt * kRow + e]) : 0u;
+                const float c = __uint_as_float(__builtin_rotateright32(u, 1));
+                const uint32_t mag = u >> 1;
+                const bool eq = in && mag == c_eq;
+                const uint64_t eqm = __ballot(eq);
+                const int eq_rank = eq_before + lanes_below(eqm, lane);
+                const bool keep = in && (mag >= c_gt || (eq && eq_rank < c_need));
+                const uint64_t km = __ballot(keep);
+                const int pos = kept_before + lanes_below(km, lane);
+                float rem = c;
+                if (keep && pos < k) {
+                    store_payload_index(idx_out, chunk * k + pos, p.idx_u8, e);
+                    store_payload_value(val_out, chunk * k + pos, p.val_dtype, c);
+                    rem = c - payload_roundtrip(p.val_dtype, c);
+                }
+                if (in) {
+                    if (coeff_dbg) coeff_dbg[chunk * S + e] = c;
+                    buf[tt * kRow + e] = rem * (e == 0 ? p.alpha0 : p.alpha);
+                }
+                kept_before += __popcll(km);
+                eq_before += __popcll(eqm);
+            }
+        }
+        wave_lds_sync();
+
+        // ---- new momentum^T = D^T * remainder^T: lane's A rows are n = 32b + t
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int m2 = 2 * (32 * b + t) + 1;
+            cur[b] = (m2 * 4 * h) % W;          // contraction index j = 4h first
+            inc[b] = m2;
+            inc5[b] = (5 * m2) % W;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[b][r] = 0.0f;
+        }
+        cos_product<NB>(&buf[t * kRow + 4 * h], tab, cur, inc, inc5, acc);
+        wave_lds_sync();
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const int n0 = 32 * b + 8 * g4 + 4 * h;
+                *reinterpret_cast<float4*>(&buf[t * kRow + n0]) =
+                    make_float4(acc[b][4 * g4], acc[b][4 * g4 + 1], acc[b][4 * g4 + 2],
+                                acc[b][4 * g4 + 3]);
+            }
+        }
+        wave_lds_sync();
+#pragma unroll 4
+        for (int it = 0; it < G::kVecIters; ++it) {
+            const int e4 = 4 * (lane + kWave * it);
+            const int row = e4 / S, col = e4 - row * S;
+            st_f4<false>(mom + base + e4, *reinterpret_cast<const float4*>(&buf[row * kRow + col]));
+        }
+        wave_lds_sync();
+    }
+}
+
+// Decompress-and-update half on full tiles of 32 chunks (transmitted indices, DCT domain).
+template <int NB, bool PARAM_BF16>
+__global__ __launch_bounds__(kWave) void decompress_mfma(
+    KParams p, int64_t tiles, const void* __restrict__ idx, int64_t idx_stride,
+    const void* __restrict__ val, int64_t val_stride, void* __restrict__ params, AdamPtrs ad,
+    float* __restrict__ presign_dbg) {
+    using G = MfmaGeom<NB>;
+    constexpr int S = G::S, kRow = G::kRow, W = G::kTab;
+    __shared__ __attribute__((aligned(16))) float buf[kMfmaChunks * kRow];
+    __shared__ float tab[W];
+
+    const int lane = threadIdx.x;
+    const int t = lane & 31, h = lane >> 5;
+    const int k = p.k;
+    build_cos_table_quarter<S>(tab, lane);
+    // entry -> chunk within a group of 8 chunks: floor(e / k) = umulhi(e, ceil(2^32 / k)),
+    // exact for e < 8*256
+    const uint32_t magic =
+        (k == 1) ? 0u : static_cast<uint32_t>(((1ull << 32) + static_cast<uint64_t>(k) - 1ull) /
+                                              static_cast<uint64_t>(k));
+    const uint32_t group_entries = 8u * static_cast<uint32_t>(k);
+    const int scatter_iters = static_cast<int>((group_entries + kWave - 1) / kWave);
+    const float out_scale = p.alpha * p.inv_R;
+    const float row0_fix = (p.alpha0 - p.alpha) * p.inv_R;
+    wave_lds_sync();
+
+    for (int64_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+        const int64_t base = tile * static_cast<int64_t>(kMfmaChunks * S);
+        const int64_t entry0 = tile * static_cast<int64_t>(kMfmaChunks) * k;
+
+        for (int v = lane; v < kMfmaChunks * kRow / 4; v += kWave)
+            *reinterpret_cast<float4*>(&buf[4 * v]) = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        wave_lds_sync();
+
+        // ---- scatter-add, replica after replica.  The tile's entries of one replica are
+        // contiguous; four groups of 8 chunks run side by side (different LDS rows).  Within
+        // one instruction the entries of a chunk must hit distinct addresses for the plain
+        // read-add-write: guaranteed when their indices ascend strictly, else LDS atomics.
+        for (int r = 0; r < p.R; ++r) {
+            const int64_t ib = r * idx_stride + entry0;
+            const int64_t vb = r * val_stride + entry0;
+            for (int it = 0; it < scatter_iters; ++it) {
+                const uint32_t el = static_cast<uint32_t>(it * kWave + lane);
+                const bool in = el < group_entries;
+                const uint32_t lrow = (k == 1) ? el : __umulhi(el, magic);
+                const bool chunk_start = (el - lrow * static_cast<uint32_t>(k)) == 0u;
+                int at[4], addr[4];
+                float v[4];
+                bool ok[4];
+                bool bad = false;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int64_t e = static_cast<int64_t>(q) * group_entries + el;
+                    at[q] = in ? load_payload_index(idx, ib + e, p.idx_u8) : -1;
+                    v[q] = in ? load_payload_value(val, vb + e, p.val_dtype) : 0.0f;
+                    ok[q] = in && at[q] >= 0 && at[q] < S;
+                    addr[q] = (8 * q + static_cast<int>(lrow)) * kRow + at[q];
+                    const int prev = __shfl_up(at[q], 1);
+                    bad = bad || (in && lane > 0 && !chunk_start && prev >= at[q]);
+                }
+                if (__any(bad)) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        if (ok[q]) atomicAdd(&buf[addr[q]], v[q]);
+                } else {
+                    float a[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) a[q] = ok[q] ? buf[addr[q]] : 0.0f;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        if (ok[q]) buf[addr[q]] = a[q] + v[q];
+                }
+            }
+        }
+        wave_lds_sync();
+
+        // ---- y^T = D^T * (alpha_j a_j / R)^T; the scale is applied to the result:
+        // y = (alpha/R) * sum_j a_j cos(..) + ((alpha0 - alpha)/R) * a_0
+        const float a0 = buf[t * kRow];
+        f32x16_t acc[NB];
+        int cur[NB], inc[NB], inc5[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int m2 = 2 * (32 * b + t) + 1;
+            cur[b] = (m2 * 4 * h) % W;
+            inc[b] = m2;
+            inc5[b] = (5 * m2) % W;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[b][r] = 0.0f;
+        }
+        cos_product<NB>(&buf[t * kRow + 4 * h], tab, cur, inc, inc5, acc);
+        wave_lds_sync();
+        const float fix = row0_fix * a0;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const int n0 = 32 * b + 8 * g4 + 4 * h;
+                *reinterpret_cast<float4*>(&buf[t * kRow + n0]) = make_float4(
+                    fmaf(acc[b][4 * g4], out_scale, fix), fmaf(acc[b][4 * g4 + 1], out_scale, fix),
+                    fmaf(acc[b][4 * g4 + 2], out_scale, fix),
+                    fmaf(acc[b][4 * g4 + 3], out_scale, fix));
+            }
+        }
+        wave_lds_sync();
+
+        // ---- sign and parameter update, coalesced
+#pragma unroll 2
+        for (int it = 0; it < G::kVecIters; ++it) {
+            const int e4 = 4 * (lane + kWave * it);
+            const int row = e4 / S, col = e4 - row * S;
+            const int64_t i = base + e4;
+            const float4 y4 = *reinterpret_cast<const float4*>(&buf[row * kRow + col]);
+            if (presign_dbg) st_f4<false>(presign_dbg + i, y4);
+            const float y[4] = {y4.x, y4.y, y4.z, y4.w};
+            float old[4], nw[4];
+            uint2 pb;
+            if constexpr (PARAM_BF16) {
+                pb = ld_u2<false>(static_cast<const uint16_t*>(params) + i);
+                old[0] = __uint_as_float(pb.x << 16);
+                old[1] = __uint_as_float(pb.x & 0xFFFF0000u);
+                old[2] = __uint_as_float(pb.y << 16);
+                old[3] = __uint_as_float(pb.y & 0xFFFF0000u);
+            } else {
+                const float4 o = ld_f4<false>(static_cast<const float*>(params) + i);
+                old[0] = o.x; old[1] = o.y; old[2] = o.z; old[3] = o.w;
+            }
+            if (p.adam) {
+                const float4 m4 = ld_f4<false>(ad.m + i), v4 = ld_f4<false>(ad.v + i);
+                float4 x4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                if (p.amsgrad) x4 = ld_f4<false>(ad.vmax + i);
+                float m[4] = {m4.x, m4.y, m4.z, m4.w}, v[4] = {v4.x, v4.y, v4.z, v4.w};
+                float x[4] = {x4.x, x4.y, x4.z, x4.w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    nw[c] = adamw_step(p, old[c], sign_or_self(y[c], p.use_sign), m[c], v[c], x[c]);
+                st_f4<false>(ad.m + i, make_float4(m[0], m[1], m[2], m[3]));
+                st_f4<false>(ad.v + i, make_float4(v[0], v[1], v[2], v[3]));
+                if (p.amsgrad) st_f4<false>(ad.vmax + i, make_float4(x[0], x[1], x[2], x[3]));
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    nw[c] = fmaf(-p.lr, sign_or_self(y[c], p.use_sign), old[c] * p.wd_scale);
+            }
+            if constexpr (PARAM_BF16) {
+                uint2 o;
+                o.x = pack_bf16x2(nw[0], nw[1]);
+                o.y = pack_bf16x2(nw[2], nw[3]);
+                *reinterpret_cast<uint2*>(static_cast<uint16_t*>(params) + i) = o;
+            } else {
+                st_f4<false>(static_cast<float*>(params) + i, make_float4(nw[0], nw[1], nw[2], nw[3]));
+            }
+        }
+        wave_lds_sync();
+    }
+}
+
+}  // namespace deto

@@ -98,17 +98,6 @@ __device__ __forceinline__ uint32_t kth_largest(const uint32_t (&A)[H], const ui
     return best;
 }
 
-// Ordering point between the LDS phases of a single-wavefront workgroup.  The LDS queue of
-// one wavefront is processed in program order, so no hardware barrier is needed; this only
-// stops the compiler from moving LDS accesses across the phase boundary.  Unlike
-// __syncthreads() it does not wait for outstanding global loads and stores, so prefetched
-// data stays in flight and finished tiles retire without waiting for their stores.
-__device__ __forceinline__ void wave_lds_sync() {
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-}
-
 template <int S>
 struct TileGeom {
     static constexpr int kRow = S + 4;           // floats per LDS row (16 B of padding)

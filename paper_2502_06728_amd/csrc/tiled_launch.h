@@ -61,4 +61,21 @@ bool launch_decompress_adamw(const DecompressLaunch& a);       // Decoupled Adam
 bool launch_compress_scheme(const CompressLaunch& a);
 bool launch_decompress_scheme(const DecompressLaunch& a);
 
+// Matrix-core kernels: tiles of 32 complete chunks, persistent single-wavefront workgroups.
+// A launcher returns the number of leading chunks it has taken (0: no kernel for this request).
+#ifdef DETO_TILED_ONLY_64_32
+#define DETO_MFMA_NB_LIST(X) X(4)
+#else
+#define DETO_MFMA_NB_LIST(X) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8)
+#endif
+
+inline unsigned mfma_grid(int64_t tiles, size_t smem_bytes) {
+    const int64_t per_cu = static_cast<int64_t>((160u * 1024u) / smem_bytes);   // LDS-limited
+    const int64_t cap = 256 * (per_cu < 8 ? per_cu : 8);
+    return static_cast<unsigned>(tiles < cap ? tiles : cap);
+}
+
+int64_t launch_compress_mfma(const CompressLaunch& a);
+int64_t launch_decompress_mfma(const DecompressLaunch& a);
+
 }  // namespace deto
