@@ -10,16 +10,19 @@ int64_t launch_decompress_mfma(const DecompressLaunch& a) {
     if (!a.idx || !p.use_dct || p.s % 32 != 0 || p.s > 256) return 0;
     const int64_t tiles = (a.n / p.s) / kMfmaChunks;
     if (tiles <= 0) return 0;
+    // 16-byte payload loads: fp32 values, int32 indices, four entries never straddle a chunk
+    // (the caller has checked the alignment of the bases and of the replica strides)
+    const int vec = (p.val_dtype == 0 && !p.idx_u8 && p.k % 4 == 0) ? 1 : 0;
 #define X(NB)                                                                                   \
     if (p.s == 32 * NB) {                                                                       \
         const unsigned grid = mfma_grid(tiles, MfmaGeom<NB>::kSmemBytes);                       \
         if (a.param_bf16)                                                                       \
             decompress_mfma<NB, true><<<grid, kWave, 0, a.stream>>>(                            \
-                p, tiles, a.idx, a.idx_stride, a.val, a.val_stride, a.params, a.adam,           \
+                p, tiles, vec, a.idx, a.idx_stride, a.val, a.val_stride, a.params, a.adam,           \
                 a.presign_dbg);                                                                 \
         else                                                                                    \
             decompress_mfma<NB, false><<<grid, kWave, 0, a.stream>>>(                           \
-                p, tiles, a.idx, a.idx_stride, a.val, a.val_stride, a.params, a.adam,           \
+                p, tiles, vec, a.idx, a.idx_stride, a.val, a.val_stride, a.params, a.adam,           \
                 a.presign_dbg);                                                                 \
         return tiles * kMfmaChunks;                                                             \
     }

@@ -33,6 +33,9 @@ struct MfmaGeom {
     static constexpr int kTab = 4 * S;         // cosine table entries
     static constexpr int kVecIters = S / 8;    // 16-byte pieces per lane in a linear pass
     static constexpr size_t kSmemBytes = sizeof(float) * (kMfmaChunks * kRow + kTab);
+    // wavefronts per SIMD the LDS leaves room for (160 KB per CU, 4 SIMDs): the register
+    // allocation is held to that occupancy
+    static constexpr int kWavesPerSimd = (NB <= 6) ? 2 : 1;
 };
 
 // tab[t] = cos(pi t / (2S)) for t in [0, 4S), from the first quarter period by symmetry
@@ -82,7 +85,8 @@ __device__ __forceinline__ int lanes_below(uint64_t mask, int lane) {
 
 // Compress half on full tiles of 32 chunks (top-k selection, DCT domain).
 template <int NB, bool GRAD_BF16>
-__global__ __launch_bounds__(kWave) void compress_mfma(KParams p, int64_t tiles,
+__global__ __launch_bounds__(kWave)
+__attribute__((amdgpu_waves_per_eu(MfmaGeom<NB>::kWavesPerSimd))) void compress_mfma(KParams p, int64_t tiles,
                                                        const void* __restrict__ grad,
                                                        float* __restrict__ mom,
                                                        void* __restrict__ idx_out,
@@ -279,10 +283,123 @@ __global__ __launch_bounds__(kWave) void compress_mfma(KParams p, int64_t tiles,
     }
 }
 
+// Scatter-add of the tile's payload for fp32 values + int32 indices with k a multiple of 4:
+// 16-byte loads (four consecutive entries of one chunk per lane), four of them in flight
+// per lane and the next group of four requested before the current one is applied.  A
+// group's read-add-write is batched (all reads, then all writes), which is exact when the
+// entries of each chunk inside the group hit distinct addresses: checked as "indices ascend
+// strictly from entry to entry within a chunk"; a group that fails the check is applied
+// with LDS atomics instead.
+template <int NB>
+__device__ __forceinline__ void scatter_add_vec(float* __restrict__ buf, const KParams& p,
+                                                int lane, const int32_t* __restrict__ idx,
+                                                int64_t idx_stride,
+                                                const float* __restrict__ val,
+                                                int64_t val_stride, int64_t entry0,
+                                                uint32_t magic) {
+    constexpr int S = MfmaGeom<NB>::S, kRow = MfmaGeom<NB>::kRow;
+    constexpr int GI = 4;                                  // 16-byte loads per lane and group
+    const int k = p.k;
+    const int quads = 8 * k;                               // 16-byte pieces per replica tile
+    const int groups_per_rep = (quads + GI * kWave - 1) / (GI * kWave);
+    const int total = p.R * groups_per_rep;
+
+    int4 ia[GI], ib[GI];
+    float4 va[GI], vb[GI];
+    auto load = [&](int gi, int4 (&I)[GI], float4 (&V)[GI]) {
+        const int r = gi / groups_per_rep, g = gi - r * groups_per_rep;
+        const int32_t* ip = idx + r * idx_stride + entry0;
+        const float* vp = val + r * val_stride + entry0;
+#pragma unroll
+        for (int i = 0; i < GI; ++i) {
+            const int q = (g * GI + i) * kWave + lane;
+            if (q < quads) {
+                const uint4 t = ld_u4<true>(ip + 4 * q);
+                I[i] = make_int4(static_cast<int>(t.x), static_cast<int>(t.y),
+                                 static_cast<int>(t.z), static_cast<int>(t.w));
+                V[i] = ld_f4<true>(vp + 4 * q);
+            } else {
+                I[i] = make_int4(-1, -1, -1, -1);
+                V[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            }
+        }
+    };
+
+    load(0, ia, va);
+    for (int gi = 0; gi < total; ++gi) {
+        if (gi + 1 < total) load(gi + 1, ib, vb);
+        const int g = gi % groups_per_rep;
+        // iterations of this group that hold entries at all (wave-uniform)
+        const int live = min(GI, (quads - g * GI * kWave + kWave - 1) / kWave);
+        int rowbase[GI];
+        bool bad = false;
+#pragma unroll
+        for (int i = 0; i < GI; ++i) {
+            if (i >= live) break;
+            const int q = (g * GI + i) * kWave + lane;
+            const bool in = q < quads;
+            const uint32_t e0 = 4u * static_cast<uint32_t>(q);
+            const uint32_t row = __umulhi(e0, magic);
+            const bool chunk_start = (e0 - row * static_cast<uint32_t>(k)) == 0u;
+            rowbase[i] = static_cast<int>(row) * kRow;
+            int prev = __shfl_up(ia[i].w, 1);
+            if (i > 0) {
+                const int wrap = __builtin_amdgcn_readlane(ia[i - 1].w, kWave - 1);
+                if (lane == 0) prev = wrap;
+            }
+            const bool first = (i == 0 && lane == 0);      // nothing of this group before it
+            const bool asc = ia[i].x < ia[i].y && ia[i].y < ia[i].z && ia[i].z < ia[i].w &&
+                             (first || chunk_start || prev < ia[i].x);
+            bad = bad || (in && !asc);
+        }
+        if (__any(bad)) {
+#pragma unroll
+            for (int i = 0; i < GI; ++i) {
+                if (i >= live) break;
+                const int at[4] = {ia[i].x, ia[i].y, ia[i].z, ia[i].w};
+                const float v[4] = {va[i].x, va[i].y, va[i].z, va[i].w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (static_cast<uint32_t>(at[c]) < static_cast<uint32_t>(S))
+                        atomicAdd(&buf[rowbase[i] + at[c]], v[c]);
+            }
+        } else {
+            float a[GI][4];
+#pragma unroll
+            for (int i = 0; i < GI; ++i) {
+                if (i >= live) break;
+                const int at[4] = {ia[i].x, ia[i].y, ia[i].z, ia[i].w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    a[i][c] = (static_cast<uint32_t>(at[c]) < static_cast<uint32_t>(S))
+                                  ? buf[rowbase[i] + at[c]] : 0.0f;
+            }
+#pragma unroll
+            for (int i = 0; i < GI; ++i) {
+                if (i >= live) break;
+                const int at[4] = {ia[i].x, ia[i].y, ia[i].z, ia[i].w};
+                const float v[4] = {va[i].x, va[i].y, va[i].z, va[i].w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (static_cast<uint32_t>(at[c]) < static_cast<uint32_t>(S))
+                        buf[rowbase[i] + at[c]] = a[i][c] + v[c];
+            }
+        }
+        // the next group follows in program order: the LDS queue keeps the two apart
+        wave_lds_sync();
+#pragma unroll
+        for (int i = 0; i < GI; ++i) {
+            ia[i] = ib[i];
+            va[i] = vb[i];
+        }
+    }
+}
+
 // Decompress-and-update half on full tiles of 32 chunks (transmitted indices, DCT domain).
 template <int NB, bool PARAM_BF16>
-__global__ __launch_bounds__(kWave) void decompress_mfma(
-    KParams p, int64_t tiles, const void* __restrict__ idx, int64_t idx_stride,
+__global__ __launch_bounds__(kWave)
+__attribute__((amdgpu_waves_per_eu(MfmaGeom<NB>::kWavesPerSimd))) void decompress_mfma(
+    KParams p, int64_t tiles, int vec_scatter, const void* __restrict__ idx, int64_t idx_stride,
     const void* __restrict__ val, int64_t val_stride, void* __restrict__ params, AdamPtrs ad,
     float* __restrict__ presign_dbg) {
     using G = MfmaGeom<NB>;
@@ -317,6 +434,10 @@ __global__ __launch_bounds__(kWave) void decompress_mfma(
         // contiguous; four groups of 8 chunks run side by side (different LDS rows).  Within
         // one instruction the entries of a chunk must hit distinct addresses for the plain
         // read-add-write: guaranteed when their indices ascend strictly, else LDS atomics.
+        if (vec_scatter)
+            scatter_add_vec<NB>(buf, p, lane, static_cast<const int32_t*>(idx), idx_stride,
+                                static_cast<const float*>(val), val_stride, entry0, magic);
+        else
         for (int r = 0; r < p.R; ++r) {
             const int64_t ib = r * idx_stride + entry0;
             const int64_t vb = r * val_stride + entry0;
