@@ -107,8 +107,9 @@ __attribute__((amdgpu_waves_per_eu(MfmaGeom<NB>::kWavesPerSimd))) void compress_
         const int64_t base = tile * static_cast<int64_t>(kMfmaChunks * S);
         const int64_t chunk0 = tile * kMfmaChunks;
 
-        // ---- m1 = beta*m + g, coalesced, into the LDS rows
-#pragma unroll 4
+        // ---- m1 = beta*m + g, coalesced, into the LDS rows (deep unroll: nothing else of
+        // this wavefront is in flight, so the loads of half a tile or more are issued at once)
+#pragma unroll 16
         for (int it = 0; it < G::kVecIters; ++it) {
             const int e4 = 4 * (lane + kWave * it);
             const int row = e4 / S, col = e4 - row * S;

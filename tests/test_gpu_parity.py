@@ -69,6 +69,15 @@ def test_other_chunk_sizes(H, s, k):
     full_step(H, cfg, s * 700 + (s // 3), R=3, seed=3)
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 8, 16])
+def test_chunk_size_16(H, k, bf16):
+    # the smallest chunk of the Appendix B sweep: lane-per-chunk kernels for k in {1,2,4,8}
+    cfg = Config(chunk=16, topk=k, sign=True)
+    full_step(H, cfg, 16 * (64 * 40 + 17) + 5, R=3, seed=k, grad_bf16=bf16, params_bf16=bf16,
+              outliers=0.01 if bf16 else 0.0)
+
+
 @pytest.mark.parametrize("grad_bf16,params_bf16", [(True, True), (True, False), (False, True)])
 def test_bf16_storage_with_outliers(H, grad_bf16, params_bf16):
     cfg = Config(chunk=64, topk=32, sign=True)
