@@ -142,8 +142,10 @@ __attribute__((amdgpu_waves_per_eu(MfmaGeom<NB>::kWavesPerSimd))) void compress_
         }
         cos_product<NB>(&buf[t * kRow + 4 * h], tab, cur, inc, inc5, acc);
         wave_lds_sync();
-        // acc[b][r] is coefficient j = 32b + 8(r/4) + 4h + r%4 of chunk t.  Stored with the
-        // sign bit rotated to the bottom, so unsigned order = magnitude order.
+        // acc[b][r] is coefficient j = 32b + 8(r/4) + 4h + r%4 of chunk t: lanes t and t+32
+        // hold half of the chunk each.  The coefficients go to the LDS rows; their magnitudes
+        // (bit patterns, 31 bits) stay in registers for the selection.
+        uint32_t mag[NB * 16];
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
 #pragma unroll
@@ -151,37 +153,39 @@ __attribute__((amdgpu_waves_per_eu(MfmaGeom<NB>::kWavesPerSimd))) void compress_
                 const int j0 = 32 * b + 8 * g4 + 4 * h;
                 float c[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) c[i] = acc[b][4 * g4 + i] * p.alpha;
-                if (b == 0 && g4 == 0 && h == 0) c[0] = acc[0][0] * p.alpha0;
-                float4 o;
-                o.x = __uint_as_float(__builtin_rotateleft32(__float_as_uint(c[0]), 1));
-                o.y = __uint_as_float(__builtin_rotateleft32(__float_as_uint(c[1]), 1));
-                o.z = __uint_as_float(__builtin_rotateleft32(__float_as_uint(c[2]), 1));
-                o.w = __uint_as_float(__builtin_rotateleft32(__float_as_uint(c[3]), 1));
-                *reinterpret_cast<float4*>(&buf[t * kRow + j0]) = o;
+                for (int i = 0; i < 4; ++i) {
+                    c[i] = acc[b][4 * g4 + i] * p.alpha;
+                    if (b == 0 && g4 == 0 && i == 0 && h == 0) c[i] = acc[0][0] * p.alpha0;
+                    mag[16 * b + 4 * g4 + i] = __float_as_uint(c[i]) & 0x7FFFFFFFu;
+                }
+                *reinterpret_cast<float4*>(&buf[t * kRow + j0]) =
+                    make_float4(c[0], c[1], c[2], c[3]);
             }
         }
-        wave_lds_sync();
 
-        // ---- k-th largest magnitude of chunk t: lanes t and t+32 count half a row each.
+        // ---- k-th largest magnitude of chunk t by binary search on its bits, counting in
+        // registers: mag - cand is exact in 32 bits and its sign bit says "below cand"; the
+        // sign bits are shifted into a collector word and counted 32 at a time.
         // thr_gt: everything at or above it is kept; thr_eq: of the entries equal to it the
         // first `need` (lowest indices) are kept as well.
-        const float* half = &buf[t * kRow + h * (S / 2)];
+        auto count_at_least = [&](uint32_t cand) -> int {
+            int below = 0;
+#pragma unroll
+            for (int w = 0; w < NB * 16; w += 32) {
+                uint32_t coll = 0u;
+#pragma unroll
+                for (int i = 0; i < 32 && w + i < NB * 16; ++i)
+                    coll = __builtin_amdgcn_alignbit(coll, mag[w + i] - cand, 31);
+                below += __popc(coll);
+            }
+            const int own = NB * 16 - below;
+            return own + __shfl_xor(own, 32);
+        };
         uint32_t T = 0u, thr_gt = 0u;
         bool done = false;
         for (int bit = 30; bit >= 0; --bit) {
             const uint32_t cand = T | (1u << bit);
-            const uint32_t c2 = cand << 1;
-            int cnt = 0;
-#pragma unroll 4
-            for (int v = 0; v < S / 8; ++v) {
-                const float4 f = *reinterpret_cast<const float4*>(half + 4 * v);
-                cnt += (__float_as_uint(f.x) >= c2) ? 1 : 0;
-                cnt += (__float_as_uint(f.y) >= c2) ? 1 : 0;
-                cnt += (__float_as_uint(f.z) >= c2) ? 1 : 0;
-                cnt += (__float_as_uint(f.w) >= c2) ? 1 : 0;
-            }
-            cnt += __shfl_xor(cnt, 32);
+            const int cnt = count_at_least(cand);
             if (!done && cnt >= k) {
                 T = cand;
                 if (cnt == k) {   // exactly k entries at or above cand: the selection is settled
@@ -193,27 +197,17 @@ __attribute__((amdgpu_waves_per_eu(MfmaGeom<NB>::kWavesPerSimd))) void compress_
         }
         uint32_t thr_eq = 0xFFFFFFFFu;
         int need = 0;
-        {
+        if (!__all(done)) {
             // lanes still open: T is the k-th largest magnitude itself
-            const bool open = !done;
-            const uint32_t gt = T + 1u;                       // <= 0x80000000
-            const uint32_t c2 = (gt > 0x7FFFFFFFu) ? 0xFFFFFFFFu : (gt << 1);
-            int cg = 0;
-#pragma unroll 4
-            for (int v = 0; v < S / 8; ++v) {
-                const float4 f = *reinterpret_cast<const float4*>(half + 4 * v);
-                cg += (__float_as_uint(f.x) >= c2) ? 1 : 0;
-                cg += (__float_as_uint(f.y) >= c2) ? 1 : 0;
-                cg += (__float_as_uint(f.z) >= c2) ? 1 : 0;
-                cg += (__float_as_uint(f.w) >= c2) ? 1 : 0;
-            }
-            cg += __shfl_xor(cg, 32);
-            if (open) {
+            const uint32_t gt = T + 1u;                       // <= 0x80000000: nothing reaches it
+            const int cg_all = count_at_least(gt & 0x7FFFFFFFu);   // every lane takes part
+            if (!done) {
                 thr_gt = gt;
                 thr_eq = T;
-                need = k - cg;
+                need = k - ((gt > 0x7FFFFFFFu) ? 0 : cg_all);
             }
         }
+        wave_lds_sync();
 
         // ---- one chunk at a time with the whole wavefront: payload out, remainder in
         for (int tt = 0; tt < kMfmaChunks; ++tt) {
@@ -226,13 +220,12 @@ __attribute__((amdgpu_waves_per_eu(MfmaGeom<NB>::kWavesPerSimd))) void compress_
             for (int e0 = 0; e0 < S; e0 += kWave) {
                 const int e = e0 + lane;
                 const bool in = (S % kWave == 0) || e < S;
-                const uint32_t u = in ? __float_as_uint(buf[tt * kRow + e]) : 0u;
-                const float c = __uint_as_float(__builtin_rotateright32(u, 1));
-                const uint32_t mag = u >> 1;
-                const bool eq = in && mag == c_eq;
+                const float c = in ? buf[tt * kRow + e] : 0.0f;
+                const uint32_t mg = __float_as_uint(c) & 0x7FFFFFFFu;
+                const bool eq = in && mg == c_eq;
                 const uint64_t eqm = __ballot(eq);
                 const int eq_rank = eq_before + lanes_below(eqm, lane);
-                const bool keep = in && (mag >= c_gt || (eq && eq_rank < c_need));
+                const bool keep = in && (mg >= c_gt || (eq && eq_rank < c_need));
                 const uint64_t km = __ballot(keep);
                 const int pos = kept_before + lanes_below(km, lane);
                 float rem = c;
