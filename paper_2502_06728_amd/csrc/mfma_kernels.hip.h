@@ -209,37 +209,102 @@ __attribute__((amdgpu_waves_per_eu(MfmaGeom<NB>::kWavesPerSimd))) void compress_
         }
         wave_lds_sync();
 
-        // ---- one chunk at a time with the whole wavefront: payload out, remainder in
-        for (int tt = 0; tt < kMfmaChunks; ++tt) {
-            const uint32_t c_gt = __builtin_amdgcn_readlane(thr_gt, tt);
-            const uint32_t c_eq = __builtin_amdgcn_readlane(thr_eq, tt);
-            const int c_need = __builtin_amdgcn_readlane(need, tt);
-            const int64_t chunk = chunk0 + tt;
-            int kept_before = 0, eq_before = 0;
+        // ---- payload out, remainder in.  Chunks whose search ended on an exact count
+        // (need == 0: the kept set is "magnitude >= thr_gt") are finished by their two lanes
+        // in parallel.  Lane (t, h) walks the index groups {8G + 4h + i}, G ascending, of its
+        // LDS row, so the payload position of an element is its rank among the lane's kept
+        // elements plus the partner lane's kept elements with a smaller index: the partner's
+        // whole groups below G and, for h = 1, its group G as well.  The partner's kept set
+        // comes over as a bit mask (bit 4G + i).
+        {
+            constexpr int NW = (NB * 16 + 31) / 32;
+            uint32_t other[NW];
 #pragma unroll
-            for (int e0 = 0; e0 < S; e0 += kWave) {
-                const int e = e0 + lane;
-                const bool in = (S % kWave == 0) || e < S;
-                const float c = in ? buf[tt * kRow + e] : 0.0f;
-                const uint32_t mg = __float_as_uint(c) & 0x7FFFFFFFu;
-                const bool eq = in && mg == c_eq;
-                const uint64_t eqm = __ballot(eq);
-                const int eq_rank = eq_before + lanes_below(eqm, lane);
-                const bool keep = in && (mg >= c_gt || (eq && eq_rank < c_need));
-                const uint64_t km = __ballot(keep);
-                const int pos = kept_before + lanes_below(km, lane);
-                float rem = c;
-                if (keep && pos < k) {
-                    store_payload_index(idx_out, chunk * k + pos, p.idx_u8, e);
-                    store_payload_value(val_out, chunk * k + pos, p.val_dtype, c);
-                    rem = c - payload_roundtrip(p.val_dtype, c);
+            for (int w = 0; w < NW; ++w) {
+                uint32_t own = 0u;
+#pragma unroll
+                for (int r = 0; r < 32 && 32 * w + r < NB * 16; ++r)
+                    own |= (mag[32 * w + r] >= thr_gt ? 1u : 0u) << r;
+                other[w] = static_cast<uint32_t>(__shfl_xor(static_cast<int>(own), 32));
+            }
+            const bool settled = (need == 0);
+            const int64_t cbase = (chunk0 + t) * k;
+            float* row = &buf[t * kRow + 4 * h];
+            float* dbg = coeff_dbg ? coeff_dbg + (chunk0 + t) * S + 4 * h : nullptr;
+            int pos = 0;                       // kept so far: own and partner's lower groups
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                constexpr int kGroupsPerWord = 8;
+                const int groups = (NB * 4 - w * kGroupsPerWord) < kGroupsPerWord
+                                       ? (NB * 4 - w * kGroupsPerWord) : kGroupsPerWord;
+                uint32_t ow = other[w];
+#pragma unroll 2
+                for (int gw = 0; gw < groups; ++gw) {
+                    const int G = w * kGroupsPerWord + gw;
+                    const int pk = __popc(ow & 0xFu);          // partner's kept in group G
+                    ow >>= 4;
+                    if (h) pos += pk;
+                    const float4 c4 = *reinterpret_cast<const float4*>(row + 8 * G);
+                    const float c[4] = {c4.x, c4.y, c4.z, c4.w};
+                    float rem[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const bool keep = (__float_as_uint(c[i]) & 0x7FFFFFFFu) >= thr_gt;
+                        rem[i] = c[i];
+                        if (settled && keep && pos < k) {
+                            store_payload_index(idx_out, cbase + pos, p.idx_u8, 8 * G + 4 * h + i);
+                            store_payload_value(val_out, cbase + pos, p.val_dtype, c[i]);
+                            rem[i] = c[i] - payload_roundtrip(p.val_dtype, c[i]);
+                        }
+                        pos += keep ? 1 : 0;
+                        rem[i] *= (i == 0 && G == 0 && h == 0) ? p.alpha0 : p.alpha;
+                    }
+                    if (!h) pos += pk;
+                    if (settled) {
+                        if (dbg) *reinterpret_cast<float4*>(dbg + 8 * G) = c4;
+                        *reinterpret_cast<float4*>(row + 8 * G) =
+                            make_float4(rem[0], rem[1], rem[2], rem[3]);
+                    }
                 }
-                if (in) {
-                    if (coeff_dbg) coeff_dbg[chunk * S + e] = c;
-                    buf[tt * kRow + e] = rem * (e == 0 ? p.alpha0 : p.alpha);
+            }
+        }
+        wave_lds_sync();
+        // ---- chunks with ties at the k-th magnitude, one at a time with the whole wavefront
+        // (their LDS rows still hold the coefficients): of the entries equal to thr_eq the
+        // `need` lowest indices are kept.
+        if (__any(need != 0)) {
+            for (int tt = 0; tt < kMfmaChunks; ++tt) {
+                const int c_need = __builtin_amdgcn_readlane(need, tt);
+                if (c_need == 0) continue;
+                const uint32_t c_gt = __builtin_amdgcn_readlane(thr_gt, tt);
+                const uint32_t c_eq = __builtin_amdgcn_readlane(thr_eq, tt);
+                const int64_t chunk = chunk0 + tt;
+                int kept_before = 0, eq_before = 0;
+#pragma unroll
+                for (int e0 = 0; e0 < S; e0 += kWave) {
+                    const int e = e0 + lane;
+                    const bool in = (S % kWave == 0) || e < S;
+                    const float c = in ? buf[tt * kRow + e] : 0.0f;
+                    const uint32_t mg = __float_as_uint(c) & 0x7FFFFFFFu;
+                    const bool eq = in && mg == c_eq;
+                    const uint64_t eqm = __ballot(eq);
+                    const int eq_rank = eq_before + lanes_below(eqm, lane);
+                    const bool keep = in && (mg >= c_gt || (eq && eq_rank < c_need));
+                    const uint64_t km = __ballot(keep);
+                    const int pos = kept_before + lanes_below(km, lane);
+                    float rem = c;
+                    if (keep && pos < k) {
+                        store_payload_index(idx_out, chunk * k + pos, p.idx_u8, e);
+                        store_payload_value(val_out, chunk * k + pos, p.val_dtype, c);
+                        rem = c - payload_roundtrip(p.val_dtype, c);
+                    }
+                    if (in) {
+                        if (coeff_dbg) coeff_dbg[chunk * S + e] = c;
+                        buf[tt * kRow + e] = rem * (e == 0 ? p.alpha0 : p.alpha);
+                    }
+                    kept_before += __popcll(km);
+                    eq_before += __popcll(eqm);
                 }
-                kept_before += __popcll(km);
-                eq_before += __popcll(eqm);
             }
         }
         wave_lds_sync();
