@@ -52,35 +52,219 @@ __device__ __forceinline__ void build_cos_table_quarter(float* tab, int lane) {
     }
 }
 
-// acc[b] += A_b * B over the whole contraction length S.  B: the calling lane's LDS row
-// (`row` points at column 4h of row t).  A for output block b: tab[cur[b]], where cur[b]
-// advances by inc[b] (mod 4S) per contraction index; inc5[b] = 5 inc[b] mod 4S bridges the
-// gap between the lane's groups of four consecutive indices.
+__device__ __forceinline__ int lanes_below(uint64_t mask, int lane) {
+    return __popcll(mask & ((1ull << lane) - 1ull));
+}
+
+// Which coefficient / element indices a lane holds after a product.  Lane (t, h) of the
+// wavefront owns, of chunk t, the groups of GS consecutive indices 2*GS*G + GS*h + e
+// (G = 0 .. kGroups-1, e < GS): its partner lane t + 32*(1-h) owns the other half.
+// Chunk sizes that are a multiple of 64 use the symmetry of the cosine (below), which pairs
+// each even index with the odd one after it: GS = 8.
 template <int NB>
-__device__ __forceinline__ void cos_product(const float* __restrict__ row,
-                                            const float* __restrict__ tab, int (&cur)[NB],
-                                            const int (&inc)[NB], const int (&inc5)[NB],
-                                            f32x16_t (&acc)[NB]) {
-    constexpr int S = 32 * NB, W = 4 * S;
+struct MfmaOwn {
+    static constexpr bool kHalf = (NB % 2 == 0);
+    static constexpr int GS = kHalf ? 8 : 4;
+    static constexpr int kGroups = 16 * NB / GS;
+};
+
+__device__ __forceinline__ void zero_acc(f32x16_t& a) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) a[r] = 0.0f;
+}
+
+// One contraction step for all NB output blocks: blocks below HB take b_lo, the others b_hi.
+template <int NB, int HB>
+__device__ __forceinline__ void mfma_step(const float* __restrict__ tab, int (&cur)[NB],
+                                          const int (&inc)[NB], const int (&inc5)[NB],
+                                          f32x16_t (&acc)[NB], float b_lo, float b_hi, bool last) {
+    constexpr int W = 4 * 32 * NB;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        const float a = tab[cur[b]];
+        acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b < HB ? b_lo : b_hi, acc[b], 0, 0, 0);
+        const int nx = cur[b] + (last ? inc5[b] : inc[b]);
+        cur[b] = nx >= W ? nx - W : nx;
+    }
+}
+
+// Forward transform of the tile: row t of `buf` (chunk t, m1) is replaced by its DCT-II
+// coefficients c; mag[] receives the magnitudes (bit patterns) of the coefficients this lane
+// owns, in ascending index order.
+//
+// NB odd:  coefficients^T = D * X^T with all S contraction steps.
+// NB even: cos(pi (2(S-1-n)+1) j / (2S)) = (-1)^j cos(pi (2n+1) j / (2S)), so even rows only
+//          see u_n = x_n + x_{S-1-n} and odd rows w_n = x_n - x_{S-1-n}, n < S/2: half the
+//          contraction length.  Blocks [0, NB/2) hold rows 2m, blocks [NB/2, NB) rows 2m+1.
+template <int NB>
+__device__ __forceinline__ void forward_to_lds(float* __restrict__ buf,
+                                               const float* __restrict__ tab, const KParams& p,
+                                               int t, int h, uint32_t (&mag)[NB * 16]) {
+    using G = MfmaGeom<NB>;
+    constexpr int S = G::S, kRow = G::kRow, W = G::kTab;
+    f32x16_t acc[NB];
+    int cur[NB], inc[NB], inc5[NB];
+    float* row = &buf[t * kRow];
+    if constexpr (!MfmaOwn<NB>::kHalf) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int j = 32 * b + t;
+            cur[b] = ((8 * h + 1) * j) % W;     // contraction index n = 4h first
+            inc[b] = 2 * j;
+            inc5[b] = (10 * j) % W;
+            zero_acc(acc[b]);
+        }
 #pragma unroll 1
-    for (int q = 0; q < S / 8; ++q) {
-        const float4 x = *reinterpret_cast<const float4*>(row + 8 * q);
-        const float xv[4] = {x.x, x.y, x.z, x.w};
+        for (int q = 0; q < S / 8; ++q) {
+            const float4 x = *reinterpret_cast<const float4*>(row + 8 * q + 4 * h);
+            const float xv[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < 4; ++i)
+                mfma_step<NB, NB>(tab, cur, inc, inc5, acc, xv[i], xv[i], i == 3);
+        }
+        wave_lds_sync();
 #pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                const float a = tab[cur[b]];
-                acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, xv[i], acc[b], 0, 0, 0);
-                const int nx = cur[b] + (i < 3 ? inc[b] : inc5[b]);
-                cur[b] = nx >= W ? nx - W : nx;
+        for (int b = 0; b < NB; ++b) {
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const int j0 = 32 * b + 8 * g4 + 4 * h;
+                float c[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    c[i] = acc[b][4 * g4 + i] * p.alpha;
+                    if (b == 0 && g4 == 0 && i == 0 && h == 0) c[i] = acc[0][0] * p.alpha0;
+                    mag[16 * b + 4 * g4 + i] = __float_as_uint(c[i]) & 0x7FFFFFFFu;
+                }
+                *reinterpret_cast<float4*>(row + j0) = make_float4(c[0], c[1], c[2], c[3]);
+            }
+        }
+    } else {
+        constexpr int HB = NB / 2;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int j = (b < HB) ? 2 * (32 * b + t) : 2 * (32 * (b - HB) + t) + 1;
+            cur[b] = ((8 * h + 1) * j) % W;
+            inc[b] = 2 * j;
+            inc5[b] = (10 * j) % W;
+            zero_acc(acc[b]);
+        }
+#pragma unroll 1
+        for (int q = 0; q < S / 16; ++q) {
+            const float4 xa = *reinterpret_cast<const float4*>(row + 8 * q + 4 * h);
+            const float4 xb = *reinterpret_cast<const float4*>(row + S - 8 * q - 4 * h - 4);
+            const float u[4] = {xa.x + xb.w, xa.y + xb.z, xa.z + xb.y, xa.w + xb.x};
+            const float w[4] = {xa.x - xb.w, xa.y - xb.z, xa.z - xb.y, xa.w - xb.x};
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                mfma_step<NB, HB>(tab, cur, inc, inc5, acc, u[i], w[i], i == 3);
+        }
+        wave_lds_sync();
+        // acc[b][r], b < HB, is coefficient 2m and acc[b + HB][r] coefficient 2m + 1 with
+        // m = 32b + 8(r/4) + 4h + r%4: eight consecutive coefficients per (b, r/4)
+#pragma unroll
+        for (int b = 0; b < HB; ++b) {
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const int j0 = 64 * b + 16 * g4 + 8 * h;
+                const int Gp = 4 * b + g4;
+                float c[8];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    c[2 * i] = acc[b][4 * g4 + i] * p.alpha;
+                    c[2 * i + 1] = acc[b + HB][4 * g4 + i] * p.alpha;
+                }
+                if (b == 0 && g4 == 0 && h == 0) c[0] = acc[0][0] * p.alpha0;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) mag[8 * Gp + e] = __float_as_uint(c[e]) & 0x7FFFFFFFu;
+                *reinterpret_cast<float4*>(row + j0) = make_float4(c[0], c[1], c[2], c[3]);
+                *reinterpret_cast<float4*>(row + j0 + 4) = make_float4(c[4], c[5], c[6], c[7]);
             }
         }
     }
 }
 
-__device__ __forceinline__ int lanes_below(uint64_t mask, int lane) {
-    return __popcll(mask & ((1ull << lane) - 1ull));
+// Inverse transform of the tile: row t of `buf` holds a_j' = alpha_j a_j (the scale already
+// applied, or applied by `post`); it is replaced by post(sum_j a_j' cos(pi (2n+1) j / (2S))).
+//
+// NB even: with E_n the sum over even j and O_n the sum over odd j, y_n = E_n + O_n and
+//          y_{S-1-n} = E_n - O_n, so only n < S/2 is computed, each half with S/2 steps.
+//          Blocks [0, NB/2) accumulate E for n = 32b + t, blocks [NB/2, NB) accumulate O.
+template <int NB, class Post>
+__device__ __forceinline__ void inverse_to_lds(float* __restrict__ buf,
+                                               const float* __restrict__ tab, int t, int h,
+                                               Post post) {
+    using G = MfmaGeom<NB>;
+    constexpr int S = G::S, kRow = G::kRow, W = G::kTab;
+    f32x16_t acc[NB];
+    int cur[NB], inc[NB], inc5[NB];
+    float* row = &buf[t * kRow];
+    if constexpr (!MfmaOwn<NB>::kHalf) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int m2 = 2 * (32 * b + t) + 1;
+            cur[b] = (m2 * 4 * h) % W;          // contraction index j = 4h first
+            inc[b] = m2;
+            inc5[b] = (5 * m2) % W;
+            zero_acc(acc[b]);
+        }
+#pragma unroll 1
+        for (int q = 0; q < S / 8; ++q) {
+            const float4 x = *reinterpret_cast<const float4*>(row + 8 * q + 4 * h);
+            const float xv[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                mfma_step<NB, NB>(tab, cur, inc, inc5, acc, xv[i], xv[i], i == 3);
+        }
+        wave_lds_sync();
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const int n0 = 32 * b + 8 * g4 + 4 * h;
+                *reinterpret_cast<float4*>(row + n0) =
+                    make_float4(post(acc[b][4 * g4]), post(acc[b][4 * g4 + 1]),
+                                post(acc[b][4 * g4 + 2]), post(acc[b][4 * g4 + 3]));
+            }
+        }
+    } else {
+        constexpr int HB = NB / 2;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int m2 = 2 * (32 * (b < HB ? b : b - HB) + t) + 1;
+            cur[b] = (((b < HB) ? 8 * h : 8 * h + 1) * m2) % W;   // j = 2*4h (+1) first
+            inc[b] = 2 * m2;
+            inc5[b] = (10 * m2) % W;
+            zero_acc(acc[b]);
+        }
+#pragma unroll 1
+        for (int q = 0; q < S / 16; ++q) {
+            const float4 lo = *reinterpret_cast<const float4*>(row + 16 * q + 8 * h);
+            const float4 hi = *reinterpret_cast<const float4*>(row + 16 * q + 8 * h + 4);
+            const float ev[4] = {lo.x, lo.z, hi.x, hi.z};
+            const float od[4] = {lo.y, lo.w, hi.y, hi.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                mfma_step<NB, HB>(tab, cur, inc, inc5, acc, ev[i], od[i], i == 3);
+        }
+        wave_lds_sync();
+#pragma unroll
+        for (int b = 0; b < HB; ++b) {
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const int n0 = 32 * b + 8 * g4 + 4 * h;
+                float lo4[4], hi4[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float e = acc[b][4 * g4 + i], o = acc[b + HB][4 * g4 + i];
+                    lo4[i] = post(e + o);       // element n0 + i
+                    hi4[i] = post(e - o);       // element S - 1 - (n0 + i)
+                }
+                *reinterpret_cast<float4*>(row + n0) = make_float4(lo4[0], lo4[1], lo4[2], lo4[3]);
+                *reinterpret_cast<float4*>(row + S - 4 - n0) =
+                    make_float4(hi4[3], hi4[2], hi4[1], hi4[0]);
+            }
+        }
+    }
 }
 
 // Compress half on full tiles of 32 chunks (top-k selection, DCT domain).
@@ -128,40 +312,9 @@ __attribute__((amdgpu_waves_per_eu(MfmaGeom<NB>::kWavesPerSimd))) void compress_
         }
         wave_lds_sync();
 
-        // ---- coefficients^T = D * X^T: lane's A rows are j = 32b + t
-        f32x16_t acc[NB];
-        int cur[NB], inc[NB], inc5[NB];
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const int j = 32 * b + t;
-            cur[b] = ((8 * h + 1) * j) % W;     // contraction index n = 4h first
-            inc[b] = 2 * j;
-            inc5[b] = (10 * j) % W;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[b][r] = 0.0f;
-        }
-        cos_product<NB>(&buf[t * kRow + 4 * h], tab, cur, inc, inc5, acc);
-        wave_lds_sync();
-        // acc[b][r] is coefficient j = 32b + 8(r/4) + 4h + r%4 of chunk t: lanes t and t+32
-        // hold half of the chunk each.  The coefficients go to the LDS rows; their magnitudes
-        // (bit patterns, 31 bits) stay in registers for the selection.
+        // ---- DCT-II of every chunk of the tile, coefficients into the LDS rows
         uint32_t mag[NB * 16];
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-#pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                const int j0 = 32 * b + 8 * g4 + 4 * h;
-                float c[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    c[i] = acc[b][4 * g4 + i] * p.alpha;
-                    if (b == 0 && g4 == 0 && i == 0 && h == 0) c[i] = acc[0][0] * p.alpha0;
-                    mag[16 * b + 4 * g4 + i] = __float_as_uint(c[i]) & 0x7FFFFFFFu;
-                }
-                *reinterpret_cast<float4*>(&buf[t * kRow + j0]) =
-                    make_float4(c[0], c[1], c[2], c[3]);
-            }
-        }
+        forward_to_lds<NB>(buf, tab, p, t, h, mag);
 
         // ---- k-th largest magnitude of chunk t by binary search on its bits, counting in
         // registers: mag - cand is exact in 32 bits and its sign bit says "below cand"; the
@@ -211,13 +364,15 @@ __attribute__((amdgpu_waves_per_eu(MfmaGeom<NB>::kWavesPerSimd))) void compress_
 
         // ---- payload out, remainder in.  Chunks whose search ended on an exact count
         // (need == 0: the kept set is "magnitude >= thr_gt") are finished by their two lanes
-        // in parallel.  Lane (t, h) walks the index groups {8G + 4h + i}, G ascending, of its
-        // LDS row, so the payload position of an element is its rank among the lane's kept
-        // elements plus the partner lane's kept elements with a smaller index: the partner's
-        // whole groups below G and, for h = 1, its group G as well.  The partner's kept set
-        // comes over as a bit mask (bit 4G + i).
+        // in parallel.  Lane (t, h) walks its index groups in ascending order, so the payload
+        // position of an element is its rank among the lane's kept elements plus the partner
+        // lane's kept elements with a smaller index: the partner's whole groups below G and,
+        // for h = 1, its group G as well.  The partner's kept set comes over as a bit mask
+        // (bit GS*G + e).
         {
+            constexpr int GS = MfmaOwn<NB>::GS;
             constexpr int NW = (NB * 16 + 31) / 32;
+            constexpr int kGroupsPerWord = 32 / GS;
             uint32_t other[NW];
 #pragma unroll
             for (int w = 0; w < NW; ++w) {
@@ -229,41 +384,50 @@ __attribute__((amdgpu_waves_per_eu(MfmaGeom<NB>::kWavesPerSimd))) void compress_
             }
             const bool settled = (need == 0);
             const int64_t cbase = (chunk0 + t) * k;
-            float* row = &buf[t * kRow + 4 * h];
-            float* dbg = coeff_dbg ? coeff_dbg + (chunk0 + t) * S + 4 * h : nullptr;
+            float* row = &buf[t * kRow + GS * h];
+            float* dbg = coeff_dbg ? coeff_dbg + (chunk0 + t) * S + GS * h : nullptr;
             int pos = 0;                       // kept so far: own and partner's lower groups
 #pragma unroll
             for (int w = 0; w < NW; ++w) {
-                constexpr int kGroupsPerWord = 8;
-                const int groups = (NB * 4 - w * kGroupsPerWord) < kGroupsPerWord
-                                       ? (NB * 4 - w * kGroupsPerWord) : kGroupsPerWord;
+                const int left = MfmaOwn<NB>::kGroups - w * kGroupsPerWord;
+                const int groups = left < kGroupsPerWord ? left : kGroupsPerWord;
                 uint32_t ow = other[w];
 #pragma unroll 2
                 for (int gw = 0; gw < groups; ++gw) {
                     const int G = w * kGroupsPerWord + gw;
-                    const int pk = __popc(ow & 0xFu);          // partner's kept in group G
-                    ow >>= 4;
+                    const int pk = __popc(ow & ((1u << GS) - 1u));   // partner's kept in group G
+                    ow >>= GS;
                     if (h) pos += pk;
-                    const float4 c4 = *reinterpret_cast<const float4*>(row + 8 * G);
-                    const float c[4] = {c4.x, c4.y, c4.z, c4.w};
-                    float rem[4];
+                    float c[GS], rem[GS];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const bool keep = (__float_as_uint(c[i]) & 0x7FFFFFFFu) >= thr_gt;
-                        rem[i] = c[i];
+                    for (int v = 0; v < GS / 4; ++v) {
+                        const float4 c4 =
+                            *reinterpret_cast<const float4*>(row + 2 * GS * G + 4 * v);
+                        c[4 * v] = c4.x; c[4 * v + 1] = c4.y; c[4 * v + 2] = c4.z; c[4 * v + 3] = c4.w;
+                    }
+#pragma unroll
+                    for (int e = 0; e < GS; ++e) {
+                        const bool keep = (__float_as_uint(c[e]) & 0x7FFFFFFFu) >= thr_gt;
+                        rem[e] = c[e];
                         if (settled && keep && pos < k) {
-                            store_payload_index(idx_out, cbase + pos, p.idx_u8, 8 * G + 4 * h + i);
-                            store_payload_value(val_out, cbase + pos, p.val_dtype, c[i]);
-                            rem[i] = c[i] - payload_roundtrip(p.val_dtype, c[i]);
+                            store_payload_index(idx_out, cbase + pos, p.idx_u8,
+                                                2 * GS * G + GS * h + e);
+                            store_payload_value(val_out, cbase + pos, p.val_dtype, c[e]);
+                            rem[e] = c[e] - payload_roundtrip(p.val_dtype, c[e]);
                         }
                         pos += keep ? 1 : 0;
-                        rem[i] *= (i == 0 && G == 0 && h == 0) ? p.alpha0 : p.alpha;
+                        rem[e] *= (e == 0 && G == 0 && h == 0) ? p.alpha0 : p.alpha;
                     }
                     if (!h) pos += pk;
                     if (settled) {
-                        if (dbg) *reinterpret_cast<float4*>(dbg + 8 * G) = c4;
-                        *reinterpret_cast<float4*>(row + 8 * G) =
-                            make_float4(rem[0], rem[1], rem[2], rem[3]);
+#pragma unroll
+                        for (int v = 0; v < GS / 4; ++v) {
+                            if (dbg)
+                                *reinterpret_cast<float4*>(dbg + 2 * GS * G + 4 * v) = make_float4(
+                                    c[4 * v], c[4 * v + 1], c[4 * v + 2], c[4 * v + 3]);
+                            *reinterpret_cast<float4*>(row + 2 * GS * G + 4 * v) = make_float4(
+                                rem[4 * v], rem[4 * v + 1], rem[4 * v + 2], rem[4 * v + 3]);
+                        }
                     }
                 }
             }
@@ -309,28 +473,8 @@ __attribute__((amdgpu_waves_per_eu(MfmaGeom<NB>::kWavesPerSimd))) void compress_
         }
         wave_lds_sync();
 
-        // ---- new momentum^T = D^T * remainder^T: lane's A rows are n = 32b + t
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const int m2 = 2 * (32 * b + t) + 1;
-            cur[b] = (m2 * 4 * h) % W;          // contraction index j = 4h first
-            inc[b] = m2;
-            inc5[b] = (5 * m2) % W;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[b][r] = 0.0f;
-        }
-        cos_product<NB>(&buf[t * kRow + 4 * h], tab, cur, inc, inc5, acc);
-        wave_lds_sync();
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-#pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                const int n0 = 32 * b + 8 * g4 + 4 * h;
-                *reinterpret_cast<float4*>(&buf[t * kRow + n0]) =
-                    make_float4(acc[b][4 * g4], acc[b][4 * g4 + 1], acc[b][4 * g4 + 2],
-                                acc[b][4 * g4 + 3]);
-            }
-        }
+        // ---- new momentum = inverse transform of the remainder
+        inverse_to_lds<NB>(buf, tab, t, h, [](float y) { return y; });
         wave_lds_sync();
 #pragma unroll 4
         for (int it = 0; it < G::kVecIters; ++it) {
@@ -537,32 +681,9 @@ __attribute__((amdgpu_waves_per_eu(MfmaGeom<NB>::kWavesPerSimd))) void decompres
 
         // ---- y^T = D^T * (alpha_j a_j / R)^T; the scale is applied to the result:
         // y = (alpha/R) * sum_j a_j cos(..) + ((alpha0 - alpha)/R) * a_0
-        const float a0 = buf[t * kRow];
-        f32x16_t acc[NB];
-        int cur[NB], inc[NB], inc5[NB];
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const int m2 = 2 * (32 * b + t) + 1;
-            cur[b] = (m2 * 4 * h) % W;
-            inc[b] = m2;
-            inc5[b] = (5 * m2) % W;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[b][r] = 0.0f;
-        }
-        cos_product<NB>(&buf[t * kRow + 4 * h], tab, cur, inc, inc5, acc);
-        wave_lds_sync();
-        const float fix = row0_fix * a0;
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-#pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                const int n0 = 32 * b + 8 * g4 + 4 * h;
-                *reinterpret_cast<float4*>(&buf[t * kRow + n0]) = make_float4(
-                    fmaf(acc[b][4 * g4], out_scale, fix), fmaf(acc[b][4 * g4 + 1], out_scale, fix),
-                    fmaf(acc[b][4 * g4 + 2], out_scale, fix),
-                    fmaf(acc[b][4 * g4 + 3], out_scale, fix));
-            }
-        }
+        const float fix = row0_fix * buf[t * kRow];
+        inverse_to_lds<NB>(buf, tab, t, h,
+                           [out_scale, fix](float y) { return fmaf(y, out_scale, fix); });
         wave_lds_sync();
 
         // ---- sign and parameter update, coalesced
