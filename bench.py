@@ -290,6 +290,29 @@ def report(args) -> int:
               f"{allc['value'] / 1e6:.1f} M ({allc['cores']} cores) | "
               f"{rec['value'] / allc['value']:.0f}x |")
     print()
+    # chunk-size sweep of Appendix B ("DeMo Chunk Size": 16 ... 256 at compression rates 1/8 and
+    # 1/16) on the OLMo-1B shard, GPU only
+    sweep = []
+    for rate in (8, 16):
+        for s_ in (16, 32, 64, 96, 128, 192, 256):
+            a = copy.copy(args)
+            a.workload, a.scheme, a.dct = "olmo-1b-1of8", "topk", False
+            a.chunk, a.topk = s_, s_ // rate
+            a.steps, a.warmup, a.no_cpu = min(args.steps, 20), 3, True
+            sweep.append(run(a))
+            print(f"# done chunk {s_} rate 1/{rate}", file=sys.stderr, flush=True)
+    print("Chunk-size sweep (Appendix B, \"DeMo Chunk Size\"), olmo-1b-1of8, top-k, R = 4:")
+    print()
+    print("| chunk | top-k | rate | compress ms | decompress ms | step ms | GPU params/s | "
+          "step GB/s (% of 8 TB/s) |")
+    print("|---|---|---|---|---|---|---|---|")
+    for rec in sweep:
+        c = rec["config"]
+        print(f"| {c['chunk']} | {c['topk']} | 1/{c['chunk'] // c['topk']} | "
+              f"{rec['kernels']['compress']['ms']:.3f} | {rec['kernels']['decompress']['ms']:.3f} | "
+              f"{rec['ms_per_step']:.3f} | {rec['value'] / 1e9:.1f} G | {rec['step_hbm_gbs']:.0f} "
+              f"({100 * rec['step_hbm_frac_of_peak']:.0f} %) |")
+    print()
     print("Oracle: the CPU reference as it stands (plain C, double arithmetic, gcc -O2, OpenMP over "
           "chunks), one full step on the leading parameters of the same shard (all cores: up to "
           "67 M parameters; 1 core: 4 M), rate scaled per parameter.  flat-1m fits the caches "
