@@ -19,7 +19,7 @@ _SRC = os.path.join(_HERE, "detonation_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
 
 SCHEME_TOPK, SCHEME_STRIDE, SCHEME_RANDOM = 0, 1, 2
-F32, BF16, F16 = 0, 1, 2
+F32, BF16, F16, TERNARY = 0, 1, 2, 3
 FLAG_SIGN, FLAG_DCT = 1, 2
 
 
@@ -95,6 +95,7 @@ def lib() -> ctypes.CDLL:
         _lib.orc_float_to_f16.argtypes = [ctypes.c_float]
         _lib.orc_f16_to_float.restype = ctypes.c_float
         _lib.orc_f16_to_float.argtypes = [ctypes.c_uint16]
+        _lib.orc_ternary_words.restype = ctypes.c_int64
     return _lib
 
 
@@ -225,6 +226,47 @@ def presign_q(cfg: Config, n: int, idx, val_bits: np.ndarray, val_dtype: int) ->
     _chk(lib().orc_presign_q(ctypes.byref(cfg.c()), ctypes.c_int64(n), ctypes.c_int32(R), _p(idx),
                              ctypes.c_int64(0 if idx is None else idx.shape[1]), _p(val_bits),
                              ctypes.c_int(val_dtype), ctypes.c_int64(val_bits.shape[1]), _p(y)))
+    return y
+
+
+def ternary_words(cfg: Config, n: int) -> int:
+    """32-bit words of one replica's ternary payload: chunks * ceil(k/16)."""
+    return int(lib().orc_ternary_words(ctypes.byref(cfg.c()), ctypes.c_int64(n)))
+
+
+def encode_ternary(cfg: Config, n: int, val: np.ndarray) -> np.ndarray:
+    """sign(val) packed two bits per entry (0, 1 = +1, 3 = -1), each chunk on a word boundary."""
+    val = _c(val, np.float32)
+    words = np.empty(ternary_words(cfg, n), dtype=np.uint32)
+    _chk(lib().orc_encode_ternary(ctypes.byref(cfg.c()), ctypes.c_int64(n), _p(val), _p(words)))
+    return words
+
+
+def decode_ternary(cfg: Config, n: int, words: np.ndarray) -> np.ndarray:
+    words = _c(words, np.uint32)
+    val = np.empty(n_chunks(cfg, n) * cfg.topk, dtype=np.float32)
+    _chk(lib().orc_decode_ternary(ctypes.byref(cfg.c()), ctypes.c_int64(n), _p(words), _p(val)))
+    return val
+
+
+def compress_t(cfg: Config, grad: np.ndarray, momentum: np.ndarray):
+    """Compress half with the ternary payload: the steps of compress(), then only the signs of
+    the kept values travel.  Returns (m_new, idx, words); the momentum is that of compress()."""
+    m_new, idx, val = compress(cfg, grad, momentum)
+    return m_new, idx, encode_ternary(cfg, np.asarray(momentum).size, val)
+
+
+def presign_t(cfg: Config, n: int, idx, words: np.ndarray) -> np.ndarray:
+    words = _c(words, np.uint32)
+    if words.ndim == 1:
+        words = words[None, :]
+    R = words.shape[0]
+    if idx is not None:
+        idx = _c(idx, np.int32).reshape(R, -1)
+    y = np.empty(n, dtype=np.float32)
+    _chk(lib().orc_presign_t(ctypes.byref(cfg.c()), ctypes.c_int64(n), ctypes.c_int32(R), _p(idx),
+                             ctypes.c_int64(0 if idx is None else idx.shape[1]), _p(words),
+                             ctypes.c_int64(words.shape[1]), _p(y)))
     return y
 
 

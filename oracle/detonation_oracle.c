@@ -449,6 +449,72 @@ int orc_presign_q(const orc_config *cfg, int64_t n, int32_t R, const int32_t *id
     return rc;
 }
 
+/* ------------------------------------------------- ternary payload (sign before sync)
+ * Discussion ("using sign before synchronizing ... The ternary system enables compressing the
+ * data even more") and Appendix B "Sign vs. No Sign": what travels is sign(c) in {-1, 0, +1}
+ * of each kept coefficient (sign(0) = 0, as torch.sign).  Two bits per entry: 0 = zero,
+ * 1 = +1, 3 = -1 (2 is never written and decodes to 0); 16 entries per 32-bit word, entry j
+ * of chunk c in word c*W + j/16 at bits [2*(j%16), 2*(j%16)+2), W = ceil(k/16), so every chunk
+ * starts on a word boundary.  The momentum loses the extracted components themselves
+ * (Algorithm 1, "remove q from m"), whatever goes on the wire. */
+int64_t orc_ternary_words(const orc_config *cfg, int64_t n)
+{
+    if (orc_check(cfg) || n < 0) return -1;
+    return ((n + cfg->chunk - 1) / cfg->chunk) * ((cfg->topk + 15) / 16);
+}
+
+int orc_encode_ternary(const orc_config *cfg, int64_t n, const float *val, uint32_t *words)
+{
+    int rc = orc_check(cfg);
+    if (rc) return rc;
+    if (n > 0 && (!val || !words)) return ORC_ERR_NULL;
+    const int k = cfg->topk, W = (k + 15) / 16;
+    const int64_t C = (n + cfg->chunk - 1) / cfg->chunk;
+    for (int64_t c = 0; c < C; ++c) {
+        for (int w = 0; w < W; ++w) words[c * W + w] = 0u;
+        for (int j = 0; j < k; ++j) {
+            const float v = val[c * k + j];
+            const uint32_t code = v > 0.0f ? 1u : (v < 0.0f ? 3u : 0u);
+            words[c * W + j / 16] |= code << (2 * (j % 16));
+        }
+    }
+    return ORC_OK;
+}
+
+int orc_decode_ternary(const orc_config *cfg, int64_t n, const uint32_t *words, float *val)
+{
+    int rc = orc_check(cfg);
+    if (rc) return rc;
+    if (n > 0 && (!val || !words)) return ORC_ERR_NULL;
+    const int k = cfg->topk, W = (k + 15) / 16;
+    const int64_t C = (n + cfg->chunk - 1) / cfg->chunk;
+    for (int64_t c = 0; c < C; ++c)
+        for (int j = 0; j < k; ++j) {
+            const uint32_t code = (words[c * W + j / 16] >> (2 * (j % 16))) & 3u;
+            val[c * k + j] = code == 1u ? 1.0f : (code == 3u ? -1.0f : 0.0f);
+        }
+    return ORC_OK;
+}
+
+/* Averaged update before sign from R ternary payloads (word_replica_stride in 32-bit words). */
+int orc_presign_t(const orc_config *cfg, int64_t n, int32_t R, const int32_t *idx,
+                  int64_t idx_replica_stride, const uint32_t *words, int64_t word_replica_stride,
+                  float *y)
+{
+    int rc = orc_check(cfg);
+    if (rc) return rc;
+    if (R < 1) return ORC_ERR_BAD_CONFIG;
+    if (n == 0) return ORC_OK;
+    if (!words || !y) return ORC_ERR_NULL;
+    const int64_t entries = ((n + cfg->chunk - 1) / cfg->chunk) * cfg->topk;
+    float *val = (float *)malloc(sizeof(float) * (size_t)(R * entries));
+    for (int r = 0; r < R && !rc; ++r)
+        rc = orc_decode_ternary(cfg, n, words + r * word_replica_stride, val + r * entries);
+    if (!rc) rc = orc_presign(cfg, n, R, idx, idx_replica_stride, val, entries, y);
+    free(val);
+    return rc;
+}
+
 /* The whole compress half: fold, transform, select, extract.
  * momentum is updated in place; idx_out may be NULL (Striding/Random callers do
  * not need it); coeff_out may be NULL. */

@@ -527,3 +527,75 @@ def test_adamw_first_step_with_sign_is_a_unit_step():
     exact = synth.from_bf16_bits(thb).astype(np.float64) - np.float64(np.float32(1e-3)) * np.sign(y)
     got = synth.from_bf16_bits(th1b).astype(np.float64)
     assert (np.abs(got - exact) <= np.abs(exact) * 2.0 ** -8 + 1e-30).all()
+
+
+# ------------------------------------------- ternary payload (Discussion, "sign before synchronizing")
+
+def _golden_ternary():
+    out = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "ternary_words.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        case, w, v = line.split()
+        out.setdefault(case, {})[int(w)] = int(v)
+    return out
+
+
+def test_ternary_layout_matches_the_hand_worked_words():
+    gold = _golden_ternary()
+    cfg = Config(chunk=8, topk=5)
+    words = oracle.encode_ternary(cfg, 8, np.array([2.5, -0.0, -1e-30, 0.0, 7.0], np.float32))
+    assert words.tolist() == [gold["A"][0]]
+    cfg = Config(chunk=32, topk=18)
+    val = np.concatenate([np.full(18, -1.0), [1.0], np.zeros(16), [-1.0]]).astype(np.float32)
+    words = oracle.encode_ternary(cfg, 64, val)
+    assert oracle.ternary_words(cfg, 64) == 4
+    assert words.tolist() == [gold["B"][i] for i in range(4)]
+    assert np.array_equal(oracle.decode_ternary(cfg, 64, words), np.sign(val))
+
+
+def test_ternary_decode_of_encode_is_numpy_sign_and_reserved_code_is_zero():
+    cfg = Config(chunk=64, topk=23)
+    n = 64 * 37
+    rng = np.random.default_rng(4)
+    val = (rng.standard_normal(37 * 23) * 10.0 ** rng.integers(-40, 38, 37 * 23)).astype(np.float32)
+    val[::7] = 0.0
+    val[3::11] = -0.0
+    val[5] = np.float32(1e-45)            # smallest subnormal
+    val[6] = -np.float32(1e-45)
+    val[8], val[9] = np.inf, -np.inf
+    words = oracle.encode_ternary(cfg, n, val)
+    assert words.size == 37 * 2
+    assert np.array_equal(oracle.decode_ternary(cfg, n, words), np.sign(val))
+    # the bits above entry k-1 of a chunk's last word stay clear
+    assert not (words[1::2] >> np.uint32(2 * (23 - 16))).any()
+    # code 2 is never written; a decoder maps it to 0
+    bad = np.array([2 | (2 << 2) | (1 << 4)], np.uint32)
+    assert oracle.decode_ternary(Config(chunk=4, topk=3), 4, bad).tolist() == [0.0, 0.0, 1.0]
+
+
+@pytest.mark.parametrize("scheme", [SCHEME_TOPK, SCHEME_RANDOM])
+def test_ternary_compress_and_presign_reduce_to_the_fp32_path_on_signs(scheme):
+    s, k, n, R = 32, 20, 32 * 50 + 7, 3
+    cfg = Config(chunk=s, topk=k, scheme=scheme, seed=3, step=1, sign=False)
+    pays, words = [], []
+    for r in range(R):
+        g, m = rnd(400 + r, n, 1e-3), rnd(500 + r, n, 1e-3)
+        m_t, idx_t, w_t = oracle.compress_t(cfg, g, m)
+        m_f, idx_f, val_f = oracle.compress(cfg, g, m)
+        # Algorithm 1: the momentum loses the extracted components themselves
+        assert np.array_equal(m_t, m_f) and np.array_equal(idx_t, idx_f)
+        assert np.array_equal(oracle.decode_ternary(cfg, n, w_t), np.sign(val_f))
+        pays.append((idx_f, np.sign(val_f).astype(np.float32)))
+        words.append(w_t)
+    idx = np.stack([p[0] for p in pays])
+    y_t = oracle.presign_t(cfg, n, idx, np.stack(words))
+    y_f = oracle.presign(cfg, n, idx, np.stack([p[1] for p in pays]))
+    assert np.array_equal(y_t, y_f)
+    # identity domain, one replica: the pre-sign update is exactly the sign pattern
+    if scheme == SCHEME_RANDOM:
+        y1 = oracle.presign_t(cfg, n, idx[:1], words[0][None])
+        dense = np.zeros(-(-n // s) * s, np.float32)
+        at = (np.arange(idx.shape[1]) // k) * s + idx[0]
+        dense[at] = pays[0][1]
+        assert np.array_equal(y1, dense[:n])
