@@ -57,8 +57,8 @@ typedef enum {
 typedef enum { DETO_SCHEME_TOPK = 0, DETO_SCHEME_STRIDE = 1, DETO_SCHEME_RANDOM = 2 } deto_scheme;
 
 /* Element types.  Gradients and parameters are F32 or BF16; payload values may also be F16
- * (IEEE half). */
-typedef enum { DETO_F32 = 0, DETO_BF16 = 1, DETO_F16 = 2 } deto_dtype;
+ * (IEEE half) or TERNARY (only the sign, two bits per entry; see detonation_compress_packed). */
+typedef enum { DETO_F32 = 0, DETO_BF16 = 1, DETO_F16 = 2, DETO_TERNARY = 3 } deto_dtype;
 
 /* Payload index width: chunk-local indices always fit a byte (s <= 256). */
 typedef enum { DETO_IDX_I32 = 0, DETO_IDX_U8 = 1 } deto_idx_dtype;
@@ -146,6 +146,16 @@ int detonation_decompress_step(const deto_config* cfg, int64_t n, int32_t R,
  * argument rules and the error codes are those of detonation_compress and
  * detonation_decompress_step, which are these calls with DETO_IDX_I32 and DETO_F32; replica
  * strides are in elements of the respective dtype.
+ *
+ * DETO_TERNARY is the paper's "sign before synchronization" (Discussion; Appendix B "Sign vs.
+ * No Sign"): only sign(c) in {-1, 0, +1} of each kept coefficient travels (sign(0) = 0).  Two
+ * bits per entry (0 = zero, 1 = +1, 3 = -1; 2 is never written and decodes to 0), 16 entries
+ * per uint32 word, entry j of chunk ch in word ch*W + j/16 at bits [2*(j%16), 2*(j%16)+2),
+ * W = ceil(k/16): every chunk starts on a word boundary and val_out / val hold
+ * detonation_ternary_words(cfg, n) = C*W words per replica (replica stride in words, pointers
+ * 4-byte aligned).  The momentum gives up the extracted components themselves (Algorithm 1,
+ * "remove q from m"), as with DETO_F32.  The receivers average the signs of the R replicas,
+ * transform back and, with DETO_FLAG_SIGN, take the sign of the result once more.
  */
 int detonation_compress_packed(const deto_config* cfg, int64_t n,
                                const void* grad, int grad_dtype,
@@ -200,10 +210,14 @@ int detonation_decompress_adamw_step(const deto_config* cfg, const deto_adamw* o
  * padded shard length); -1 if cfg is invalid. */
 int64_t detonation_payload_entries(const deto_config* cfg, int64_t n);
 
+/* 32-bit words of one replica's DETO_TERNARY payload, ceil(n/s)*ceil(k/16); -1 if cfg is
+ * invalid. */
+int64_t detonation_ternary_words(const deto_config* cfg, int64_t n);
+
 /* Static, human-readable name of a deto_status. */
 const char* detonation_status_string(int status);
 
-/* ABI version of this header: major*1000 + minor (1001: the *_packed entry points; 1002: Decoupled AdamW). */
+/* ABI version of this header: major*1000 + minor (1001: the *_packed entry points; 1002: Decoupled AdamW; 1003: DETO_TERNARY). */
 int detonation_version(void);
 
 #ifdef __cplusplus

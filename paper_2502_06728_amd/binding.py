@@ -15,13 +15,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("DETONATION_LIB", os.path.join(_HERE, "libdetonation.so"))
 
 SCHEME_TOPK, SCHEME_STRIDE, SCHEME_RANDOM = 0, 1, 2
-F32, BF16, F16 = 0, 1, 2
+F32, BF16, F16, TERNARY = 0, 1, 2, 3
 IDX_I32, IDX_U8 = 0, 1
 FLAG_SIGN, FLAG_DCT = 1, 2
 
 EXPORTS = ("detonation_compress", "detonation_decompress_step", "detonation_compress_packed",
            "detonation_decompress_step_packed", "detonation_decompress_adamw_step",
-           "detonation_payload_entries",
+           "detonation_payload_entries", "detonation_ternary_words",
            "detonation_status_string", "detonation_version")
 
 
@@ -105,6 +105,8 @@ def load() -> ctypes.CDLL:
         lib.detonation_decompress_adamw_step.restype = ctypes.c_int
         lib.detonation_payload_entries.argtypes = [cfgp, i64]
         lib.detonation_payload_entries.restype = i64
+        lib.detonation_ternary_words.argtypes = [cfgp, i64]
+        lib.detonation_ternary_words.restype = i64
         lib.detonation_status_string.argtypes = [ctypes.c_int]
         lib.detonation_status_string.restype = ctypes.c_char_p
         lib.detonation_version.restype = ctypes.c_int
@@ -124,6 +126,10 @@ def payload_entries(cfg: Config, n: int) -> int:
     return int(load().detonation_payload_entries(ctypes.byref(cfg.c()), n))
 
 
+def ternary_words(cfg: Config, n: int) -> int:
+    return int(load().detonation_ternary_words(ctypes.byref(cfg.c()), n))
+
+
 def _ptr(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
@@ -137,6 +143,12 @@ def _dtype(t) -> int:
     if t.dtype == torch.float16:
         return F16
     raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _val_dtype(t) -> int:
+    """Payload value format from the tensor's dtype; an int32 tensor holds ternary words."""
+    import torch
+    return TERNARY if t.dtype == torch.int32 else _dtype(t)
 
 
 def _idx_dtype(t) -> int:
@@ -196,12 +208,12 @@ def detonation_decompress_step(cfg: Config, R: int, idx, val, params, presign_db
 def detonation_compress_packed(cfg: Config, grad, momentum, idx_out, val_out, coeff_dbg=None,
                                stream=None, n: int | None = None) -> None:
     """Compress half with the payload format given by the output tensors' dtypes: indices
-    int32 or uint8, values float32, bfloat16 or float16."""
+    int32 or uint8, values float32, bfloat16, float16, or int32 words of the ternary payload."""
     _check(grad, momentum, idx_out, val_out, coeff_dbg)
     n = momentum.numel() if n is None else n
     rc = load().detonation_compress_packed(ctypes.byref(cfg.c()), n, _ptr(grad), _dtype(grad),
                                            _ptr(momentum), _ptr(idx_out), _idx_dtype(idx_out),
-                                           _ptr(val_out), _dtype(val_out), _ptr(coeff_dbg),
+                                           _ptr(val_out), _val_dtype(val_out), _ptr(coeff_dbg),
                                            _stream(stream))
     if rc != 0:
         raise DetonationError(rc)
@@ -215,10 +227,13 @@ def detonation_decompress_step_packed(cfg: Config, R: int, idx, val, params, pre
     _check(idx, val, params, presign_dbg)
     n = params.numel() if n is None else n
     entries = payload_entries(cfg, n)
-    vs = entries if val_replica_stride is None else val_replica_stride
+    vdt = _val_dtype(val)
+    vs = val_replica_stride
+    if vs is None:
+        vs = ternary_words(cfg, n) if vdt == TERNARY else entries
     istr = entries if idx_replica_stride is None else idx_replica_stride
     rc = load().detonation_decompress_step_packed(ctypes.byref(cfg.c()), n, R, _ptr(idx),
-                                                  _idx_dtype(idx), istr, _ptr(val), _dtype(val), vs,
+                                                  _idx_dtype(idx), istr, _ptr(val), vdt, vs,
                                                   _ptr(params), _dtype(params), _ptr(presign_dbg),
                                                   _stream(stream))
     if rc != 0:

@@ -30,13 +30,15 @@ int validate(const deto_config* cfg) {
 
 bool valid_dtype(int d) { return d == DETO_F32 || d == DETO_BF16; }
 
-bool valid_val_dtype(int d) { return d == DETO_F32 || d == DETO_BF16 || d == DETO_F16; }
+bool valid_val_dtype(int d) {
+    return d == DETO_F32 || d == DETO_BF16 || d == DETO_F16 || d == DETO_TERNARY;
+}
 
 bool valid_idx_dtype(int d) { return d == DETO_IDX_I32 || d == DETO_IDX_U8; }
 
 size_t idx_size(int d) { return d == DETO_IDX_U8 ? 1 : 4; }
 
-size_t val_size(int d) { return d == DETO_F32 ? 4 : 2; }
+size_t val_size(int d) { return (d == DETO_F32 || d == DETO_TERNARY) ? 4 : 2; }
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
@@ -213,7 +215,9 @@ int decompress_impl(const deto_config* cfg, const deto_adamw* opt, int64_t n, in
     }
     const int64_t C = chunks_of(n, p.s);
     const int64_t entries = C * p.k;
-    if (R > 1 && (val_replica_stride < entries || (idx && idx_replica_stride < entries)))
+    // a replica's values: one element per entry, or ceil(k/16) words per chunk (ternary)
+    const int64_t val_elems = val_dtype == DETO_TERNARY ? C * ((p.k + 15) / 16) : entries;
+    if (R > 1 && (val_replica_stride < val_elems || (idx && idx_replica_stride < entries)))
         return DETO_ERR_BAD_CONFIG;
     hipStream_t st = static_cast<hipStream_t>(stream);
 
@@ -306,6 +310,11 @@ int64_t detonation_payload_entries(const deto_config* cfg, int64_t n) {
     return chunks_of(n, cfg->chunk) * cfg->topk;
 }
 
+int64_t detonation_ternary_words(const deto_config* cfg, int64_t n) {
+    if (validate(cfg) != DETO_OK || n < 0) return -1;
+    return chunks_of(n, cfg->chunk) * ((cfg->topk + 15) / 16);
+}
+
 const char* detonation_status_string(int status) {
     switch (status) {
         case DETO_OK: return "ok";
@@ -318,6 +327,6 @@ const char* detonation_status_string(int status) {
     }
 }
 
-int detonation_version(void) { return 1002; }
+int detonation_version(void) { return 1003; }
 
 }  // extern "C"

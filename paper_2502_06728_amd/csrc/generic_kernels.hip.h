@@ -68,11 +68,47 @@ __device__ __forceinline__ void compact_flags(int s, int lane, const int* flag, 
 }
 
 // Payload access in whatever format the caller chose (runtime switch: these kernels are the
-// general path).
+// general path).  What the momentum gives up for a kept coefficient v: the value the receivers
+// decode for the 16-bit formats; v itself for fp32 and for the ternary payload (Algorithm 1:
+// the extracted components leave the momentum, whatever goes on the wire).
 __device__ __forceinline__ float payload_roundtrip(int val_dtype, float v) {
     if (val_dtype == 1) return decode16<1>(encode16<1>(v));
     if (val_dtype == 2) return decode16<2>(encode16<2>(v));
     return v;
+}
+
+// ---- ternary payload: sign(v) in two bits (0 = zero, 1 = +1, 3 = -1), 16 entries per 32-bit
+// word, every chunk on a word boundary (ceil(k/16) words per chunk).
+__device__ __forceinline__ int ternary_words_per_chunk(int k) { return (k + 15) >> 4; }
+
+// bit i of x (i < 16) -> bit 2i
+__device__ __forceinline__ uint32_t spread16(uint32_t x) {
+    x = (x | (x << 8)) & 0x00FF00FFu;
+    x = (x | (x << 4)) & 0x0F0F0F0Fu;
+    x = (x | (x << 2)) & 0x33333333u;
+    x = (x | (x << 1)) & 0x55555555u;
+    return x;
+}
+
+__device__ __forceinline__ float ternary_decode(uint32_t word, int j) {
+    const uint32_t code = (word >> (2 * (j & 15))) & 3u;
+    return (code & 1u) ? ((code & 2u) ? -1.0f : 1.0f) : 0.0f;
+}
+
+// The k kept values of one chunk, sval[0..k) in LDS, to the chunk's words (whole wavefront).
+__device__ __forceinline__ void store_ternary_chunk(uint32_t* __restrict__ words, int k, int lane,
+                                                    const float* sval) {
+    for (int j0 = 0; j0 < k; j0 += kWave) {
+        const int j = j0 + lane;
+        const float v = (j < k) ? sval[j] : 0.0f;
+        const uint64_t nz = __ballot(v != 0.0f);
+        const uint64_t ng = __ballot(v < 0.0f);
+        if (lane < 4 && j0 + 16 * lane < k) {
+            const uint32_t a = static_cast<uint32_t>(nz >> (16 * lane)) & 0xFFFFu;
+            const uint32_t b = static_cast<uint32_t>(ng >> (16 * lane)) & 0xFFFFu;
+            words[(j0 >> 4) + lane] = spread16(a) | (spread16(b) << 1);
+        }
+    }
 }
 
 __device__ __forceinline__ void store_payload_value(void* base, int64_t e, int val_dtype, float v) {
@@ -187,9 +223,12 @@ __device__ __forceinline__ void compress_generic_chunks(
         compact_flags(s, lane, flag, cf, sidx, sval);
         // what travels is the value in the transfer dtype; the residual below removes exactly
         // what the receivers will decode
+        if (p.val_dtype == 3)
+            store_ternary_chunk(static_cast<uint32_t*>(val_out) + c * ternary_words_per_chunk(k), k,
+                                lane, sval);
         for (int j = lane; j < k; j += kWave) {
             if (idx_out) store_payload_index(idx_out, c * k + j, p.idx_u8, sidx[j]);
-            store_payload_value(val_out, c * k + j, p.val_dtype, sval[j]);
+            if (p.val_dtype != 3) store_payload_value(val_out, c * k + j, p.val_dtype, sval[j]);
             sval[j] = payload_roundtrip(p.val_dtype, sval[j]);
         }
         __syncthreads();
@@ -259,9 +298,15 @@ __device__ __forceinline__ void decompress_generic_chunks(
             for (int j = lane; j < k; j += kWave) {
                 const int at =
                     idx ? load_payload_index(idx, r * idx_stride + c * k + j, p.idx_u8) : sidx[j];
-                if (at >= 0 && at < s)
-                    atomicAdd(&a[at],
-                              load_payload_value(val, r * val_stride + c * k + j, p.val_dtype));
+                if (at >= 0 && at < s) {
+                    const float v =
+                        (p.val_dtype == 3)
+                            ? ternary_decode(static_cast<const uint32_t*>(
+                                                 val)[r * val_stride +
+                                                      c * ternary_words_per_chunk(k) + (j >> 4)], j)
+                            : load_payload_value(val, r * val_stride + c * k + j, p.val_dtype);
+                    atomicAdd(&a[at], v);
+                }
             }
             __syncthreads();
         }

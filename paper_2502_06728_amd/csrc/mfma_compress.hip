@@ -7,6 +7,7 @@ namespace deto {
 int64_t launch_compress_mfma(const CompressLaunch& a) {
     const KParams& p = a.p;
     if (p.scheme != 0 || !p.use_dct || p.s % 32 != 0 || p.s > 256) return 0;
+    if (p.val_dtype == 3) return 0;   // two-bit payload: general kernels
     const int64_t tiles = (a.n / p.s) / kMfmaChunks;
     if (tiles <= 0) return 0;
 #define X(NB)                                                                                   \

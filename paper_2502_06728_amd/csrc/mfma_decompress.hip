@@ -8,6 +8,7 @@ namespace deto {
 int64_t launch_decompress_mfma(const DecompressLaunch& a) {
     const KParams& p = a.p;
     if (!a.idx || !p.use_dct || p.s % 32 != 0 || p.s > 256) return 0;
+    if (p.val_dtype == 3) return 0;   // two-bit payload: general kernels
     const int64_t tiles = (a.n / p.s) / kMfmaChunks;
     if (tiles <= 0) return 0;
     // 16-byte payload loads: fp32 values, int32 indices, four entries never straddle a chunk

@@ -12,7 +12,7 @@
 namespace deto {
 
 bool launch_compress_topk_packed(const CompressLaunch& a) {
-    if (a.p.val_dtype == 0 || !a.p.idx_u8 || a.p.scheme != 0) return false;
+    if ((a.p.val_dtype != 1 && a.p.val_dtype != 2) || !a.p.idx_u8 || a.p.scheme != 0) return false;
     const unsigned grid = tiled_grid(a.tiles, a.n_chunks);
     const TailRange tail{a.n, a.n_chunks};
 #define LAUNCH(S, K, G, V)                                                                      \
@@ -34,7 +34,8 @@ bool launch_compress_topk_packed(const CompressLaunch& a) {
 }
 
 bool launch_decompress_idx_packed(const DecompressLaunch& a) {
-    if (a.p.val_dtype == 0 || !a.p.idx_u8 || !a.idx || a.p.adam) return false;
+    if ((a.p.val_dtype != 1 && a.p.val_dtype != 2) || !a.p.idx_u8 || !a.idx || a.p.adam)
+        return false;
     const unsigned grid = tiled_grid(a.tiles, a.n_chunks);
     const TailRange tail{a.n, a.n_chunks};
 #define LAUNCH(S, K, B, V)                                                                      \

@@ -98,3 +98,35 @@ def gpu_decompress_packed(cfg: oracle.Config, idx: np.ndarray, val_bits: np.ndar
     binding.detonation_decompress_step_packed(bcfg(cfg), R, i, v, p, y)
     torch.cuda.synchronize()
     return to_host(p), to_host(y)
+
+
+def gpu_compress_ternary(cfg: oracle.Config, grad: np.ndarray, mom: np.ndarray, idx_u8: bool,
+                         want_idx: bool = True):
+    """Returns (momentum, idx as int32 or None, ternary words as uint32, coefficients)."""
+    n = mom.size
+    C = -(-n // cfg.chunk)
+    g, m = to_dev(grad), to_dev(mom)
+    idx = (torch.full((C * cfg.topk,), 251 if idx_u8 else -7,
+                      dtype=torch.uint8 if idx_u8 else torch.int32, device=DEV) if want_idx else None)
+    words = torch.full((binding.ternary_words(bcfg(cfg), n),), -1, dtype=torch.int32, device=DEV)
+    coeff = torch.full((C * cfg.chunk,), float("nan"), dtype=torch.float32, device=DEV)
+    binding.detonation_compress_packed(bcfg(cfg), g, m, idx, words, coeff)
+    torch.cuda.synchronize()
+    return (to_host(m), None if idx is None else idx.cpu().numpy().astype(np.int32),
+            words.cpu().numpy().view(np.uint32), to_host(coeff))
+
+
+def gpu_decompress_ternary(cfg: oracle.Config, idx, words: np.ndarray, params: np.ndarray,
+                           idx_u8: bool):
+    R = words.shape[0]
+    n = params.size
+    i = None
+    if idx is not None:
+        i = torch.from_numpy(np.ascontiguousarray(
+            idx.reshape(R, -1).astype(np.uint8 if idx_u8 else np.int32))).to(DEV)
+    w = torch.from_numpy(np.ascontiguousarray(words).view(np.int32)).to(DEV)
+    p = to_dev(params)
+    y = torch.full((n,), float("nan"), dtype=torch.float32, device=DEV)
+    binding.detonation_decompress_step_packed(bcfg(cfg), R, i, w, p, y)
+    torch.cuda.synchronize()
+    return to_host(p), to_host(y)

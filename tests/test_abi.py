@@ -33,7 +33,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_version_and_status_strings(lib):
-    assert binding.version() == 1002
+    assert binding.version() == 1003
     assert binding.status_string(0) == "ok"
     assert len({binding.status_string(i) for i in range(6)}) == 6
 
@@ -93,12 +93,17 @@ def test_packed_entry_points_validate_formats(lib):
     ok = ctypes.byref(binding.Config(chunk=64, topk=8).c())
     c = lib.detonation_compress_packed
     assert c(ok, 10, vp(1024), 0, vp(1024), vp(1024), 7, vp(1024), 0, None, None) == 2   # idx dtype
-    assert c(ok, 10, vp(1024), 0, vp(1024), vp(1024), 0, vp(1024), 3, None, None) == 2   # val dtype
+    assert c(ok, 10, vp(1024), 0, vp(1024), vp(1024), 0, vp(1024), 4, None, None) == 2   # val dtype
+    assert c(ok, 10, vp(1024), 0, vp(1024), vp(1024), 0, vp(1026), 3, None, None) == 4   # ternary words
     assert c(ok, 10, vp(1024), 0, vp(1024), vp(1025), 0, vp(1024), 0, None, None) == 4   # int32 idx
     assert c(ok, 10, vp(1024), 0, vp(1024), vp(1024), 1, vp(1025), 2, None, None) == 4   # fp16 val
     d = lib.detonation_decompress_step_packed
     assert d(ok, 10, 1, vp(1024), 2, 8, vp(1024), 0, 8, vp(1024), 0, None, None) == 2
     assert d(ok, 0, 1, None, 1, 0, None, 2, 0, None, 0, None, None) == 0
+    # ternary payload: replica stride counted in 32-bit words, ceil(k/16) per chunk
+    assert d(ok, 128, 2, vp(1024), 0, 16, vp(1024), 3, 1, vp(1024), 0, None, None) == 2
+    assert lib.detonation_ternary_words(ok, 128) == 2
+    assert lib.detonation_ternary_words(ctypes.byref(binding.Config(chunk=64, topk=33).c()), 65) == 6
 
 
 def test_adamw_entry_point_validation(lib):

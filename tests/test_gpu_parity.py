@@ -590,3 +590,43 @@ def test_byte_indices_with_fp32_values(H):
         H.bcfg(cfg), R, torch.from_numpy(idx.astype(np.uint8)).to(H.DEV), H.to_dev(vals), p, y)
     torch.cuda.synchronize()
     parity.check_decompress(cfg, idx, vals, th, H.to_host(p), H.to_host(y))
+
+
+@pytest.mark.parametrize("idx_u8", [False, True])
+@pytest.mark.parametrize("s,k,n", [(64, 32, 64 * 3000 + 13), (64, 16, 64 * 1000), (32, 4, 32 * 777 + 5),
+                                   (96, 20, 96 * 300 + 1), (128, 48, 128 * 100), (16, 2, 16 * 500 + 3)])
+def test_ternary_payload(H, idx_u8, s, k, n):
+    """The paper's "sign before synchronization": only sign(c) of the kept coefficients travels,
+    two bits per entry; the momentum loses the extracted components themselves."""
+    cfg = Config(chunk=s, topk=k, sign=True, decay=0.999, lr=1e-3)
+    g, m, th = make_inputs(n, seed=s + k, grad_bf16=True, params_bf16=True, outliers=0.01)
+    m_gpu, idx_gpu, words_gpu, coeff_gpu = H.gpu_compress_ternary(cfg, g, m, idx_u8)
+    C = -(-n // s)
+    kept = coeff_gpu.reshape(C, s)[np.arange(C)[:, None], idx_gpu.reshape(C, k)].reshape(-1)
+    # coefficients, selection and momentum: the fp32 protocol with the kept values as payload
+    parity.check_compress(cfg, g, m, m_gpu, idx_gpu, kept, coeff_gpu)
+    assert np.array_equal(words_gpu, oracle.encode_ternary(cfg, n, kept))
+    R = 3
+    pays = [oracle.compress_t(cfg, *make_inputs(n, seed=900 + r, grad_bf16=True, outliers=0.01)[:2])[1:]
+            for r in range(R)]
+    idx = np.stack([p[0] for p in pays])
+    words = np.stack([p[1] for p in pays])
+    th_gpu, y_gpu = H.gpu_decompress_ternary(cfg, idx, words, th, idx_u8)
+    signs = np.stack([oracle.decode_ternary(cfg, n, w) for w in words])
+    parity.check_decompress(cfg, idx, signs, th, th_gpu, y_gpu)
+
+
+@pytest.mark.parametrize("scheme", [SCHEME_STRIDE, SCHEME_RANDOM])
+def test_ternary_payload_striding_random(H, scheme):
+    # values only; identity domain: the pre-sign update is an exact average of signs
+    n, s, k = 64 * 400 + 9, 64, 16
+    cfg = Config(chunk=s, topk=k, scheme=scheme, seed=4, step=3, sign=False)
+    g, m, th = make_inputs(n, seed=12)
+    m_gpu, _, words_gpu, _ = H.gpu_compress_ternary(cfg, g, m, False, want_idx=False)
+    m_o, idx_o, words_o = oracle.compress_t(cfg, g, m)
+    assert np.array_equal(words_gpu, words_o) and np.array_equal(m_gpu, m_o)
+    words = np.stack([words_o, oracle.compress_t(cfg, *make_inputs(n, seed=13)[:2])[2]])
+    th_gpu, y_gpu = H.gpu_decompress_ternary(cfg, None, words, th, False)
+    assert np.array_equal(y_gpu, oracle.presign_t(cfg, n, None, words))
+    th_o = oracle.update(cfg, y_gpu, th)
+    assert np.abs(th_gpu - th_o).max() <= 1e-6 * np.abs(th_o).max()
