@@ -26,11 +26,11 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 
 
 def algorithmic_bytes(n: int, s: int, k: int, R: int, grad_bytes: int, param_bytes: int,
-                      with_idx: bool, val_bytes: int = 4, idx_bytes: int = 4) -> dict:
+                      with_idx: bool, val_bytes: float = 4, idx_bytes: int = 4) -> dict:
     """Bytes the method itself must move per launch: compress reads g and m, writes m and
     the payload; decompress reads R payloads, reads and writes the parameters."""
     C = -(-n // s)
-    pay = C * k * (val_bytes + (idx_bytes if with_idx else 0))
+    pay = int(C * k * (val_bytes + (idx_bytes if with_idx else 0)))
     return {"compress": n * (grad_bytes + 8) + pay, "decompress": R * pay + 2 * n * param_bytes}
 
 
@@ -68,7 +68,7 @@ def main() -> int:
     ap.add_argument("--workload", default="olmo-1b-1of8")
     ap.add_argument("--scheme", default="topk", choices=["topk", "stride", "random"])
     ap.add_argument("--dct", action="store_true", help="coefficient domain for stride/random")
-    ap.add_argument("--payload", default="f32i32", choices=["f32i32", "bf16u8", "f16u8"],
+    ap.add_argument("--payload", default="f32i32", choices=["f32i32", "bf16u8", "f16u8", "ternaryu8"],
                     help="payload format: value dtype + index width (top-k)")
     ap.add_argument("--optimizer", default="sgd", choices=["sgd", "adamw"],
                     help="underlying optimizer of the update: DeMo-SGD or Decoupled AdamW")
@@ -123,10 +123,13 @@ def run(args) -> dict:
     grad, mom, params = up(g_np), up(m_np), up(th_np)
     del g_np, m_np, th_np
     packed = args.payload != "f32i32"
-    val_t = {"f32i32": torch.float32, "bf16u8": torch.bfloat16, "f16u8": torch.float16}[args.payload]
+    ternary = args.payload == "ternaryu8"     # signs only: int32 words of 16 two-bit codes
+    val_t = {"f32i32": torch.float32, "bf16u8": torch.bfloat16, "f16u8": torch.float16,
+             "ternaryu8": torch.int32}[args.payload]
     idx_t = torch.uint8 if packed else torch.int32
     idx = torch.zeros((R, entries), dtype=idx_t, device=dev) if with_idx else None
-    val = torch.zeros((R, entries), dtype=val_t, device=dev)
+    val = torch.zeros((R, binding.ternary_words(cfg, n) if ternary else entries), dtype=val_t,
+                      device=dev)
     compress = binding.detonation_compress_packed if packed else binding.detonation_compress
     decompress = (binding.detonation_decompress_step_packed if packed
                   else binding.detonation_decompress_step)
@@ -184,7 +187,8 @@ def run(args) -> dict:
     t_d = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
     ms_per_step = wall * 1e3 / args.steps
     ab = algorithmic_bytes(n, s, k, R, grad.element_size(), params.element_size(), with_idx,
-                           val.element_size(), idx.element_size() if with_idx else 0)
+                           0.25 if ternary else val.element_size(),
+                           idx.element_size() if with_idx else 0)
     if adamw:
         ab["decompress"] += 16 * n          # exp_avg and exp_avg_sq, fp32, read and written
     gbs_c = ab["compress"] / (t_c * 1e-3) / 1e9

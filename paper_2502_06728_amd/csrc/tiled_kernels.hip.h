@@ -248,7 +248,48 @@ __device__ __forceinline__ void compact_and_store_payload(const float (&c)[S],
         });
     }
     wave_lds_sync();
-    if constexpr (VAL != 0) {
+    if constexpr (VAL == 3) {
+        // ternary: the lane packs the signs of its chunk's K staged values, two bits each
+        // (0 = zero, 1 = +1, 3 = -1), into K/16 words; byte indices leave as in the 16-bit case
+        static_assert(K % 16 == 0, "whole words per chunk");
+        constexpr int W = K / 16;
+        uint32_t* words = static_cast<uint32_t*>(val_out_v) + (pbase / K) * W + lane * W;
+        uint32_t wv[W];
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+            wv[w] = 0u;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 v = *reinterpret_cast<const float4*>(vrow + 16 * w + 4 * q);
+                const int b[4] = {__float_as_int(v.x), __float_as_int(v.y), __float_as_int(v.z),
+                                  __float_as_int(v.w)};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t code =
+                        b[e] > 0 ? 1u : (static_cast<uint32_t>(b[e]) > 0x80000000u ? 3u : 0u);
+                    wv[w] |= code << (2 * (4 * q + e));
+                }
+            }
+        }
+        if constexpr (W == 1) words[0] = wv[0];
+        else if constexpr (W == 2) *reinterpret_cast<uint2*>(words) = make_uint2(wv[0], wv[1]);
+        else {
+#pragma unroll
+            for (int w = 0; w < W; ++w) words[w] = wv[w];
+        }
+        uint8_t* idx8 = static_cast<uint8_t*>(idx_out_v);
+        if (idx8) {
+#pragma unroll
+            for (int it = 0; it < K / 4; ++it) {
+                const int e = it * 256 + lane * 4;
+                const int r = e / K, col = e % K;
+                *reinterpret_cast<uint32_t*>(idx8 + pbase + e) =
+                    *reinterpret_cast<const uint32_t*>(ibytes + r * PR + col);
+            }
+        }
+        wave_lds_sync();
+        return;
+    } else if constexpr (VAL != 0) {
         static_assert(K % 4 == 0, "16-bit payloads are stored four entries at a time");
         uint16_t* val16 = static_cast<uint16_t*>(val_out_v);
         uint8_t* idx8 = static_cast<uint8_t*>(idx_out_v);
@@ -430,7 +471,7 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void compress_ti
         });
     }
 
-    if constexpr (VAL != 0) {
+    if constexpr (VAL == 1 || VAL == 2) {
         // 16-bit transfer: the payload carries the rounded coefficient, and the rounding
         // error of a kept coefficient stays behind in the momentum with the dropped ones
         static_assert(!kLean, "16-bit payloads are built for chunk sizes up to 64");
@@ -559,6 +600,29 @@ struct PayloadRegs {
     __device__ __forceinline__ float val(int it) const {
         const uint32_t w = (C < 2) ? v[it].x : v[it].y;
         return decode16<VAL>(static_cast<uint16_t>((C & 1) ? (w >> 16) : (w & 0xFFFFu)));
+    }
+};
+
+// Ternary values + byte indices, K a multiple of 16: the words of a replica are then a dense
+// array of two-bit codes indexed by entry, and the four entries of a lane's vector are one byte.
+template <int K>
+struct PayloadRegs<K, 3> {
+    static_assert(K % 16 == 0, "whole words per chunk");
+    static constexpr int kVec = K / 4;
+    uint32_t i[kVec];
+    uint32_t v[kVec];
+    __device__ __forceinline__ void load(int it, const void* ir, const void* vr, int e) {
+        i[it] = ld_u1<DETO_NT_DECOMPRESS_LD>(static_cast<const uint8_t*>(ir) + e);
+        v[it] = static_cast<const uint8_t*>(vr)[e >> 2];
+    }
+    template <int C>
+    __device__ __forceinline__ uint32_t idx(int it) const {
+        return (i[it] >> (8 * C)) & 0xFFu;
+    }
+    template <int C>
+    __device__ __forceinline__ float val(int it) const {
+        const uint32_t code = (v[it] >> (2 * C)) & 3u;
+        return (code & 1u) ? ((code & 2u) ? -1.0f : 1.0f) : 0.0f;
     }
 };
 
@@ -810,10 +874,13 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_
     const int64_t ebase = t * G::kElems;
     const int64_t pbase = t * (kWave * K);
     // replica r's entries of this tile, in bytes from the array bases
+    // (ternary: four entries per byte, replica stride in 32-bit words)
     constexpr int kIdxBytes = VAL ? 1 : 4, kValBytes = VAL ? 2 : 4;
     const char* idx = static_cast<const char*>(idx_v) + pbase * kIdxBytes;
-    const char* val = static_cast<const char*>(val_v) + pbase * kValBytes;
-    const int64_t idx_step = idx_stride * kIdxBytes, val_step = val_stride * kValBytes;
+    const char* val =
+        static_cast<const char*>(val_v) + (VAL == 3 ? pbase / 4 : pbase * kValBytes);
+    const int64_t idx_step = idx_stride * kIdxBytes;
+    const int64_t val_step = val_stride * (VAL == 3 ? 4 : kValBytes);
 
     // zero the accumulator tile
 #pragma unroll
