@@ -206,6 +206,25 @@ int detonation_decompress_adamw_step(const deto_config* cfg, const deto_adamw* o
                                      float* presign_dbg,
                                      void* stream);
 
+/*
+ * The first line of Algorithm 1 alone: momentum <- beta*momentum + grad, nothing extracted and
+ * nothing sent.  For replicators that do not exchange on every step (paper, "Replication
+ * Schemes": DiLoCo "denotes synchronization every n'th optimization step"): the steps in between
+ * accumulate with this call; the synchronising step is detonation_compress with
+ * DETO_SCHEME_STRIDE and topk = chunk (every position is taken, so the whole momentum is the
+ * payload and restarts from zero) followed by detonation_decompress_step.
+ *
+ *   grad        device, [n] of grad_dtype, read only
+ *   momentum    device, [n] fp32, updated in place
+ *
+ * Only cfg->decay is used, but cfg is validated as a whole.  Errors: DETO_ERR_NULL,
+ * DETO_ERR_BAD_CONFIG, DETO_ERR_ALIGN, DETO_ERR_HIP.  n = 0 is a no-op.
+ */
+int detonation_accumulate(const deto_config* cfg, int64_t n,
+                          const void* grad, int grad_dtype,
+                          float* momentum,
+                          void* stream);
+
 /* Payload entries per replica, ceil(n/s)*k (the paper's compression rate k/s times the
  * padded shard length); -1 if cfg is invalid. */
 int64_t detonation_payload_entries(const deto_config* cfg, int64_t n);
@@ -217,7 +236,7 @@ int64_t detonation_ternary_words(const deto_config* cfg, int64_t n);
 /* Static, human-readable name of a deto_status. */
 const char* detonation_status_string(int status);
 
-/* ABI version of this header: major*1000 + minor (1001: the *_packed entry points; 1002: Decoupled AdamW; 1003: DETO_TERNARY). */
+/* ABI version of this header: major*1000 + minor (1001: the *_packed entry points; 1002: Decoupled AdamW; 1003: DETO_TERNARY; 1004: detonation_accumulate). */
 int detonation_version(void);
 
 #ifdef __cplusplus

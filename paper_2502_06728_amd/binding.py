@@ -20,6 +20,7 @@ IDX_I32, IDX_U8 = 0, 1
 FLAG_SIGN, FLAG_DCT = 1, 2
 
 EXPORTS = ("detonation_compress", "detonation_decompress_step", "detonation_compress_packed",
+           "detonation_accumulate",
            "detonation_decompress_step_packed", "detonation_decompress_adamw_step",
            "detonation_payload_entries", "detonation_ternary_words",
            "detonation_status_string", "detonation_version")
@@ -103,6 +104,8 @@ def load() -> ctypes.CDLL:
                                                          vp, i64, vp, i64, vp, ctypes.c_int, vp,
                                                          vp, vp, vp, vp]
         lib.detonation_decompress_adamw_step.restype = ctypes.c_int
+        lib.detonation_accumulate.argtypes = [cfgp, i64, vp, ctypes.c_int, vp, vp]
+        lib.detonation_accumulate.restype = ctypes.c_int
         lib.detonation_payload_entries.argtypes = [cfgp, i64]
         lib.detonation_payload_entries.restype = i64
         lib.detonation_ternary_words.argtypes = [cfgp, i64]
@@ -201,6 +204,17 @@ def detonation_decompress_step(cfg: Config, R: int, idx, val, params, presign_db
     rc = load().detonation_decompress_step(ctypes.byref(cfg.c()), n, R, _ptr(idx), istr, _ptr(val),
                                            vs, _ptr(params), _dtype(params), _ptr(presign_dbg),
                                            _stream(stream))
+    if rc != 0:
+        raise DetonationError(rc)
+
+
+def detonation_accumulate(cfg: Config, grad, momentum, stream=None, n: int | None = None) -> None:
+    """momentum <- beta*momentum + grad (Algorithm 1's first line alone; the steps of a DiLoCo
+    cycle that do not synchronise)."""
+    _check(grad, momentum)
+    n = momentum.numel() if n is None else n
+    rc = load().detonation_accumulate(ctypes.byref(cfg.c()), n, _ptr(grad), _dtype(grad),
+                                      _ptr(momentum), _stream(stream))
     if rc != 0:
         raise DetonationError(rc)
 

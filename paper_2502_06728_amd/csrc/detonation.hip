@@ -307,6 +307,31 @@ int detonation_decompress_step(const deto_config* cfg, int64_t n, int32_t R, con
                                              presign_dbg, stream);
 }
 
+int detonation_accumulate(const deto_config* cfg, int64_t n, const void* grad, int grad_dtype,
+                          float* momentum, void* stream) {
+    int rc = validate(cfg);
+    if (rc) return rc;
+    if (n < 0 || !valid_dtype(grad_dtype)) return DETO_ERR_BAD_CONFIG;
+    if (n == 0) return DETO_OK;
+    if (!grad || !momentum) return DETO_ERR_NULL;
+    if (!aligned(grad, elem_size(grad_dtype)) || !aligned(momentum, 4)) return DETO_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool vec = aligned16(grad) && aligned16(momentum);
+    // 256 CUs x 8 workgroups of 256 lanes, grid-stride
+    const int64_t want = (n / 8 + 255) / 256 + 1;
+    const unsigned grid = static_cast<unsigned>(want < 2048 ? want : 2048);
+    const bool bf16 = grad_dtype == DETO_BF16;
+    if (vec && bf16)
+        deto::accumulate_kernel<true, true><<<grid, 256, 0, st>>>(cfg->decay, n, grad, momentum);
+    else if (vec)
+        deto::accumulate_kernel<false, true><<<grid, 256, 0, st>>>(cfg->decay, n, grad, momentum);
+    else if (bf16)
+        deto::accumulate_kernel<true, false><<<grid, 256, 0, st>>>(cfg->decay, n, grad, momentum);
+    else
+        deto::accumulate_kernel<false, false><<<grid, 256, 0, st>>>(cfg->decay, n, grad, momentum);
+    return launched();
+}
+
 int64_t detonation_payload_entries(const deto_config* cfg, int64_t n) {
     if (validate(cfg) != DETO_OK || n < 0) return -1;
     return chunks_of(n, cfg->chunk) * cfg->topk;
@@ -329,6 +354,6 @@ const char* detonation_status_string(int status) {
     }
 }
 
-int detonation_version(void) { return 1003; }
+int detonation_version(void) { return 1004; }
 
 }  // extern "C"

@@ -358,4 +358,47 @@ __global__ __launch_bounds__(kWave) void decompress_generic(
                                           presign_dbg);
 }
 
+// m <- beta*m + g over the whole shard (Algorithm 1, first line), nothing else: eight
+// elements per lane and iteration with 16-byte accesses when the buffers allow it.
+template <bool GRAD_BF16, bool VEC>
+__global__ __launch_bounds__(256) void accumulate_kernel(float beta, int64_t n,
+                                                         const void* __restrict__ grad,
+                                                         float* __restrict__ mom) {
+    const int64_t tid = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const int64_t nthreads = static_cast<int64_t>(gridDim.x) * blockDim.x;
+    int64_t done = 0;
+    if constexpr (VEC) {
+        const int64_t groups = n / 8;
+        for (int64_t q = tid; q < groups; q += nthreads) {
+            const int64_t e = 8 * q;
+            float g[8];
+            if constexpr (GRAD_BF16) {
+                const uint4 raw = ld_u4<true>(static_cast<const uint16_t*>(grad) + e);
+                const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    g[2 * j] = __uint_as_float(w[j] << 16);
+                    g[2 * j + 1] = __uint_as_float(w[j] & 0xFFFF0000u);
+                }
+            } else {
+                const float4 a = ld_f4<true>(static_cast<const float*>(grad) + e);
+                const float4 b = ld_f4<true>(static_cast<const float*>(grad) + e + 4);
+                g[0] = a.x; g[1] = a.y; g[2] = a.z; g[3] = a.w;
+                g[4] = b.x; g[5] = b.y; g[6] = b.z; g[7] = b.w;
+            }
+            const float4 ma = ld_f4<false>(mom + e), mb = ld_f4<false>(mom + e + 4);
+            st_f4<false>(mom + e, make_float4(fmaf(beta, ma.x, g[0]), fmaf(beta, ma.y, g[1]),
+                                              fmaf(beta, ma.z, g[2]), fmaf(beta, ma.w, g[3])));
+            st_f4<false>(mom + e + 4, make_float4(fmaf(beta, mb.x, g[4]), fmaf(beta, mb.y, g[5]),
+                                                  fmaf(beta, mb.z, g[6]), fmaf(beta, mb.w, g[7])));
+        }
+        done = groups * 8;
+    }
+    for (int64_t i = done + tid; i < n; i += nthreads) {
+        const float g = GRAD_BF16 ? bf16_to_f32(static_cast<const uint16_t*>(grad)[i])
+                                  : static_cast<const float*>(grad)[i];
+        mom[i] = fmaf(beta, mom[i], g);
+    }
+}
+
 }  // namespace deto

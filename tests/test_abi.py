@@ -33,7 +33,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_version_and_status_strings(lib):
-    assert binding.version() == 1003
+    assert binding.version() == 1004
     assert binding.status_string(0) == "ok"
     assert len({binding.status_string(i) for i in range(6)}) == 6
 
@@ -104,6 +104,18 @@ def test_packed_entry_points_validate_formats(lib):
     assert d(ok, 128, 2, vp(1024), 0, 16, vp(1024), 3, 1, vp(1024), 0, None, None) == 2
     assert lib.detonation_ternary_words(ok, 128) == 2
     assert lib.detonation_ternary_words(ctypes.byref(binding.Config(chunk=64, topk=33).c()), 65) == 6
+
+
+def test_accumulate_validation(lib):
+    vp = ctypes.c_void_p
+    ok = ctypes.byref(binding.Config(chunk=64, topk=8).c())
+    f = lib.detonation_accumulate
+    assert f(None, 10, vp(1024), 0, vp(1024), None) == 1
+    assert f(ok, 10, None, 0, vp(1024), None) == 1
+    assert f(ok, 10, vp(1024), 7, vp(1024), None) == 2
+    assert f(ok, -1, vp(1024), 0, vp(1024), None) == 2
+    assert f(ok, 10, vp(1025), 1, vp(1024), None) == 4
+    assert f(ok, 0, None, 0, None, None) == 0
 
 
 def test_adamw_entry_point_validation(lib):

@@ -630,3 +630,43 @@ def test_ternary_payload_striding_random(H, scheme):
     assert np.array_equal(y_gpu, oracle.presign_t(cfg, n, None, words))
     th_o = oracle.update(cfg, y_gpu, th)
     assert np.abs(th_gpu - th_o).max() <= 1e-6 * np.abs(th_o).max()
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_diloco_cycle_accumulate_then_full_synchronisation(H, bf16):
+    """DiLoCo as a replicator ("synchronization every n'th optimization step"): the steps in
+    between only accumulate (detonation_accumulate), the n'th extracts the whole momentum
+    (Striding with k = s) and averages it over the replicas.  Raw domain: momentum, payload
+    and averaged update equal the oracle's bit for bit."""
+    import torch
+    from paper_2502_06728_amd import binding
+    s, every, T, R = 64, 3, 7, 2
+    for n in (64 * 700 + 13, 37):
+        g0, m0, th0 = make_inputs(n, seed=n, grad_bf16=bf16, params_bf16=bf16)
+        m_dev, th_dev = H.to_dev(m0), H.to_dev(th0)
+        m_o = m0.copy()
+        m_other = make_inputs(n, seed=n + 1)[1]
+        for step in range(T):
+            cfg = Config(chunk=s, topk=s, scheme=SCHEME_STRIDE, decay=0.9, lr=1e-2, sign=False,
+                         step=step)
+            g = make_inputs(n, seed=100 + step, grad_bf16=bf16)[0]
+            g_other = make_inputs(n, seed=200 + step)[0]
+            if (step + 1) % every:
+                binding.detonation_accumulate(H.bcfg(cfg), H.to_dev(g), m_dev)
+                torch.cuda.synchronize()
+                m_o = oracle.fold(cfg, g, m_o)
+                m_other = oracle.fold(cfg, g_other, m_other)
+                assert np.array_equal(H.to_host(m_dev), m_o)
+                continue
+            m_other, _, val_other = oracle.compress(cfg, g_other, m_other)
+            m_new, _, val_g, _ = H.gpu_compress(cfg, g, H.to_host(m_dev), want_idx=False,
+                                                want_coeff=False)
+            m_o, _, val_o = oracle.compress(cfg, g, m_o)
+            assert np.array_equal(val_g, val_o) and not m_new.any() and not m_o.any()
+            m_dev = H.to_dev(m_new)
+            val = np.stack([val_g, val_other])
+            th_in = H.to_host(th_dev)
+            th_new, y = H.gpu_decompress(cfg, None, val, th_in)
+            assert np.array_equal(y, oracle.presign(cfg, n, None, val))
+            parity.check_decompress(cfg, None, val, th_in, th_new, y)   # one rounding of theta
+            th_dev = H.to_dev(th_new)

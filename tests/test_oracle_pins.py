@@ -599,3 +599,34 @@ def test_ternary_compress_and_presign_reduce_to_the_fp32_path_on_signs(scheme):
         at = (np.arange(idx.shape[1]) // k) * s + idx[0]
         dense[at] = pays[0][1]
         assert np.array_equal(y1, dense[:n])
+
+
+# ---------------------- DiLoCo replicator ("Replication Schemes": synchronization every n'th step)
+
+def test_diloco_cycle_closed_form():
+    """Reading: between synchronisations a rank only accumulates (Algorithm 1's first line,
+    m <- beta*m + g); the n'th step extracts everything (Striding with k = s takes every
+    position, so q = m and the momentum restarts from zero) and the replicas' q are averaged.
+    With a constant gradient g the momentum after j accumulations is g*(1 - beta^j)/(1 - beta)."""
+    s, n, every, beta, eta = 16, 16 * 40 + 5, 4, 0.5, 0.25
+    R = 3
+    g = [np.full(n, 1.0 + r, np.float32) for r in range(R)]
+    m = [np.zeros(n, np.float32) for _ in range(R)]
+    th = np.zeros(n, np.float32)
+    sync = Config(chunk=s, topk=s, scheme=SCHEME_STRIDE, decay=beta, lr=eta, sign=False)
+    for step in range(2 * every):
+        sync.step = step
+        if (step + 1) % every:
+            m = [oracle.fold(sync, g[r], m[r]) for r in range(R)]
+            continue
+        pays = [oracle.compress(sync, g[r], m[r]) for r in range(R)]
+        geo = (1.0 - beta ** every) / (1.0 - beta)
+        for r, (m_new, idx, val) in enumerate(pays):
+            assert not m_new.any()                                  # everything was extracted
+            assert np.allclose(val[:n], (1.0 + r) * geo, rtol=1e-6)
+        m = [p[0] for p in pays]
+        th_new = oracle.decompress_step(sync, None, np.stack([p[2] for p in pays]), th)
+        # the update is the mean over the replicas of their accumulated momenta
+        want = th.astype(np.float64) - eta * geo * np.mean([1.0 + r for r in range(R)])
+        assert np.allclose(th_new, want, rtol=1e-6)
+        th = th_new
