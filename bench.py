@@ -34,8 +34,9 @@ def algorithmic_bytes(n: int, s: int, k: int, R: int, grad_bytes: int, param_byt
     return {"compress": n * (grad_bytes + 8) + pay, "decompress": R * pay + 2 * n * param_bytes}
 
 
-def cpu_baseline(w, cfg_kwargs: dict, sample_params: int) -> dict:
-    """The oracle as it stands, on the host cores, on the leading `sample_params` of the shard."""
+def cpu_baseline(w, cfg_kwargs: dict, sample_params: int, every: int = 1) -> dict:
+    """The oracle as it stands, on the host cores, on the leading `sample_params` of the shard.
+    every > 1 (DiLoCo): every-1 accumulate-only steps, then the synchronising step."""
     import numpy as np
     import oracle
     from paper_2502_06728_amd import synth
@@ -51,12 +52,15 @@ def cpu_baseline(w, cfg_kwargs: dict, sample_params: int) -> dict:
         idx[r], val[r] = synth.structured_payload(w.seed + r, C, cfg.chunk, cfg.topk, w.momentum_std)
     oracle.lib()
     t0 = time.perf_counter()
+    for _ in range(every - 1):
+        m = oracle.fold(cfg, g, m)
     m_new, idx0, val0 = oracle.compress(cfg, g, m)
     idx[0], val[0] = idx0, val0
-    oracle.decompress_step(cfg, idx, val, th)
+    oracle.decompress_step(cfg, idx if cfg.scheme == 0 else None, val, th)
     dt = time.perf_counter() - t0
-    return {"value": n / dt, "unit": "params/s", "cores": oracle.threads(), "kind": "oracle",
-            "sample": f"leading {n} of {w.n} parameters of the same shard, one full step "
+    what = "one full step" if every == 1 else f"{every - 1} accumulate-only steps and one full step"
+    return {"value": every * n / dt, "unit": "params/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"leading {n} of {w.n} parameters of the same shard, {what} "
                       f"(compress + decompress, R={R}), {dt:.1f} s, gcc -O2 + OpenMP"}
 
 
@@ -66,7 +70,10 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="olmo-1b-1of8")
-    ap.add_argument("--scheme", default="topk", choices=["topk", "stride", "random"])
+    ap.add_argument("--scheme", default="topk", choices=["topk", "stride", "random", "diloco"],
+                    help="diloco: accumulate only, and every --diloco-every'th step extract and "
+                         "average the whole momentum (Striding with k = chunk)")
+    ap.add_argument("--diloco-every", type=int, default=4)
     ap.add_argument("--dct", action="store_true", help="coefficient domain for stride/random")
     ap.add_argument("--payload", default="f32i32", choices=["f32i32", "bf16u8", "f16u8", "ternaryu8"],
                     help="payload format: value dtype + index width (top-k)")
@@ -103,8 +110,13 @@ def run(args) -> dict:
     if args.chunk or args.topk:
         import dataclasses
         w = dataclasses.replace(w, chunk=args.chunk or w.chunk, topk=args.topk or w.topk)
+    diloco = args.scheme == "diloco"
+    every = max(1, args.diloco_every) if diloco else 1
+    if diloco:
+        import dataclasses
+        w = dataclasses.replace(w, topk=w.chunk)
     scheme = {"topk": binding.SCHEME_TOPK, "stride": binding.SCHEME_STRIDE,
-              "random": binding.SCHEME_RANDOM}[args.scheme]
+              "random": binding.SCHEME_RANDOM, "diloco": binding.SCHEME_STRIDE}[args.scheme]
     cfg_kwargs = dict(chunk=w.chunk, topk=w.topk, scheme=scheme, sign=w.sign, dct=args.dct,
                       decay=w.decay, lr=w.lr, weight_decay=w.weight_decay, seed=w.seed, step=0)
     cfg = binding.Config(**cfg_kwargs)
@@ -160,6 +172,12 @@ def run(args) -> dict:
         cfg.step += 1
         if ev:
             ev[0].record()
+        if cfg.step % every:                 # DiLoCo: a step that only accumulates
+            binding.detonation_accumulate(cfg, grad, mom)
+            if ev:
+                ev[1].record()
+                ev[2].record()
+            return
         compress(cfg, grad, mom, None if idx is None else idx[0], val[0])
         if ev:
             ev[1].record()
@@ -183,8 +201,13 @@ def run(args) -> dict:
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
-    t_c = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps   # ms per launch
-    t_d = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
+    # ms per launch; with DiLoCo only every `every`-th step runs compress + decompress
+    first = cfg.step - args.steps + 1
+    sync = [e for i, e in enumerate(events) if (first + i) % every == 0] or events
+    t_c = sum(e[0].elapsed_time(e[1]) for e in sync) / len(sync)
+    t_d = sum(e[1].elapsed_time(e[2]) for e in sync) / len(sync)
+    acc = [e for i, e in enumerate(events) if (first + i) % every != 0]
+    t_a = sum(e[0].elapsed_time(e[1]) for e in acc) / len(acc) if acc else None
     ms_per_step = wall * 1e3 / args.steps
     ab = algorithmic_bytes(n, s, k, R, grad.element_size(), params.element_size(), with_idx,
                            0.25 if ternary else val.element_size(),
@@ -206,6 +229,9 @@ def run(args) -> dict:
             if len(f) == 2 and f[0] == dom:
                 traffic = float(f[1])
 
+    # bytes of an average step (DiLoCo: every-1 accumulations of g and m per synchronisation)
+    ab_acc = n * (grad.element_size() + 8)
+    step_bytes = (ab["compress"] + ab["decompress"] + (every - 1) * ab_acc) / every
     out = {
         "metric": "optimizer_step_params_per_sec", "value": n * args.steps / wall,
         "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -217,9 +243,8 @@ def run(args) -> dict:
                    "grad_dtype": str(grad.dtype).split(".")[-1],
                    "param_dtype": str(params.dtype).split(".")[-1], "momentum_dtype": "float32",
                    "sign": w.sign, "decay": w.decay, "lr": w.lr},
-        "step_hbm_gbs": (ab["compress"] + ab["decompress"]) / (ms_per_step * 1e-3) / 1e9,
-        "step_hbm_frac_of_peak": (ab["compress"] + ab["decompress"]) / (ms_per_step * 1e-3) / 1e9
-                                 / HBM_PEAK_GBS,
+        "step_hbm_gbs": step_bytes / (ms_per_step * 1e-3) / 1e9,
+        "step_hbm_frac_of_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "kernels": {
             "compress": {"ms": t_c, "algorithmic_bytes": ab["compress"], "gbs": gbs_c,
                          "frac": gbs_c / HBM_PEAK_GBS},
@@ -228,10 +253,16 @@ def run(args) -> dict:
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS, "traffic": traffic},
     }
+    if diloco:
+        out["config"]["diloco_every"] = every
+        if t_a:
+            out["kernels"]["accumulate"] = {"ms": t_a, "algorithmic_bytes": ab_acc,
+                                            "gbs": ab_acc / (t_a * 1e-3) / 1e9,
+                                            "frac": ab_acc / (t_a * 1e-3) / 1e9 / HBM_PEAK_GBS}
     del grad, mom, params, idx, val
     torch.cuda.empty_cache()
     if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(w, cfg_kwargs, args.cpu_sample)
+        out["cpu_baseline"] = cpu_baseline(w, cfg_kwargs, args.cpu_sample, every)
     return out
 
 
@@ -259,7 +290,8 @@ def report(args) -> int:
     plan = [("flat-1m", "topk", False), ("t5-base-1of8", "topk", False),
             ("vit-b16-1of8", "topk", False), ("olmo-1b-1of8", "topk", False),
             ("olmo-7b-1of8", "topk", False), ("olmo-7b-1of8", "stride", False),
-            ("olmo-7b-1of8", "random", False), ("olmo-7b-1of8", "random", True)]
+            ("olmo-7b-1of8", "random", False), ("olmo-7b-1of8", "random", True),
+            ("olmo-1b-1of8", "diloco", False)]
     for workload, scheme, dct in plan:
         a = copy.copy(args)
         a.workload, a.scheme, a.dct = workload, scheme, dct
@@ -273,10 +305,13 @@ def report(args) -> int:
         threads = oracle.threads()
         oracle.set_threads(1)
         w = synth.workloads()[workload]
+        if scheme == "diloco":
+            w = dataclasses.replace(w, topk=w.chunk)
         one = cpu_baseline(w, dict(chunk=w.chunk, topk=w.topk,
-                                   scheme={"topk": 0, "stride": 1, "random": 2}[scheme],
+                                   scheme={"topk": 0, "stride": 1, "random": 2, "diloco": 1}[scheme],
                                    sign=w.sign, dct=dct, decay=w.decay, lr=w.lr,
-                                   weight_decay=w.weight_decay, seed=w.seed, step=0), 1 << 22)
+                                   weight_decay=w.weight_decay, seed=w.seed, step=0), 1 << 22,
+                           max(1, args.diloco_every) if scheme == "diloco" else 1)
         oracle.set_threads(threads)
         rows.append((rec, all_cores, one))
         print(f"# done {workload} {scheme}{' dct' if dct else ''}", file=sys.stderr, flush=True)
@@ -287,6 +322,8 @@ def report(args) -> int:
     for rec, allc, one in rows:
         c = rec["config"]
         name = c["scheme"] + (" (coefficients)" if c["scheme"] != "topk" and c["dct_domain"] else "")
+        if c["scheme"] == "diloco":
+            name = f"diloco (sync every {c['diloco_every']})"
         print(f"| {c['workload']} | {name} | {c['params']:,} | {rec['ms_per_step']:.3f} | "
               f"{rec['value'] / 1e9:.1f} G | {rec['step_hbm_gbs']:.0f} "
               f"({100 * rec['step_hbm_frac_of_peak']:.0f} %) | {rec['kernels']['compress']['gbs']:.0f} | "

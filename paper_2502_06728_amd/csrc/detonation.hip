@@ -75,6 +75,12 @@ unsigned grid_for(int64_t chunks) {
 
 int launched() { return hipGetLastError() == hipSuccess ? DETO_OK : DETO_ERR_HIP; }
 
+// grid of a grid-stride streaming kernel (256 lanes per workgroup) over `items` lane-items
+unsigned stream_grid(int64_t items) {
+    const int64_t want = (items + 255) / 256 + 1;
+    return static_cast<unsigned>(want < 4096 ? want : 4096);
+}
+
 bool aligned16(const void* p) { return aligned(p, 16); }
 
 // tiled kernels take one 64-chunk tile per workgroup
@@ -115,6 +121,29 @@ int detonation_compress_packed(const deto_config* cfg, int64_t n, const void* gr
     const KParams p = resolve(cfg, 1, val_dtype, idx_dtype);
     const int64_t C = chunks_of(n, p.s);
     hipStream_t st = static_cast<hipStream_t>(stream);
+
+    // every position kept in the raw domain: the payload is the folded momentum itself
+    if (p.scheme != DETO_SCHEME_TOPK && !p.use_dct && p.k == p.s && val_dtype == DETO_F32 &&
+        idx_dtype == DETO_IDX_I32) {
+        const bool vec = p.s % 4 == 0 && aligned16(grad) && aligned16(momentum) &&
+                         aligned16(idx_out) && aligned16(val_out) && aligned16(coeff_dbg);
+        const unsigned grid = stream_grid(C * p.s / 4);
+        int32_t* io = static_cast<int32_t*>(idx_out);
+        float* vo = static_cast<float*>(val_out);
+        const int64_t entries = C * p.s;
+        if (grad_dtype == DETO_BF16) {
+            if (vec) deto::compress_dense_kernel<true, true><<<grid, 256, 0, st>>>(
+                         p, n, entries, grad, momentum, io, vo, coeff_dbg);
+            else deto::compress_dense_kernel<true, false><<<grid, 256, 0, st>>>(
+                         p, n, entries, grad, momentum, io, vo, coeff_dbg);
+        } else {
+            if (vec) deto::compress_dense_kernel<false, true><<<grid, 256, 0, st>>>(
+                         p, n, entries, grad, momentum, io, vo, coeff_dbg);
+            else deto::compress_dense_kernel<false, false><<<grid, 256, 0, st>>>(
+                         p, n, entries, grad, momentum, io, vo, coeff_dbg);
+        }
+        return launched();
+    }
 
     // a tiled kernel if one exists (full 64-chunk tiles plus, in the same launch, the tail
     // chunks on the general code), else the general kernel for everything
@@ -221,6 +250,26 @@ int decompress_impl(const deto_config* cfg, const deto_adamw* opt, int64_t n, in
     if (R > 1 && (val_replica_stride < val_elems || (idx && idx_replica_stride < entries)))
         return DETO_ERR_BAD_CONFIG;
     hipStream_t st = static_cast<hipStream_t>(stream);
+
+    // every position kept in the raw domain: the mean of R dense arrays drives the update
+    if (!idx && !opt && !p.use_dct && p.k == p.s && val_dtype == DETO_F32) {
+        const bool vec = aligned16(val) && aligned16(params) && aligned16(presign_dbg) &&
+                         (R == 1 || val_replica_stride % 4 == 0);
+        const unsigned grid = stream_grid(n / 4);
+        const float* v = static_cast<const float*>(val);
+        if (param_dtype == DETO_BF16) {
+            if (vec) deto::decompress_dense_kernel<true, true><<<grid, 256, 0, st>>>(
+                         p, n, v, val_replica_stride, params, presign_dbg);
+            else deto::decompress_dense_kernel<true, false><<<grid, 256, 0, st>>>(
+                         p, n, v, val_replica_stride, params, presign_dbg);
+        } else {
+            if (vec) deto::decompress_dense_kernel<false, true><<<grid, 256, 0, st>>>(
+                         p, n, v, val_replica_stride, params, presign_dbg);
+            else deto::decompress_dense_kernel<false, false><<<grid, 256, 0, st>>>(
+                         p, n, v, val_replica_stride, params, presign_dbg);
+        }
+        return launched();
+    }
 
     int64_t c0 = 0;
     const int64_t tiles = (n / p.s) / deto::kWave;

@@ -401,4 +401,115 @@ __global__ __launch_bounds__(256) void accumulate_kernel(float beta, int64_t n,
     }
 }
 
+// ---- k = s in the raw domain (Striding or Random that keep every position: the synchronising
+// step of a DiLoCo cycle): the payload is the whole folded momentum and the momentum restarts
+// from zero; the receivers average R dense arrays.  Plain streaming kernels, four elements per
+// lane and iteration with 16-byte accesses when the buffers allow it.
+template <bool GRAD_BF16, bool VEC>
+__global__ __launch_bounds__(256) void compress_dense_kernel(KParams p, int64_t n, int64_t entries,
+                                                             const void* __restrict__ grad,
+                                                             float* __restrict__ mom,
+                                                             int32_t* __restrict__ idx_out,
+                                                             float* __restrict__ val_out,
+                                                             float* __restrict__ coeff_dbg) {
+    const int64_t tid = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const int64_t nthreads = static_cast<int64_t>(gridDim.x) * blockDim.x;
+    int64_t done = 0;
+    if constexpr (VEC) {
+        const int64_t groups = n / 4;
+        for (int64_t q = tid; q < groups; q += nthreads) {
+            const int64_t e = 4 * q;
+            float4 g;
+            if constexpr (GRAD_BF16) {
+                const uint2 raw = ld_u2<true>(static_cast<const uint16_t*>(grad) + e);
+                g = make_float4(__uint_as_float(raw.x << 16), __uint_as_float(raw.x & 0xFFFF0000u),
+                                __uint_as_float(raw.y << 16), __uint_as_float(raw.y & 0xFFFF0000u));
+            } else {
+                g = ld_f4<true>(static_cast<const float*>(grad) + e);
+            }
+            const float4 m = ld_f4<false>(mom + e);
+            const float4 v = make_float4(fmaf(p.beta, m.x, g.x), fmaf(p.beta, m.y, g.y),
+                                         fmaf(p.beta, m.z, g.z), fmaf(p.beta, m.w, g.w));
+            st_f4<false>(val_out + e, v);
+            st_f4<false>(mom + e, make_float4(0.0f, 0.0f, 0.0f, 0.0f));
+            if (coeff_dbg) st_f4<false>(coeff_dbg + e, v);
+            if (idx_out) {
+                const int at = static_cast<int>(e % p.s);      // s is a multiple of 4 here
+                *reinterpret_cast<int4*>(idx_out + e) = make_int4(at, at + 1, at + 2, at + 3);
+            }
+        }
+        done = groups * 4;
+    }
+    // the elements the vector loop did not take, and the zero-extension of the last chunk
+    for (int64_t e = done + tid; e < entries; e += nthreads) {
+        float v = 0.0f;
+        if (e < n) {
+            const float g = GRAD_BF16 ? bf16_to_f32(static_cast<const uint16_t*>(grad)[e])
+                                      : static_cast<const float*>(grad)[e];
+            v = fmaf(p.beta, mom[e], g);
+            mom[e] = 0.0f;
+        }
+        val_out[e] = v;
+        if (coeff_dbg) coeff_dbg[e] = v;
+        if (idx_out) idx_out[e] = static_cast<int32_t>(e % p.s);
+    }
+}
+
+template <bool PARAM_BF16, bool VEC>
+__global__ __launch_bounds__(256) void decompress_dense_kernel(KParams p, int64_t n,
+                                                               const float* __restrict__ val,
+                                                               int64_t val_stride,
+                                                               void* __restrict__ params,
+                                                               float* __restrict__ presign_dbg) {
+    const int64_t tid = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const int64_t nthreads = static_cast<int64_t>(gridDim.x) * blockDim.x;
+    int64_t done = 0;
+    if constexpr (VEC) {
+        const int64_t groups = n / 4;
+        for (int64_t q = tid; q < groups; q += nthreads) {
+            const int64_t e = 4 * q;
+            float4 a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            for (int r = 0; r < p.R; ++r) {           // replica after replica: a fixed order
+                const float4 v = ld_f4<true>(val + r * val_stride + e);
+                a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
+            }
+            const float y[4] = {a.x * p.inv_R, a.y * p.inv_R, a.z * p.inv_R, a.w * p.inv_R};
+            if (presign_dbg) st_f4<false>(presign_dbg + e, make_float4(y[0], y[1], y[2], y[3]));
+            float nw[4], old[4];
+            if constexpr (PARAM_BF16) {
+                const uint2 raw = ld_u2<true>(static_cast<const uint16_t*>(params) + e);
+                old[0] = __uint_as_float(raw.x << 16);
+                old[1] = __uint_as_float(raw.x & 0xFFFF0000u);
+                old[2] = __uint_as_float(raw.y << 16);
+                old[3] = __uint_as_float(raw.y & 0xFFFF0000u);
+            } else {
+                const float4 o = ld_f4<true>(static_cast<const float*>(params) + e);
+                old[0] = o.x; old[1] = o.y; old[2] = o.z; old[3] = o.w;
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                nw[c] = fmaf(-p.lr, sign_or_self(y[c], p.use_sign), old[c] * p.wd_scale);
+            if constexpr (PARAM_BF16) {
+                *reinterpret_cast<uint2*>(static_cast<uint16_t*>(params) + e) =
+                    make_uint2(pack_bf16x2(nw[0], nw[1]), pack_bf16x2(nw[2], nw[3]));
+            } else {
+                st_f4<false>(static_cast<float*>(params) + e,
+                             make_float4(nw[0], nw[1], nw[2], nw[3]));
+            }
+        }
+        done = groups * 4;
+    }
+    for (int64_t i = done + tid; i < n; i += nthreads) {
+        float a = 0.0f;
+        for (int r = 0; r < p.R; ++r) a += val[r * val_stride + i];
+        const float y = a * p.inv_R;
+        if (presign_dbg) presign_dbg[i] = y;
+        const float old = PARAM_BF16 ? bf16_to_f32(static_cast<uint16_t*>(params)[i])
+                                     : static_cast<float*>(params)[i];
+        const float nw = fmaf(-p.lr, sign_or_self(y, p.use_sign), old * p.wd_scale);
+        if (PARAM_BF16) static_cast<uint16_t*>(params)[i] = f32_to_bf16(nw);
+        else static_cast<float*>(params)[i] = nw;
+    }
+}
+
 }  // namespace deto

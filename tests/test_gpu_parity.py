@@ -670,3 +670,20 @@ def test_diloco_cycle_accumulate_then_full_synchronisation(H, bf16):
             assert np.array_equal(y, oracle.presign(cfg, n, None, val))
             parity.check_decompress(cfg, None, val, th_in, th_new, y)   # one rounding of theta
             th_dev = H.to_dev(th_new)
+
+
+@pytest.mark.parametrize("scheme", [SCHEME_STRIDE, SCHEME_RANDOM])
+@pytest.mark.parametrize("s,n", [(64, 64 * 900 + 7), (32, 32 * 100), (6, 6 * 50 + 1), (256, 256 * 9 + 100)])
+def test_every_position_kept_in_the_raw_domain(H, scheme, s, n):
+    # k = s without the transform: the payload is the folded momentum, the momentum restarts
+    # from zero, the receivers average dense arrays (streaming kernels)
+    cfg = Config(chunk=s, topk=s, scheme=scheme, seed=2, step=5, sign=True, lr=1e-3,
+                 weight_decay=0.05)
+    st_c, st_d = full_step(H, cfg, n, R=3, seed=s, grad_bf16=True, params_bf16=True)
+    g, m, th = make_inputs(n, seed=1)
+    m_gpu, idx_gpu, val_gpu, coeff_gpu = H.gpu_compress(cfg, g, m, want_idx=True)
+    C = -(-n // s)
+    assert np.array_equal(idx_gpu.reshape(C, s), np.tile(np.arange(s, dtype=np.int32), (C, 1)))
+    assert not m_gpu.any()
+    assert np.array_equal(val_gpu[:n], oracle.fold(cfg, g, m)) and not val_gpu[n:].any()
+    assert np.array_equal(coeff_gpu, val_gpu)
