@@ -22,7 +22,7 @@ HIPCC_FLAGS = [
 # (the longest-compiling units first)
 UNITS = ["tiled_topk_s128_k16.hip", "tiled_topk_s128_k4.hip", "mfma_compress.hip",
          "mfma_decompress.hip",
-         "tiled_topk_packed.hip", "tiled_topk_ternary.hip", "tiled_adamw.hip", "tiled_scheme.hip", "tiled_topk_s64.hip", "tiled_topk_s32.hip", "tiled_topk_s16.hip", "detonation.hip"]
+         "tiled_topk_packed.hip", "tiled_topk_ternary.hip", "tiled_adamw.hip", "tiled_scheme.hip", "tiled_scheme_small.hip", "tiled_topk_s64.hip", "tiled_topk_s32.hip", "tiled_topk_s16.hip", "detonation.hip"]
 
 
 def _run(cmd: list[str], verbose: bool) -> None:

@@ -64,6 +64,8 @@ bool launch_decompress_idx_ternary(const DecompressLaunch& a);
 bool launch_decompress_adamw(const DecompressLaunch& a);       // Decoupled AdamW update
 bool launch_compress_scheme(const CompressLaunch& a);
 bool launch_decompress_scheme(const DecompressLaunch& a);
+bool launch_compress_scheme_small(const CompressLaunch& a);    // low compression rates
+bool launch_decompress_scheme_small(const DecompressLaunch& a);
 
 // Matrix-core kernels: tiles of 32 complete chunks, persistent single-wavefront workgroups.
 // A launcher returns the number of leading chunks it has taken (0: no kernel for this request).

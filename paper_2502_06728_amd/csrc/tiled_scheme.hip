@@ -1,60 +1,10 @@
-// Tiled Striding / Random kernels (raw-momentum or coefficient domain): compress, and
-// decompress without transmitted indices.
-#include "tiled_kernels.hip.h"
-#include "tiled_launch.h"
-
+// Tiled Striding / Random kernels (compress, and decompress without transmitted indices):
+// compression rates 1/2 ... 1/8 at chunk sizes 64 and 32.
 #ifdef DETO_TILED_ONLY_64_32
 #define DETO_SCHEME_LIST(X) X(64, 32)
 #else
 #define DETO_SCHEME_LIST(X) X(64, 32) X(64, 16) X(64, 8) X(32, 16) X(32, 8)
 #endif
-
-namespace deto {
-
-namespace {
-MaskWords words(const uint32_t (&w)[4]) { return MaskWords{{w[0], w[1], w[2], w[3]}}; }
-}  // namespace
-
-bool launch_compress_scheme(const CompressLaunch& a) {
-    if (a.p.val_dtype != 0 || a.p.idx_u8) return false;   // fp32 values, int32 indices only
-    const unsigned grid = tiled_grid(a.tiles, a.n_chunks);
-    const TailRange tail{a.n, a.n_chunks};
-#define X(S, K)                                                                                 \
-    if (a.p.s == S && a.p.k == K) {                                                             \
-        if (a.grad_bf16)                                                                        \
-            compress_tiled_scheme<S, K, true><<<grid, kWave, 0, a.stream>>>(                    \
-                a.p, words(a.stride_mask), a.tiles, tail, a.grad, a.mom, static_cast<int32_t*>(a.idx),        \
-                static_cast<float*>(a.val), a.coeff_dbg);         \
-        else                                                                                    \
-            compress_tiled_scheme<S, K, false><<<grid, kWave, 0, a.stream>>>(                   \
-                a.p, words(a.stride_mask), a.tiles, tail, a.grad, a.mom, static_cast<int32_t*>(a.idx),        \
-                static_cast<float*>(a.val), a.coeff_dbg);         \
-        return true;                                                                            \
-    }
-    DETO_SCHEME_LIST(X)
-#undef X
-    return false;
-}
-
-bool launch_decompress_scheme(const DecompressLaunch& a) {
-    if (a.idx || a.p.val_dtype != 0 || a.p.adam) return false;
-    const unsigned grid = tiled_grid(a.tiles, a.n_chunks);
-    const TailRange tail{a.n, a.n_chunks};
-#define X(S, K)                                                                                 \
-    if (a.p.s == S && a.p.k == K) {                                                             \
-        if (a.param_bf16)                                                                       \
-            decompress_tiled_scheme<S, K, true><<<grid, kWave, 0, a.stream>>>(                  \
-                a.p, words(a.stride_mask), a.tiles, tail, static_cast<const float*>(a.val), a.val_stride,     \
-                a.params, a.presign_dbg);     \
-        else                                                                                    \
-            decompress_tiled_scheme<S, K, false><<<grid, kWave, 0, a.stream>>>(                 \
-                a.p, words(a.stride_mask), a.tiles, tail, static_cast<const float*>(a.val), a.val_stride,     \
-                a.params, a.presign_dbg);     \
-        return true;                                                                            \
-    }
-    DETO_SCHEME_LIST(X)
-#undef X
-    return false;
-}
-
-}  // namespace deto
+#define DETO_COMPRESS_SCHEME_FN launch_compress_scheme
+#define DETO_DECOMPRESS_SCHEME_FN launch_decompress_scheme
+#include "tiled_scheme_impl.hip.h"

@@ -101,6 +101,17 @@ def test_striding_and_random_other_shapes(H, scheme, s, k):
     full_step(H, cfg, s * 900 + 1, R=2, seed=5)
 
 
+@pytest.mark.parametrize("scheme", [SCHEME_STRIDE, SCHEME_RANDOM])
+@pytest.mark.parametrize("dct", [False, True])
+@pytest.mark.parametrize("s,k", [(64, 16), (64, 8), (32, 16), (32, 8), (32, 4), (32, 2), (32, 1),
+                                 (64, 4), (64, 2), (16, 2)])
+def test_striding_and_random_low_rates(H, scheme, dct, s, k):
+    # the rates of the paper's experiments (chunk 32, k from 16 down to 1): lane-per-chunk kernels
+    cfg = Config(chunk=s, topk=k, scheme=scheme, dct=dct, seed=77, step=s + k, sign=True)
+    full_step(H, cfg, s * (64 * 30 + 9) + 3, R=3, seed=k, grad_bf16=(k % 2 == 0),
+              params_bf16=(k % 2 == 0))
+
+
 @pytest.mark.parametrize("n", [1, 5, 63, 64, 65, 64 * 64, 64 * 64 + 1, 64 * 129 - 1])
 def test_small_and_ragged_lengths(H, n):
     cfg = Config(chunk=64, topk=8)
