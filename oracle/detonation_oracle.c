@@ -183,6 +183,11 @@ static uint16_t transfer_encode(int val_dtype, float v)
     return val_dtype == ORC_F16 ? orc_float_to_f16(v) : orc_double_to_bf16((double)v);
 }
 
+/* defined further down; used by the quantised-payload variants above it */
+int orc_presign(const orc_config *cfg, int64_t n, int32_t R, const int32_t *idx,
+                int64_t idx_replica_stride, const float *val, int64_t val_replica_stride,
+                float *y);
+
 /* ------------------------------------------------------- DCT-II matrix (S1) */
 
 /* D[j*s + n], orthonormal DCT-II of length s. */
