@@ -122,3 +122,16 @@ def test_decoupled_adamw(H, amsgrad):
             assert np.abs(vm.cpu().numpy() - vm_o).max() <= 1e-5 * np.abs(vm_o).max()
         got, want = H.to_host(p).astype(np.float64), th_o.astype(np.float64)
         assert (np.abs(got - want) <= parity.TOL_F32 * np.abs(want) + parity.TOL_F32 * cfg.lr).all()
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("s,k", [(128, 64), (256, 32), (96, 12)])
+def test_olmo_1b_shard_full_size_chunk_sweep(H, s, k):
+    # the OLMo-1B shard (147,095,552 parameters) at the larger chunk sizes of the Appendix B
+    # sweep, in the launch configuration bench.py --chunk/--topk times; sampled chunk runs
+    import dataclasses
+    from tests.test_gpu_parity import _full_size_check
+    w = dataclasses.replace(synth.workloads()["olmo-1b-1of8"], chunk=s, topk=k)
+    cfg = Config(chunk=s, topk=k, decay=w.decay, lr=w.lr, sign=w.sign)
+    worst = _full_size_check(H, w, cfg, runs_count=10)
+    print(f"olmo-1b full size, chunk {s}, k {k}:", worst)
