@@ -163,6 +163,8 @@ int detonation_compress_packed(const deto_config* cfg, int64_t n, const void* gr
                                  deto::launch_compress_topk_s128_k16(a) ||
                                  deto::launch_compress_topk_s128_k1(a) ||
                                  deto::launch_compress_topk_s128_k8(a) ||
+                                 deto::launch_compress_topk_s128_k32(a) ||
+                                 deto::launch_compress_topk_s128_k64(a) ||
                                  deto::launch_compress_topk_packed(a) ||
                                  deto::launch_compress_topk_ternary(a))
                               : (deto::launch_compress_scheme(a) ||
@@ -297,6 +299,8 @@ int decompress_impl(const deto_config* cfg, const deto_adamw* opt, int64_t n, in
                                  deto::launch_decompress_idx_s128_k16(a) ||
                                  deto::launch_decompress_idx_s128_k1(a) ||
                                  deto::launch_decompress_idx_s128_k8(a) ||
+                                 deto::launch_decompress_idx_s128_k32(a) ||
+                                 deto::launch_decompress_idx_s128_k64(a) ||
                                  deto::launch_decompress_idx_packed(a) ||
                                  deto::launch_decompress_idx_ternary(a))
                               : (deto::launch_decompress_scheme(a) ||

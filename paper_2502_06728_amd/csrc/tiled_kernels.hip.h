@@ -418,8 +418,47 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void compress_ti
     // threshold: K-th largest magnitude.  Beyond S = 64 the coefficients wait in the lane's
     // LDS row (free by now) while their magnitudes are sorted, to stay within the registers.
     constexpr bool kLean = S > 64;
+    // Large k at S = 128: the two 64-entry sorts plus the k-th-largest merge take minutes to
+    // compile and hundreds of registers; there the threshold comes from a binary search over
+    // the 31 magnitude bits instead (signs parked in four mask words meanwhile, so that the
+    // count per step is two instructions per coefficient: mag - cand is exact, its sign bit
+    // goes into a collector word, one popcount per 32).
+    constexpr bool kSearch = kLean && K > 16;
     uint32_t T;
-    {
+    if constexpr (kSearch) {
+        uint32_t sgn[S / 32];
+#pragma unroll
+        for (int w = 0; w < S / 32; ++w) sgn[w] = 0u;
+        static_for<0, S>([&](auto I) {
+            constexpr int i = S - 1 - I;   // descending so that shifting lands bit i at i
+            const uint32_t b = __float_as_uint(c[i]);
+            sgn[i / 32] = (sgn[i / 32] << 1) | (b >> 31);
+            c[i] = __uint_as_float(b & 0x7FFFFFFFu);
+        });
+        T = 0u;
+        bool settled = false;   // a candidate with exactly K magnitudes at or above it separates
+#pragma unroll 1
+        for (int bit = 30; bit >= 0; --bit) {
+            const uint32_t cand = T | (1u << bit);
+            int below = 0;
+#pragma unroll
+            for (int w = 0; w < S / 32; ++w) {
+                uint32_t coll = 0u;
+#pragma unroll
+                for (int i = 0; i < 32; ++i)
+                    coll = __builtin_amdgcn_alignbit(coll, __float_as_uint(c[32 * w + i]) - cand, 31);
+                below += __popc(coll);
+            }
+            if (!settled && S - below >= K) {
+                T = cand;
+                settled = (S - below == K);
+            }
+            if (__all(settled)) break;
+        }
+        static_for<0, S>([&](auto i) {
+            c[i] = __uint_as_float(__float_as_uint(c[i]) | (((sgn[i / 32] >> (i % 32)) & 1u) << 31));
+        });
+    } else {
         uint32_t A[H], B[H];
         static_for<0, H>([&](auto i) {
             A[i] = __float_as_uint(c[i]) & 0x7FFFFFFFu;

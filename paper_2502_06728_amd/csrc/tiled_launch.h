@@ -57,10 +57,14 @@ bool launch_compress_topk_s128_k4(const CompressLaunch& a);
 bool launch_compress_topk_s128_k16(const CompressLaunch& a);
 bool launch_compress_topk_s128_k1(const CompressLaunch& a);
 bool launch_compress_topk_s128_k8(const CompressLaunch& a);
+bool launch_compress_topk_s128_k32(const CompressLaunch& a);
+bool launch_compress_topk_s128_k64(const CompressLaunch& a);
 bool launch_decompress_idx_s128_k4(const DecompressLaunch& a);
 bool launch_decompress_idx_s128_k16(const DecompressLaunch& a);
 bool launch_decompress_idx_s128_k1(const DecompressLaunch& a);
 bool launch_decompress_idx_s128_k8(const DecompressLaunch& a);
+bool launch_decompress_idx_s128_k32(const DecompressLaunch& a);
+bool launch_decompress_idx_s128_k64(const DecompressLaunch& a);
 bool launch_compress_topk_packed(const CompressLaunch& a);     // byte indices + 16-bit values
 bool launch_decompress_idx_packed(const DecompressLaunch& a);
 bool launch_compress_topk_ternary(const CompressLaunch& a);    // byte indices + two-bit signs
