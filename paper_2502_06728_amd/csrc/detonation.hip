@@ -159,6 +159,7 @@ int detonation_compress_packed(const deto_config* cfg, int64_t n, const void* gr
                               ? (deto::launch_compress_topk_s64(a) ||
                                  deto::launch_compress_topk_s32(a) ||
                                  deto::launch_compress_topk_s16(a) ||
+                                 deto::launch_compress_topk_s96(a) ||
                                  deto::launch_compress_topk_s128_k4(a) ||
                                  deto::launch_compress_topk_s128_k16(a) ||
                                  deto::launch_compress_topk_s128_k1(a) ||
@@ -295,6 +296,7 @@ int decompress_impl(const deto_config* cfg, const deto_adamw* opt, int64_t n, in
                                  deto::launch_decompress_idx_s64(a) ||
                                  deto::launch_decompress_idx_s32(a) ||
                                  deto::launch_decompress_idx_s16(a) ||
+                                 deto::launch_decompress_idx_s96(a) ||
                                  deto::launch_decompress_idx_s128_k4(a) ||
                                  deto::launch_decompress_idx_s128_k16(a) ||
                                  deto::launch_decompress_idx_s128_k1(a) ||

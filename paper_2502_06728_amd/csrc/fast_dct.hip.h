@@ -14,6 +14,8 @@
 //            y[0] = A[0], y[2l] = A[l] + B[N/2-l], y[2l+1] = A[l+1] - B[N/2-l-1],
 //            y[N-1] = -B[0]
 //   dct3_N : the transpose of dct2_N (dct4 is its own transpose)
+// The recursion ends at N = 1, or at N = 3 (direct 3-point transforms) for sizes 3 * 2^a
+// such as the chunk size 96 of the paper's Appendix B.
 // Definitions (unnormalised):
 //   dct2(x)[k] = sum_n x[n] cos(pi (2n+1) k / (2N))
 //   dct4(x)[k] = sum_n x[n] cos(pi (2n+1)(2k+1) / (4N))
@@ -63,6 +65,9 @@ struct Rot {
 };
 
 constexpr float kCosPi4 = 0.70710678118654752440f;
+constexpr float kCosPi6 = 0.86602540378443864676f;    // cos(pi/6)
+constexpr float kCosPi12 = 0.96592582628906828675f;   // cos(pi/12)
+constexpr float kCos5Pi12 = 0.25881904510252076235f;  // cos(5 pi/12)
 
 template <int N>
 struct FastDct {
@@ -71,6 +76,12 @@ struct FastDct {
     static __device__ __forceinline__ void dct2(float (&x)[N]) {
         if constexpr (N == 1) {
             return;
+        } else if constexpr (N == 3) {
+            // cos(pi (2n+1) k / 6): rows (1, 1, 1), (c, 0, -c), (1/2, -1, 1/2), c = cos(pi/6)
+            const float a = x[0], b = x[1], d = x[2];
+            x[0] = a + b + d;
+            x[1] = kCosPi6 * (a - d);
+            x[2] = fmaf(0.5f, a + d, -b);
         } else {
             float u[H], v[H];
             static_for<0, H>([&](auto i) {
@@ -89,6 +100,13 @@ struct FastDct {
     static __device__ __forceinline__ void dct4(float (&x)[N]) {
         if constexpr (N == 1) {
             x[0] *= kCosPi4;
+        } else if constexpr (N == 3) {
+            // cos(pi (2n+1)(2k+1) / 12) with p = cos(pi/12), q = cos(pi/4), r = cos(5 pi/12):
+            // rows (p, q, r), (q, -q, -q), (r, -q, p)
+            const float a = x[0], b = x[1], d = x[2];
+            x[0] = fmaf(kCosPi12, a, fmaf(kCosPi4, b, kCos5Pi12 * d));
+            x[1] = kCosPi4 * (a - b - d);
+            x[2] = fmaf(kCos5Pi12, a, fmaf(-kCosPi4, b, kCosPi12 * d));
         } else {
             float a[H], b[H];
             static_for<0, H>([&](auto j) {
@@ -110,6 +128,12 @@ struct FastDct {
     static __device__ __forceinline__ void dct3(float (&x)[N]) {
         if constexpr (N == 1) {
             return;
+        } else if constexpr (N == 3) {
+            // transpose of the 3-point dct2: columns (1, c, 1/2), (1, 0, -1), (1, -c, 1/2)
+            const float a = x[0], b = kCosPi6 * x[1], d = x[2];
+            x[0] = a + b + 0.5f * d;
+            x[1] = a - d;
+            x[2] = a - b + 0.5f * d;
         } else {
             float u[H], v[H];
             static_for<0, H>([&](auto i) {

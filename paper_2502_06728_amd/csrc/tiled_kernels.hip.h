@@ -423,7 +423,7 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void compress_ti
     // the 31 magnitude bits instead (signs parked in four mask words meanwhile, so that the
     // count per step is two instructions per coefficient: mag - cand is exact, its sign bit
     // goes into a collector word, one popcount per 32).
-    constexpr bool kSearch = kLean && K > 16;
+    constexpr bool kSearch = kLean && (K > 16 || (S & (S - 1)) != 0);   // or S not a power of 2
     uint32_t T;
     if constexpr (kSearch) {
         uint32_t sgn[S / 32];
@@ -686,14 +686,28 @@ __device__ __forceinline__ void scatter_payload(const PayloadRegs<K, VAL>& r, fl
     constexpr int kIt = K / 4;
     constexpr uint32_t kS = static_cast<uint32_t>(S);
     bool ok = true;
-    const bool first = (lane % kIt) == 0;       // first lane of its chunk (kIt lanes a chunk)
+    [[maybe_unused]] uint32_t tail_prev = 0u;   // last index of lane 63's previous vector
 #pragma unroll
     for (int it = 0; it < kIt; ++it) {
         const uint32_t x = r.template idx<0>(it), y = r.template idx<1>(it),
                        z = r.template idx<2>(it), w = r.template idx<3>(it);
-        // previous lane's last index (row_shr:1; kIt divides the 16-lane DPP row)
-        const uint32_t pw = static_cast<uint32_t>(
-            __builtin_amdgcn_update_dpp(0, static_cast<int>(w), 0x111, 0xf, 0xf, false));
+        // the lane's vector holds entries it*256 + 4*lane ... + 3: the first of its chunk?
+        const bool first = ((it * 256 + lane * 4) % K) == 0;
+        // previous lane's last index: a DPP shift inside the 16-lane row when chunks never
+        // straddle rows (K/4 divides 16 and 256), a full-wavefront shift otherwise
+        uint32_t pw;
+        if constexpr (16 % kIt == 0)
+            pw = static_cast<uint32_t>(
+                __builtin_amdgcn_update_dpp(0, static_cast<int>(w), 0x111, 0xf, 0xf, false));
+        else
+            pw = static_cast<uint32_t>(__shfl_up(static_cast<int>(w), 1));
+        // lane 0 may continue a chunk begun by lane 63 of the previous vector (only when K
+        // does not divide 256; for it = 0 lane 0 is always the first of its chunk)
+        if constexpr (256 % K != 0) {
+            if (lane == 0) pw = tail_prev;
+            tail_prev = static_cast<uint32_t>(
+                __builtin_amdgcn_readlane(static_cast<int>(w), kWave - 1));
+        }
         ok = ok && (x < y) && (y < z) && (z < w) && (first || pw < x);
     }
     if (!__any(!ok)) {

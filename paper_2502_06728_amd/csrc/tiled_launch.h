@@ -50,9 +50,11 @@ inline unsigned tiled_grid(int64_t tiles, int64_t n_chunks) {
 bool launch_compress_topk_s64(const CompressLaunch& a);
 bool launch_compress_topk_s32(const CompressLaunch& a);
 bool launch_compress_topk_s16(const CompressLaunch& a);
+bool launch_compress_topk_s96(const CompressLaunch& a);
 bool launch_decompress_idx_s64(const DecompressLaunch& a);
 bool launch_decompress_idx_s32(const DecompressLaunch& a);
 bool launch_decompress_idx_s16(const DecompressLaunch& a);
+bool launch_decompress_idx_s96(const DecompressLaunch& a);
 bool launch_compress_topk_s128_k4(const CompressLaunch& a);
 bool launch_compress_topk_s128_k16(const CompressLaunch& a);
 bool launch_compress_topk_s128_k1(const CompressLaunch& a);

@@ -78,6 +78,30 @@ def test_chunk_size_16(H, k, bf16):
               outliers=0.01 if bf16 else 0.0)
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("k", [6, 12, 24, 48, 5, 96])
+def test_chunk_size_96(H, k, bf16):
+    # 96 = 3 * 32: lane-per-chunk kernels whose fast DCT ends in 3-point transforms
+    # (k in {6, 12, 24, 48}); other k on the matrix-core kernels
+    cfg = Config(chunk=96, topk=k, sign=True)
+    full_step(H, cfg, 96 * (64 * 20 + 31) + 50, R=3, seed=k, grad_bf16=bf16, params_bf16=bf16,
+              outliers=0.01 if bf16 else 0.0)
+
+
+def test_chunk_size_96_ties(H):
+    # zero chunks tie everywhere; single spikes give coefficients of pairwise equal magnitude
+    s, k = 96, 12
+    n = s * 128
+    cfg = Config(chunk=s, topk=k, decay=0.0)
+    g = np.zeros(n, np.float32)
+    for c in range(0, 128, 3):
+        g[c * s + (7 * c) % s] = 1.0 + c
+    m = np.zeros(n, np.float32)
+    m_gpu, idx_gpu, val_gpu, coeff_gpu = H.gpu_compress(cfg, g, m)
+    parity.check_compress(cfg, g, m, m_gpu, idx_gpu, val_gpu, coeff_gpu)
+    assert np.array_equal(idx_gpu.reshape(-1, k)[1], np.arange(k))
+
+
 @pytest.mark.parametrize("grad_bf16,params_bf16", [(True, True), (True, False), (False, True)])
 def test_bf16_storage_with_outliers(H, grad_bf16, params_bf16):
     cfg = Config(chunk=64, topk=32, sign=True)
@@ -698,3 +722,23 @@ def test_every_position_kept_in_the_raw_domain(H, scheme, s, n):
     assert not m_gpu.any()
     assert np.array_equal(val_gpu[:n], oracle.fold(cfg, g, m)) and not val_gpu[n:].any()
     assert np.array_equal(coeff_gpu, val_gpu)
+
+
+@pytest.mark.parametrize("s,k", [(96, 12), (96, 24), (96, 48), (128, 64), (64, 32), (16, 8)])
+def test_unordered_payloads_on_every_vector_scatter(H, s, k):
+    # duplicates, disorder and out-of-range indices at the k values whose chunks straddle the
+    # 64-lane vectors of the scatter (k not dividing 256) and at those that do not
+    n = s * 64 * 6
+    C = n // s
+    cfg = Config(chunk=s, topk=k, sign=False)
+    rng = np.random.default_rng(s + k)
+    idx = np.stack([np.sort(rng.integers(0, s, size=(C, k)), axis=1).reshape(-1),      # repeats
+                    rng.integers(-2, s + 2, size=C * k),                                # anything
+                    np.tile(np.arange(k), C)]).astype(np.int32)                         # clean
+    # a clean chunk sequence broken exactly at vector boundaries (entry 256*j - 1 and 256*j)
+    for j in range(1, (C * k) // 256):
+        idx[2, 256 * j] = idx[2, 256 * j - 1]
+    val = rng.standard_normal((3, C * k)).astype(np.float32)
+    th = make_inputs(n, 3)[2]
+    th_gpu, y_gpu = H.gpu_decompress(cfg, idx, val, th)
+    parity.check_decompress(cfg, idx, val, th, th_gpu, y_gpu)
