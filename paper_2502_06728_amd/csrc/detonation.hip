@@ -175,9 +175,10 @@ int detonation_compress_packed(const deto_config* cfg, int64_t n, const void* gr
             if (rc) return rc;
             c0 = C;   // the tail chunks rode along in the same launch
         } else {
-            // no lane-per-chunk kernel for this (s, k): the matrix-core kernel takes the
-            // leading multiple of 32 chunks
-            c0 = deto::launch_compress_mfma(a);
+            // no lane-per-chunk kernel for this (s, k): the two-lanes-per-chunk kernel (chunk
+            // 192, 256) or the matrix-core kernel takes the leading multiple of 32 chunks
+            c0 = deto::launch_compress_pair(a);
+            if (c0 == 0) c0 = deto::launch_compress_mfma(a);
             if (c0 > 0) {
                 rc = launched();
                 if (rc) return rc;
@@ -312,7 +313,8 @@ int decompress_impl(const deto_config* cfg, const deto_adamw* opt, int64_t n, in
             if (rc) return rc;
             c0 = C;   // the tail chunks rode along in the same launch
         } else {
-            c0 = deto::launch_decompress_mfma(a);
+            c0 = deto::launch_decompress_pair(a);
+            if (c0 == 0) c0 = deto::launch_decompress_mfma(a);
             if (c0 > 0) {
                 rc = launched();
                 if (rc) return rc;

@@ -1,6 +1,6 @@
-// Matrix-core kernels for the chunk sizes the lane-per-chunk tiled kernels do not cover
-// (any multiple of 32 up to 256, any k, top-k selection): the DCT of Algorithm 1 as the dense
-// product it is defined as, on v_mfma_f32_32x32x2f32.
+// Matrix-core kernels for the (chunk size, k) pairs the lane-per-chunk and two-lanes-per-chunk
+// kernels do not cover (chunk sizes 32 ... 224 in steps of 32, any k, top-k selection): the DCT
+// of Algorithm 1 as the dense product it is defined as, on v_mfma_f32_32x32x2f32.
 //
 // One wavefront (= one workgroup) owns a tile of 32 complete chunks, held as a 32 x S matrix
 // in LDS (row = chunk).  With X the tile and D the S x S DCT-II matrix:
@@ -267,6 +267,100 @@ __device__ __forceinline__ void inverse_to_lds(float* __restrict__ buf,
     }
 }
 
+// ---- tile streaming and bookkeeping shared by the 32-chunk-tile kernels (NB = S / 32)
+
+// m1 = beta*m + g for the tile's 32*S contiguous elements, coalesced, into the LDS rows (deep
+// unroll: nothing else of this wavefront is in flight, so the loads of half a tile or more are
+// issued at once)
+template <int NB, bool GRAD_BF16>
+__device__ __forceinline__ void fold_tile_rows(float* __restrict__ buf, const KParams& p, int lane,
+                                               const void* __restrict__ grad,
+                                               const float* __restrict__ mom, int64_t base) {
+    using G = MfmaGeom<NB>;
+    constexpr int S = G::S, kRow = G::kRow;
+#pragma unroll 16
+    for (int it = 0; it < G::kVecIters; ++it) {
+        const int e4 = 4 * (lane + kWave * it);
+        const int row = e4 / S, col = e4 - row * S;
+        const float4 m = ld_f4<false>(mom + base + e4);
+        float4 g;
+        if constexpr (GRAD_BF16) {
+            const uint2 gb = ld_u2<false>(static_cast<const uint16_t*>(grad) + base + e4);
+            g = make_float4(__uint_as_float(gb.x << 16), __uint_as_float(gb.x & 0xFFFF0000u),
+                            __uint_as_float(gb.y << 16), __uint_as_float(gb.y & 0xFFFF0000u));
+        } else {
+            g = ld_f4<false>(static_cast<const float*>(grad) + base + e4);
+        }
+        const float4 x = make_float4(fmaf(p.beta, m.x, g.x), fmaf(p.beta, m.y, g.y),
+                                     fmaf(p.beta, m.z, g.z), fmaf(p.beta, m.w, g.w));
+        *reinterpret_cast<float4*>(&buf[row * kRow + col]) = x;
+    }
+}
+
+// the LDS rows (new momentum) out, coalesced
+template <int NB>
+__device__ __forceinline__ void store_tile_rows(const float* __restrict__ buf, int lane,
+                                                float* __restrict__ mom, int64_t base) {
+    using G = MfmaGeom<NB>;
+    constexpr int S = G::S, kRow = G::kRow;
+#pragma unroll 4
+    for (int it = 0; it < G::kVecIters; ++it) {
+        const int e4 = 4 * (lane + kWave * it);
+        const int row = e4 / S, col = e4 - row * S;
+        st_f4<false>(mom + base + e4, *reinterpret_cast<const float4*>(&buf[row * kRow + col]));
+    }
+}
+
+// Chunks with ties at the k-th magnitude (need != 0 on the chunk's lanes), one at a time with
+// the whole wavefront; their LDS rows hold the coefficients.  Everything above thr_eq is kept
+// and, of the entries equal to it, the `need` lowest indices.  The payload goes out and the
+// row is left holding alpha_j * remainder.
+template <int NB>
+__device__ __forceinline__ void emit_tied_chunks(float* __restrict__ buf, const KParams& p,
+                                                 int lane, int need, uint32_t thr_gt,
+                                                 uint32_t thr_eq, int64_t chunk0,
+                                                 void* __restrict__ idx_out,
+                                                 void* __restrict__ val_out,
+                                                 float* __restrict__ coeff_dbg) {
+    using G = MfmaGeom<NB>;
+    constexpr int S = G::S, kRow = G::kRow;
+    const int k = p.k;
+    if (!__any(need != 0)) return;
+    for (int tt = 0; tt < kMfmaChunks; ++tt) {
+        const int c_need = __builtin_amdgcn_readlane(need, tt);
+        if (c_need == 0) continue;
+        const uint32_t c_gt = __builtin_amdgcn_readlane(thr_gt, tt);
+        const uint32_t c_eq = __builtin_amdgcn_readlane(thr_eq, tt);
+        const int64_t chunk = chunk0 + tt;
+        int kept_before = 0, eq_before = 0;
+#pragma unroll
+        for (int e0 = 0; e0 < S; e0 += kWave) {
+            const int e = e0 + lane;
+            const bool in = (S % kWave == 0) || e < S;
+            const float c = in ? buf[tt * kRow + e] : 0.0f;
+            const uint32_t mg = __float_as_uint(c) & 0x7FFFFFFFu;
+            const bool eq = in && mg == c_eq;
+            const uint64_t eqm = __ballot(eq);
+            const int eq_rank = eq_before + lanes_below(eqm, lane);
+            const bool keep = in && (mg >= c_gt || (eq && eq_rank < c_need));
+            const uint64_t km = __ballot(keep);
+            const int pos = kept_before + lanes_below(km, lane);
+            float rem = c;
+            if (keep && pos < k) {
+                store_payload_index(idx_out, chunk * k + pos, p.idx_u8, e);
+                store_payload_value(val_out, chunk * k + pos, p.val_dtype, c);
+                rem = c - payload_roundtrip(p.val_dtype, c);
+            }
+            if (in) {
+                if (coeff_dbg) coeff_dbg[chunk * S + e] = c;
+                buf[tt * kRow + e] = rem * (e == 0 ? p.alpha0 : p.alpha);
+            }
+            kept_before += __popcll(km);
+            eq_before += __popcll(eqm);
+        }
+    }
+}
+
 // Compress half on full tiles of 32 chunks (top-k selection, DCT domain).
 template <int NB, bool GRAD_BF16>
 __global__ __launch_bounds__(kWave)
@@ -291,25 +385,7 @@ __attribute__((amdgpu_waves_per_eu(MfmaGeom<NB>::kWavesPerSimd))) void compress_
         const int64_t base = tile * static_cast<int64_t>(kMfmaChunks * S);
         const int64_t chunk0 = tile * kMfmaChunks;
 
-        // ---- m1 = beta*m + g, coalesced, into the LDS rows (deep unroll: nothing else of
-        // this wavefront is in flight, so the loads of half a tile or more are issued at once)
-#pragma unroll 16
-        for (int it = 0; it < G::kVecIters; ++it) {
-            const int e4 = 4 * (lane + kWave * it);
-            const int row = e4 / S, col = e4 - row * S;
-            const float4 m = ld_f4<false>(mom + base + e4);
-            float4 g;
-            if constexpr (GRAD_BF16) {
-                const uint2 gb = ld_u2<false>(static_cast<const uint16_t*>(grad) + base + e4);
-                g = make_float4(__uint_as_float(gb.x << 16), __uint_as_float(gb.x & 0xFFFF0000u),
-                                __uint_as_float(gb.y << 16), __uint_as_float(gb.y & 0xFFFF0000u));
-            } else {
-                g = ld_f4<false>(static_cast<const float*>(grad) + base + e4);
-            }
-            const float4 x = make_float4(fmaf(p.beta, m.x, g.x), fmaf(p.beta, m.y, g.y),
-                                         fmaf(p.beta, m.z, g.z), fmaf(p.beta, m.w, g.w));
-            *reinterpret_cast<float4*>(&buf[row * kRow + col]) = x;
-        }
+        fold_tile_rows<NB, GRAD_BF16>(buf, p, lane, grad, mom, base);
         wave_lds_sync();
 
         // ---- DCT-II of every chunk of the tile, coefficients into the LDS rows
@@ -433,55 +509,13 @@ __attribute__((amdgpu_waves_per_eu(MfmaGeom<NB>::kWavesPerSimd))) void compress_
             }
         }
         wave_lds_sync();
-        // ---- chunks with ties at the k-th magnitude, one at a time with the whole wavefront
-        // (their LDS rows still hold the coefficients): of the entries equal to thr_eq the
-        // `need` lowest indices are kept.
-        if (__any(need != 0)) {
-            for (int tt = 0; tt < kMfmaChunks; ++tt) {
-                const int c_need = __builtin_amdgcn_readlane(need, tt);
-                if (c_need == 0) continue;
-                const uint32_t c_gt = __builtin_amdgcn_readlane(thr_gt, tt);
-                const uint32_t c_eq = __builtin_amdgcn_readlane(thr_eq, tt);
-                const int64_t chunk = chunk0 + tt;
-                int kept_before = 0, eq_before = 0;
-#pragma unroll
-                for (int e0 = 0; e0 < S; e0 += kWave) {
-                    const int e = e0 + lane;
-                    const bool in = (S % kWave == 0) || e < S;
-                    const float c = in ? buf[tt * kRow + e] : 0.0f;
-                    const uint32_t mg = __float_as_uint(c) & 0x7FFFFFFFu;
-                    const bool eq = in && mg == c_eq;
-                    const uint64_t eqm = __ballot(eq);
-                    const int eq_rank = eq_before + lanes_below(eqm, lane);
-                    const bool keep = in && (mg >= c_gt || (eq && eq_rank < c_need));
-                    const uint64_t km = __ballot(keep);
-                    const int pos = kept_before + lanes_below(km, lane);
-                    float rem = c;
-                    if (keep && pos < k) {
-                        store_payload_index(idx_out, chunk * k + pos, p.idx_u8, e);
-                        store_payload_value(val_out, chunk * k + pos, p.val_dtype, c);
-                        rem = c - payload_roundtrip(p.val_dtype, c);
-                    }
-                    if (in) {
-                        if (coeff_dbg) coeff_dbg[chunk * S + e] = c;
-                        buf[tt * kRow + e] = rem * (e == 0 ? p.alpha0 : p.alpha);
-                    }
-                    kept_before += __popcll(km);
-                    eq_before += __popcll(eqm);
-                }
-            }
-        }
+        emit_tied_chunks<NB>(buf, p, lane, need, thr_gt, thr_eq, chunk0, idx_out, val_out, coeff_dbg);
         wave_lds_sync();
 
         // ---- new momentum = inverse transform of the remainder
         inverse_to_lds<NB>(buf, tab, t, h, [](float y) { return y; });
         wave_lds_sync();
-#pragma unroll 4
-        for (int it = 0; it < G::kVecIters; ++it) {
-            const int e4 = 4 * (lane + kWave * it);
-            const int row = e4 / S, col = e4 - row * S;
-            st_f4<false>(mom + base + e4, *reinterpret_cast<const float4*>(&buf[row * kRow + col]));
-        }
+        store_tile_rows<NB>(buf, lane, mom, base);
         wave_lds_sync();
     }
 }
@@ -598,6 +632,137 @@ __device__ __forceinline__ void scatter_add_vec(float* __restrict__ buf, const K
     }
 }
 
+// Entry -> chunk inside a group of 8 chunks of k entries: floor(e / k) = umulhi(e, magic) with
+// magic = ceil(2^32 / k), exact for e < 2^13 (k = 1 is the identity)
+__device__ __forceinline__ uint32_t entry_magic(int k) {
+    return (k == 1) ? 0u
+                    : static_cast<uint32_t>(((1ull << 32) + static_cast<uint64_t>(k) - 1ull) /
+                                            static_cast<uint64_t>(k));
+}
+
+// Zero the accumulator rows and scatter-add the tile's entries of all R replicas, replica
+// after replica.  vec_scatter: fp32 values + int32 indices with k a multiple of 4 (16-byte
+// loads); otherwise any payload format with 4-byte (or narrower) coalesced loads: the tile's
+// entries of one replica are contiguous, four groups of 8 chunks run side by side (different
+// LDS rows).  Within one instruction the entries of a chunk must hit distinct addresses for
+// the plain read-add-write: guaranteed when their indices ascend strictly, else LDS atomics.
+template <int NB>
+__device__ __forceinline__ void scatter_tile(float* __restrict__ buf, const KParams& p, int lane,
+                                             int vec_scatter, const void* __restrict__ idx,
+                                             int64_t idx_stride, const void* __restrict__ val,
+                                             int64_t val_stride, int64_t entry0, uint32_t magic) {
+    using G = MfmaGeom<NB>;
+    constexpr int S = G::S, kRow = G::kRow;
+    const int k = p.k;
+    const uint32_t group_entries = 8u * static_cast<uint32_t>(k);
+    const int scatter_iters = static_cast<int>((group_entries + kWave - 1) / kWave);
+    for (int v = lane; v < kMfmaChunks * kRow / 4; v += kWave)
+        *reinterpret_cast<float4*>(&buf[4 * v]) = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    wave_lds_sync();
+
+    // ---- scatter-add, replica after replica.  The tile's entries of one replica are
+    // contiguous; four groups of 8 chunks run side by side (different LDS rows).  Within
+    // one instruction the entries of a chunk must hit distinct addresses for the plain
+    // read-add-write: guaranteed when their indices ascend strictly, else LDS atomics.
+    if (vec_scatter)
+        scatter_add_vec<NB>(buf, p, lane, static_cast<const int32_t*>(idx), idx_stride,
+                            static_cast<const float*>(val), val_stride, entry0, magic);
+    else
+    for (int r = 0; r < p.R; ++r) {
+        const int64_t ib = r * idx_stride + entry0;
+        const int64_t vb = r * val_stride + entry0;
+        for (int it = 0; it < scatter_iters; ++it) {
+            const uint32_t el = static_cast<uint32_t>(it * kWave + lane);
+            const bool in = el < group_entries;
+            const uint32_t lrow = (k == 1) ? el : __umulhi(el, magic);
+            const bool chunk_start = (el - lrow * static_cast<uint32_t>(k)) == 0u;
+            int at[4], addr[4];
+            float v[4];
+            bool ok[4];
+            bool bad = false;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int64_t e = static_cast<int64_t>(q) * group_entries + el;
+                at[q] = in ? load_payload_index(idx, ib + e, p.idx_u8) : -1;
+                v[q] = in ? load_payload_value(val, vb + e, p.val_dtype) : 0.0f;
+                ok[q] = in && at[q] >= 0 && at[q] < S;
+                addr[q] = (8 * q + static_cast<int>(lrow)) * kRow + at[q];
+                const int prev = __shfl_up(at[q], 1);
+                bad = bad || (in && lane > 0 && !chunk_start && prev >= at[q]);
+            }
+            if (__any(bad)) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (ok[q]) atomicAdd(&buf[addr[q]], v[q]);
+            } else {
+                float a[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) a[q] = ok[q] ? buf[addr[q]] : 0.0f;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (ok[q]) buf[addr[q]] = a[q] + v[q];
+            }
+        }
+    }
+    wave_lds_sync();
+}
+
+// Last phase of decompress: y (four consecutive elements of a row from get_y4(row, col)),
+// optional sign, parameter update (plain or Decoupled AdamW), coalesced.
+template <int NB, bool PARAM_BF16, class GetY>
+__device__ __forceinline__ void update_params_rows(const KParams& p, int lane, int64_t base,
+                                                   void* __restrict__ params, const AdamPtrs& ad,
+                                                   float* __restrict__ presign_dbg, GetY get_y4) {
+    using G = MfmaGeom<NB>;
+    constexpr int S = G::S;
+    #pragma unroll 2
+    for (int it = 0; it < G::kVecIters; ++it) {
+        const int e4 = 4 * (lane + kWave * it);
+        const int row = e4 / S, col = e4 - row * S;
+        const int64_t i = base + e4;
+        const float4 y4 = get_y4(row, col);
+        if (presign_dbg) st_f4<false>(presign_dbg + i, y4);
+        const float y[4] = {y4.x, y4.y, y4.z, y4.w};
+        float old[4], nw[4];
+        uint2 pb;
+        if constexpr (PARAM_BF16) {
+            pb = ld_u2<false>(static_cast<const uint16_t*>(params) + i);
+            old[0] = __uint_as_float(pb.x << 16);
+            old[1] = __uint_as_float(pb.x & 0xFFFF0000u);
+            old[2] = __uint_as_float(pb.y << 16);
+            old[3] = __uint_as_float(pb.y & 0xFFFF0000u);
+        } else {
+            const float4 o = ld_f4<false>(static_cast<const float*>(params) + i);
+            old[0] = o.x; old[1] = o.y; old[2] = o.z; old[3] = o.w;
+        }
+        if (p.adam) {
+            const float4 m4 = ld_f4<false>(ad.m + i), v4 = ld_f4<false>(ad.v + i);
+            float4 x4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (p.amsgrad) x4 = ld_f4<false>(ad.vmax + i);
+            float m[4] = {m4.x, m4.y, m4.z, m4.w}, v[4] = {v4.x, v4.y, v4.z, v4.w};
+            float x[4] = {x4.x, x4.y, x4.z, x4.w};
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                nw[c] = adamw_step(p, old[c], sign_or_self(y[c], p.use_sign), m[c], v[c], x[c]);
+            st_f4<false>(ad.m + i, make_float4(m[0], m[1], m[2], m[3]));
+            st_f4<false>(ad.v + i, make_float4(v[0], v[1], v[2], v[3]));
+            if (p.amsgrad) st_f4<false>(ad.vmax + i, make_float4(x[0], x[1], x[2], x[3]));
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                nw[c] = fmaf(-p.lr, sign_or_self(y[c], p.use_sign), old[c] * p.wd_scale);
+        }
+        if constexpr (PARAM_BF16) {
+            uint2 o;
+            o.x = pack_bf16x2(nw[0], nw[1]);
+            o.y = pack_bf16x2(nw[2], nw[3]);
+            *reinterpret_cast<uint2*>(static_cast<uint16_t*>(params) + i) = o;
+        } else {
+            st_f4<false>(static_cast<float*>(params) + i, make_float4(nw[0], nw[1], nw[2], nw[3]));
+        }
+    }
+}
+
 // Decompress-and-update half on full tiles of 32 chunks (transmitted indices, DCT domain).
 template <int NB, bool PARAM_BF16>
 __global__ __launch_bounds__(kWave)
@@ -616,11 +781,7 @@ __attribute__((amdgpu_waves_per_eu(MfmaGeom<NB>::kWavesPerSimd))) void decompres
     build_cos_table_quarter<S>(tab, lane);
     // entry -> chunk within a group of 8 chunks: floor(e / k) = umulhi(e, ceil(2^32 / k)),
     // exact for e < 8*256
-    const uint32_t magic =
-        (k == 1) ? 0u : static_cast<uint32_t>(((1ull << 32) + static_cast<uint64_t>(k) - 1ull) /
-                                              static_cast<uint64_t>(k));
-    const uint32_t group_entries = 8u * static_cast<uint32_t>(k);
-    const int scatter_iters = static_cast<int>((group_entries + kWave - 1) / kWave);
+    const uint32_t magic = entry_magic(k);
     const float out_scale = p.alpha * p.inv_R;
     const float row0_fix = (p.alpha0 - p.alpha) * p.inv_R;
     wave_lds_sync();
@@ -629,54 +790,7 @@ __attribute__((amdgpu_waves_per_eu(MfmaGeom<NB>::kWavesPerSimd))) void decompres
         const int64_t base = tile * static_cast<int64_t>(kMfmaChunks * S);
         const int64_t entry0 = tile * static_cast<int64_t>(kMfmaChunks) * k;
 
-        for (int v = lane; v < kMfmaChunks * kRow / 4; v += kWave)
-            *reinterpret_cast<float4*>(&buf[4 * v]) = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        wave_lds_sync();
-
-        // ---- scatter-add, replica after replica.  The tile's entries of one replica are
-        // contiguous; four groups of 8 chunks run side by side (different LDS rows).  Within
-        // one instruction the entries of a chunk must hit distinct addresses for the plain
-        // read-add-write: guaranteed when their indices ascend strictly, else LDS atomics.
-        if (vec_scatter)
-            scatter_add_vec<NB>(buf, p, lane, static_cast<const int32_t*>(idx), idx_stride,
-                                static_cast<const float*>(val), val_stride, entry0, magic);
-        else
-        for (int r = 0; r < p.R; ++r) {
-            const int64_t ib = r * idx_stride + entry0;
-            const int64_t vb = r * val_stride + entry0;
-            for (int it = 0; it < scatter_iters; ++it) {
-                const uint32_t el = static_cast<uint32_t>(it * kWave + lane);
-                const bool in = el < group_entries;
-                const uint32_t lrow = (k == 1) ? el : __umulhi(el, magic);
-                const bool chunk_start = (el - lrow * static_cast<uint32_t>(k)) == 0u;
-                int at[4], addr[4];
-                float v[4];
-                bool ok[4];
-                bool bad = false;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int64_t e = static_cast<int64_t>(q) * group_entries + el;
-                    at[q] = in ? load_payload_index(idx, ib + e, p.idx_u8) : -1;
-                    v[q] = in ? load_payload_value(val, vb + e, p.val_dtype) : 0.0f;
-                    ok[q] = in && at[q] >= 0 && at[q] < S;
-                    addr[q] = (8 * q + static_cast<int>(lrow)) * kRow + at[q];
-                    const int prev = __shfl_up(at[q], 1);
-                    bad = bad || (in && lane > 0 && !chunk_start && prev >= at[q]);
-                }
-                if (__any(bad)) {
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        if (ok[q]) atomicAdd(&buf[addr[q]], v[q]);
-                } else {
-                    float a[4];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) a[q] = ok[q] ? buf[addr[q]] : 0.0f;
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        if (ok[q]) buf[addr[q]] = a[q] + v[q];
-                }
-            }
-        }
+        scatter_tile<NB>(buf, p, lane, vec_scatter, idx, idx_stride, val, val_stride, entry0, magic);
         wave_lds_sync();
 
         // ---- y^T = D^T * (alpha_j a_j / R)^T; the scale is applied to the result:
@@ -687,52 +801,11 @@ __attribute__((amdgpu_waves_per_eu(MfmaGeom<NB>::kWavesPerSimd))) void decompres
         wave_lds_sync();
 
         // ---- sign and parameter update, coalesced
-#pragma unroll 2
-        for (int it = 0; it < G::kVecIters; ++it) {
-            const int e4 = 4 * (lane + kWave * it);
-            const int row = e4 / S, col = e4 - row * S;
-            const int64_t i = base + e4;
-            const float4 y4 = *reinterpret_cast<const float4*>(&buf[row * kRow + col]);
-            if (presign_dbg) st_f4<false>(presign_dbg + i, y4);
-            const float y[4] = {y4.x, y4.y, y4.z, y4.w};
-            float old[4], nw[4];
-            uint2 pb;
-            if constexpr (PARAM_BF16) {
-                pb = ld_u2<false>(static_cast<const uint16_t*>(params) + i);
-                old[0] = __uint_as_float(pb.x << 16);
-                old[1] = __uint_as_float(pb.x & 0xFFFF0000u);
-                old[2] = __uint_as_float(pb.y << 16);
-                old[3] = __uint_as_float(pb.y & 0xFFFF0000u);
-            } else {
-                const float4 o = ld_f4<false>(static_cast<const float*>(params) + i);
-                old[0] = o.x; old[1] = o.y; old[2] = o.z; old[3] = o.w;
-            }
-            if (p.adam) {
-                const float4 m4 = ld_f4<false>(ad.m + i), v4 = ld_f4<false>(ad.v + i);
-                float4 x4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-                if (p.amsgrad) x4 = ld_f4<false>(ad.vmax + i);
-                float m[4] = {m4.x, m4.y, m4.z, m4.w}, v[4] = {v4.x, v4.y, v4.z, v4.w};
-                float x[4] = {x4.x, x4.y, x4.z, x4.w};
-#pragma unroll
-                for (int c = 0; c < 4; ++c)
-                    nw[c] = adamw_step(p, old[c], sign_or_self(y[c], p.use_sign), m[c], v[c], x[c]);
-                st_f4<false>(ad.m + i, make_float4(m[0], m[1], m[2], m[3]));
-                st_f4<false>(ad.v + i, make_float4(v[0], v[1], v[2], v[3]));
-                if (p.amsgrad) st_f4<false>(ad.vmax + i, make_float4(x[0], x[1], x[2], x[3]));
-            } else {
-#pragma unroll
-                for (int c = 0; c < 4; ++c)
-                    nw[c] = fmaf(-p.lr, sign_or_self(y[c], p.use_sign), old[c] * p.wd_scale);
-            }
-            if constexpr (PARAM_BF16) {
-                uint2 o;
-                o.x = pack_bf16x2(nw[0], nw[1]);
-                o.y = pack_bf16x2(nw[2], nw[3]);
-                *reinterpret_cast<uint2*>(static_cast<uint16_t*>(params) + i) = o;
-            } else {
-                st_f4<false>(static_cast<float*>(params) + i, make_float4(nw[0], nw[1], nw[2], nw[3]));
-            }
-        }
+        update_params_rows<NB, PARAM_BF16>(p, lane, base, params, ad, presign_dbg,
+                                           [&](int row, int col) {
+                                               return *reinterpret_cast<const float4*>(
+                                                   &buf[row * kRow + col]);
+                                           });
         wave_lds_sync();
     }
 }

@@ -82,7 +82,7 @@ bool launch_decompress_scheme_small(const DecompressLaunch& a);
 #ifdef DETO_TILED_ONLY_64_32
 #define DETO_MFMA_NB_LIST(X) X(4)
 #else
-#define DETO_MFMA_NB_LIST(X) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8)
+#define DETO_MFMA_NB_LIST(X) X(1) X(2) X(3) X(4) X(5) X(7)   // 6 and 8: two-lanes-per-chunk kernels
 #endif
 
 inline unsigned mfma_grid(int64_t tiles, size_t smem_bytes) {
@@ -93,5 +93,20 @@ inline unsigned mfma_grid(int64_t tiles, size_t smem_bytes) {
 
 int64_t launch_compress_mfma(const CompressLaunch& a);
 int64_t launch_decompress_mfma(const DecompressLaunch& a);
+
+// Two-lanes-per-chunk kernels (register-resident fast DCT split between lanes t and t+32): the
+// chunk sizes that do not fit one lane.  Same tiles and return convention.
+#ifdef DETO_TILED_ONLY_64_32
+#define DETO_PAIR_S_LIST(X)
+#else
+#define DETO_PAIR_S_LIST(X) X(192) X(256)
+#endif
+int64_t launch_compress_pair_192(const CompressLaunch& a);   // one translation unit each:
+int64_t launch_compress_pair_256(const CompressLaunch& a);   // the longest compiles
+inline int64_t launch_compress_pair(const CompressLaunch& a) {
+    const int64_t c = launch_compress_pair_192(a);
+    return c ? c : launch_compress_pair_256(a);
+}
+int64_t launch_decompress_pair(const DecompressLaunch& a);
 
 }  // namespace deto
