@@ -1,7 +1,8 @@
-"""GPU parity for the chunk sizes and k values that run on the matrix-core kernels (tiles of
-32 complete chunks; chunk size a multiple of 32 without a lane-per-chunk kernel), against the
-CPU oracle with the staged protocol of tests/parity.py.  Every shard here has full tiles,
-tail chunks that fall to the general kernels, and a ragged last chunk."""
+"""GPU parity for the chunk sizes and k values beyond the headline kernels: the matrix-core
+kernels (chunk size a multiple of 32 without a lane-per-chunk kernel), the two-lanes-per-chunk
+kernels (chunk 192 and 256) and the lane-per-chunk kernels of chunk 96 and 128, against the CPU
+oracle with the staged protocol of tests/parity.py.  Every shard here has full tiles, tail
+chunks that fall to the general kernels, and a ragged last chunk."""
 import numpy as np
 import pytest
 
@@ -76,8 +77,9 @@ def test_duplicate_unordered_and_out_of_range_indices(H):
 
 @pytest.mark.parametrize("val_dtype", [oracle.BF16, oracle.F16])
 @pytest.mark.parametrize("idx_u8", [True, False])
-def test_packed_payload_formats(H, val_dtype, idx_u8):
-    s, k, n = 128, 16, 128 * 200 + 9
+@pytest.mark.parametrize("s,k", [(128, 16), (256, 32), (192, 12)])
+def test_packed_payload_formats(H, val_dtype, idx_u8, s, k):
+    n = s * 200 + 9
     cfg = Config(chunk=s, topk=k, sign=True, decay=0.999, lr=1e-3)
     g, m, th = make_inputs(n, seed=8, grad_bf16=True, params_bf16=True, outliers=0.01)
     m_gpu, idx_gpu, vbits_gpu, coeff_gpu = H.gpu_compress_packed(cfg, g, m, val_dtype, idx_u8)
@@ -91,10 +93,11 @@ def test_packed_payload_formats(H, val_dtype, idx_u8):
 
 
 @pytest.mark.parametrize("amsgrad", [False, True])
-def test_decoupled_adamw(H, amsgrad):
+@pytest.mark.parametrize("s,k", [(128, 64), (256, 32), (192, 24), (160, 20)])
+def test_decoupled_adamw(H, amsgrad, s, k):
     import torch
     from paper_2502_06728_amd import binding
-    s, k, n, R = 128, 64, 128 * 150 + 5, 2
+    n, R = s * 150 + 5, 2
     cfg = Config(chunk=s, topk=k, sign=True, lr=1e-3, weight_decay=0.01)
     th = make_inputs(n, 5)[2]
     p = H.to_dev(th)
