@@ -742,3 +742,58 @@ def test_unordered_payloads_on_every_vector_scatter(H, s, k):
     th = make_inputs(n, 3)[2]
     th_gpu, y_gpu = H.gpu_decompress(cfg, idx, val, th)
     parity.check_decompress(cfg, idx, val, th, th_gpu, y_gpu)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("s,k,scheme", [(64, 32, SCHEME_TOPK), (128, 64, SCHEME_TOPK), (256, 32, SCHEME_TOPK),
+                                        (64, 16, SCHEME_RANDOM), (64, 64, SCHEME_STRIDE)])
+def test_buffers_aligned_to_their_element_size_only(H, bf16, s, k, scheme):
+    """The ABI asks for element-size alignment only: every buffer here starts one element past a
+    16-byte boundary (slices of larger tensors), which sends the calls to the general kernels."""
+    import torch
+    from paper_2502_06728_amd import binding
+    n, R = s * 300 + 11, 2
+    C = -(-n // s)
+    cfg = Config(chunk=s, topk=k, scheme=scheme, seed=3, step=1, sign=True, lr=1e-3)
+    g, m, th = make_inputs(n, seed=s + k, grad_bf16=bf16, params_bf16=bf16)
+    send_idx = scheme == SCHEME_TOPK
+
+    def off(a_np=None, size=None, dtype=None, fill=None):
+        """a device tensor whose data pointer is one element past a 16-byte boundary"""
+        if a_np is not None:
+            src = H.to_dev(a_np)
+            big = torch.empty(src.numel() + 1, dtype=src.dtype, device=H.DEV)
+            big[1:].copy_(src)
+            return big[1:]
+        big = torch.full((size + 1,), fill, dtype=dtype, device=H.DEV)
+        return big[1:]
+
+    gd, md = off(g), off(m)
+    idx = off(size=C * k, dtype=torch.int32, fill=-7) if send_idx else None
+    val = off(size=C * k, dtype=torch.float32, fill=float("nan"))
+    coeff = off(size=C * s, dtype=torch.float32, fill=float("nan"))
+    assert gd.data_ptr() % 16 != 0 and md.data_ptr() % 16 != 0 and val.data_ptr() % 16 != 0
+    binding.detonation_compress(H.bcfg(cfg), gd, md, idx, val, coeff)
+    torch.cuda.synchronize()
+    parity.check_compress(cfg, g, m, H.to_host(md), None if idx is None else H.to_host(idx),
+                          H.to_host(val), H.to_host(coeff))
+    pays = [oracle.compress(cfg, *make_inputs(n, seed=40 + r)[:2])[1:] for r in range(R)]
+    idx_np = np.stack([p[0] for p in pays]) if send_idx else None
+    val_np = np.stack([p[1] for p in pays])
+    stride = C * k + 3                                  # replica 1 is misaligned differently
+    vbuf = off(size=R * stride, dtype=torch.float32, fill=float("nan"))
+    ibuf = off(size=R * stride, dtype=torch.int32, fill=999) if send_idx else None
+    for r in range(R):
+        vbuf[r * stride:r * stride + C * k].copy_(H.to_dev(val_np[r]))
+        if send_idx:
+            ibuf[r * stride:r * stride + C * k].copy_(H.to_dev(idx_np[r]))
+    pd, yd = off(th), off(size=n, dtype=torch.float32, fill=float("nan"))
+    binding.detonation_decompress_step(H.bcfg(cfg), R, ibuf, vbuf, pd, yd,
+                                       idx_replica_stride=stride, val_replica_stride=stride)
+    torch.cuda.synchronize()
+    parity.check_decompress(cfg, idx_np, val_np, th, H.to_host(pd), H.to_host(yd))
+    # accumulate on misaligned buffers
+    m2 = off(m)
+    binding.detonation_accumulate(H.bcfg(cfg), gd, m2)
+    torch.cuda.synchronize()
+    assert np.array_equal(H.to_host(m2), oracle.fold(cfg, g, m))
