@@ -306,7 +306,8 @@ int decompress_impl(const deto_config* cfg, const deto_adamw* opt, int64_t n, in
                                  deto::launch_decompress_idx_s128_k64(a) ||
                                  deto::launch_decompress_idx_packed(a) ||
                                  deto::launch_decompress_idx_ternary(a))
-                              : (deto::launch_decompress_scheme(a) ||
+                              : (deto::launch_decompress_scheme_adamw(a) ||
+                                 deto::launch_decompress_scheme(a) ||
                                  deto::launch_decompress_scheme_small(a));
         if (done) {
             rc = launched();

@@ -1008,10 +1008,10 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_
 // replica kept the same positions, so the R value arrays are summed entry by entry while
 // they stream in, and each chunk's lane spreads the k sums over the positions of its bit
 // pattern.
-template <int S, int K, bool PARAM_BF16>
+template <int S, int K, bool PARAM_BF16, bool ADAM = false>
 __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_tiled_scheme(
     KParams p, MaskWords stride_mask, int64_t n_tiles, TailRange tail,
-    const float* __restrict__ val, int64_t val_stride, void* __restrict__ params,
+    const float* __restrict__ val, int64_t val_stride, void* __restrict__ params, AdamPtrs ad,
     float* __restrict__ presign_dbg) {
     using G = TileGeom<S>;
     __shared__ __attribute__((aligned(16))) char smem[G::kDecompressBytes];
@@ -1022,8 +1022,8 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_
         decompress_generic_chunks<PARAM_BF16>(p, tail.n, n_tiles * kWave + (t - n_tiles),
                                               tail.n_chunks, gridDim.x - n_tiles,
                                               *reinterpret_cast<GenericDecompressSmem*>(smem),
-                                              nullptr, 0, val, val_stride, params,
-                                              AdamPtrs{nullptr, nullptr, nullptr}, presign_dbg);
+                                              nullptr, 0, val, val_stride, params, ad,
+                                              presign_dbg);
         return;
     }
     const int64_t ebase = t * G::kElems;
@@ -1088,7 +1088,8 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_
     float* row = tile + lane * G::kRow;
     finish_chunk<S>(p, y, row, presign_dbg, ebase, lane);
     wave_lds_sync();
-    update_params_from_tile<S, PARAM_BF16>(p, tile, th, params, ebase, lane);
+    if constexpr (ADAM) update_params_adamw_from_tile<S, PARAM_BF16>(p, tile, th, params, ad, ebase, lane);
+    else update_params_from_tile<S, PARAM_BF16>(p, tile, th, params, ebase, lane);
 }
 
 }  // namespace deto

@@ -40,11 +40,11 @@ bool DETO_DECOMPRESS_SCHEME_FN(const DecompressLaunch& a) {
         if (a.param_bf16)                                                                       \
             decompress_tiled_scheme<S, K, true><<<grid, kWave, 0, a.stream>>>(                  \
                 a.p, words(a.stride_mask), a.tiles, tail, static_cast<const float*>(a.val), a.val_stride,     \
-                a.params, a.presign_dbg);     \
+                a.params, AdamPtrs{nullptr, nullptr, nullptr}, a.presign_dbg);     \
         else                                                                                    \
             decompress_tiled_scheme<S, K, false><<<grid, kWave, 0, a.stream>>>(                 \
                 a.p, words(a.stride_mask), a.tiles, tail, static_cast<const float*>(a.val), a.val_stride,     \
-                a.params, a.presign_dbg);     \
+                a.params, AdamPtrs{nullptr, nullptr, nullptr}, a.presign_dbg);     \
         return true;                                                                            \
     }
     DETO_SCHEME_LIST(X)

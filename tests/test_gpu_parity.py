@@ -474,7 +474,8 @@ def test_packed_striding_random_values_only(H):
 
 @pytest.mark.parametrize("amsgrad", [False, True])
 @pytest.mark.parametrize("s,k,n,params_bf16", [(64, 32, 64 * 2500 + 7, True), (64, 16, 64 * 1000, False),
-                                               (32, 8, 32 * 900 + 3, False)])
+                                               (32, 8, 32 * 900 + 3, False), (32, 16, 32 * 4000 + 9, True),
+                                               (32, 2, 32 * 3000, False), (32, 1, 32 * 3000 + 1, True)])
 def test_decoupled_adamw_steps(H, amsgrad, s, k, n, params_bf16):
     """Decoupled AdamW as the underlying optimizer (section "Decoupled AdamW"): T steps with
     local moments; every step is judged from the GPU's own state, sign decided on the GPU's
@@ -797,3 +798,43 @@ def test_buffers_aligned_to_their_element_size_only(H, bf16, s, k, scheme):
     binding.detonation_accumulate(H.bcfg(cfg), gd, m2)
     torch.cuda.synchronize()
     assert np.array_equal(H.to_host(m2), oracle.fold(cfg, g, m))
+
+
+@pytest.mark.parametrize("scheme", [SCHEME_STRIDE, SCHEME_RANDOM])
+@pytest.mark.parametrize("s,k,params_bf16", [(32, 8, False), (64, 32, True), (32, 2, False), (96, 12, False)])
+def test_decoupled_adamw_without_transmitted_indices(H, scheme, s, k, params_bf16):
+    """Decoupled AdamW under the Striding / Random replicators (values only; the indices are
+    regenerated): three steps, the moments local to the rank."""
+    import torch
+    from paper_2502_06728_amd import binding
+    n, R, amsgrad = s * (64 * 12 + 5) + 3, 3, True
+    th = make_inputs(n, 5, params_bf16=params_bf16)[2]
+    p = H.to_dev(th)
+    m = torch.zeros(n, device=H.DEV)
+    v = torch.zeros(n, device=H.DEV)
+    vm = torch.zeros(n, device=H.DEV)
+    for t in (1, 2, 3):
+        cfg = Config(chunk=s, topk=k, scheme=scheme, seed=8, step=t, sign=True, lr=1e-3,
+                     weight_decay=0.01)
+        val = np.stack([oracle.compress(cfg, *make_inputs(n, 100 * t + r)[:2])[2] for r in range(R)])
+        th_in, m_in, v_in, vm_in = H.to_host(p), m.cpu().numpy(), v.cpu().numpy(), vm.cpu().numpy()
+        y = torch.empty(n, dtype=torch.float32, device=H.DEV)
+        binding.detonation_decompress_adamw_step(
+            H.bcfg(cfg), binding.AdamW(0.9, 0.95, 1e-8, amsgrad, t), R, None, H.to_dev(val),
+            p, m, v, vm, y)
+        torch.cuda.synchronize()
+        y_gpu = H.to_host(y)
+        assert parity.rel_chunk_err(y_gpu, oracle.presign(cfg, n, None, val), s) <= parity.TOL_F32
+        th_o, m_o, v_o, vm_o = oracle.adamw_update(cfg, oracle.AdamW(0.9, 0.95, 1e-8, amsgrad, t),
+                                                   y_gpu, th_in, m_in, v_in, vm_in)
+        assert np.abs(m.cpu().numpy() - m_o).max() <= 1e-5 * np.abs(m_o).max()
+        assert np.abs(v.cpu().numpy() - v_o).max() <= 1e-5 * np.abs(v_o).max()
+        assert np.abs(vm.cpu().numpy() - vm_o).max() <= 1e-5 * np.abs(vm_o).max()
+        got = H.to_host(p)
+        if params_bf16:
+            got = synth.from_bf16_bits(got).astype(np.float64)
+            want = synth.from_bf16_bits(th_o).astype(np.float64)
+            tol = parity.TOL_BF16
+        else:
+            got, want, tol = got.astype(np.float64), th_o.astype(np.float64), parity.TOL_F32
+        assert (np.abs(got - want) <= tol * np.abs(want) + tol * cfg.lr).all()
