@@ -210,7 +210,7 @@ def run(args) -> dict:
     t_a = sum(e[0].elapsed_time(e[1]) for e in acc) / len(acc) if acc else None
     ms_per_step = wall * 1e3 / args.steps
     ab = algorithmic_bytes(n, s, k, R, grad.element_size(), params.element_size(), with_idx,
-                           0.25 if ternary else val.element_size(),
+                           4.0 * -(-k // 16) / k if ternary else val.element_size(),   # whole words per chunk
                            idx.element_size() if with_idx else 0)
     if adamw:
         ab["decompress"] += 16 * n          # exp_avg and exp_avg_sq, fp32, read and written

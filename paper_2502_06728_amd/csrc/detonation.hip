@@ -167,6 +167,7 @@ int detonation_compress_packed(const deto_config* cfg, int64_t n, const void* gr
                                  deto::launch_compress_topk_s128_k32(a) ||
                                  deto::launch_compress_topk_s128_k64(a) ||
                                  deto::launch_compress_topk_packed(a) ||
+                                 deto::launch_compress_topk_packed_s32(a) ||
                                  deto::launch_compress_topk_ternary(a))
                               : (deto::launch_compress_scheme(a) ||
                                  deto::launch_compress_scheme_small(a));
@@ -305,6 +306,7 @@ int decompress_impl(const deto_config* cfg, const deto_adamw* opt, int64_t n, in
                                  deto::launch_decompress_idx_s128_k32(a) ||
                                  deto::launch_decompress_idx_s128_k64(a) ||
                                  deto::launch_decompress_idx_packed(a) ||
+                                 deto::launch_decompress_idx_packed_s32(a) ||
                                  deto::launch_decompress_idx_ternary(a))
                               : (deto::launch_decompress_scheme_adamw(a) ||
                                  deto::launch_decompress_scheme(a) ||

@@ -248,68 +248,77 @@ __device__ __forceinline__ void compact_and_store_payload(const float (&c)[S],
         });
     }
     wave_lds_sync();
-    if constexpr (VAL == 3) {
-        // ternary: the lane packs the signs of its chunk's K staged values, two bits each
-        // (0 = zero, 1 = +1, 3 = -1), into K/16 words; byte indices leave as in the 16-bit case
-        static_assert(K % 16 == 0, "whole words per chunk");
-        constexpr int W = K / 16;
-        uint32_t* words = static_cast<uint32_t*>(val_out_v) + (pbase / K) * W + lane * W;
-        uint32_t wv[W];
-#pragma unroll
-        for (int w = 0; w < W; ++w) {
-            wv[w] = 0u;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float4 v = *reinterpret_cast<const float4*>(vrow + 16 * w + 4 * q);
-                const int b[4] = {__float_as_int(v.x), __float_as_int(v.y), __float_as_int(v.z),
-                                  __float_as_int(v.w)};
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const uint32_t code =
-                        b[e] > 0 ? 1u : (static_cast<uint32_t>(b[e]) > 0x80000000u ? 3u : 0u);
-                    wv[w] |= code << (2 * (4 * q + e));
-                }
-            }
-        }
-        if constexpr (W == 1) words[0] = wv[0];
-        else if constexpr (W == 2) *reinterpret_cast<uint2*>(words) = make_uint2(wv[0], wv[1]);
-        else {
-#pragma unroll
-            for (int w = 0; w < W; ++w) words[w] = wv[w];
-        }
+    if constexpr (VAL != 0) {
         uint8_t* idx8 = static_cast<uint8_t*>(idx_out_v);
-        if (idx8) {
+        if constexpr (VAL == 3) {
+            // ternary: the lane packs the signs of its chunk's K staged values, two bits each
+            // (0 = zero, 1 = +1, 3 = -1), into ceil(K/16) words
+            constexpr int W = (K + 15) / 16;
+            uint32_t* words = static_cast<uint32_t*>(val_out_v) + (pbase / K) * W + lane * W;
+            uint32_t wv[W];
+#pragma unroll
+            for (int w = 0; w < W; ++w) wv[w] = 0u;
+            auto put = [&](int j, float v) {
+                const int b = __float_as_int(v);
+                const uint32_t code =
+                    b > 0 ? 1u : (static_cast<uint32_t>(b) > 0x80000000u ? 3u : 0u);
+                wv[j / 16] |= code << (2 * (j % 16));
+            };
+            if constexpr (K % 4 == 0) {
+#pragma unroll
+                for (int q = 0; q < K / 4; ++q) {
+                    const float4 v = *reinterpret_cast<const float4*>(vrow + 4 * q);
+                    put(4 * q, v.x); put(4 * q + 1, v.y); put(4 * q + 2, v.z); put(4 * q + 3, v.w);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < K; ++j) put(j, vrow[j]);
+            }
+            if constexpr (W == 2) *reinterpret_cast<uint2*>(words) = make_uint2(wv[0], wv[1]);
+            else {
+#pragma unroll
+                for (int w = 0; w < W; ++w) words[w] = wv[w];
+            }
+        } else if constexpr (K % 4 == 0) {
+            // 16-bit values, four entries per lane and store
+            uint16_t* val16 = static_cast<uint16_t*>(val_out_v);
 #pragma unroll
             for (int it = 0; it < K / 4; ++it) {
                 const int e = it * 256 + lane * 4;
                 const int r = e / K, col = e % K;
-                *reinterpret_cast<uint32_t*>(idx8 + pbase + e) =
-                    *reinterpret_cast<const uint32_t*>(ibytes + r * PR + col);
+                const float4 v = *reinterpret_cast<const float4*>(tile + r * PR + col);
+                uint2 packed;
+                if constexpr (VAL == 1) {
+                    packed.x = pack_bf16x2(v.x, v.y);
+                    packed.y = pack_bf16x2(v.z, v.w);
+                } else {
+                    packed.x =
+                        encode16<VAL>(v.x) | (static_cast<uint32_t>(encode16<VAL>(v.y)) << 16);
+                    packed.y =
+                        encode16<VAL>(v.z) | (static_cast<uint32_t>(encode16<VAL>(v.w)) << 16);
+                }
+                *reinterpret_cast<uint2*>(val16 + pbase + e) = packed;
             }
-        }
-        wave_lds_sync();
-        return;
-    } else if constexpr (VAL != 0) {
-        static_assert(K % 4 == 0, "16-bit payloads are stored four entries at a time");
-        uint16_t* val16 = static_cast<uint16_t*>(val_out_v);
-        uint8_t* idx8 = static_cast<uint8_t*>(idx_out_v);
+        } else {
+            // k = 1, 2: the lane stores its own chunk's entries
+            uint16_t* val16 = static_cast<uint16_t*>(val_out_v) + pbase + lane * K;
 #pragma unroll
-        for (int it = 0; it < K / 4; ++it) {
-            const int e = it * 256 + lane * 4;
-            const int r = e / K, col = e % K;
-            const float4 v = *reinterpret_cast<const float4*>(tile + r * PR + col);
-            uint2 packed;
-            if constexpr (VAL == 1) {
-                packed.x = pack_bf16x2(v.x, v.y);
-                packed.y = pack_bf16x2(v.z, v.w);
+            for (int j = 0; j < K; ++j) val16[j] = encode16<VAL>(vrow[j]);
+        }
+        // byte indices
+        if (idx8) {
+            if constexpr (K % 4 == 0) {
+#pragma unroll
+                for (int it = 0; it < K / 4; ++it) {
+                    const int e = it * 256 + lane * 4;
+                    const int r = e / K, col = e % K;
+                    *reinterpret_cast<uint32_t*>(idx8 + pbase + e) =
+                        *reinterpret_cast<const uint32_t*>(ibytes + r * PR + col);
+                }
             } else {
-                packed.x = encode16<VAL>(v.x) | (static_cast<uint32_t>(encode16<VAL>(v.y)) << 16);
-                packed.y = encode16<VAL>(v.z) | (static_cast<uint32_t>(encode16<VAL>(v.w)) << 16);
+#pragma unroll
+                for (int j = 0; j < K; ++j) idx8[pbase + lane * K + j] = irow[j];
             }
-            *reinterpret_cast<uint2*>(val16 + pbase + e) = packed;
-            if (idx8)
-                *reinterpret_cast<uint32_t*>(idx8 + pbase + e) =
-                    *reinterpret_cast<const uint32_t*>(ibytes + r * PR + col);
         }
         wave_lds_sync();
         return;
@@ -642,17 +651,18 @@ struct PayloadRegs {
     }
 };
 
-// Ternary values + byte indices, K a multiple of 16: the words of a replica are then a dense
-// array of two-bit codes indexed by entry, and the four entries of a lane's vector are one byte.
+// Ternary values + byte indices, K a multiple of 4: a chunk's two-bit codes start on a word
+// boundary (ceil(K/16) words per chunk), and the four entries of a lane's vector are one byte.
 template <int K>
 struct PayloadRegs<K, 3> {
-    static_assert(K % 16 == 0, "whole words per chunk");
+    static_assert(K % 4 == 0, "vector path");
     static constexpr int kVec = K / 4;
+    static constexpr int kChunkBytes = 4 * ((K + 15) / 16);
     uint32_t i[kVec];
     uint32_t v[kVec];
     __device__ __forceinline__ void load(int it, const void* ir, const void* vr, int e) {
         i[it] = ld_u1<DETO_NT_DECOMPRESS_LD>(static_cast<const uint8_t*>(ir) + e);
-        v[it] = static_cast<const uint8_t*>(vr)[e >> 2];
+        v[it] = static_cast<const uint8_t*>(vr)[(e / K) * kChunkBytes + (e % K) / 4];
     }
     template <int C>
     __device__ __forceinline__ uint32_t idx(int it) const {
@@ -927,11 +937,12 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_
     const int64_t ebase = t * G::kElems;
     const int64_t pbase = t * (kWave * K);
     // replica r's entries of this tile, in bytes from the array bases
-    // (ternary: four entries per byte, replica stride in 32-bit words)
+    // (ternary: ceil(K/16) words per chunk, replica stride in 32-bit words)
     constexpr int kIdxBytes = VAL ? 1 : 4, kValBytes = VAL ? 2 : 4;
+    constexpr int kTernaryWords = (K + 15) / 16;
     const char* idx = static_cast<const char*>(idx_v) + pbase * kIdxBytes;
-    const char* val =
-        static_cast<const char*>(val_v) + (VAL == 3 ? pbase / 4 : pbase * kValBytes);
+    const char* val = static_cast<const char*>(val_v) +
+                      (VAL == 3 ? t * (kWave * kTernaryWords * 4) : pbase * kValBytes);
     const int64_t idx_step = idx_stride * kIdxBytes;
     const int64_t val_step = val_stride * (VAL == 3 ? 4 : kValBytes);
 
@@ -979,15 +990,32 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_
         }
     } else {
         // K entries per chunk, lane = chunk: the lane owns its row, plain sequential adds
-        static_assert(VAL == 0 || K % 4 == 0, "16-bit payloads use the vector path");
         for (int r = 0; r < p.R; ++r) {
-            const int32_t* ir = reinterpret_cast<const int32_t*>(idx + r * idx_step) + lane * K;
-            const float* vr = reinterpret_cast<const float*>(val + r * val_step) + lane * K;
+            const char* ir = idx + r * idx_step + lane * K * kIdxBytes;
+            const char* vr = val + r * val_step;
             float* arow = tile + lane * G::kRow;
+            [[maybe_unused]] uint32_t word = 0u;
+            if constexpr (VAL == 3) {
+                static_assert(K < 16, "one word per chunk");
+                word = reinterpret_cast<const uint32_t*>(vr)[lane];
+            }
 #pragma unroll
             for (int j = 0; j < K; ++j) {
-                const uint32_t at = min(static_cast<uint32_t>(ir[j]), static_cast<uint32_t>(S));
-                arow[at] += vr[j];
+                uint32_t at;
+                float v;
+                if constexpr (VAL == 0) {
+                    at = static_cast<uint32_t>(reinterpret_cast<const int32_t*>(ir)[j]);
+                    v = reinterpret_cast<const float*>(vr)[lane * K + j];
+                } else {
+                    at = reinterpret_cast<const uint8_t*>(ir)[j];
+                    if constexpr (VAL == 3) {
+                        const uint32_t code = (word >> (2 * j)) & 3u;
+                        v = (code & 1u) ? ((code & 2u) ? -1.0f : 1.0f) : 0.0f;
+                    } else {
+                        v = decode16<VAL>(reinterpret_cast<const uint16_t*>(vr)[lane * K + j]);
+                    }
+                }
+                arow[min(at, static_cast<uint32_t>(S))] += v;
             }
         }
     }

@@ -69,6 +69,8 @@ bool launch_decompress_idx_s128_k32(const DecompressLaunch& a);
 bool launch_decompress_idx_s128_k64(const DecompressLaunch& a);
 bool launch_compress_topk_packed(const CompressLaunch& a);     // byte indices + 16-bit values
 bool launch_decompress_idx_packed(const DecompressLaunch& a);
+bool launch_compress_topk_packed_s32(const CompressLaunch& a);
+bool launch_decompress_idx_packed_s32(const DecompressLaunch& a);
 bool launch_compress_topk_ternary(const CompressLaunch& a);    // byte indices + two-bit signs
 bool launch_decompress_idx_ternary(const DecompressLaunch& a);
 bool launch_decompress_adamw(const DecompressLaunch& a);       // Decoupled AdamW update

@@ -1,54 +1,13 @@
 // Tiled top-k compress and indexed decompress with the ternary payload: byte indices and the
-// signs of the kept coefficients, two bits per entry (chunk size 64, k a multiple of 16).
-#include "tiled_kernels.hip.h"
-#include "tiled_launch.h"
-
+// signs of the kept coefficients, two bits per entry.  Chunk size 64 at rates 1/2 and 1/4, and
+// chunk size 32 at rates 1/2 ... 1/32: sign-only synchronisation at chunk size 32 is the
+// configuration of the paper's experiments ("Overall Setup").
+#define DETO_NARROW_TERNARY
 #ifdef DETO_TILED_ONLY_64_32
-#define DETO_TERNARY_LIST(X) X(64, 32)
+#define DETO_NARROW_LIST(X) X(64, 32)
 #else
-#define DETO_TERNARY_LIST(X) X(64, 32) X(64, 16)
+#define DETO_NARROW_LIST(X) X(64, 32) X(64, 16) X(32, 16) X(32, 8) X(32, 4) X(32, 2) X(32, 1)
 #endif
-
-namespace deto {
-
-bool launch_compress_topk_ternary(const CompressLaunch& a) {
-    if (a.p.val_dtype != 3 || !a.p.idx_u8 || a.p.scheme != 0) return false;
-    const unsigned grid = tiled_grid(a.tiles, a.n_chunks);
-    const TailRange tail{a.n, a.n_chunks};
-#define X(S, K)                                                                                 \
-    if (a.p.s == S && a.p.k == K) {                                                             \
-        if (a.grad_bf16)                                                                        \
-            compress_tiled_topk<S, K, true, 3><<<grid, kWave, 0, a.stream>>>(                   \
-                a.p, a.tiles, tail, a.grad, a.mom, a.idx, a.val, a.coeff_dbg);                  \
-        else                                                                                    \
-            compress_tiled_topk<S, K, false, 3><<<grid, kWave, 0, a.stream>>>(                  \
-                a.p, a.tiles, tail, a.grad, a.mom, a.idx, a.val, a.coeff_dbg);                  \
-        return true;                                                                            \
-    }
-    DETO_TERNARY_LIST(X)
-#undef X
-    return false;
-}
-
-bool launch_decompress_idx_ternary(const DecompressLaunch& a) {
-    if (a.p.val_dtype != 3 || !a.p.idx_u8 || !a.idx || a.p.adam) return false;
-    const unsigned grid = tiled_grid(a.tiles, a.n_chunks);
-    const TailRange tail{a.n, a.n_chunks};
-#define X(S, K)                                                                                 \
-    if (a.p.s == S && a.p.k == K) {                                                             \
-        if (a.param_bf16)                                                                       \
-            decompress_tiled<S, K, true, 3><<<grid, kWave, 0, a.stream>>>(                      \
-                a.p, a.tiles, tail, a.idx, a.idx_stride, a.val, a.val_stride, a.params,         \
-                AdamPtrs{nullptr, nullptr, nullptr}, a.presign_dbg);                            \
-        else                                                                                    \
-            decompress_tiled<S, K, false, 3><<<grid, kWave, 0, a.stream>>>(                     \
-                a.p, a.tiles, tail, a.idx, a.idx_stride, a.val, a.val_stride, a.params,         \
-                AdamPtrs{nullptr, nullptr, nullptr}, a.presign_dbg);                            \
-        return true;                                                                            \
-    }
-    DETO_TERNARY_LIST(X)
-#undef X
-    return false;
-}
-
-}  // namespace deto
+#define DETO_COMPRESS_NARROW_FN launch_compress_topk_ternary
+#define DETO_DECOMPRESS_NARROW_FN launch_decompress_idx_ternary
+#include "tiled_narrow_impl.hip.h"

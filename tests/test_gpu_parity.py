@@ -429,7 +429,11 @@ def test_multi_step_trajectory(H, scheme):
 @pytest.mark.parametrize("val_dtype", [oracle.BF16, oracle.F16])
 @pytest.mark.parametrize("idx_u8", [True, False])
 @pytest.mark.parametrize("s,k,n", [(64, 32, 64 * 3000 + 13), (64, 8, 64 * 2000), (32, 4, 32 * 777 + 5),
-                                   (96, 12, 96 * 300 + 1)])
+                                   (96, 12, 96 * 300 + 1),
+                                   # chunk 32 at the rates 1/2 ... 1/32; 336 chunks, so every
+                                   # replica's arrays start 16-byte aligned (lane-per-chunk kernels)
+                                   (32, 16, 32 * 335 + 5), (32, 8, 32 * 335 + 5), (32, 4, 32 * 335 + 5),
+                                   (32, 2, 32 * 335 + 5), (32, 1, 32 * 335 + 5)])
 def test_packed_payload_formats(H, val_dtype, idx_u8, s, k, n):
     """16-bit transfer values (Appendix B, communication dtype) and byte indices: the payload is
     the fp32 payload rounded to the transfer dtype, and the momentum keeps the rounding error."""
@@ -630,7 +634,10 @@ def test_byte_indices_with_fp32_values(H):
 
 @pytest.mark.parametrize("idx_u8", [False, True])
 @pytest.mark.parametrize("s,k,n", [(64, 32, 64 * 3000 + 13), (64, 16, 64 * 1000), (32, 4, 32 * 777 + 5),
-                                   (96, 20, 96 * 300 + 1), (128, 48, 128 * 100), (16, 2, 16 * 500 + 3)])
+                                   (96, 20, 96 * 300 + 1), (128, 48, 128 * 100), (16, 2, 16 * 500 + 3),
+                                   # the paper's own setting: chunk 32, signs only, rates 1/2 ... 1/32
+                                   (32, 16, 32 * 335 + 5), (32, 8, 32 * 335 + 5), (32, 4, 32 * 335 + 5),
+                                   (32, 2, 32 * 335 + 5), (32, 1, 32 * 335 + 5)])
 def test_ternary_payload(H, idx_u8, s, k, n):
     """The paper's "sign before synchronization": only sign(c) of the kept coefficients travels,
     two bits per entry; the momentum loses the extracted components themselves."""
