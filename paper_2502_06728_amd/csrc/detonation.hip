@@ -170,7 +170,9 @@ int detonation_compress_packed(const deto_config* cfg, int64_t n, const void* gr
                                  deto::launch_compress_topk_packed_s32(a) ||
                                  deto::launch_compress_topk_ternary(a))
                               : (deto::launch_compress_scheme(a) ||
-                                 deto::launch_compress_scheme_small(a));
+                                 deto::launch_compress_scheme_small(a) ||
+                                 deto::launch_compress_scheme_narrow_s32(a) ||
+                                 deto::launch_compress_scheme_narrow_s64(a));
         if (done) {
             rc = launched();
             if (rc) return rc;
@@ -310,7 +312,9 @@ int decompress_impl(const deto_config* cfg, const deto_adamw* opt, int64_t n, in
                                  deto::launch_decompress_idx_ternary(a))
                               : (deto::launch_decompress_scheme_adamw(a) ||
                                  deto::launch_decompress_scheme(a) ||
-                                 deto::launch_decompress_scheme_small(a));
+                                 deto::launch_decompress_scheme_small(a) ||
+                                 deto::launch_decompress_scheme_narrow_s32(a) ||
+                                 deto::launch_decompress_scheme_narrow_s64(a));
         if (done) {
             rc = launched();
             if (rc) return rc;

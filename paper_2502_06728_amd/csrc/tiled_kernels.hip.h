@@ -552,11 +552,12 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void compress_ti
 // Compress half for Striding and Random on full tiles, in the raw-momentum domain or (with
 // p.use_dct) on DCT coefficients.  Same three phases; the kept set is a bit pattern that does
 // not depend on the data: `stride_mask` for Striding, a per-chunk shuffle for Random.
-template <int S, int K, bool GRAD_BF16>
+// VAL as in compact_and_store_payload (narrow formats: byte indices, if any are asked for).
+template <int S, int K, bool GRAD_BF16, int VAL = 0>
 __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void compress_tiled_scheme(
     KParams p, MaskWords stride_mask, int64_t n_tiles, TailRange tail,
-    const void* __restrict__ grad, float* __restrict__ mom, int32_t* __restrict__ idx_out,
-    float* __restrict__ val_out, float* __restrict__ coeff_dbg) {
+    const void* __restrict__ grad, float* __restrict__ mom, void* __restrict__ idx_out,
+    void* __restrict__ val_out, float* __restrict__ coeff_dbg) {
     using G = TileGeom<S>;
     __shared__ __attribute__((aligned(16))) char smem[G::kCompressBytes];
     float* tile = reinterpret_cast<float*>(smem);
@@ -592,9 +593,23 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void compress_ti
         wave_lds_sync();
     }
 
-    compact_and_store_payload<S, K>(c, mk, tile, lane, idx_out, val_out, t * (kWave * K));
-
-    static_for<0, S>([&](auto i) { c[i] = mk.bit(i) ? 0.0f : c[i]; });
+    if constexpr (VAL == 1 || VAL == 2) {
+        // 16-bit transfer: the payload carries the rounded value; the rounding error of a
+        // kept value stays behind in the momentum
+        float u[S];
+        static_for<0, S>([&](auto i) {
+            const float r = decode16<VAL>(encode16<VAL>(c[i]));
+            u[i] = mk.bit(i) ? (c[i] - r) : c[i];
+            c[i] = r;
+        });
+        compact_and_store_payload<S, K, VAL>(c, mk, tile, lane, idx_out, val_out,
+                                             t * (kWave * K));
+        static_for<0, S>([&](auto i) { c[i] = u[i]; });
+    } else {
+        compact_and_store_payload<S, K, VAL>(c, mk, tile, lane, idx_out, val_out,
+                                             t * (kWave * K));
+        static_for<0, S>([&](auto i) { c[i] = mk.bit(i) ? 0.0f : c[i]; });
+    }
     if (p.use_dct) {
         c[0] *= p.alpha0;
         static_for<1, S>([&](auto i) { c[i] *= p.alpha; });
@@ -1036,10 +1051,10 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_
 // replica kept the same positions, so the R value arrays are summed entry by entry while
 // they stream in, and each chunk's lane spreads the k sums over the positions of its bit
 // pattern.
-template <int S, int K, bool PARAM_BF16, bool ADAM = false>
+template <int S, int K, bool PARAM_BF16, bool ADAM = false, int VAL = 0>
 __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_tiled_scheme(
     KParams p, MaskWords stride_mask, int64_t n_tiles, TailRange tail,
-    const float* __restrict__ val, int64_t val_stride, void* __restrict__ params, AdamPtrs ad,
+    const void* __restrict__ val_v, int64_t val_stride, void* __restrict__ params, AdamPtrs ad,
     float* __restrict__ presign_dbg) {
     using G = TileGeom<S>;
     __shared__ __attribute__((aligned(16))) char smem[G::kDecompressBytes];
@@ -1050,7 +1065,7 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_
         decompress_generic_chunks<PARAM_BF16>(p, tail.n, n_tiles * kWave + (t - n_tiles),
                                               tail.n_chunks, gridDim.x - n_tiles,
                                               *reinterpret_cast<GenericDecompressSmem*>(smem),
-                                              nullptr, 0, val, val_stride, params, ad,
+                                              nullptr, 0, val_v, val_stride, params, ad,
                                               presign_dbg);
         return;
     }
@@ -1062,18 +1077,41 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_
     ParamRegs<S, PARAM_BF16> th;
     load_params<S, PARAM_BF16>(th, params, ebase, lane);
 
-    // sum over replicas, coalesced; staged as [chunk][k]
+    // sum over replicas, coalesced; staged as [chunk][k].  One replica's four consecutive
+    // entries it*256 + 4*lane ... of this tile, decoded (k a multiple of 4):
+    [[maybe_unused]] auto load4 = [&](int r, int it) -> float4 {
+        const int e = it * 256 + lane * 4;
+        if constexpr (VAL == 0) {
+            return ld_f4<DETO_NT_DECOMPRESS_LD>(static_cast<const float*>(val_v) + r * val_stride +
+                                                pbase + e);
+        } else if constexpr (VAL == 3) {
+            // two-bit signs: ceil(K/16) words per chunk, replica stride in words
+            constexpr int kChunkBytes = 4 * ((K + 15) / 16);
+            const uint8_t* bytes = static_cast<const uint8_t*>(val_v) + r * val_stride * 4 +
+                                   t * (kWave * kChunkBytes);
+            const uint32_t b = bytes[(e / K) * kChunkBytes + (e % K) / 4];
+            auto dec = [](uint32_t code) {
+                return (code & 1u) ? ((code & 2u) ? -1.0f : 1.0f) : 0.0f;
+            };
+            return make_float4(dec(b & 3u), dec((b >> 2) & 3u), dec((b >> 4) & 3u),
+                               dec((b >> 6) & 3u));
+        } else {
+            const uint2 w = ld_u2<DETO_NT_DECOMPRESS_LD>(static_cast<const uint16_t*>(val_v) +
+                                                         r * val_stride + pbase + e);
+            return make_float4(decode16<VAL>(static_cast<uint16_t>(w.x & 0xFFFFu)),
+                               decode16<VAL>(static_cast<uint16_t>(w.x >> 16)),
+                               decode16<VAL>(static_cast<uint16_t>(w.y & 0xFFFFu)),
+                               decode16<VAL>(static_cast<uint16_t>(w.y >> 16)));
+        }
+    };
     if constexpr (K % 4 == 0) {
         float4 acc[K / 4];
 #pragma unroll
-        for (int it = 0; it < K / 4; ++it)
-            acc[it] = ld_f4<DETO_NT_DECOMPRESS_LD>(val + pbase + it * 256 + lane * 4);
+        for (int it = 0; it < K / 4; ++it) acc[it] = load4(0, it);
         for (int r = 1; r < p.R; ++r) {
             float4 nxt[K / 4];
 #pragma unroll
-            for (int it = 0; it < K / 4; ++it)
-                nxt[it] = ld_f4<DETO_NT_DECOMPRESS_LD>(val + r * val_stride + pbase + it * 256 +
-                                                       lane * 4);
+            for (int it = 0; it < K / 4; ++it) nxt[it] = load4(r, it);
 #pragma unroll
             for (int it = 0; it < K / 4; ++it) {
                 acc[it].x += nxt[it].x; acc[it].y += nxt[it].y;
@@ -1086,12 +1124,33 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_
             *reinterpret_cast<float4*>(tile + (e / K) * PR + (e % K)) = acc[it];
         }
     } else {
+        // k = 1, 2 (3): the lane sums its own chunk's entries
+        float a[K];
 #pragma unroll
-        for (int j = 0; j < K; ++j) {
-            float a = 0.0f;
-            for (int r = 0; r < p.R; ++r) a += val[r * val_stride + pbase + lane * K + j];
-            tile[lane * PR + j] = a;
+        for (int j = 0; j < K; ++j) a[j] = 0.0f;
+        for (int r = 0; r < p.R; ++r) {
+            if constexpr (VAL == 3) {
+                static_assert(K < 16, "one word per chunk");
+                const uint32_t word = static_cast<const uint32_t*>(val_v)[r * val_stride +
+                                                                          t * kWave + lane];
+#pragma unroll
+                for (int j = 0; j < K; ++j) {
+                    const uint32_t code = (word >> (2 * j)) & 3u;
+                    a[j] += (code & 1u) ? ((code & 2u) ? -1.0f : 1.0f) : 0.0f;
+                }
+            } else if constexpr (VAL == 0) {
+#pragma unroll
+                for (int j = 0; j < K; ++j)
+                    a[j] += static_cast<const float*>(val_v)[r * val_stride + pbase + lane * K + j];
+            } else {
+#pragma unroll
+                for (int j = 0; j < K; ++j)
+                    a[j] += decode16<VAL>(
+                        static_cast<const uint16_t*>(val_v)[r * val_stride + pbase + lane * K + j]);
+            }
         }
+#pragma unroll
+        for (int j = 0; j < K; ++j) tile[lane * PR + j] = a[j];
     }
     ChunkMask<S> mk = mask_from_words<S>(stride_mask);
     if (p.scheme == 2)

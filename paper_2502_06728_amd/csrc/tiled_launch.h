@@ -75,6 +75,10 @@ bool launch_compress_topk_ternary(const CompressLaunch& a);    // byte indices +
 bool launch_decompress_idx_ternary(const DecompressLaunch& a);
 bool launch_decompress_adamw(const DecompressLaunch& a);       // Decoupled AdamW update
 bool launch_decompress_scheme_adamw(const DecompressLaunch& a);   // ... without transmitted indices
+bool launch_compress_scheme_narrow_s32(const CompressLaunch& a);   // Striding / Random, narrow payload
+bool launch_decompress_scheme_narrow_s32(const DecompressLaunch& a);
+bool launch_compress_scheme_narrow_s64(const CompressLaunch& a);
+bool launch_decompress_scheme_narrow_s64(const DecompressLaunch& a);
 bool launch_compress_scheme(const CompressLaunch& a);
 bool launch_decompress_scheme(const DecompressLaunch& a);
 bool launch_compress_scheme_small(const CompressLaunch& a);    // low compression rates

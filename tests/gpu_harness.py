@@ -91,7 +91,8 @@ def gpu_decompress_packed(cfg: oracle.Config, idx: np.ndarray, val_bits: np.ndar
                           params: np.ndarray, val_dtype: int, idx_u8: bool):
     R = val_bits.shape[0]
     n = params.size
-    i = torch.from_numpy(np.ascontiguousarray(idx.astype(np.uint8 if idx_u8 else np.int32))).to(DEV)
+    i = (None if idx is None else
+         torch.from_numpy(np.ascontiguousarray(idx.astype(np.uint8 if idx_u8 else np.int32))).to(DEV))
     v = bits16_to_dev(np.ascontiguousarray(val_bits), val_dtype)
     p = to_dev(params)
     y = torch.full((n,), float("nan"), dtype=torch.float32, device=DEV)

@@ -659,6 +659,40 @@ def test_ternary_payload(H, idx_u8, s, k, n):
     parity.check_decompress(cfg, idx, signs, th, th_gpu, y_gpu)
 
 
+@pytest.mark.parametrize("dct", [False, True])
+@pytest.mark.parametrize("scheme", [SCHEME_STRIDE, SCHEME_RANDOM])
+@pytest.mark.parametrize("val_dtype", [oracle.BF16, oracle.F16, oracle.TERNARY])
+@pytest.mark.parametrize("s,k", [(32, 16), (32, 4), (32, 2), (32, 1), (64, 32), (64, 4)])
+def test_narrow_payload_striding_random(H, s, k, val_dtype, scheme, dct):
+    """Striding / Random with 16-bit values or signs only, no indices on the wire (the paper's
+    experiments synchronise only signs at chunk size 32): 336 chunks, so every replica's array
+    starts 16-byte aligned and the lane-per-chunk kernels take five tiles plus a ragged tail."""
+    n, R = s * 335 + 5, 3
+    C = -(-n // s)
+    cfg = Config(chunk=s, topk=k, scheme=scheme, dct=dct, seed=5, step=3, sign=True, decay=0.999, lr=1e-3)
+    g, m, th = make_inputs(n, seed=s + k, grad_bf16=True, params_bf16=True, outliers=0.01)
+    others = [make_inputs(n, seed=900 + r, grad_bf16=True, outliers=0.01)[:2] for r in range(R)]
+    if val_dtype == oracle.TERNARY:
+        m_gpu, idx_gpu, words_gpu, coeff_gpu = H.gpu_compress_ternary(cfg, g, m, True)
+        kept = coeff_gpu.reshape(C, s)[np.arange(C)[:, None], idx_gpu.reshape(C, k)].reshape(-1)
+        parity.check_compress(cfg, g, m, m_gpu, idx_gpu, kept, coeff_gpu)
+        assert np.array_equal(words_gpu, oracle.encode_ternary(cfg, n, kept))
+        pays = [oracle.compress_t(cfg, *o)[1:] for o in others]
+        idx = np.stack([p[0] for p in pays])
+        words = np.stack([p[1] for p in pays])
+        th_gpu, y_gpu = H.gpu_decompress_ternary(cfg, None, words, th, False)
+        signs = np.stack([oracle.decode_ternary(cfg, n, w) for w in words])
+        parity.check_decompress(cfg, idx, signs, th, th_gpu, y_gpu)
+    else:
+        m_gpu, idx_gpu, vbits_gpu, coeff_gpu = H.gpu_compress_packed(cfg, g, m, val_dtype, True)
+        parity.check_compress_packed(cfg, g, m, m_gpu, idx_gpu, vbits_gpu, coeff_gpu, val_dtype)
+        pays = [oracle.compress_q(cfg, *o, val_dtype)[1:] for o in others]
+        idx = np.stack([p[0] for p in pays])
+        vbits = np.stack([p[1] for p in pays])
+        th_gpu, y_gpu = H.gpu_decompress_packed(cfg, None, vbits, th, val_dtype, False)
+        parity.check_decompress_packed(cfg, idx, vbits, val_dtype, th, th_gpu, y_gpu)
+
+
 @pytest.mark.parametrize("scheme", [SCHEME_STRIDE, SCHEME_RANDOM])
 def test_ternary_payload_striding_random(H, scheme):
     # values only; identity domain: the pre-sign update is an exact average of signs
