@@ -163,7 +163,6 @@ def run(args) -> dict:
 
     adamw = args.optimizer == "adamw"
     if adamw:
-        assert not packed, "the AdamW update takes fp32 values and int32 indices"
         exp_avg = torch.zeros(n, dtype=torch.float32, device=dev)
         exp_avg_sq = torch.zeros(n, dtype=torch.float32, device=dev)
         opt = binding.AdamW(0.9, 0.95, 1e-8, False, 0)
@@ -183,8 +182,9 @@ def run(args) -> dict:
             ev[1].record()
         if adamw:
             opt.step += 1
-            binding.detonation_decompress_adamw_step(cfg, opt, R, idx, val, params, exp_avg,
-                                                     exp_avg_sq)
+            (binding.detonation_decompress_adamw_step_packed if packed
+             else binding.detonation_decompress_adamw_step)(cfg, opt, R, idx, val, params,
+                                                            exp_avg, exp_avg_sq)
         else:
             decompress(cfg, R, idx, val, params)
         if ev:

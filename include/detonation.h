@@ -207,6 +207,26 @@ int detonation_decompress_adamw_step(const deto_config* cfg, const deto_adamw* o
                                      void* stream);
 
 /*
+ * detonation_decompress_adamw_step for payloads in the formats of
+ * detonation_decompress_step_packed (paper, "Overall Setup": the experiments synchronise only
+ * the signs, and Decoupled AdamW is one of the underlying optimizers they run on top of that;
+ * Appendix B, "Communication Floating Point Data Type" for the 16-bit formats).  idx / val,
+ * their dtypes and replica strides as for detonation_decompress_step_packed; the optimizer
+ * state and all errors as for detonation_decompress_adamw_step.
+ */
+int detonation_decompress_adamw_step_packed(const deto_config* cfg, const deto_adamw* opt,
+                                            int64_t n, int32_t R,
+                                            const void* idx, int idx_dtype,
+                                            int64_t idx_replica_stride,
+                                            const void* val, int val_dtype,
+                                            int64_t val_replica_stride,
+                                            void* params, int param_dtype,
+                                            float* exp_avg, float* exp_avg_sq,
+                                            float* max_exp_avg_sq,
+                                            float* presign_dbg,
+                                            void* stream);
+
+/*
  * The first line of Algorithm 1 alone: momentum <- beta*momentum + grad, nothing extracted and
  * nothing sent.  For replicators that do not exchange on every step (paper, "Replication
  * Schemes": DiLoCo "denotes synchronization every n'th optimization step"): the steps in between
@@ -236,7 +256,7 @@ int64_t detonation_ternary_words(const deto_config* cfg, int64_t n);
 /* Static, human-readable name of a deto_status. */
 const char* detonation_status_string(int status);
 
-/* ABI version of this header: major*1000 + minor (1001: the *_packed entry points; 1002: Decoupled AdamW; 1003: DETO_TERNARY; 1004: detonation_accumulate). */
+/* ABI version of this header: major*1000 + minor (1001: the *_packed entry points; 1002: Decoupled AdamW; 1003: DETO_TERNARY; 1004: detonation_accumulate; 1005: detonation_decompress_adamw_step_packed). */
 int detonation_version(void);
 
 #ifdef __cplusplus

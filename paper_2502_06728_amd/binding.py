@@ -22,6 +22,7 @@ FLAG_SIGN, FLAG_DCT = 1, 2
 EXPORTS = ("detonation_compress", "detonation_decompress_step", "detonation_compress_packed",
            "detonation_accumulate",
            "detonation_decompress_step_packed", "detonation_decompress_adamw_step",
+           "detonation_decompress_adamw_step_packed",
            "detonation_payload_entries", "detonation_ternary_words",
            "detonation_status_string", "detonation_version")
 
@@ -104,6 +105,10 @@ def load() -> ctypes.CDLL:
                                                          vp, i64, vp, i64, vp, ctypes.c_int, vp,
                                                          vp, vp, vp, vp]
         lib.detonation_decompress_adamw_step.restype = ctypes.c_int
+        lib.detonation_decompress_adamw_step_packed.argtypes = [
+            cfgp, ctypes.POINTER(deto_adamw), i64, i32, vp, ctypes.c_int, i64, vp, ctypes.c_int,
+            i64, vp, ctypes.c_int, vp, vp, vp, vp, vp]
+        lib.detonation_decompress_adamw_step_packed.restype = ctypes.c_int
         lib.detonation_accumulate.argtypes = [cfgp, i64, vp, ctypes.c_int, vp, vp]
         lib.detonation_accumulate.restype = ctypes.c_int
         lib.detonation_payload_entries.argtypes = [cfgp, i64]
@@ -271,5 +276,27 @@ def detonation_decompress_adamw_step(cfg: Config, opt: AdamW, R: int, idx, val, 
                                                  _dtype(params), _ptr(exp_avg), _ptr(exp_avg_sq),
                                                  _ptr(max_exp_avg_sq), _ptr(presign_dbg),
                                                  _stream(stream))
+    if rc != 0:
+        raise DetonationError(rc)
+
+
+def detonation_decompress_adamw_step_packed(cfg: Config, opt: AdamW, R: int, idx, val, params,
+                                            exp_avg, exp_avg_sq, max_exp_avg_sq=None,
+                                            presign_dbg=None, stream=None, n: int | None = None,
+                                            idx_replica_stride: int | None = None,
+                                            val_replica_stride: int | None = None) -> None:
+    """Decoupled AdamW on payloads in the format given by the tensors' dtypes."""
+    _check(idx, val, params, exp_avg, exp_avg_sq, max_exp_avg_sq, presign_dbg)
+    n = params.numel() if n is None else n
+    entries = payload_entries(cfg, n)
+    vdt = _val_dtype(val)
+    vs = val_replica_stride
+    if vs is None:
+        vs = ternary_words(cfg, n) if vdt == TERNARY else entries
+    istr = entries if idx_replica_stride is None else idx_replica_stride
+    rc = load().detonation_decompress_adamw_step_packed(
+        ctypes.byref(cfg.c()), ctypes.byref(opt.c()), n, R, _ptr(idx), _idx_dtype(idx), istr,
+        _ptr(val), vdt, vs, _ptr(params), _dtype(params), _ptr(exp_avg), _ptr(exp_avg_sq),
+        _ptr(max_exp_avg_sq), _ptr(presign_dbg), _stream(stream))
     if rc != 0:
         raise DetonationError(rc)

@@ -297,6 +297,7 @@ int decompress_impl(const deto_config* cfg, const deto_adamw* opt, int64_t n, in
         stride_pattern(p, a.stride_mask);
         const bool done = tiles == 0 ? false
                           : idx ? (deto::launch_decompress_adamw(a) ||
+                                 deto::launch_decompress_adamw_narrow(a) ||
                                  deto::launch_decompress_idx_s64(a) ||
                                  deto::launch_decompress_idx_s32(a) ||
                                  deto::launch_decompress_idx_s16(a) ||
@@ -311,6 +312,7 @@ int decompress_impl(const deto_config* cfg, const deto_adamw* opt, int64_t n, in
                                  deto::launch_decompress_idx_packed_s32(a) ||
                                  deto::launch_decompress_idx_ternary(a))
                               : (deto::launch_decompress_scheme_adamw(a) ||
+                                 deto::launch_decompress_adamw_narrow(a) ||
                                  deto::launch_decompress_scheme(a) ||
                                  deto::launch_decompress_scheme_small(a) ||
                                  deto::launch_decompress_scheme_narrow_s32(a) ||
@@ -364,6 +366,19 @@ int detonation_decompress_adamw_step(const deto_config* cfg, const deto_adamw* o
                                      float* max_exp_avg_sq, float* presign_dbg, void* stream) {
     if (!opt) return DETO_ERR_NULL;
     return decompress_impl(cfg, opt, n, R, idx, DETO_IDX_I32, idx_replica_stride, val, DETO_F32,
+                           val_replica_stride, params, param_dtype,
+                           deto::AdamPtrs{exp_avg, exp_avg_sq, max_exp_avg_sq}, presign_dbg, stream);
+}
+
+int detonation_decompress_adamw_step_packed(const deto_config* cfg, const deto_adamw* opt,
+                                            int64_t n, int32_t R, const void* idx, int idx_dtype,
+                                            int64_t idx_replica_stride, const void* val,
+                                            int val_dtype, int64_t val_replica_stride,
+                                            void* params, int param_dtype, float* exp_avg,
+                                            float* exp_avg_sq, float* max_exp_avg_sq,
+                                            float* presign_dbg, void* stream) {
+    if (!opt) return DETO_ERR_NULL;
+    return decompress_impl(cfg, opt, n, R, idx, idx_dtype, idx_replica_stride, val, val_dtype,
                            val_replica_stride, params, param_dtype,
                            deto::AdamPtrs{exp_avg, exp_avg_sq, max_exp_avg_sq}, presign_dbg, stream);
 }
@@ -424,6 +439,6 @@ const char* detonation_status_string(int status) {
     }
 }
 
-int detonation_version(void) { return 1004; }
+int detonation_version(void) { return 1005; }
 
 }  // extern "C"

@@ -74,6 +74,7 @@ bool launch_decompress_idx_packed_s32(const DecompressLaunch& a);
 bool launch_compress_topk_ternary(const CompressLaunch& a);    // byte indices + two-bit signs
 bool launch_decompress_idx_ternary(const DecompressLaunch& a);
 bool launch_decompress_adamw(const DecompressLaunch& a);       // Decoupled AdamW update
+bool launch_decompress_adamw_narrow(const DecompressLaunch& a);   // ... narrow payloads, with or without indices
 bool launch_decompress_scheme_adamw(const DecompressLaunch& a);   // ... without transmitted indices
 bool launch_compress_scheme_narrow_s32(const CompressLaunch& a);   // Striding / Random, narrow payload
 bool launch_decompress_scheme_narrow_s32(const DecompressLaunch& a);

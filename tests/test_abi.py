@@ -33,7 +33,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_version_and_status_strings(lib):
-    assert binding.version() == 1004
+    assert binding.version() == 1005
     assert binding.status_string(0) == "ok"
     assert len({binding.status_string(i) for i in range(6)}) == 6
 
@@ -135,6 +135,18 @@ def test_adamw_entry_point_validation(lib):
     assert call(good, m=1026) == 4
     assert call(good, n=0) == 0
     assert ctypes.sizeof(binding.deto_adamw) == 24
+    # the same update on narrow payloads
+    fp = lib.detonation_decompress_adamw_step_packed
+
+    def callp(opt, idx_dtype=1, val_dtype=3, val=1024, m=1024, n=10):
+        return fp(ok, opt, n, 1, vp(1024), idx_dtype, 8, vp(val), val_dtype, 8, vp(1024), 0,
+                  vp(m) if m else None, vp(1024), None, None, None)
+    assert callp(None) == 1
+    assert callp(good, idx_dtype=5) == 2
+    assert callp(good, val_dtype=4) == 2
+    assert callp(good, val=1026) == 4                                     # ternary words
+    assert callp(good, m=None) == 1
+    assert callp(good, n=0) == 0
 
 
 def test_header_is_plain_c(tmp_path):

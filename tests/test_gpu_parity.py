@@ -879,3 +879,69 @@ def test_decoupled_adamw_without_transmitted_indices(H, scheme, s, k, params_bf1
         else:
             got, want, tol = got.astype(np.float64), th_o.astype(np.float64), parity.TOL_F32
         assert (np.abs(got - want) <= tol * np.abs(want) + tol * cfg.lr).all()
+
+
+@pytest.mark.parametrize("scheme", [SCHEME_TOPK, SCHEME_RANDOM])
+@pytest.mark.parametrize("val_dtype", [oracle.BF16, oracle.F16, oracle.TERNARY])
+@pytest.mark.parametrize("s,k,params_bf16", [(32, 16, True), (32, 4, False), (32, 1, True), (64, 32, True),
+                                             (96, 12, False)])
+def test_decoupled_adamw_narrow_payloads(H, s, k, params_bf16, val_dtype, scheme):
+    """Decoupled AdamW on what the paper's experiments put on the wire (signs only at chunk
+    size 32, "Overall Setup") and on 16-bit values: byte indices under top-k, no indices under
+    Random; two steps with local moments.  336 chunks, so the replicas' arrays start 16-byte
+    aligned (lane-per-chunk kernels; chunk 96 runs on the general ones)."""
+    import torch
+    from paper_2502_06728_amd import binding
+    n, R, amsgrad = s * 335 + 5, 3, True
+    th = make_inputs(n, 5, params_bf16=params_bf16)[2]
+    p = H.to_dev(th)
+    m = torch.zeros(n, device=H.DEV)
+    v = torch.zeros(n, device=H.DEV)
+    vm = torch.zeros(n, device=H.DEV)
+    for t in (1, 2):
+        cfg = Config(chunk=s, topk=k, scheme=scheme, seed=8, step=t, sign=True, lr=1e-3,
+                     weight_decay=0.01)
+        ins = [make_inputs(n, 100 * t + r)[:2] for r in range(R)]
+        if val_dtype == oracle.TERNARY:
+            pays = [oracle.compress_t(cfg, *i)[1:] for i in ins]
+            val = np.stack([q[1] for q in pays])
+            val_dev = torch.from_numpy(np.ascontiguousarray(val).view(np.int32)).to(H.DEV)
+        else:
+            pays = [oracle.compress_q(cfg, *i, val_dtype)[1:] for i in ins]
+            val = np.stack([q[1] for q in pays])
+            val_dev = H.bits16_to_dev(np.ascontiguousarray(val), val_dtype)
+        idx = np.stack([q[0] for q in pays])
+        idx_dev = (torch.from_numpy(np.ascontiguousarray(idx.reshape(R, -1).astype(np.uint8))).to(H.DEV)
+                   if scheme == SCHEME_TOPK else None)
+        th_in, m_in, v_in, vm_in = H.to_host(p), m.cpu().numpy(), v.cpu().numpy(), vm.cpu().numpy()
+        y = torch.empty(n, dtype=torch.float32, device=H.DEV)
+        binding.detonation_decompress_adamw_step_packed(
+            H.bcfg(cfg), binding.AdamW(0.9, 0.95, 1e-8, amsgrad, t), R, idx_dev, val_dev,
+            p, m, v, vm, y)
+        torch.cuda.synchronize()
+        y_gpu = H.to_host(y)
+        y_o = (oracle.presign_t(cfg, n, idx, val) if val_dtype == oracle.TERNARY
+               else oracle.presign_q(cfg, n, idx, val, val_dtype))
+        # replicas can cancel: the scale is the chunk's largest transmitted magnitude (1 for signs)
+        C = -(-n // s)
+        if val_dtype == oracle.TERNARY:
+            vmax = np.ones(C)
+        else:
+            dec = ((val.astype(np.uint32) << 16).view(np.float32) if val_dtype == oracle.BF16
+                   else val.view(np.float16).astype(np.float32))
+            vmax = np.abs(dec.astype(np.float64).reshape(R, C, k)).max(axis=(0, 2))
+        scale = np.maximum(np.repeat(vmax, s)[:n], parity.parity_chunk_max(y_o, s))
+        assert parity.rel_chunk_err(y_gpu, y_o, s, scale=scale) <= parity.TOL_F32
+        th_o, m_o, v_o, vm_o = oracle.adamw_update(cfg, oracle.AdamW(0.9, 0.95, 1e-8, amsgrad, t),
+                                                   y_gpu, th_in, m_in, v_in, vm_in)
+        assert np.abs(m.cpu().numpy() - m_o).max() <= 1e-5 * np.abs(m_o).max()
+        assert np.abs(v.cpu().numpy() - v_o).max() <= 1e-5 * np.abs(v_o).max()
+        assert np.abs(vm.cpu().numpy() - vm_o).max() <= 1e-5 * np.abs(vm_o).max()
+        got = H.to_host(p)
+        if params_bf16:
+            got = synth.from_bf16_bits(got).astype(np.float64)
+            want = synth.from_bf16_bits(th_o).astype(np.float64)
+            tol = parity.TOL_BF16
+        else:
+            got, want, tol = got.astype(np.float64), th_o.astype(np.float64), parity.TOL_F32
+        assert (np.abs(got - want) <= tol * np.abs(want) + tol * cfg.lr).all()
