@@ -708,57 +708,74 @@ __device__ __forceinline__ void scatter_tile(float* __restrict__ buf, const KPar
 }
 
 // Last phase of decompress: y (four consecutive elements of a row from get_y4(row, col)),
-// optional sign, parameter update (plain or Decoupled AdamW), coalesced.
+// optional sign, parameter update (plain or Decoupled AdamW), coalesced.  Nothing else of this
+// wavefront is in flight here and the transform's registers are free, so the parameters (and
+// moments) of a batch of iterations are requested at once before any of them is used: with one
+// wavefront per SIMD every separate wait costs a full memory latency.
 template <int NB, bool PARAM_BF16, class GetY>
 __device__ __forceinline__ void update_params_rows(const KParams& p, int lane, int64_t base,
                                                    void* __restrict__ params, const AdamPtrs& ad,
                                                    float* __restrict__ presign_dbg, GetY get_y4) {
     using G = MfmaGeom<NB>;
     constexpr int S = G::S;
-    #pragma unroll 2
-    for (int it = 0; it < G::kVecIters; ++it) {
-        const int e4 = 4 * (lane + kWave * it);
-        const int row = e4 / S, col = e4 - row * S;
-        const int64_t i = base + e4;
-        const float4 y4 = get_y4(row, col);
-        if (presign_dbg) st_f4<false>(presign_dbg + i, y4);
-        const float y[4] = {y4.x, y4.y, y4.z, y4.w};
-        float old[4], nw[4];
-        uint2 pb;
-        if constexpr (PARAM_BF16) {
-            pb = ld_u2<false>(static_cast<const uint16_t*>(params) + i);
-            old[0] = __uint_as_float(pb.x << 16);
-            old[1] = __uint_as_float(pb.x & 0xFFFF0000u);
-            old[2] = __uint_as_float(pb.y << 16);
-            old[3] = __uint_as_float(pb.y & 0xFFFF0000u);
-        } else {
-            const float4 o = ld_f4<false>(static_cast<const float*>(params) + i);
-            old[0] = o.x; old[1] = o.y; old[2] = o.z; old[3] = o.w;
-        }
-        if (p.adam) {
-            const float4 m4 = ld_f4<false>(ad.m + i), v4 = ld_f4<false>(ad.v + i);
-            float4 x4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-            if (p.amsgrad) x4 = ld_f4<false>(ad.vmax + i);
-            float m[4] = {m4.x, m4.y, m4.z, m4.w}, v[4] = {v4.x, v4.y, v4.z, v4.w};
-            float x[4] = {x4.x, x4.y, x4.z, x4.w};
+    constexpr int kBatch = (G::kVecIters % 8 == 0) ? 8 : 4;
+    static_assert(G::kVecIters % kBatch == 0, "whole batches");
+#pragma unroll 1
+    for (int b = 0; b < G::kVecIters; b += kBatch) {
+        float4 old4[kBatch], m4[kBatch], v4[kBatch], x4[kBatch];
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-                nw[c] = adamw_step(p, old[c], sign_or_self(y[c], p.use_sign), m[c], v[c], x[c]);
-            st_f4<false>(ad.m + i, make_float4(m[0], m[1], m[2], m[3]));
-            st_f4<false>(ad.v + i, make_float4(v[0], v[1], v[2], v[3]));
-            if (p.amsgrad) st_f4<false>(ad.vmax + i, make_float4(x[0], x[1], x[2], x[3]));
-        } else {
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-                nw[c] = fmaf(-p.lr, sign_or_self(y[c], p.use_sign), old[c] * p.wd_scale);
+        for (int j = 0; j < kBatch; ++j) {
+            const int64_t i = base + 4 * (lane + kWave * (b + j));
+            if constexpr (PARAM_BF16) {
+                const uint2 pb = ld_u2<false>(static_cast<const uint16_t*>(params) + i);
+                old4[j] = make_float4(__uint_as_float(pb.x << 16),
+                                      __uint_as_float(pb.x & 0xFFFF0000u),
+                                      __uint_as_float(pb.y << 16),
+                                      __uint_as_float(pb.y & 0xFFFF0000u));
+            } else {
+                old4[j] = ld_f4<false>(static_cast<const float*>(params) + i);
+            }
+            x4[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (p.adam) {
+                m4[j] = ld_f4<false>(ad.m + i);
+                v4[j] = ld_f4<false>(ad.v + i);
+                if (p.amsgrad) x4[j] = ld_f4<false>(ad.vmax + i);
+            }
         }
-        if constexpr (PARAM_BF16) {
-            uint2 o;
-            o.x = pack_bf16x2(nw[0], nw[1]);
-            o.y = pack_bf16x2(nw[2], nw[3]);
-            *reinterpret_cast<uint2*>(static_cast<uint16_t*>(params) + i) = o;
-        } else {
-            st_f4<false>(static_cast<float*>(params) + i, make_float4(nw[0], nw[1], nw[2], nw[3]));
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const int e4 = 4 * (lane + kWave * (b + j));
+            const int row = e4 / S, col = e4 - row * S;
+            const int64_t i = base + e4;
+            const float4 y4 = get_y4(row, col);
+            if (presign_dbg) st_f4<false>(presign_dbg + i, y4);
+            const float y[4] = {y4.x, y4.y, y4.z, y4.w};
+            const float old[4] = {old4[j].x, old4[j].y, old4[j].z, old4[j].w};
+            float nw[4];
+            if (p.adam) {
+                float m[4] = {m4[j].x, m4[j].y, m4[j].z, m4[j].w};
+                float v[4] = {v4[j].x, v4[j].y, v4[j].z, v4[j].w};
+                float x[4] = {x4[j].x, x4[j].y, x4[j].z, x4[j].w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    nw[c] = adamw_step(p, old[c], sign_or_self(y[c], p.use_sign), m[c], v[c], x[c]);
+                st_f4<false>(ad.m + i, make_float4(m[0], m[1], m[2], m[3]));
+                st_f4<false>(ad.v + i, make_float4(v[0], v[1], v[2], v[3]));
+                if (p.amsgrad) st_f4<false>(ad.vmax + i, make_float4(x[0], x[1], x[2], x[3]));
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    nw[c] = fmaf(-p.lr, sign_or_self(y[c], p.use_sign), old[c] * p.wd_scale);
+            }
+            if constexpr (PARAM_BF16) {
+                uint2 o;
+                o.x = pack_bf16x2(nw[0], nw[1]);
+                o.y = pack_bf16x2(nw[2], nw[3]);
+                *reinterpret_cast<uint2*>(static_cast<uint16_t*>(params) + i) = o;
+            } else {
+                st_f4<false>(static_cast<float*>(params) + i,
+                             make_float4(nw[0], nw[1], nw[2], nw[3]));
+            }
         }
     }
 }

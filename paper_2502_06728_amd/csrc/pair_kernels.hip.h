@@ -91,7 +91,12 @@ __global__ __launch_bounds__(kWave) void compress_pair(KParams p, int64_t tiles,
     const int t = lane & 31, h = lane >> 5;
     const int k = p.k;
 
-    for (int64_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    // One tile per workgroup.  A loop over tiles invites the compiler to hoist what does not
+    // change from tile to tile (the lane's payload index constants, row addresses) out of it
+    // and, with every register taken, to spill it: a scratch reload per coefficient.
+    const int64_t tile = blockIdx.x;
+    if (tile >= tiles) return;
+    {
         const int64_t base = tile * static_cast<int64_t>(kMfmaChunks * S);
         const int64_t chunk0 = tile * kMfmaChunks;
         float* row = &buf[t * kRow];
@@ -295,7 +300,12 @@ __global__ __launch_bounds__(kWave) void decompress_pair(
     const uint32_t magic = entry_magic(k);
     const float scale = p.alpha * p.inv_R, scale0 = p.alpha0 * p.inv_R;
 
-    for (int64_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    // One tile per workgroup.  A loop over tiles invites the compiler to hoist what does not
+    // change from tile to tile (the lane's payload index constants, row addresses) out of it
+    // and, with every register taken, to spill it: a scratch reload per coefficient.
+    const int64_t tile = blockIdx.x;
+    if (tile >= tiles) return;
+    {
         const int64_t base = tile * static_cast<int64_t>(kMfmaChunks * S);
         const int64_t entry0 = tile * static_cast<int64_t>(kMfmaChunks) * k;
         float* row = &buf[t * kRow];
