@@ -220,6 +220,17 @@ __device__ __forceinline__ void regs_to_global(float* dst, const float (&x)[S]) 
             make_float4(x[4 * j], x[4 * j + 1], x[4 * j + 2], x[4 * j + 3]);
 }
 
+// Length in floats of a chunk's row in the [chunk][k] staging block of the payload: room for
+// k entries plus a spare slot, a multiple of 4 when k is one (the block leaves with 16-byte
+// reads), and then an odd multiple of 4: the 64 lanes' rows start in 16 different groups of four
+// LDS banks instead of 4 or 8 (k = 12 or 4), which would pile the lanes' scalar writes onto a
+// few banks.
+constexpr int staging_row(int k) {
+    int pr = k + 4;
+    if (k % 4 == 0 && (pr / 4) % 2 == 0) pr += 4;
+    return pr;
+}
+
 // ---- phase 3a of compress: compact the kept (index, value) pairs of each chunk, ascending,
 // and store the tile's payload coalesced.  The tile must be free (every lane holds its row
 // in registers).  Every element is written at the running position, which only advances
@@ -234,7 +245,7 @@ __device__ __forceinline__ void compact_and_store_payload(const float (&c)[S],
                                                           void* __restrict__ val_out_v,
                                                           int64_t pbase) {
     using G = TileGeom<S>;
-    constexpr int PR = K + 4;                       // staging row, one spare slot + pad
+    constexpr int PR = staging_row(K);              // staging row, one spare slot + pad
     float* vrow = tile + lane * PR;
     uint8_t* ibytes = reinterpret_cast<uint8_t*>(tile + kWave * PR);   // indices as bytes
     uint8_t* irow = ibytes + lane * PR;
@@ -1071,7 +1082,7 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_
     }
     const int64_t ebase = t * G::kElems;
     const int64_t pbase = t * (kWave * K);
-    constexpr int PR = K + 4;
+    constexpr int PR = staging_row(K);
     static_assert(kWave * PR * 4 + kWave * G::kPermStride <= G::kFloats * 4, "LDS layout");
 
     ParamRegs<S, PARAM_BF16> th;
