@@ -285,7 +285,6 @@ number for this kernel path):
 def report(args) -> int:
     """All benchmark configurations, one row each, with the CPU oracle timed in the same run."""
     import copy
-    import oracle
     rows = []
     plan = [("flat-1m", "topk", False), ("t5-base-1of8", "topk", False),
             ("vit-b16-1of8", "topk", False), ("olmo-1b-1of8", "topk", False),
@@ -298,6 +297,7 @@ def report(args) -> int:
         a.steps, a.warmup, a.no_cpu = min(args.steps, 20), 3, False
         a.cpu_sample = 1 << 26           # oracle on at most 67 M leading parameters (labelled)
         rec = run(a)
+        import oracle      # after the GPU leg, as in a plain run (the oracle brings its OpenMP pool)
         all_cores = rec["cpu_baseline"]
         # single-threaded oracle on a smaller sample of the same shard
         import dataclasses
