@@ -81,6 +81,8 @@ def main() -> int:
                     help="underlying optimizer of the update: DeMo-SGD or Decoupled AdamW")
     ap.add_argument("--chunk", type=int, default=0, help="override the workload's chunk size")
     ap.add_argument("--topk", type=int, default=0, help="override the workload's k")
+    ap.add_argument("--replicas", type=int, default=0,
+                    help="override the workload's R, the size of the replication group")
     ap.add_argument("--cpu-sample", type=int, default=1 << 28)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--report", action="store_true",
@@ -110,6 +112,9 @@ def run(args) -> dict:
     if args.chunk or args.topk:
         import dataclasses
         w = dataclasses.replace(w, chunk=args.chunk or w.chunk, topk=args.topk or w.topk)
+    if getattr(args, "replicas", 0):
+        import dataclasses
+        w = dataclasses.replace(w, replicas=args.replicas)
     diloco = args.scheme == "diloco"
     every = max(1, args.diloco_every) if diloco else 1
     if diloco:

@@ -938,6 +938,48 @@ __device__ __forceinline__ void finish_chunk(const KParams& p, float (&y)[S], fl
     regs_to_row<S>(row, y);
 }
 
+// Four consecutive payload values as they are loaded (VAL = 0: fp32; 1 / 2: bf16 / fp16;
+// 3: four two-bit signs in one byte), decoded only when they are used: a batch of loads can
+// then be requested before the first wait.
+template <int VAL>
+struct RawQuad {
+    uint2 w;
+    __device__ __forceinline__ float4 get() const {
+        return make_float4(decode16<VAL>(static_cast<uint16_t>(w.x & 0xFFFFu)),
+                           decode16<VAL>(static_cast<uint16_t>(w.x >> 16)),
+                           decode16<VAL>(static_cast<uint16_t>(w.y & 0xFFFFu)),
+                           decode16<VAL>(static_cast<uint16_t>(w.y >> 16)));
+    }
+};
+template <>
+struct RawQuad<0> {
+    float4 v;
+    __device__ __forceinline__ float4 get() const { return v; }
+};
+template <>
+struct RawQuad<3> {
+    uint32_t b;
+    __device__ __forceinline__ float4 get() const {
+        auto dec = [](uint32_t code) { return (code & 1u) ? ((code & 2u) ? -1.0f : 1.0f) : 0.0f; };
+        return make_float4(dec(b & 3u), dec((b >> 2) & 3u), dec((b >> 4) & 3u),
+                           dec((b >> 6) & 3u));
+    }
+};
+
+// One payload value as loaded, for the entry-by-entry paths (k < 4): fp32 bits, a 16-bit
+// pattern, or (VAL = 3) the chunk's word of two-bit signs with the entry's number.
+template <int VAL>
+__device__ __forceinline__ float decode_entry(uint32_t raw, int j) {
+    if constexpr (VAL == 0) {
+        return __uint_as_float(raw);
+    } else if constexpr (VAL == 3) {
+        const uint32_t code = (raw >> (2 * j)) & 3u;
+        return (code & 1u) ? ((code & 2u) ? -1.0f : 1.0f) : 0.0f;
+    } else {
+        return decode16<VAL>(static_cast<uint16_t>(raw));
+    }
+}
+
 // Decompress-and-update half on full tiles, indices transmitted (top-k, or any scheme whose
 // caller passes indices).  Up to three replicas' payloads are in flight while one is
 // scattered into LDS; LDS operations of one wavefront complete in order, so the additions
@@ -977,71 +1019,67 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_
     for (int i = 0; i < G::kFloats / (kWave * 4); ++i)
         *reinterpret_cast<float4*>(tile + (i * kWave + lane) * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
     wave_lds_sync();
-    if constexpr (K % 4 == 0 && K > 32) {
-        // large k: two replicas in flight
-        PayloadRegs<K, VAL> b0, b1;
-        auto fetch = [&](PayloadRegs<K, VAL>& b, int r) {
-            load_payload<K, VAL>(b, idx + r * idx_step, val + r * val_step, lane);
+    if constexpr (K % 4 == 0) {
+        // kBuf replicas' payloads in flight (as many as the registers allow: a replica's
+        // entries are 2K registers in the widest format) while one is scattered; with a large
+        // replication group and a small k every separate wait would cost a memory latency
+        constexpr int kBuf = K > 32 ? 2 : (K > 8 ? 3 : 8);
+        PayloadRegs<K, VAL> b[kBuf];
+        auto fetch = [&](PayloadRegs<K, VAL>& dst, int r) {
+            load_payload<K, VAL>(dst, idx + r * idx_step, val + r * val_step, lane);
         };
-        fetch(b0, 0);
-        if (p.R > 1) fetch(b1, 1);
-        int r = 0;
-        while (true) {
-            scatter_payload<S, K, VAL>(b0, tile, lane);
-            if (r + 2 < p.R) fetch(b0, r + 2);
-            if (++r >= p.R) break;
-            scatter_payload<S, K, VAL>(b1, tile, lane);
-            if (r + 2 < p.R) fetch(b1, r + 2);
-            if (++r >= p.R) break;
-        }
-    } else if constexpr (K % 4 == 0) {
-        PayloadRegs<K, VAL> b0, b1, b2;
-        auto fetch = [&](PayloadRegs<K, VAL>& b, int r) {
-            load_payload<K, VAL>(b, idx + r * idx_step, val + r * val_step, lane);
-        };
-        fetch(b0, 0);
-        if (p.R > 1) fetch(b1, 1);
-        if (p.R > 2) fetch(b2, 2);
-        int r = 0;
-        while (true) {
-            scatter_payload<S, K, VAL>(b0, tile, lane);
-            if (r + 3 < p.R) fetch(b0, r + 3);
-            if (++r >= p.R) break;
-            scatter_payload<S, K, VAL>(b1, tile, lane);
-            if (r + 3 < p.R) fetch(b1, r + 3);
-            if (++r >= p.R) break;
-            scatter_payload<S, K, VAL>(b2, tile, lane);
-            if (r + 3 < p.R) fetch(b2, r + 3);
-            if (++r >= p.R) break;
+#pragma unroll
+        for (int i = 0; i < kBuf; ++i)
+            if (i < p.R) fetch(b[i], i);
+        for (int r0 = 0; r0 < p.R; r0 += kBuf) {
+#pragma unroll
+            for (int i = 0; i < kBuf; ++i) {
+                if (r0 + i < p.R) {
+                    scatter_payload<S, K, VAL>(b[i], tile, lane);
+                    if (r0 + i + kBuf < p.R) fetch(b[i], r0 + i + kBuf);
+                }
+            }
         }
     } else {
-        // K entries per chunk, lane = chunk: the lane owns its row, plain sequential adds
-        for (int r = 0; r < p.R; ++r) {
-            const char* ir = idx + r * idx_step + lane * K * kIdxBytes;
-            const char* vr = val + r * val_step;
-            float* arow = tile + lane * G::kRow;
-            [[maybe_unused]] uint32_t word = 0u;
-            if constexpr (VAL == 3) {
-                static_assert(K < 16, "one word per chunk");
-                word = reinterpret_cast<const uint32_t*>(vr)[lane];
-            }
+        // K entries per chunk, lane = chunk: the lane owns its row, plain sequential adds.
+        // Eight replicas' entries are requested before the first is added.
+        constexpr int kBatch = 8;
+        float* arow = tile + lane * G::kRow;
+        for (int r0 = 0; r0 < p.R; r0 += kBatch) {
+            uint32_t at[kBatch][K];
+            uint32_t raw[kBatch][K];    // values as loaded; VAL = 3: the chunk's word in raw[i][0]
 #pragma unroll
-            for (int j = 0; j < K; ++j) {
-                uint32_t at;
-                float v;
-                if constexpr (VAL == 0) {
-                    at = static_cast<uint32_t>(reinterpret_cast<const int32_t*>(ir)[j]);
-                    v = reinterpret_cast<const float*>(vr)[lane * K + j];
-                } else {
-                    at = reinterpret_cast<const uint8_t*>(ir)[j];
+            for (int i = 0; i < kBatch; ++i) {
+                if (r0 + i < p.R) {
+                    const int r = r0 + i;
+                    const char* ir = idx + r * idx_step + lane * K * kIdxBytes;
+                    const char* vr = val + r * val_step;
                     if constexpr (VAL == 3) {
-                        const uint32_t code = (word >> (2 * j)) & 3u;
-                        v = (code & 1u) ? ((code & 2u) ? -1.0f : 1.0f) : 0.0f;
-                    } else {
-                        v = decode16<VAL>(reinterpret_cast<const uint16_t*>(vr)[lane * K + j]);
+                        static_assert(K < 16, "one word per chunk");
+                        raw[i][0] = reinterpret_cast<const uint32_t*>(vr)[lane];
+                    }
+#pragma unroll
+                    for (int j = 0; j < K; ++j) {
+                        if constexpr (VAL == 0) {
+                            at[i][j] =
+                                static_cast<uint32_t>(reinterpret_cast<const int32_t*>(ir)[j]);
+                            raw[i][j] = reinterpret_cast<const uint32_t*>(vr)[lane * K + j];
+                        } else {
+                            at[i][j] = reinterpret_cast<const uint8_t*>(ir)[j];
+                            if constexpr (VAL != 3)
+                                raw[i][j] = reinterpret_cast<const uint16_t*>(vr)[lane * K + j];
+                        }
                     }
                 }
-                arow[min(at, static_cast<uint32_t>(S))] += v;
+            }
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                if (r0 + i < p.R) {
+#pragma unroll
+                    for (int j = 0; j < K; ++j)
+                        arow[min(at[i][j], static_cast<uint32_t>(S))] +=
+                            decode_entry<VAL>(raw[i][VAL == 3 ? 0 : j], j);
+                }
             }
         }
     }
@@ -1089,44 +1127,52 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_
     load_params<S, PARAM_BF16>(th, params, ebase, lane);
 
     // sum over replicas, coalesced; staged as [chunk][k].  One replica's four consecutive
-    // entries it*256 + 4*lane ... of this tile, decoded (k a multiple of 4):
-    [[maybe_unused]] auto load4 = [&](int r, int it) -> float4 {
+    // entries it*256 + 4*lane ... of this tile, as loaded (k a multiple of 4):
+    [[maybe_unused]] auto load4 = [&](int r, int it) -> RawQuad<VAL> {
         const int e = it * 256 + lane * 4;
+        RawQuad<VAL> q;
         if constexpr (VAL == 0) {
-            return ld_f4<DETO_NT_DECOMPRESS_LD>(static_cast<const float*>(val_v) + r * val_stride +
-                                                pbase + e);
+            q.v = ld_f4<DETO_NT_DECOMPRESS_LD>(static_cast<const float*>(val_v) + r * val_stride +
+                                               pbase + e);
         } else if constexpr (VAL == 3) {
             // two-bit signs: ceil(K/16) words per chunk, replica stride in words
             constexpr int kChunkBytes = 4 * ((K + 15) / 16);
             const uint8_t* bytes = static_cast<const uint8_t*>(val_v) + r * val_stride * 4 +
                                    t * (kWave * kChunkBytes);
-            const uint32_t b = bytes[(e / K) * kChunkBytes + (e % K) / 4];
-            auto dec = [](uint32_t code) {
-                return (code & 1u) ? ((code & 2u) ? -1.0f : 1.0f) : 0.0f;
-            };
-            return make_float4(dec(b & 3u), dec((b >> 2) & 3u), dec((b >> 4) & 3u),
-                               dec((b >> 6) & 3u));
+            q.b = bytes[(e / K) * kChunkBytes + (e % K) / 4];
         } else {
-            const uint2 w = ld_u2<DETO_NT_DECOMPRESS_LD>(static_cast<const uint16_t*>(val_v) +
-                                                         r * val_stride + pbase + e);
-            return make_float4(decode16<VAL>(static_cast<uint16_t>(w.x & 0xFFFFu)),
-                               decode16<VAL>(static_cast<uint16_t>(w.x >> 16)),
-                               decode16<VAL>(static_cast<uint16_t>(w.y & 0xFFFFu)),
-                               decode16<VAL>(static_cast<uint16_t>(w.y >> 16)));
+            q.w = ld_u2<DETO_NT_DECOMPRESS_LD>(static_cast<const uint16_t*>(val_v) +
+                                               r * val_stride + pbase + e);
         }
+        return q;
     };
     if constexpr (K % 4 == 0) {
         float4 acc[K / 4];
 #pragma unroll
-        for (int it = 0; it < K / 4; ++it) acc[it] = load4(0, it);
-        for (int r = 1; r < p.R; ++r) {
-            float4 nxt[K / 4];
+        for (int it = 0; it < K / 4; ++it) acc[it] = load4(0, it).get();
+        // the other replicas in batches: all loads of a batch are requested before the first
+        // is added (a large replication group with a small k would otherwise pay a memory
+        // latency per replica); the order of the additions stays r = 0, 1, 2, ...
+        constexpr int kBatch = K >= 32 ? 2 : (K >= 16 ? 4 : 8);
+        for (int r0 = 1; r0 < p.R; r0 += kBatch) {
+            RawQuad<VAL> nxt[kBatch][K / 4];
 #pragma unroll
-            for (int it = 0; it < K / 4; ++it) nxt[it] = load4(r, it);
+            for (int i = 0; i < kBatch; ++i) {
+                if (r0 + i < p.R) {
 #pragma unroll
-            for (int it = 0; it < K / 4; ++it) {
-                acc[it].x += nxt[it].x; acc[it].y += nxt[it].y;
-                acc[it].z += nxt[it].z; acc[it].w += nxt[it].w;
+                    for (int it = 0; it < K / 4; ++it) nxt[i][it] = load4(r0 + i, it);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                if (r0 + i < p.R) {
+#pragma unroll
+                    for (int it = 0; it < K / 4; ++it) {
+                        const float4 v = nxt[i][it].get();
+                        acc[it].x += v.x; acc[it].y += v.y;
+                        acc[it].z += v.z; acc[it].w += v.w;
+                    }
+                }
             }
         }
 #pragma unroll
@@ -1135,29 +1181,41 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_
             *reinterpret_cast<float4*>(tile + (e / K) * PR + (e % K)) = acc[it];
         }
     } else {
-        // k = 1, 2 (3): the lane sums its own chunk's entries
+        // k = 1, 2 (3): the lane sums its own chunk's entries, eight replicas per batch of loads
+        constexpr int kBatch = 8;
         float a[K];
 #pragma unroll
         for (int j = 0; j < K; ++j) a[j] = 0.0f;
-        for (int r = 0; r < p.R; ++r) {
-            if constexpr (VAL == 3) {
-                static_assert(K < 16, "one word per chunk");
-                const uint32_t word = static_cast<const uint32_t*>(val_v)[r * val_stride +
-                                                                          t * kWave + lane];
+        for (int r0 = 0; r0 < p.R; r0 += kBatch) {
+            uint32_t x[kBatch][K];      // as loaded; VAL = 3: the chunk's word in x[i][0]
 #pragma unroll
-                for (int j = 0; j < K; ++j) {
-                    const uint32_t code = (word >> (2 * j)) & 3u;
-                    a[j] += (code & 1u) ? ((code & 2u) ? -1.0f : 1.0f) : 0.0f;
+            for (int i = 0; i < kBatch; ++i) {
+                if (r0 + i < p.R) {
+                    const int64_t r = r0 + i;
+                    if constexpr (VAL == 3) {
+                        static_assert(K < 16, "one word per chunk");
+                        x[i][0] =
+                            static_cast<const uint32_t*>(val_v)[r * val_stride + t * kWave + lane];
+                    } else if constexpr (VAL == 0) {
+#pragma unroll
+                        for (int j = 0; j < K; ++j)
+                            x[i][j] = static_cast<const uint32_t*>(
+                                val_v)[r * val_stride + pbase + lane * K + j];
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < K; ++j)
+                            x[i][j] = static_cast<const uint16_t*>(
+                                val_v)[r * val_stride + pbase + lane * K + j];
+                    }
                 }
-            } else if constexpr (VAL == 0) {
+            }
 #pragma unroll
-                for (int j = 0; j < K; ++j)
-                    a[j] += static_cast<const float*>(val_v)[r * val_stride + pbase + lane * K + j];
-            } else {
+            for (int i = 0; i < kBatch; ++i) {
+                if (r0 + i < p.R) {
 #pragma unroll
-                for (int j = 0; j < K; ++j)
-                    a[j] += decode16<VAL>(
-                        static_cast<const uint16_t*>(val_v)[r * val_stride + pbase + lane * K + j]);
+                    for (int j = 0; j < K; ++j)
+                        a[j] += decode_entry<VAL>(x[i][VAL == 3 ? 0 : j], j);
+                }
             }
         }
 #pragma unroll
