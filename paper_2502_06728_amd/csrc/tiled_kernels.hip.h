@@ -858,7 +858,9 @@ __device__ __forceinline__ void update_params_from_tile(const KParams& p, const 
 }
 
 // Last phase of decompress with Decoupled AdamW: the tile rows hold Q; the moments stream
-// through (read, update, write) together with the parameters.
+// through (read, update, write) together with the parameters.  The moments of a batch of
+// iterations are requested before the first is used: the stores of one iteration go to the
+// arrays the next one loads from, so the compiler cannot move those loads up by itself.
 template <int S, bool PARAM_BF16>
 __device__ __forceinline__ void update_params_adamw_from_tile(const KParams& p, const float* tile,
                                                               const ParamRegs<S, PARAM_BF16>& th,
@@ -866,55 +868,71 @@ __device__ __forceinline__ void update_params_adamw_from_tile(const KParams& p, 
                                                               const AdamPtrs& ad, int64_t ebase,
                                                               int lane) {
     using G = TileGeom<S>;
+    constexpr int kIt = S / 8;
+    constexpr int kBatch = kIt < 4 ? kIt : 4;
+    static_assert(kIt % kBatch == 0, "whole batches");
+    auto load8 = [&](const float* base, int pe, float (&x)[8]) {
+        const float4 a = ld_f4<DETO_NT_DECOMPRESS_LD>(base + ebase + pe);
+        const float4 b = ld_f4<DETO_NT_DECOMPRESS_LD>(base + ebase + pe + 4);
+        x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
+        x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+    };
+    auto store8 = [&](float* base, int pe, const float (&x)[8]) {
+        st_f4<DETO_NT_DECOMPRESS_ST>(base + ebase + pe, make_float4(x[0], x[1], x[2], x[3]));
+        st_f4<DETO_NT_DECOMPRESS_ST>(base + ebase + pe + 4, make_float4(x[4], x[5], x[6], x[7]));
+    };
 #pragma unroll
-    for (int it = 0; it < S / 8; ++it) {
-        const int pe = it * 512 + lane * 8;
-        const float* src = tile + (pe / S) * G::kRow + (pe % S);
-        const float4 qa = *reinterpret_cast<const float4*>(src);
-        const float4 qb = *reinterpret_cast<const float4*>(src + 4);
-        const float q[8] = {qa.x, qa.y, qa.z, qa.w, qb.x, qb.y, qb.z, qb.w};
-        float m[8], v[8], vm[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, old[8], nw[8];
-        auto load8 = [&](const float* base, float (&x)[8]) {
-            const float4 a = ld_f4<DETO_NT_DECOMPRESS_LD>(base + ebase + pe);
-            const float4 b = ld_f4<DETO_NT_DECOMPRESS_LD>(base + ebase + pe + 4);
-            x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
-            x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
-        };
-        auto store8 = [&](float* base, const float (&x)[8]) {
-            st_f4<DETO_NT_DECOMPRESS_ST>(base + ebase + pe, make_float4(x[0], x[1], x[2], x[3]));
-            st_f4<DETO_NT_DECOMPRESS_ST>(base + ebase + pe + 4,
-                                         make_float4(x[4], x[5], x[6], x[7]));
-        };
-        load8(ad.m, m);
-        load8(ad.v, v);
-        if (p.amsgrad) load8(ad.vmax, vm);
-        if constexpr (PARAM_BF16) {
-            const uint4 raw = th.b[it];
-            const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+    for (int b0 = 0; b0 < kIt; b0 += kBatch) {
+        float m[kBatch][8], v[kBatch][8], vm[kBatch][8];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                old[2 * j] = __uint_as_float(w[j] << 16);
-                old[2 * j + 1] = __uint_as_float(w[j] & 0xFFFF0000u);
+        for (int j = 0; j < kBatch; ++j) {
+            const int pe = (b0 + j) * 512 + lane * 8;
+            load8(ad.m, pe, m[j]);
+            load8(ad.v, pe, v[j]);
+            if (p.amsgrad) load8(ad.vmax, pe, vm[j]);
+            else {
+#pragma unroll
+                for (int c = 0; c < 8; ++c) vm[j][c] = 0.0f;
             }
-        } else {
-            const float4 a = th.f[2 * it], b = th.f[2 * it + 1];
-            old[0] = a.x; old[1] = a.y; old[2] = a.z; old[3] = a.w;
-            old[4] = b.x; old[5] = b.y; old[6] = b.z; old[7] = b.w;
         }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) nw[j] = adamw_step(p, old[j], q[j], m[j], v[j], vm[j]);
-        store8(ad.m, m);
-        store8(ad.v, v);
-        if (p.amsgrad) store8(ad.vmax, vm);
-        if constexpr (PARAM_BF16) {
-            uint4 out;
-            out.x = pack_bf16x2(nw[0], nw[1]);
-            out.y = pack_bf16x2(nw[2], nw[3]);
-            out.z = pack_bf16x2(nw[4], nw[5]);
-            out.w = pack_bf16x2(nw[6], nw[7]);
-            st_u4<DETO_NT_DECOMPRESS_ST>(static_cast<uint16_t*>(params) + ebase + pe, out);
-        } else {
-            store8(static_cast<float*>(params), nw);
+        for (int j = 0; j < kBatch; ++j) {
+            const int it = b0 + j;
+            const int pe = it * 512 + lane * 8;
+            const float* src = tile + (pe / S) * G::kRow + (pe % S);
+            const float4 qa = *reinterpret_cast<const float4*>(src);
+            const float4 qb = *reinterpret_cast<const float4*>(src + 4);
+            const float q[8] = {qa.x, qa.y, qa.z, qa.w, qb.x, qb.y, qb.z, qb.w};
+            float old[8], nw[8];
+            if constexpr (PARAM_BF16) {
+                const uint4 raw = th.b[it];
+                const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    old[2 * c] = __uint_as_float(w[c] << 16);
+                    old[2 * c + 1] = __uint_as_float(w[c] & 0xFFFF0000u);
+                }
+            } else {
+                const float4 a = th.f[2 * it], b = th.f[2 * it + 1];
+                old[0] = a.x; old[1] = a.y; old[2] = a.z; old[3] = a.w;
+                old[4] = b.x; old[5] = b.y; old[6] = b.z; old[7] = b.w;
+            }
+#pragma unroll
+            for (int c = 0; c < 8; ++c)
+                nw[c] = adamw_step(p, old[c], q[c], m[j][c], v[j][c], vm[j][c]);
+            store8(ad.m, pe, m[j]);
+            store8(ad.v, pe, v[j]);
+            if (p.amsgrad) store8(ad.vmax, pe, vm[j]);
+            if constexpr (PARAM_BF16) {
+                uint4 out;
+                out.x = pack_bf16x2(nw[0], nw[1]);
+                out.y = pack_bf16x2(nw[2], nw[3]);
+                out.z = pack_bf16x2(nw[4], nw[5]);
+                out.w = pack_bf16x2(nw[6], nw[7]);
+                st_u4<DETO_NT_DECOMPRESS_ST>(static_cast<uint16_t*>(params) + ebase + pe, out);
+            } else {
+                store8(static_cast<float*>(params), pe, nw);
+            }
         }
     }
 }
