@@ -77,7 +77,8 @@ __device__ __forceinline__ float4 combine_halves(const float* __restrict__ row, 
 
 // Compress half on full tiles of 32 chunks (top-k selection, DCT domain).
 template <int S, bool GRAD_BF16>
-__global__ __launch_bounds__(kWave) void compress_pair(KParams p, int64_t tiles,
+__global__ __launch_bounds__(kWave) void compress_pair(KParams p, int64_t tiles, int64_t n,
+                                                       int64_t n_chunks,
                                                        const void* __restrict__ grad,
                                                        float* __restrict__ mom,
                                                        void* __restrict__ idx_out,
@@ -95,7 +96,16 @@ __global__ __launch_bounds__(kWave) void compress_pair(KParams p, int64_t tiles,
     // change from tile to tile (the lane's payload index constants, row addresses) out of it
     // and, with every register taken, to spill it: a scratch reload per coefficient.
     const int64_t tile = blockIdx.x;
-    if (tile >= tiles) return;
+    if (tile >= tiles) {
+        // surplus workgroups: the chunks past the last full tile, one each, on the general
+        // per-chunk code, side by side with the tiles instead of in a launch of their own
+        static_assert(sizeof(GenericCompressSmem) <= sizeof(buf), "tail code borrows the tile");
+        compress_generic_chunks<GRAD_BF16>(p, n, tiles * kMfmaChunks + (tile - tiles), n_chunks,
+                                           gridDim.x - tiles,
+                                           *reinterpret_cast<GenericCompressSmem*>(buf), grad, mom,
+                                           idx_out, val_out, coeff_dbg);
+        return;
+    }
     {
         const int64_t base = tile * static_cast<int64_t>(kMfmaChunks * S);
         const int64_t chunk0 = tile * kMfmaChunks;
@@ -287,9 +297,9 @@ __global__ __launch_bounds__(kWave) void compress_pair(KParams p, int64_t tiles,
 // Decompress-and-update half on full tiles of 32 chunks (transmitted indices, DCT domain).
 template <int S, bool PARAM_BF16>
 __global__ __launch_bounds__(kWave) void decompress_pair(
-    KParams p, int64_t tiles, int vec_scatter, const void* __restrict__ idx, int64_t idx_stride,
-    const void* __restrict__ val, int64_t val_stride, void* __restrict__ params, AdamPtrs ad,
-    float* __restrict__ presign_dbg) {
+    KParams p, int64_t tiles, int64_t n, int64_t n_chunks, int vec_scatter,
+    const void* __restrict__ idx, int64_t idx_stride, const void* __restrict__ val,
+    int64_t val_stride, void* __restrict__ params, AdamPtrs ad, float* __restrict__ presign_dbg) {
     using G = PairGeom<S>;
     constexpr int NB = G::NB, H = G::H, kRow = G::kRow;
     __shared__ __attribute__((aligned(16))) float buf[kMfmaChunks * kRow];
@@ -304,7 +314,15 @@ __global__ __launch_bounds__(kWave) void decompress_pair(
     // change from tile to tile (the lane's payload index constants, row addresses) out of it
     // and, with every register taken, to spill it: a scratch reload per coefficient.
     const int64_t tile = blockIdx.x;
-    if (tile >= tiles) return;
+    if (tile >= tiles) {
+        static_assert(sizeof(GenericDecompressSmem) <= sizeof(buf), "tail code borrows the tile");
+        decompress_generic_chunks<PARAM_BF16>(p, n, tiles * kMfmaChunks + (tile - tiles), n_chunks,
+                                              gridDim.x - tiles,
+                                              *reinterpret_cast<GenericDecompressSmem*>(buf), idx,
+                                              idx_stride, val, val_stride, params, ad,
+                                              presign_dbg);
+        return;
+    }
     {
         const int64_t base = tile * static_cast<int64_t>(kMfmaChunks * S);
         const int64_t entry0 = tile * static_cast<int64_t>(kMfmaChunks) * k;
