@@ -945,3 +945,35 @@ def test_decoupled_adamw_narrow_payloads(H, s, k, params_bf16, val_dtype, scheme
         else:
             got, want, tol = got.astype(np.float64), th_o.astype(np.float64), parity.TOL_F32
         assert (np.abs(got - want) <= tol * np.abs(want) + tol * cfg.lr).all()
+
+
+@pytest.mark.parametrize("R", [9, 64])
+@pytest.mark.parametrize("mode", ["topk-f32", "random-f32", "topk-signs", "random-signs", "random-f16"])
+@pytest.mark.parametrize("s,k", [(32, 1), (32, 4), (64, 8)])
+def test_large_replication_groups(H, s, k, mode, R):
+    """The replication group of the paper's scaling runs has 64 members ("OLMo2: Scaling Up").
+    Decompress keeps several replicas' payloads in flight and requests the others in batches:
+    replica counts that are and are not a multiple of the batch, on every payload path (144
+    chunks, so each replica's arrays start 16-byte aligned and the lane-per-chunk kernels run)."""
+    n = s * 143 + 5
+    scheme = SCHEME_TOPK if mode.startswith("topk") else SCHEME_RANDOM
+    cfg = Config(chunk=s, topk=k, scheme=scheme, seed=3, step=R, sign=(R != 9), lr=1e-3)
+    th = make_inputs(n, seed=R, params_bf16=(R == 64))[2]
+    ins = [make_inputs(n, seed=1000 + r)[:2] for r in range(R)]
+    if mode.endswith("f32"):
+        pays = [oracle.compress(cfg, *i)[1:] for i in ins]
+        idx, val = np.stack([q[0] for q in pays]), np.stack([q[1] for q in pays])
+        th_gpu, y_gpu = H.gpu_decompress(cfg, idx if scheme == SCHEME_TOPK else None, val, th)
+        parity.check_decompress(cfg, idx, val, th, th_gpu, y_gpu)
+    elif mode.endswith("signs"):
+        pays = [oracle.compress_t(cfg, *i)[1:] for i in ins]
+        idx, words = np.stack([q[0] for q in pays]), np.stack([q[1] for q in pays])
+        th_gpu, y_gpu = H.gpu_decompress_ternary(cfg, idx if scheme == SCHEME_TOPK else None,
+                                                 words, th, True)
+        signs = np.stack([oracle.decode_ternary(cfg, n, w) for w in words])
+        parity.check_decompress(cfg, idx, signs, th, th_gpu, y_gpu)
+    else:
+        pays = [oracle.compress_q(cfg, *i, oracle.F16)[1:] for i in ins]
+        idx, vbits = np.stack([q[0] for q in pays]), np.stack([q[1] for q in pays])
+        th_gpu, y_gpu = H.gpu_decompress_packed(cfg, None, vbits, th, oracle.F16, False)
+        parity.check_decompress_packed(cfg, idx, vbits, oracle.F16, th, th_gpu, y_gpu)
