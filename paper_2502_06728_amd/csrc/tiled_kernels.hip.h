@@ -999,8 +999,8 @@ __device__ __forceinline__ float decode_entry(uint32_t raw, int j) {
 }
 
 // Decompress-and-update half on full tiles, indices transmitted (top-k, or any scheme whose
-// caller passes indices).  Up to three replicas' payloads are in flight while one is
-// scattered into LDS; LDS operations of one wavefront complete in order, so the additions
+// caller passes indices).  Several replicas' payloads (two to eight, by k) are in flight while
+// one is scattered into LDS; LDS operations of one wavefront complete in order, so the additions
 // into one accumulator happen replica after replica and the result does not depend on timing.
 template <int S, int K, bool PARAM_BF16, int VAL = 0, bool ADAM = false>
 __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void decompress_tiled(
