@@ -20,10 +20,23 @@ HIPCC_FLAGS = [
 
 # one translation unit per kernel family, compiled side by side
 # (the longest-compiling units first)
-UNITS = ["pair_compress_256.hip", "pair_compress_192.hip", "tiled_topk_s96.hip", "pair_decompress.hip", "tiled_topk_s128_k16.hip", "tiled_topk_s128_k4.hip", "tiled_topk_s128_k8.hip",
-         "tiled_topk_s128_k1.hip", "tiled_topk_s128_k32.hip", "tiled_topk_s128_k64.hip", "mfma_compress.hip",
-         "mfma_decompress.hip",
-         "tiled_topk_packed.hip", "tiled_topk_packed_s32.hip", "tiled_topk_ternary.hip", "tiled_adamw.hip", "tiled_adamw_narrow.hip", "tiled_scheme.hip", "tiled_scheme_small.hip", "tiled_scheme_narrow_s32.hip", "tiled_scheme_narrow_s64.hip", "tiled_topk_s64.hip", "tiled_topk_s32.hip", "tiled_topk_s16.hip", "detonation.hip"]
+UNITS = [
+    # two lanes per chunk (chunk 192, 256)
+    "pair_compress_256.hip", "pair_compress_192.hip", "pair_decompress.hip",
+    # lane per chunk, top-k with fp32 values and int32 indices, by chunk size
+    "tiled_topk_s96.hip", "tiled_topk_s128_k16.hip", "tiled_topk_s128_k4.hip",
+    "tiled_topk_s128_k8.hip", "tiled_topk_s128_k1.hip", "tiled_topk_s128_k32.hip",
+    "tiled_topk_s128_k64.hip",
+    # matrix-core kernels (every other multiple of 32)
+    "mfma_compress.hip", "mfma_decompress.hip",
+    # lane per chunk: narrow payloads, Decoupled AdamW, Striding / Random
+    "tiled_topk_packed.hip", "tiled_topk_packed_s32.hip", "tiled_topk_ternary.hip",
+    "tiled_adamw.hip", "tiled_adamw_narrow.hip", "tiled_scheme.hip", "tiled_scheme_small.hip",
+    "tiled_scheme_narrow_s32.hip", "tiled_scheme_narrow_s64.hip",
+    "tiled_topk_s64.hip", "tiled_topk_s32.hip", "tiled_topk_s16.hip",
+    # validation, dispatch, general kernels
+    "detonation.hip",
+]
 
 
 def _run(cmd: list[str], verbose: bool) -> None:
