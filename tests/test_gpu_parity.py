@@ -128,7 +128,7 @@ def test_striding_and_random_other_shapes(H, scheme, s, k):
 @pytest.mark.parametrize("scheme", [SCHEME_STRIDE, SCHEME_RANDOM])
 @pytest.mark.parametrize("dct", [False, True])
 @pytest.mark.parametrize("s,k", [(64, 16), (64, 8), (32, 16), (32, 8), (32, 4), (32, 2), (32, 1),
-                                 (64, 4), (64, 2), (16, 2)])
+                                 (64, 4), (64, 2), (64, 1), (16, 2), (16, 1)])
 def test_striding_and_random_low_rates(H, scheme, dct, s, k):
     # the rates of the paper's experiments (chunk 32, k from 16 down to 1): lane-per-chunk kernels
     cfg = Config(chunk=s, topk=k, scheme=scheme, dct=dct, seed=77, step=s + k, sign=True)
