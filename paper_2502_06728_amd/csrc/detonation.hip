@@ -190,6 +190,27 @@ int detonation_compress_packed(const deto_config* cfg, int64_t n, const void* gr
             }
         }
     }
+    // Striding in the raw domain at a shape without a lane-per-chunk kernel: it does not look
+    // at the values, so a plain streaming kernel serves any chunk size and k
+    if (c0 == 0 && p.scheme == DETO_SCHEME_STRIDE && !p.use_dct && val_dtype == DETO_F32 &&
+        idx_dtype == DETO_IDX_I32) {
+        const int stride = p.s / p.k;
+        const int off = static_cast<int>(p.step % static_cast<uint64_t>(stride));
+        const int64_t padded = C * p.s;
+        const int64_t wgs = (padded + deto::kStrideSpan - 1) / deto::kStrideSpan;
+        if (wgs <= 0x7FFFFFFF) {
+            const unsigned grid = static_cast<unsigned>(wgs);
+            if (grad_dtype == DETO_BF16)
+                deto::compress_stride_kernel<true><<<grid, 256, 0, st>>>(
+                    p, n, padded, stride, off, grad, momentum, static_cast<int32_t*>(idx_out),
+                    static_cast<float*>(val_out), coeff_dbg);
+            else
+                deto::compress_stride_kernel<false><<<grid, 256, 0, st>>>(
+                    p, n, padded, stride, off, grad, momentum, static_cast<int32_t*>(idx_out),
+                    static_cast<float*>(val_out), coeff_dbg);
+            return launched();
+        }
+    }
     if (c0 < C) {
         const unsigned grid = grid_for(C - c0);
         if (grad_dtype == DETO_BF16)
@@ -330,6 +351,23 @@ int decompress_impl(const deto_config* cfg, const deto_adamw* opt, int64_t n, in
                 rc = launched();
                 if (rc) return rc;
             }
+        }
+    }
+    // Striding in the raw domain without transmitted indices, any chunk size and k
+    if (c0 == 0 && !idx && p.scheme == DETO_SCHEME_STRIDE && !p.use_dct && val_dtype == DETO_F32) {
+        const int stride = p.s / p.k;
+        const int off = static_cast<int>(p.step % static_cast<uint64_t>(stride));
+        const int64_t wgs = (n + deto::kStrideSpan - 1) / deto::kStrideSpan;
+        if (wgs <= 0x7FFFFFFF) {
+            const unsigned grid = static_cast<unsigned>(wgs);
+            const float* v = static_cast<const float*>(val);
+            if (param_dtype == DETO_BF16)
+                deto::decompress_stride_kernel<true><<<grid, 256, 0, st>>>(
+                    p, n, stride, off, v, val_replica_stride, params, adam, presign_dbg);
+            else
+                deto::decompress_stride_kernel<false><<<grid, 256, 0, st>>>(
+                    p, n, stride, off, v, val_replica_stride, params, adam, presign_dbg);
+            return launched();
         }
     }
     if (c0 < C) {

@@ -512,4 +512,129 @@ __global__ __launch_bounds__(256) void decompress_dense_kernel(KParams p, int64_
     }
 }
 
+// ---- Striding in the raw domain at any chunk size and k (paper, "Replication Schemes": the
+// selection of every n'th index; it does not look at the values, so nothing per chunk needs
+// computing): plain streaming kernels, one workgroup of 256 lanes per kStrideSpan consecutive
+// elements, every access a coalesced lane access of one element (no alignment beyond the
+// element size is needed).  Position r of chunk c is kept when r = o + j*stride for some
+// j < k and then becomes entry j of the chunk.  The shapes the lane-per-chunk kernels serve
+// run there.
+constexpr int kStrideSpan = 2048;
+
+struct StridePos {
+    int64_t chunk;
+    int r;        // position in the chunk
+    int j;        // entry number if kept
+    bool kept;
+};
+
+__device__ __forceinline__ StridePos stride_position(const KParams& p, int stride, int off,
+                                                     int64_t c_base, int r_base, int local) {
+    // r_base + local < s + kStrideSpan: a small 32-bit division
+    const unsigned t = static_cast<unsigned>(r_base + local);
+    const unsigned dc = t / static_cast<unsigned>(p.s);
+    StridePos q;
+    q.chunk = c_base + dc;
+    q.r = static_cast<int>(t - dc * static_cast<unsigned>(p.s));
+    const int d = q.r - off;
+    q.j = d >= 0 ? d / stride : 0;
+    q.kept = d >= 0 && q.j * stride == d && q.j < p.k;
+    return q;
+}
+
+template <bool GRAD_BF16>
+__global__ __launch_bounds__(256) void compress_stride_kernel(
+    KParams p, int64_t n, int64_t padded, int stride, int off, const void* __restrict__ grad,
+    float* __restrict__ mom, int32_t* __restrict__ idx_out, float* __restrict__ val_out,
+    float* __restrict__ coeff_dbg) {
+    constexpr int kIt = kStrideSpan / 256;
+    const int64_t base = static_cast<int64_t>(blockIdx.x) * kStrideSpan;
+    const int64_t c_base = base / p.s;
+    const int r_base = static_cast<int>(base - c_base * p.s);
+    // all loads of the workgroup's span first
+    float g[kIt], m[kIt];
+#pragma unroll
+    for (int q = 0; q < kIt; ++q) {
+        const int64_t i = base + threadIdx.x + 256 * q;
+        g[q] = 0.0f;
+        m[q] = 0.0f;
+        if (i < n) {
+            g[q] = GRAD_BF16 ? bf16_to_f32(static_cast<const uint16_t*>(grad)[i])
+                             : static_cast<const float*>(grad)[i];
+            m[q] = mom[i];
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < kIt; ++q) {
+        const int local = threadIdx.x + 256 * q;
+        const int64_t i = base + local;
+        if (i < padded) {       // positions n <= i < padded: the zero-extension of the last chunk
+            const float v = i < n ? fmaf(p.beta, m[q], g[q]) : 0.0f;
+            const StridePos at = stride_position(p, stride, off, c_base, r_base, local);
+            if (at.kept) {
+                const int64_t e = at.chunk * p.k + at.j;
+                val_out[e] = v;
+                if (idx_out) idx_out[e] = at.r;
+            }
+            if (i < n) mom[i] = at.kept ? 0.0f : v;
+            if (coeff_dbg) coeff_dbg[i] = v;
+        }
+    }
+}
+
+template <bool PARAM_BF16>
+__global__ __launch_bounds__(256) void decompress_stride_kernel(
+    KParams p, int64_t n, int stride, int off, const float* __restrict__ val, int64_t val_stride,
+    void* __restrict__ params, AdamPtrs ad, float* __restrict__ presign_dbg) {
+    constexpr int kIt = kStrideSpan / 256;
+    const int64_t base = static_cast<int64_t>(blockIdx.x) * kStrideSpan;
+    const int64_t c_base = base / p.s;
+    const int r_base = static_cast<int>(base - c_base * p.s);
+    // the parameters and, replica after replica, the kept positions' values of the whole span
+    // are requested side by side (the eight elements of a lane are independent)
+    float old[kIt], a[kIt];
+    int64_t entry[kIt];          // the position's payload entry, -1 if it is not kept
+#pragma unroll
+    for (int q = 0; q < kIt; ++q) {
+        const int local = threadIdx.x + 256 * q;
+        const int64_t i = base + local;
+        old[q] = 0.0f;
+        a[q] = 0.0f;
+        entry[q] = -1;
+        if (i < n) {
+            old[q] = PARAM_BF16 ? bf16_to_f32(static_cast<const uint16_t*>(params)[i])
+                                : static_cast<const float*>(params)[i];
+            const StridePos at = stride_position(p, stride, off, c_base, r_base, local);
+            if (at.kept) entry[q] = at.chunk * p.k + at.j;
+        }
+    }
+    for (int r = 0; r < p.R; ++r) {           // replica after replica: a fixed order
+        const float* v = val + r * val_stride;
+#pragma unroll
+        for (int q = 0; q < kIt; ++q)
+            if (entry[q] >= 0) a[q] += v[entry[q]];
+    }
+#pragma unroll
+    for (int q = 0; q < kIt; ++q) {
+        const int64_t i = base + threadIdx.x + 256 * q;
+        if (i < n) {
+            const float y = entry[q] >= 0 ? a[q] * p.inv_R : 0.0f;
+            if (presign_dbg) presign_dbg[i] = y;
+            const float qv = sign_or_self(y, p.use_sign);
+            float nw;
+            if (p.adam) {
+                float m1 = ad.m[i], v1 = ad.v[i], x1 = p.amsgrad ? ad.vmax[i] : 0.0f;
+                nw = adamw_step(p, old[q], qv, m1, v1, x1);
+                ad.m[i] = m1;
+                ad.v[i] = v1;
+                if (p.amsgrad) ad.vmax[i] = x1;
+            } else {
+                nw = fmaf(-p.lr, qv, old[q] * p.wd_scale);
+            }
+            if constexpr (PARAM_BF16) static_cast<uint16_t*>(params)[i] = f32_to_bf16(nw);
+            else static_cast<float*>(params)[i] = nw;
+        }
+    }
+}
+
 }  // namespace deto

@@ -136,6 +136,25 @@ def test_striding_and_random_low_rates(H, scheme, dct, s, k):
               params_bf16=(k % 2 == 0))
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("step", [0, 5, 2**40 + 3])
+@pytest.mark.parametrize("s,k", [(128, 16), (256, 32), (256, 1), (96, 12), (48, 6), (100, 7), (64, 3),
+                                 (200, 100), (7, 2), (1, 1), (192, 191)])
+def test_striding_raw_domain_any_shape(H, s, k, step, bf16):
+    """Striding does not look at the values ("every n'th index"): at shapes without a
+    lane-per-chunk kernel a plain streaming kernel serves it.  Several workgroup spans, chunk
+    boundaries inside a lane's span, k that does not divide s, a ragged last chunk."""
+    cfg = Config(chunk=s, topk=k, scheme=SCHEME_STRIDE, seed=1, step=step, sign=(step != 5), lr=1e-3,
+                 weight_decay=0.01 if step == 5 else 0.0)
+    n = 2048 * 3 + 517 + s // 2
+    full_step(H, cfg, n, R=3, seed=s + k, grad_bf16=bf16, params_bf16=bf16,
+              outliers=0.01 if bf16 else 0.0)
+    # the indices, when the caller asks for them
+    g, m, _ = make_inputs(n, s + k, bf16, bf16, 0.01 if bf16 else 0.0)
+    _, idx_gpu, _, _ = H.gpu_compress(cfg, g, m, want_idx=True)
+    assert np.array_equal(idx_gpu, oracle.select(cfg, None, -(-n // s)))
+
+
 @pytest.mark.parametrize("n", [1, 5, 63, 64, 65, 64 * 64, 64 * 64 + 1, 64 * 129 - 1])
 def test_small_and_ragged_lengths(H, n):
     cfg = Config(chunk=64, topk=8)
