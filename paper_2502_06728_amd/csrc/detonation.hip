@@ -194,19 +194,18 @@ int detonation_compress_packed(const deto_config* cfg, int64_t n, const void* gr
     // at the values, so a plain streaming kernel serves any chunk size and k
     if (c0 == 0 && p.scheme == DETO_SCHEME_STRIDE && !p.use_dct && val_dtype == DETO_F32 &&
         idx_dtype == DETO_IDX_I32) {
-        const int stride = p.s / p.k;
-        const int off = static_cast<int>(p.step % static_cast<uint64_t>(stride));
+        const deto::StrideGeom sg = deto::stride_geom(p.s, p.k, p.step);
         const int64_t padded = C * p.s;
         const int64_t wgs = (padded + deto::kStrideSpan - 1) / deto::kStrideSpan;
         if (wgs <= 0x7FFFFFFF) {
             const unsigned grid = static_cast<unsigned>(wgs);
             if (grad_dtype == DETO_BF16)
                 deto::compress_stride_kernel<true><<<grid, 256, 0, st>>>(
-                    p, n, padded, stride, off, grad, momentum, static_cast<int32_t*>(idx_out),
+                    p, n, padded, sg, grad, momentum, static_cast<int32_t*>(idx_out),
                     static_cast<float*>(val_out), coeff_dbg);
             else
                 deto::compress_stride_kernel<false><<<grid, 256, 0, st>>>(
-                    p, n, padded, stride, off, grad, momentum, static_cast<int32_t*>(idx_out),
+                    p, n, padded, sg, grad, momentum, static_cast<int32_t*>(idx_out),
                     static_cast<float*>(val_out), coeff_dbg);
             return launched();
         }
@@ -355,18 +354,17 @@ int decompress_impl(const deto_config* cfg, const deto_adamw* opt, int64_t n, in
     }
     // Striding in the raw domain without transmitted indices, any chunk size and k
     if (c0 == 0 && !idx && p.scheme == DETO_SCHEME_STRIDE && !p.use_dct && val_dtype == DETO_F32) {
-        const int stride = p.s / p.k;
-        const int off = static_cast<int>(p.step % static_cast<uint64_t>(stride));
+        const deto::StrideGeom sg = deto::stride_geom(p.s, p.k, p.step);
         const int64_t wgs = (n + deto::kStrideSpan - 1) / deto::kStrideSpan;
         if (wgs <= 0x7FFFFFFF) {
             const unsigned grid = static_cast<unsigned>(wgs);
             const float* v = static_cast<const float*>(val);
             if (param_dtype == DETO_BF16)
                 deto::decompress_stride_kernel<true><<<grid, 256, 0, st>>>(
-                    p, n, stride, off, v, val_replica_stride, params, adam, presign_dbg);
+                    p, n, sg, v, val_replica_stride, params, adam, presign_dbg);
             else
                 deto::decompress_stride_kernel<false><<<grid, 256, 0, st>>>(
-                    p, n, stride, off, v, val_replica_stride, params, adam, presign_dbg);
+                    p, n, sg, v, val_replica_stride, params, adam, presign_dbg);
             return launched();
         }
     }

@@ -528,23 +528,42 @@ struct StridePos {
     bool kept;
 };
 
-__device__ __forceinline__ StridePos stride_position(const KParams& p, int stride, int off,
+// Divisions by the chunk size and by the stride as multiply-and-shift, exact for the small
+// numerators that occur: t < s + kStrideSpan <= 2304 with ceil(2^20/s) (the error term
+// t*(m*s - 2^20) stays below 2^20 for s <= 256), d < 256 with ceil(2^16/stride).
+struct StrideGeom {
+    int stride;
+    int off;
+    uint32_t chunk_magic;    // ceil(2^20 / s)
+    uint32_t stride_magic;   // ceil(2^16 / stride)
+};
+
+__host__ __device__ inline StrideGeom stride_geom(int s, int k, uint64_t step) {
+    StrideGeom g;
+    g.stride = s / k;
+    g.off = static_cast<int>(step % static_cast<uint64_t>(g.stride));
+    g.chunk_magic = ((1u << 20) + static_cast<uint32_t>(s) - 1u) / static_cast<uint32_t>(s);
+    g.stride_magic =
+        ((1u << 16) + static_cast<uint32_t>(g.stride) - 1u) / static_cast<uint32_t>(g.stride);
+    return g;
+}
+
+__device__ __forceinline__ StridePos stride_position(const KParams& p, const StrideGeom& sg,
                                                      int64_t c_base, int r_base, int local) {
-    // r_base + local < s + kStrideSpan: a small 32-bit division
-    const unsigned t = static_cast<unsigned>(r_base + local);
-    const unsigned dc = t / static_cast<unsigned>(p.s);
+    const uint32_t t = static_cast<uint32_t>(r_base + local);
+    const uint32_t dc = (t * sg.chunk_magic) >> 20;
     StridePos q;
     q.chunk = c_base + dc;
-    q.r = static_cast<int>(t - dc * static_cast<unsigned>(p.s));
-    const int d = q.r - off;
-    q.j = d >= 0 ? d / stride : 0;
-    q.kept = d >= 0 && q.j * stride == d && q.j < p.k;
+    q.r = static_cast<int>(t - dc * static_cast<uint32_t>(p.s));
+    const int d = q.r - sg.off;
+    q.j = d >= 0 ? static_cast<int>((static_cast<uint32_t>(d) * sg.stride_magic) >> 16) : 0;
+    q.kept = d >= 0 && q.j * sg.stride == d && q.j < p.k;
     return q;
 }
 
 template <bool GRAD_BF16>
 __global__ __launch_bounds__(256) void compress_stride_kernel(
-    KParams p, int64_t n, int64_t padded, int stride, int off, const void* __restrict__ grad,
+    KParams p, int64_t n, int64_t padded, StrideGeom sg, const void* __restrict__ grad,
     float* __restrict__ mom, int32_t* __restrict__ idx_out, float* __restrict__ val_out,
     float* __restrict__ coeff_dbg) {
     constexpr int kIt = kStrideSpan / 256;
@@ -570,7 +589,7 @@ __global__ __launch_bounds__(256) void compress_stride_kernel(
         const int64_t i = base + local;
         if (i < padded) {       // positions n <= i < padded: the zero-extension of the last chunk
             const float v = i < n ? fmaf(p.beta, m[q], g[q]) : 0.0f;
-            const StridePos at = stride_position(p, stride, off, c_base, r_base, local);
+            const StridePos at = stride_position(p, sg, c_base, r_base, local);
             if (at.kept) {
                 const int64_t e = at.chunk * p.k + at.j;
                 val_out[e] = v;
@@ -584,7 +603,7 @@ __global__ __launch_bounds__(256) void compress_stride_kernel(
 
 template <bool PARAM_BF16>
 __global__ __launch_bounds__(256) void decompress_stride_kernel(
-    KParams p, int64_t n, int stride, int off, const float* __restrict__ val, int64_t val_stride,
+    KParams p, int64_t n, StrideGeom sg, const float* __restrict__ val, int64_t val_stride,
     void* __restrict__ params, AdamPtrs ad, float* __restrict__ presign_dbg) {
     constexpr int kIt = kStrideSpan / 256;
     const int64_t base = static_cast<int64_t>(blockIdx.x) * kStrideSpan;
@@ -604,15 +623,19 @@ __global__ __launch_bounds__(256) void decompress_stride_kernel(
         if (i < n) {
             old[q] = PARAM_BF16 ? bf16_to_f32(static_cast<const uint16_t*>(params)[i])
                                 : static_cast<const float*>(params)[i];
-            const StridePos at = stride_position(p, stride, off, c_base, r_base, local);
+            const StridePos at = stride_position(p, sg, c_base, r_base, local);
             if (at.kept) entry[q] = at.chunk * p.k + at.j;
         }
     }
+    // unconditional loads (entry 0 stands in for positions that are not kept) so that the
+    // eight of a replica are requested together; a load under a branch is waited for there
     for (int r = 0; r < p.R; ++r) {           // replica after replica: a fixed order
         const float* v = val + r * val_stride;
+        float x[kIt];
 #pragma unroll
-        for (int q = 0; q < kIt; ++q)
-            if (entry[q] >= 0) a[q] += v[entry[q]];
+        for (int q = 0; q < kIt; ++q) x[q] = v[entry[q] >= 0 ? entry[q] : 0];
+#pragma unroll
+        for (int q = 0; q < kIt; ++q) a[q] += entry[q] >= 0 ? x[q] : 0.0f;
     }
 #pragma unroll
     for (int q = 0; q < kIt; ++q) {
