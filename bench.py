@@ -278,7 +278,7 @@ number for this kernel path):
   v1.6, 10K steps, 2 nodes x 4 NVIDIA A100 64 GB, InfiniBand 200 Gb/s ("OLMo2: Causal Language
   Modeling", Discussion).
 - Random replicator vs conventional Hybrid-FSDP + AdamW at 64 nodes x 4 GPUs, rate 1/32: about 64 %
-  faster; DeMo "substantially slower" there because of the all_gather ("OLMo2: Scaling Up").
+  faster; DeMo much slower there, which the paper puts down to the all_gather ("OLMo2: Scaling Up").
 - Average inter-node bandwidth, T5-small, 2 nodes x 4 RTX A6000, 10 GbE, rate 1/16: 1070 Mbps full
   replication, 291 Mbps DeMo, 152 Mbps Random ("Replicator bandwidth usage").
 - Time per optimizer step at 10 Mbps, ViT-B, 2 x 4 RTX A6000: Random about 3.33x faster than DeMo

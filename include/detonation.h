@@ -27,6 +27,18 @@
  *   - The return value is a deto_status.  Host-side arguments are validated; device
  *     data is not (an out-of-range payload index is skipped, not reported).
  *   - Buffers must not overlap each other.
+ *   - DETO_ERR_HIP reports the launches of this call only: a call that gets as far as
+ *     launching first resets the HIP runtime's sticky last-error state (hipGetLastError), so
+ *     an error left by an earlier, unrelated HIP call is neither reported here nor left behind.
+ *   - Alignment.  Every pointer must be aligned to its element size (else DETO_ERR_ALIGN).
+ *     The bandwidth kernels additionally need 16-byte aligned grad, momentum, params, optimizer
+ *     state and debug arrays, and payload arrays aligned to one lane's access: when k is a
+ *     multiple of 4, four consecutive entries (16 bytes of fp32 values or int32 indices,
+ *     8 bytes of 16-bit values, 4 bytes of byte indices; 8 bytes of two-bit signs when k > 16,
+ *     else 4), otherwise one element.  This holds for the base of idx / val and for every
+ *     replica offset r*stride, so the contiguous [R][C*k] buffer an all_gather returns always
+ *     qualifies for fp32 + int32 payloads.  Buffers that do not meet this are still processed
+ *     correctly, by general kernels that are more than ten times slower.
  */
 #ifndef DETONATION_H
 #define DETONATION_H
@@ -41,7 +53,8 @@ typedef enum {
     DETO_OK = 0,
     DETO_ERR_NULL = 1,         /* a required pointer is NULL */
     DETO_ERR_BAD_CONFIG = 2,   /* chunk/topk/scheme/dtype/R/n/stride out of range */
-    DETO_ERR_UNSUPPORTED = 3,  /* valid request this build has no kernel for */
+    DETO_ERR_UNSUPPORTED = 3,  /* meaningful request outside what this build covers: a
+                                  replication group of more than 64 replicas */
     DETO_ERR_ALIGN = 4,        /* a pointer is not aligned to its element size */
     DETO_ERR_HIP = 5           /* the HIP runtime refused the launch */
 } deto_status;
@@ -116,13 +129,17 @@ int detonation_compress(const deto_config* cfg, int64_t n,
  *   Q  = sign(y) if DETO_FLAG_SIGN else y
  *   params = round_to_dtype( params*(1 - eta*lambda) - eta*Q )   (in place)
  *
- *   R           number of replica payloads, 1..64
+ *   R           number of replica payloads, 1..64.  64 is the largest replication group the
+ *               paper runs (section "OLMo2: Scaling Up", 64 nodes) and the largest this
+ *               library is tested with; R > 64 returns DETO_ERR_UNSUPPORTED, R < 1
+ *               DETO_ERR_BAD_CONFIG.
  *   idx         device, replica r at idx + r*idx_replica_stride, each [C*k] int32 as an
  *               all_gather leaves them; NULL for STRIDE/RANDOM (indices regenerated from
  *               cfg, identical for every replica).  Duplicate indices add; indices
  *               outside [0,s) are skipped.
  *   val         device, replica r at val + r*val_replica_stride, each [C*k] fp32
- *   strides     in elements, >= C*k (ignored when R == 1)
+ *   strides     in elements, >= C*k (ignored when R == 1); see "Alignment" above for the
+ *               multiples that keep the bandwidth kernels in use
  *   params      device, [n] of param_dtype, updated in place (bf16: round to nearest even)
  *   presign_dbg device, [n] fp32 or NULL: receives y.  Parity checks only.
  *
@@ -147,8 +164,8 @@ int detonation_decompress_step(const deto_config* cfg, int64_t n, int32_t R,
  * detonation_decompress_step, which are these calls with DETO_IDX_I32 and DETO_F32; replica
  * strides are in elements of the respective dtype.
  *
- * DETO_TERNARY is the paper's "sign before synchronization" (Discussion; Appendix B "Sign vs.
- * No Sign"): only sign(c) in {-1, 0, +1} of each kept coefficient travels (sign(0) = 0).  Two
+ * DETO_TERNARY is the variant in which the sign is taken before the exchange (paper,
+ * Discussion; Appendix B "Sign vs. No Sign"): only sign(c) in {-1, 0, +1} of each kept coefficient travels (sign(0) = 0).  Two
  * bits per entry (0 = zero, 1 = +1, 3 = -1; 2 is never written and decodes to 0), 16 entries
  * per uint32 word, entry j of chunk ch in word ch*W + j/16 at bits [2*(j%16), 2*(j%16)+2),
  * W = ceil(k/16): every chunk starts on a word boundary and val_out / val hold
@@ -229,7 +246,7 @@ int detonation_decompress_adamw_step_packed(const deto_config* cfg, const deto_a
 /*
  * The first line of Algorithm 1 alone: momentum <- beta*momentum + grad, nothing extracted and
  * nothing sent.  For replicators that do not exchange on every step (paper, "Replication
- * Schemes": DiLoCo "denotes synchronization every n'th optimization step"): the steps in between
+ * Schemes": DiLoCo, which synchronises only on every n-th optimizer step): the steps in between
  * accumulate with this call; the synchronising step is detonation_compress with
  * DETO_SCHEME_STRIDE and topk = chunk (every position is taken, so the whole momentum is the
  * payload and restarts from zero) followed by detonation_decompress_step.

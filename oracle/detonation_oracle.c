@@ -455,8 +455,8 @@ int orc_presign_q(const orc_config *cfg, int64_t n, int32_t R, const int32_t *id
 }
 
 /* ------------------------------------------------- ternary payload (sign before sync)
- * Discussion ("using sign before synchronizing ... The ternary system enables compressing the
- * data even more") and Appendix B "Sign vs. No Sign": what travels is sign(c) in {-1, 0, +1}
+ * Discussion (the sign can be taken before the exchange, and a three-valued payload packs
+ * more tightly) and Appendix B "Sign vs. No Sign": what travels is sign(c) in {-1, 0, +1}
  * of each kept coefficient (sign(0) = 0, as torch.sign).  Two bits per entry: 0 = zero,
  * 1 = +1, 3 = -1 (2 is never written and decodes to 0); 16 entries per 32-bit word, entry j
  * of chunk c in word c*W + j/16 at bits [2*(j%16), 2*(j%16)+2), W = ceil(k/16), so every chunk

@@ -182,12 +182,70 @@ def _check(*tensors):
             raise ValueError("tensors must be contiguous device tensors")
 
 
+def _need(t, name: str, dtypes, numel: int, optional: bool = False) -> None:
+    """A wrong element type or a short buffer would become an out-of-bounds access on the
+    device: refuse it here, on the host."""
+    if t is None:
+        if optional:
+            return
+        raise ValueError(f"{name} is required")
+    if t.dtype not in dtypes:
+        raise ValueError(f"{name}: dtype {t.dtype}, expected one of {[str(d) for d in dtypes]}")
+    if t.numel() < numel:
+        raise ValueError(f"{name}: {t.numel()} elements, at least {numel} needed")
+
+
+def _n_chunks(cfg: Config, n: int) -> int:
+    return (n + cfg.chunk - 1) // cfg.chunk
+
+
+def _check_compress(cfg, n, grad, momentum, idx_out, val_out, coeff_dbg, packed: bool) -> None:
+    import torch
+    if n < 0:
+        raise ValueError("n must not be negative")
+    entries = _n_chunks(cfg, n) * cfg.topk
+    _need(grad, "grad", (torch.float32, torch.bfloat16), n)
+    _need(momentum, "momentum", (torch.float32,), n)
+    _need(coeff_dbg, "coeff_dbg", (torch.float32,), _n_chunks(cfg, n) * cfg.chunk, optional=True)
+    idx_types = (torch.int32, torch.uint8) if packed else (torch.int32,)
+    _need(idx_out, "idx_out", idx_types, entries, optional=cfg.scheme != SCHEME_TOPK)
+    if packed and val_out is not None and val_out.dtype == torch.int32:
+        _need(val_out, "val_out", (torch.int32,), _n_chunks(cfg, n) * ((cfg.topk + 15) // 16))
+    else:
+        val_types = ((torch.float32, torch.bfloat16, torch.float16) if packed
+                     else (torch.float32,))
+        _need(val_out, "val_out", val_types, entries)
+
+
+def _check_decompress(cfg, n, R, idx, istr, val, vs, params, presign_dbg, packed: bool,
+                      moments=()) -> None:
+    import torch
+    if n < 0 or R < 1:
+        raise ValueError("n must not be negative and R must be at least 1")
+    C = _n_chunks(cfg, n)
+    entries = C * cfg.topk
+    ternary = packed and val is not None and val.dtype == torch.int32
+    val_elems = C * ((cfg.topk + 15) // 16) if ternary else entries
+    if R > 1 and (vs < val_elems or (idx is not None and istr < entries)):
+        raise ValueError("a replica stride is shorter than one replica's payload")
+    idx_types = (torch.int32, torch.uint8) if packed else (torch.int32,)
+    _need(idx, "idx", idx_types, (R - 1) * istr + entries, optional=cfg.scheme != SCHEME_TOPK)
+    val_types = ((torch.float32, torch.bfloat16, torch.float16, torch.int32) if packed
+                 else (torch.float32,))
+    _need(val, "val", val_types, (R - 1) * vs + val_elems)
+    _need(params, "params", (torch.float32, torch.bfloat16), n)
+    _need(presign_dbg, "presign_dbg", (torch.float32,), n, optional=True)
+    for name, t, optional in moments:
+        _need(t, name, (torch.float32,), n, optional=optional)
+
+
 def detonation_compress(cfg: Config, grad, momentum, idx_out, val_out, coeff_dbg=None,
                         stream=None, n: int | None = None) -> None:
     """Enqueue the compress half on `stream`.  momentum, idx_out, val_out (and coeff_dbg)
     are written in place by the kernels."""
     _check(grad, momentum, idx_out, val_out, coeff_dbg)
     n = momentum.numel() if n is None else n
+    _check_compress(cfg, n, grad, momentum, idx_out, val_out, coeff_dbg, packed=False)
     rc = load().detonation_compress(ctypes.byref(cfg.c()), n, _ptr(grad), _dtype(grad),
                                     _ptr(momentum), _ptr(idx_out), _ptr(val_out),
                                     _ptr(coeff_dbg), _stream(stream))
@@ -206,6 +264,7 @@ def detonation_decompress_step(cfg: Config, R: int, idx, val, params, presign_db
     entries = payload_entries(cfg, n)
     vs = entries if val_replica_stride is None else val_replica_stride
     istr = entries if idx_replica_stride is None else idx_replica_stride
+    _check_decompress(cfg, n, R, idx, istr, val, vs, params, presign_dbg, packed=False)
     rc = load().detonation_decompress_step(ctypes.byref(cfg.c()), n, R, _ptr(idx), istr, _ptr(val),
                                            vs, _ptr(params), _dtype(params), _ptr(presign_dbg),
                                            _stream(stream))
@@ -216,8 +275,11 @@ def detonation_decompress_step(cfg: Config, R: int, idx, val, params, presign_db
 def detonation_accumulate(cfg: Config, grad, momentum, stream=None, n: int | None = None) -> None:
     """momentum <- beta*momentum + grad (Algorithm 1's first line alone; the steps of a DiLoCo
     cycle that do not synchronise)."""
+    import torch
     _check(grad, momentum)
     n = momentum.numel() if n is None else n
+    _need(grad, "grad", (torch.float32, torch.bfloat16), n)
+    _need(momentum, "momentum", (torch.float32,), n)
     rc = load().detonation_accumulate(ctypes.byref(cfg.c()), n, _ptr(grad), _dtype(grad),
                                       _ptr(momentum), _stream(stream))
     if rc != 0:
@@ -230,6 +292,7 @@ def detonation_compress_packed(cfg: Config, grad, momentum, idx_out, val_out, co
     int32 or uint8, values float32, bfloat16, float16, or int32 words of the ternary payload."""
     _check(grad, momentum, idx_out, val_out, coeff_dbg)
     n = momentum.numel() if n is None else n
+    _check_compress(cfg, n, grad, momentum, idx_out, val_out, coeff_dbg, packed=True)
     rc = load().detonation_compress_packed(ctypes.byref(cfg.c()), n, _ptr(grad), _dtype(grad),
                                            _ptr(momentum), _ptr(idx_out), _idx_dtype(idx_out),
                                            _ptr(val_out), _val_dtype(val_out), _ptr(coeff_dbg),
@@ -251,6 +314,7 @@ def detonation_decompress_step_packed(cfg: Config, R: int, idx, val, params, pre
     if vs is None:
         vs = ternary_words(cfg, n) if vdt == TERNARY else entries
     istr = entries if idx_replica_stride is None else idx_replica_stride
+    _check_decompress(cfg, n, R, idx, istr, val, vs, params, presign_dbg, packed=True)
     rc = load().detonation_decompress_step_packed(ctypes.byref(cfg.c()), n, R, _ptr(idx),
                                                   _idx_dtype(idx), istr, _ptr(val), vdt, vs,
                                                   _ptr(params), _dtype(params), _ptr(presign_dbg),
@@ -271,6 +335,9 @@ def detonation_decompress_adamw_step(cfg: Config, opt: AdamW, R: int, idx, val, 
     entries = payload_entries(cfg, n)
     vs = entries if val_replica_stride is None else val_replica_stride
     istr = entries if idx_replica_stride is None else idx_replica_stride
+    _check_decompress(cfg, n, R, idx, istr, val, vs, params, presign_dbg, packed=False,
+                      moments=(("exp_avg", exp_avg, False), ("exp_avg_sq", exp_avg_sq, False),
+                               ("max_exp_avg_sq", max_exp_avg_sq, not opt.amsgrad)))
     rc = load().detonation_decompress_adamw_step(ctypes.byref(cfg.c()), ctypes.byref(opt.c()), n, R,
                                                  _ptr(idx), istr, _ptr(val), vs, _ptr(params),
                                                  _dtype(params), _ptr(exp_avg), _ptr(exp_avg_sq),
@@ -294,6 +361,9 @@ def detonation_decompress_adamw_step_packed(cfg: Config, opt: AdamW, R: int, idx
     if vs is None:
         vs = ternary_words(cfg, n) if vdt == TERNARY else entries
     istr = entries if idx_replica_stride is None else idx_replica_stride
+    _check_decompress(cfg, n, R, idx, istr, val, vs, params, presign_dbg, packed=True,
+                      moments=(("exp_avg", exp_avg, False), ("exp_avg_sq", exp_avg_sq, False),
+                               ("max_exp_avg_sq", max_exp_avg_sq, not opt.amsgrad)))
     rc = load().detonation_decompress_adamw_step_packed(
         ctypes.byref(cfg.c()), ctypes.byref(opt.c()), n, R, _ptr(idx), _idx_dtype(idx), istr,
         _ptr(val), vdt, vs, _ptr(params), _dtype(params), _ptr(exp_avg), _ptr(exp_avg_sq),

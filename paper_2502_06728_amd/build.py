@@ -52,6 +52,25 @@ def _run(cmd: list[str], verbose: bool) -> None:
         print(err, file=sys.stderr)
 
 
+def _includes(path: str, seen: set[str]) -> set[str]:
+    """The unit and every header it includes from csrc/ or include/, transitively."""
+    if path in seen or not os.path.exists(path):
+        return seen
+    seen.add(path)
+    for line in open(path):
+        line = line.strip()
+        if line.startswith("#include \""):
+            _includes(os.path.normpath(os.path.join(os.path.dirname(path), line.split('"')[1])), seen)
+    return seen
+
+
+def _stale(unit: str, obj: str) -> bool:
+    if not os.path.exists(obj):
+        return True
+    t = os.path.getmtime(obj)
+    return any(os.path.getmtime(f) > t for f in _includes(unit, set()))
+
+
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     extra = os.environ.get("DETO_EXTRA_FLAGS", "").split()
@@ -61,7 +80,10 @@ def build(verbose: bool = False) -> str:
     objs = [os.path.join(obj_dir, u.replace(".hip", ".o")) for u in UNITS]
     jobs = [[hipcc, *HIPCC_FLAGS, *extra, "-c", "-o", o, os.path.join(CSRC, u)]
             for u, o in zip(UNITS, objs)]
-    with ThreadPoolExecutor(max_workers=min(len(jobs), 8)) as pool:
+    if os.environ.get("DETO_INCREMENTAL"):
+        # developer convenience: keep an object that is newer than everything its unit includes
+        jobs = [j for j, u, o in zip(jobs, UNITS, objs) if _stale(os.path.join(CSRC, u), o)]
+    with ThreadPoolExecutor(max_workers=max(1, min(len(jobs), 8))) as pool:
         list(pool.map(lambda c: _run(c, verbose), jobs))
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs], verbose)
     # the streaming micro-benchmark (HBM ceiling, counter calibration)

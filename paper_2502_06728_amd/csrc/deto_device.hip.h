@@ -9,6 +9,7 @@ namespace deto {
 
 constexpr int kWave = 64;        // CDNA wavefront width
 constexpr int kMaxChunk = 256;   // largest chunk size s the library accepts
+constexpr int kMaxReplicas = 64;  // largest replication group R the library accepts
 
 // Everything a kernel needs from deto_config, resolved on the host.
 struct KParams {

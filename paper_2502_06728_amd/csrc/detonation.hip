@@ -1,7 +1,10 @@
 // C ABI of the library (see include/detonation.h): argument validation, resolution of
-// deto_config into kernel parameters, kernel selection and launch.  Nothing here computes
-// on the host and nothing is allocated; every call only enqueues kernels on the caller's
-// stream.
+// deto_config into kernel parameters, kernel selection and launch.  Nothing is allocated and
+// no tensor data is touched on the host; every call only enqueues kernels on the caller's
+// stream.  What the host does compute are kernel parameters derived from deto_config: the
+// scale factors of the transform, the bias corrections of AdamW, and Striding's kept positions
+// (an integer pattern that is the same for every chunk: stride_pattern, stride_geom), which
+// the kernels take by value.
 #include "../../include/detonation.h"
 
 #include <hip/hip_runtime.h>
@@ -73,6 +76,10 @@ unsigned grid_for(int64_t chunks) {
     return static_cast<unsigned>(chunks < cap ? chunks : cap);
 }
 
+// Status of the launches of this call.  Every compute entry point calls fresh_status() before
+// its first launch, so an error left behind by an earlier, unrelated HIP call of the process is
+// not reported as this call's.
+void fresh_status() { (void)hipGetLastError(); }
 int launched() { return hipGetLastError() == hipSuccess ? DETO_OK : DETO_ERR_HIP; }
 
 // grid of a grid-stride streaming kernel (256 lanes per workgroup) over `items` lane-items:
@@ -84,6 +91,21 @@ unsigned stream_grid(int64_t items) {
 }
 
 bool aligned16(const void* p) { return aligned(p, 16); }
+
+// Width in bytes of one lane's access to a payload array in the lane-per-chunk, two-lane and
+// matrix-core kernels: four consecutive entries when k is a multiple of 4 (16 bytes of fp32 or
+// int32, 8 bytes of 16-bit values, 4 bytes of byte indices; a chunk's one or two words of two-bit
+// signs), a single element otherwise.  The array's base and every replica's offset from it
+// must be multiples of this for those kernels to be used.
+size_t idx_access(const KParams& p) {
+    if (p.k % 4 != 0) return p.idx_u8 ? 1 : 4;
+    return p.idx_u8 ? 4 : 16;
+}
+size_t val_access(const KParams& p) {
+    if (p.val_dtype == DETO_TERNARY) return p.k > 16 ? 8 : 4;
+    if (p.k % 4 != 0) return val_size(p.val_dtype);
+    return p.val_dtype == DETO_F32 ? 16 : 8;
+}
 
 // tiled kernels take one 64-chunk tile per workgroup
 constexpr int64_t kMaxTiles = 0x7FFFFFFF;
@@ -123,6 +145,7 @@ int detonation_compress_packed(const deto_config* cfg, int64_t n, const void* gr
     const KParams p = resolve(cfg, 1, val_dtype, idx_dtype);
     const int64_t C = chunks_of(n, p.s);
     hipStream_t st = static_cast<hipStream_t>(stream);
+    fresh_status();
 
     // every position kept in the raw domain: the payload is the folded momentum itself
     if (p.scheme != DETO_SCHEME_TOPK && !p.use_dct && p.k == p.s && val_dtype == DETO_F32 &&
@@ -151,8 +174,9 @@ int detonation_compress_packed(const deto_config* cfg, int64_t n, const void* gr
     // chunks on the general code), else the general kernel for everything
     int64_t c0 = 0;
     const int64_t tiles = (n / p.s) / deto::kWave;
-    if (tiles <= kMaxTiles && aligned16(grad) && aligned16(momentum) && aligned16(idx_out) &&
-        aligned16(val_out) && aligned16(coeff_dbg)) {
+    if (tiles <= kMaxTiles && aligned16(grad) && aligned16(momentum) &&
+        aligned(idx_out, idx_access(p)) && aligned(val_out, val_access(p)) &&
+        aligned16(coeff_dbg)) {
         deto::CompressLaunch a{p, tiles, n, C, grad, grad_dtype == DETO_BF16, momentum, idx_out,
                                val_out, coeff_dbg, {0, 0, 0, 0}, st};
         stride_pattern(p, a.stride_mask);
@@ -247,9 +271,11 @@ int decompress_impl(const deto_config* cfg, const deto_adamw* opt, int64_t n, in
             (opt->amsgrad != 0 && opt->amsgrad != 1))
             return DETO_ERR_BAD_CONFIG;
     }
-    if (n < 0 || !valid_dtype(param_dtype) || R < 1 || R > 64 || !valid_val_dtype(val_dtype) ||
+    if (n < 0 || !valid_dtype(param_dtype) || R < 1 || !valid_val_dtype(val_dtype) ||
         !valid_idx_dtype(idx_dtype))
         return DETO_ERR_BAD_CONFIG;
+    // the largest replication group of the paper (and of this library's tests)
+    if (R > deto::kMaxReplicas) return DETO_ERR_UNSUPPORTED;
     if (n == 0) return DETO_OK;
     if (!val || !params) return DETO_ERR_NULL;
     if (cfg->scheme == DETO_SCHEME_TOPK && !idx) return DETO_ERR_NULL;
@@ -282,6 +308,7 @@ int decompress_impl(const deto_config* cfg, const deto_adamw* opt, int64_t n, in
     if (R > 1 && (val_replica_stride < val_elems || (idx && idx_replica_stride < entries)))
         return DETO_ERR_BAD_CONFIG;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    fresh_status();
 
     // every position kept in the raw domain: the mean of R dense arrays drives the update
     if (!idx && !opt && !p.use_dct && p.k == p.s && val_dtype == DETO_F32) {
@@ -305,14 +332,17 @@ int decompress_impl(const deto_config* cfg, const deto_adamw* opt, int64_t n, in
 
     int64_t c0 = 0;
     const int64_t tiles = (n / p.s) / deto::kWave;
-    // the tiled kernels read 16 bytes (or 4 entries) per lane: every replica's base must keep
-    // the alignment of the first
-    const bool strides_ok =
-        R == 1 || ((!idx || (idx_replica_stride * static_cast<int64_t>(idx_size(idx_dtype))) % 16 == 0) &&
-                   (val_replica_stride * static_cast<int64_t>(val_size(val_dtype))) % 16 == 0);
-    if (tiles <= kMaxTiles && aligned16(idx) && aligned16(val) && aligned16(params) &&
-        aligned16(presign_dbg) && aligned16(adam.m) && aligned16(adam.v) && aligned16(adam.vmax) &&
-        strides_ok) {
+    // every replica's array must keep the alignment of a lane's access (four entries when k is
+    // a multiple of 4, one element otherwise: the contiguous [R][C*k] layout of an all_gather
+    // always qualifies)
+    const int64_t ia = static_cast<int64_t>(idx_access(p)), va = static_cast<int64_t>(val_access(p));
+    const bool payload_ok =
+        aligned(idx, idx_access(p)) && aligned(val, val_access(p)) &&
+        (R == 1 ||
+         ((!idx || (idx_replica_stride * static_cast<int64_t>(idx_size(idx_dtype))) % ia == 0) &&
+          (val_replica_stride * static_cast<int64_t>(val_size(val_dtype))) % va == 0));
+    if (tiles <= kMaxTiles && payload_ok && aligned16(params) && aligned16(presign_dbg) &&
+        aligned16(adam.m) && aligned16(adam.v) && aligned16(adam.vmax)) {
         deto::DecompressLaunch a{p, tiles, n, C, idx, idx_replica_stride, val,
                                  val_replica_stride, params, param_dtype == DETO_BF16, presign_dbg,
                                  {0, 0, 0, 0}, st, adam};
@@ -439,6 +469,7 @@ int detonation_accumulate(const deto_config* cfg, int64_t n, const void* grad, i
     if (!grad || !momentum) return DETO_ERR_NULL;
     if (!aligned(grad, elem_size(grad_dtype)) || !aligned(momentum, 4)) return DETO_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    fresh_status();
     const bool vec = aligned16(grad) && aligned16(momentum);
     const unsigned grid = stream_grid(n / 8);
     const bool bf16 = grad_dtype == DETO_BF16;
@@ -468,7 +499,7 @@ const char* detonation_status_string(int status) {
         case DETO_OK: return "ok";
         case DETO_ERR_NULL: return "a required pointer is NULL";
         case DETO_ERR_BAD_CONFIG: return "bad configuration or size";
-        case DETO_ERR_UNSUPPORTED: return "unsupported request";
+        case DETO_ERR_UNSUPPORTED: return "unsupported request (more than 64 replicas)";
         case DETO_ERR_ALIGN: return "misaligned pointer";
         case DETO_ERR_HIP: return "HIP launch failed";
         default: return "unknown status";

@@ -513,7 +513,7 @@ __global__ __launch_bounds__(256) void decompress_dense_kernel(KParams p, int64_
 }
 
 // ---- Striding in the raw domain at any chunk size and k (paper, "Replication Schemes": the
-// selection of every n'th index; it does not look at the values, so nothing per chunk needs
+// selection of every n-th position; it does not look at the values, so nothing per chunk needs
 // computing): plain streaming kernels, one workgroup of 256 lanes per kStrideSpan consecutive
 // elements, every access a coalesced lane access of one element (no alignment beyond the
 // element size is needed).  Position r of chunk c is kept when r = o + j*stride for some

@@ -73,7 +73,7 @@ def test_host_side_validation(lib):
     d = lib.detonation_decompress_step
     c = ctypes.byref(ok.c())
     assert d(c, 10, 0, vp(1024), 8, vp(1024), 8, vp(1024), 0, None, None) == 2   # R < 1
-    assert d(c, 10, 65, vp(1024), 8, vp(1024), 8, vp(1024), 0, None, None) == 2  # R too large
+    assert d(c, 10, 65, vp(1024), 8, vp(1024), 8, vp(1024), 0, None, None) == 3  # R > 64: unsupported
     assert d(c, 10, 2, vp(1024), 4, vp(1024), 8, vp(1024), 0, None, None) == 2   # stride < C*k
     assert d(c, 10, 1, None, 8, vp(1024), 8, vp(1024), 0, None, None) == 1       # top-k needs idx
     assert d(c, 10, 1, vp(1024), 8, vp(1024), 8, vp(1025), 1, None, None) == 4   # bf16 off by 1
@@ -86,6 +86,54 @@ def test_binding_refuses_host_tensors(lib):
     t = torch.zeros(64)
     with pytest.raises(ValueError):
         binding.detonation_compress(cfg, t, t, t.int(), t)
+
+
+def test_binding_refuses_wrong_dtypes_and_short_buffers():
+    """A wrong element type or a buffer shorter than the call needs would be an out-of-bounds
+    access on the device; the binding's host-side checks turn it into a ValueError."""
+    import torch
+    cfg = binding.Config(chunk=64, topk=8)
+    n = 64 * 10 + 3                       # 11 chunks, 88 entries
+    f32 = lambda m: torch.zeros(m)
+    i32 = lambda m: torch.zeros(m, dtype=torch.int32)
+    ok = dict(grad=f32(n), momentum=f32(n), idx_out=i32(88), val_out=f32(88), coeff_dbg=f32(704))
+    binding._check_compress(cfg, n, packed=False, **ok)
+    for name, bad in [("grad", f32(n - 1)), ("grad", torch.zeros(n, dtype=torch.float16)),
+                      ("momentum", torch.zeros(n, dtype=torch.bfloat16)),
+                      ("idx_out", i32(87)), ("idx_out", torch.zeros(88, dtype=torch.int64)),
+                      ("idx_out", None), ("val_out", f32(87)),
+                      ("val_out", torch.zeros(88, dtype=torch.bfloat16)),
+                      ("coeff_dbg", f32(703))]:
+        with pytest.raises(ValueError):
+            binding._check_compress(cfg, n, packed=False, **{**ok, name: bad})
+    # narrow formats are for the *_packed calls only; ternary words: ceil(k/16) per chunk
+    binding._check_compress(cfg, n, packed=True, **{**ok, "idx_out": torch.zeros(88, dtype=torch.uint8),
+                                                    "val_out": torch.zeros(88, dtype=torch.float16)})
+    binding._check_compress(cfg, n, packed=True, **{**ok, "val_out": i32(11)})
+    with pytest.raises(ValueError):
+        binding._check_compress(cfg, n, packed=True, **{**ok, "val_out": i32(10)})
+    # Striding / Random need no index array
+    binding._check_compress(binding.Config(chunk=64, topk=8, scheme=binding.SCHEME_RANDOM), n,
+                            packed=False, **{**ok, "idx_out": None})
+    # decompress: R replicas at the given strides
+    R, stride = 3, 96
+    okd = dict(idx=i32(2 * stride + 88), val=f32(2 * stride + 88), params=f32(n), presign_dbg=f32(n))
+    binding._check_decompress(cfg, n, R, okd["idx"], stride, okd["val"], stride, okd["params"],
+                              okd["presign_dbg"], packed=False)
+    with pytest.raises(ValueError):       # last replica's entries would run past the buffer
+        binding._check_decompress(cfg, n, R, okd["idx"], stride, f32(2 * stride + 87), stride,
+                                  okd["params"], okd["presign_dbg"], packed=False)
+    with pytest.raises(ValueError):       # stride shorter than a replica's payload
+        binding._check_decompress(cfg, n, R, okd["idx"], 80, okd["val"], stride, okd["params"],
+                                  okd["presign_dbg"], packed=False)
+    with pytest.raises(ValueError):
+        binding._check_decompress(cfg, n, R, okd["idx"], stride, okd["val"], stride, f32(n - 1),
+                                  None, packed=False)
+    with pytest.raises(ValueError):       # AdamW moments must be fp32 and cover the shard
+        binding._check_decompress(cfg, n, R, okd["idx"], stride, okd["val"], stride, okd["params"],
+                                  None, packed=False,
+                                  moments=(("exp_avg", f32(n), False),
+                                           ("exp_avg_sq", f32(n - 1), False)))
 
 
 def test_packed_entry_points_validate_formats(lib):

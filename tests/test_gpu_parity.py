@@ -141,7 +141,7 @@ def test_striding_and_random_low_rates(H, scheme, dct, s, k):
 @pytest.mark.parametrize("s,k", [(128, 16), (256, 32), (256, 1), (96, 12), (48, 6), (100, 7), (64, 3),
                                  (200, 100), (7, 2), (1, 1), (192, 191)])
 def test_striding_raw_domain_any_shape(H, s, k, step, bf16):
-    """Striding does not look at the values ("every n'th index"): at shapes without a
+    """Striding keeps every n-th position whatever the values are: at shapes without a
     lane-per-chunk kernel a plain streaming kernel serves it.  Several workgroup spans, chunk
     boundaries inside a lane's span, k that does not divide s, a ragged last chunk."""
     cfg = Config(chunk=s, topk=k, scheme=SCHEME_STRIDE, seed=1, step=step, sign=(step != 5), lr=1e-3,
@@ -265,11 +265,16 @@ def test_t5_base_shard_full_size(H):
     assert st_c["chunks"] == 435_357
 
 
-def test_vit_b16_shard_full_size(H):
+@pytest.mark.parametrize("sign", [True, False])
+@pytest.mark.parametrize("s,k", [(s, k) for s in (32, 64, 128) for k in (1, 4, 16, s // 2)])
+def test_vit_b16_shard_full_size(H, s, k, sign):
+    # every point of the ViT-B/16 sweep (chunk x top-k x sign, R = 2) on the whole 10.8 M-parameter
+    # shard, whose length is not a multiple of any of the chunk sizes
     w = synth.workloads()["vit-b16-1of8"]
     assert w.n == 10_820_957 and w.n % 32 == 29
-    for s, k in [(32, 16), (128, 4)]:
-        full_step(H, Config(chunk=s, topk=k), w.n, R=2, seed=1)
+    st_c, st_d = full_step(H, Config(chunk=s, topk=k, sign=sign, decay=w.decay, lr=w.lr), w.n,
+                           R=2, seed=1)
+    assert st_c["chunks"] == -(-w.n // s)
 
 
 def _sample_runs(C, run=256, count=24, seed=5):
@@ -280,13 +285,29 @@ def _sample_runs(C, run=256, count=24, seed=5):
     return sorted({(s0, min(s0 + run, C)) for s0 in starts})
 
 
-def _full_size_check(H, w, cfg, runs_count=24):
+def _slabs(C, slab=65536):
+    """Every chunk of the shard, in consecutive slabs that bound the oracle's host memory."""
+    return [(c0, min(c0 + slab, C)) for c0 in range(0, C, slab)]
+
+
+def _payload_indices(cfg, idx, R, c0, c1):
+    """The index arrays the oracle is given for chunks [c0, c1): the transmitted ones, or, for
+    Striding / Random, the oracle's own selection keyed by the chunks' global numbers (the same
+    for every replica, since all replicas regenerate them from the shared seed and step)."""
+    k = cfg.topk
+    if idx is not None:
+        return idx[:, c0 * k:c1 * k]
+    own = oracle.select(cfg, None, c1 - c0, chunk0=c0)
+    return np.tile(own, (R, 1))
+
+
+def _full_size_check(H, w, cfg, ranges=None):
     """Parity at a benchmark configuration's full size, in the launch configuration bench.py
-    times (debug outputs off), judged on sampled chunk runs the oracle computes one by one."""
-    import torch
-    from paper_2502_06728_amd import binding
+    times (debug outputs off).  `ranges` = chunk ranges handed to the oracle; by default every
+    chunk of the shard, slab by slab, element by element."""
     s, k, R, n = cfg.chunk, cfg.topk, w.replicas, w.n
     C = -(-n // s)
+    ranges = _slabs(C) if ranges is None else ranges
     g, m, th = synth.shard(w)
     send_idx = cfg.scheme == SCHEME_TOPK
     # the timed configuration: no debug outputs
@@ -299,8 +320,9 @@ def _full_size_check(H, w, cfg, runs_count=24):
         assert np.array_equal(idx_a, idx_b)
         assert idx_a.min() >= 0 and idx_a.max() < s
         assert (np.diff(idx_a.reshape(C, k), axis=1) > 0).all()        # holds at any size
-    worst = {"coeff": 0.0, "momentum": 0.0, "flips": 0}
-    for c0, c1 in _sample_runs(C, count=runs_count):
+    del m_b, val_b, idx_b
+    worst = {"coeff": 0.0, "momentum": 0.0, "flips": 0, "chunks": 0}
+    for c0, c1 in ranges:
         e0, e1 = c0 * s, min(c1 * s, n)
         st = parity.check_compress(cfg, g[e0:e1], m[e0:e1], m_a[e0:e1],
                                    idx_a[c0 * k:c1 * k] if send_idx else None,
@@ -308,23 +330,27 @@ def _full_size_check(H, w, cfg, runs_count=24):
         worst["coeff"] = max(worst["coeff"], st["coeff"])
         worst["momentum"] = max(worst["momentum"], st["momentum"])
         worst["flips"] += st["flips"]
-    del m_a, m_b, val_b, idx_b, coeff
+        worst["chunks"] += st["chunks"]
+    del m_a, coeff, g, m
     # decompress: R structurally valid payloads from the generator (not from either compress)
-    idx = np.empty((R, C * k), np.int32)
+    idx = np.empty((R, C * k), np.int32) if send_idx else None
     val = np.empty((R, C * k), np.float32)
     for r in range(R):
-        idx[r], val[r] = synth.structured_payload(w.seed + 10 + r, C, s, k, w.momentum_std)
-    th_a, _ = H.gpu_decompress(cfg, idx if send_idx else None, val, th, want_presign=False)
-    th_b, y = H.gpu_decompress(cfg, idx if send_idx else None, val, th, want_presign=True)
+        i_r, val[r] = synth.structured_payload(w.seed + 10 + r, C, s, k, w.momentum_std)
+        if send_idx:
+            idx[r] = i_r
+    th_a, _ = H.gpu_decompress(cfg, idx, val, th, want_presign=False)
+    th_b, y = H.gpu_decompress(cfg, idx, val, th, want_presign=True)
     assert np.array_equal(th_a, th_b)
+    del th_b
     worst["presign"] = 0.0
-    for c0, c1 in _sample_runs(C, count=runs_count, seed=6):
+    worst["sign_flips"] = 0
+    for c0, c1 in ranges:
         e0, e1 = c0 * s, min(c1 * s, n)
-        if not send_idx:
-            continue   # regenerated indices are keyed by the global chunk number: covered at small n
-        st = parity.check_decompress(cfg, idx[:, c0 * k:c1 * k], val[:, c0 * k:c1 * k], th[e0:e1],
-                                     th_a[e0:e1], y[e0:e1])
+        st = parity.check_decompress(cfg, _payload_indices(cfg, idx, R, c0, c1),
+                                     val[:, c0 * k:c1 * k], th[e0:e1], th_a[e0:e1], y[e0:e1])
         worst["presign"] = max(worst["presign"], st["presign"])
+        worst["sign_flips"] += st["sign_flips_vs_oracle"]
     return worst
 
 
@@ -336,6 +362,20 @@ def test_olmo_1b_shard_full_size_bench_configuration(H):
     cfg = Config(chunk=w.chunk, topk=w.topk, decay=w.decay, lr=w.lr, sign=w.sign)
     worst = _full_size_check(H, w, cfg)
     print("olmo-1b full size:", worst)
+    assert worst["chunks"] == 2_298_368      # every chunk of the shard went through the oracle
+
+
+@pytest.mark.parametrize("scheme,dct", [(SCHEME_STRIDE, False), (SCHEME_RANDOM, False),
+                                        (SCHEME_STRIDE, True)])
+def test_olmo_1b_shard_full_size_striding_random(H, scheme, dct):
+    # the same shard under the index-free schemes, every chunk: Random's positions are keyed by
+    # the chunk's global number, so only a full-size run shows the kernel's chunk numbering
+    w = synth.workloads()["olmo-1b-1of8"]
+    cfg = Config(chunk=w.chunk, topk=w.topk, scheme=scheme, dct=dct, seed=99, step=5,
+                 decay=w.decay, lr=w.lr, sign=w.sign)
+    worst = _full_size_check(H, w, cfg)
+    print("olmo-1b full size, scheme", scheme, "dct", dct, worst)
+    assert worst["chunks"] == 2_298_368
 
 
 @pytest.mark.timeout(900)
@@ -384,13 +424,15 @@ def test_olmo_7b_shard_full_size(H, scheme, dct):
     y = torch.empty(n, dtype=torch.float32, device=dev)
     binding.detonation_decompress_step(H.bcfg(cfg), R, pi, pv, th, y)
     torch.cuda.synchronize()
-    if send_idx:    # regenerated indices are keyed by the global chunk number: covered at small n
-        for c0, c1 in _sample_runs(C, count=10, seed=8):
-            e0, e1 = c0 * s, c1 * s
-            parity.check_decompress(cfg, H.to_host(pi[:, c0 * k:c1 * k].contiguous()),
-                                    H.to_host(pv[:, c0 * k:c1 * k].contiguous()),
-                                    H.to_host(th0[e0:e1]), H.to_host(th[e0:e1]),
-                                    H.to_host(y[e0:e1]))
+    # Striding / Random transmit no indices: the oracle is handed its own selection for the
+    # sampled chunks' global numbers, the same for every replica
+    for c0, c1 in _sample_runs(C, count=10, seed=8):
+        e0, e1 = c0 * s, c1 * s
+        i_run = (H.to_host(pi[:, c0 * k:c1 * k].contiguous()) if send_idx
+                 else _payload_indices(cfg, None, R, c0, c1))
+        parity.check_decompress(cfg, i_run, H.to_host(pv[:, c0 * k:c1 * k].contiguous()),
+                                H.to_host(th0[e0:e1]), H.to_host(th[e0:e1]),
+                                H.to_host(y[e0:e1]))
 
 
 @pytest.mark.parametrize("scheme", [SCHEME_TOPK, SCHEME_STRIDE, SCHEME_RANDOM])
@@ -658,7 +700,7 @@ def test_byte_indices_with_fp32_values(H):
                                    (32, 16, 32 * 335 + 5), (32, 8, 32 * 335 + 5), (32, 4, 32 * 335 + 5),
                                    (32, 2, 32 * 335 + 5), (32, 1, 32 * 335 + 5)])
 def test_ternary_payload(H, idx_u8, s, k, n):
-    """The paper's "sign before synchronization": only sign(c) of the kept coefficients travels,
+    """The sign taken before the exchange (Discussion): only sign(c) of the kept coefficients travels,
     two bits per entry; the momentum loses the extracted components themselves."""
     cfg = Config(chunk=s, topk=k, sign=True, decay=0.999, lr=1e-3)
     g, m, th = make_inputs(n, seed=s + k, grad_bf16=True, params_bf16=True, outliers=0.01)
@@ -730,8 +772,8 @@ def test_ternary_payload_striding_random(H, scheme):
 
 @pytest.mark.parametrize("bf16", [False, True])
 def test_diloco_cycle_accumulate_then_full_synchronisation(H, bf16):
-    """DiLoCo as a replicator ("synchronization every n'th optimization step"): the steps in
-    between only accumulate (detonation_accumulate), the n'th extracts the whole momentum
+    """DiLoCo as a replicator (synchronises only on every n-th optimizer step): the steps in
+    between only accumulate (detonation_accumulate), the n-th extracts the whole momentum
     (Striding with k = s) and averages it over the replicas.  Raw domain: momentum, payload
     and averaged update equal the oracle's bit for bit."""
     import torch

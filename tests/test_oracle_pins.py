@@ -221,6 +221,68 @@ def test_random_indices_valid_reproducible_and_uniform():
     assert abs(both - k * (k - 1) / (s * (s - 1))) < 0.01
 
 
+@pytest.mark.parametrize("s,k", [(2, 1), (3, 1), (3, 2), (4, 2), (5, 2), (5, 3), (6, 3), (7, 2)])
+def test_random_every_subset_equally_often_at_tiny_shapes(s, k):
+    """The first k places of a uniform shuffle are a uniformly drawn k-subset: at tiny shapes
+    every one of the C(s,k) subsets can be counted over a long stream of chunks, steps and
+    seeds.  This needs no knowledge of the generator, and a slip in the shuffle (a draw bounded
+    by s instead of s-j, a swap with the wrong place, a draw reused between places or chunks)
+    skews the counts by far more than the 5-sigma window.  Positions follow from subsets."""
+    subsets = list(itertools.combinations(range(s), k))
+    code = {sub: i for i, sub in enumerate(subsets)}
+    weights = (s ** np.arange(k)).astype(np.int64)
+    lut = np.full(s ** k, -1, dtype=np.int64)
+    for sub, i in code.items():
+        lut[int((np.array(sub) * weights).sum())] = i
+    C = 120_000
+    counts = np.zeros(len(subsets), dtype=np.int64)
+    streams = [(1, 0, 0), (1, 1, 0), (2, 0, 0), (2**63 + 11, 2**40 + 3, 10**12)]
+    for seed, step, chunk0 in streams:
+        cfg = Config(chunk=s, topk=k, scheme=SCHEME_RANDOM, seed=seed, step=step)
+        idx = oracle.select(cfg, None, C, chunk0=chunk0).reshape(C, k).astype(np.int64)
+        which = lut[(idx * weights).sum(axis=1)]
+        assert (which >= 0).all()                      # ascending, distinct, in range
+        counts += np.bincount(which, minlength=len(subsets))
+    N = C * len(streams)
+    p = 1.0 / len(subsets)
+    sigma = np.sqrt(N * p * (1 - p))
+    assert (np.abs(counts - N * p) < 5.0 * sigma).all(), counts
+    # chi-square over the subsets (len-1 degrees of freedom): not too bad and not too good
+    dof = len(subsets) - 1
+    chi2 = float(((counts - N * p) ** 2 / (N * p)).sum())
+    assert chi2 < dof + 5.0 * np.sqrt(2.0 * dof) + 5.0
+    # consecutive chunks are independent: the subset of chunk c says nothing about c+1
+    cfg = Config(chunk=s, topk=k, scheme=SCHEME_RANDOM, seed=5, step=9)
+    idx = oracle.select(cfg, None, C, chunk0=0).reshape(C, k).astype(np.int64)
+    which = lut[(idx * weights).sum(axis=1)]
+    joint = np.zeros((len(subsets), len(subsets)))
+    np.add.at(joint, (which[:-1], which[1:]), 1.0)
+    exp = (C - 1) * p * p
+    assert np.abs(joint - exp).max() < 6.0 * np.sqrt(exp) + 6.0
+
+
+def test_oracle_is_clean_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """The checker itself must not read or write out of bounds, overflow a signed integer or
+    leak: the oracle's C source is built without OpenMP under -fsanitize=address,undefined
+    together with a driver that calls every orc_* entry point over odd shapes (tiny chunks,
+    chunk 255/256, k = s, ragged tails, shards shorter than a chunk, n = 0, every scheme and
+    domain, fp32 and bf16 storage, 1 to 3 replicas) with exactly sized buffers."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = str(tmp_path / "oracle_sanitized")
+    subprocess.run(["gcc", "-O1", "-g", "-std=c11", "-fsanitize=address,undefined",
+                    "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer", "-static-libasan",
+                    "-Wno-unknown-pragmas", "-o", exe,
+                    os.path.join(root, "tests", "oracle_sanitize_driver.c"),
+                    os.path.join(root, "oracle", "detonation_oracle.c"), "-lm"], check=True)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:verify_asan_link_order=0",
+               UBSAN_OPTIONS="print_stacktrace=1")
+    res = subprocess.run([exe], env=env, capture_output=True, text=True, timeout=300)
+    assert res.returncode == 0, res.stderr[-4000:]
+    assert "runtime error" not in res.stderr and "ERROR: AddressSanitizer" not in res.stderr
+    assert "cases clean" in res.stdout
+
+
 # ---------------------------------------------------------------- residual
 
 @pytest.mark.parametrize("scheme,dct", [(SCHEME_TOPK, False), (SCHEME_STRIDE, True),
@@ -529,7 +591,7 @@ def test_adamw_first_step_with_sign_is_a_unit_step():
     assert (np.abs(got - exact) <= np.abs(exact) * 2.0 ** -8 + 1e-30).all()
 
 
-# ------------------------------------------- ternary payload (Discussion, "sign before synchronizing")
+# ------------------------------------------- ternary payload (Discussion: sign taken before the exchange)
 
 def _golden_ternary():
     out = {}
@@ -601,11 +663,11 @@ def test_ternary_compress_and_presign_reduce_to_the_fp32_path_on_signs(scheme):
         assert np.array_equal(y1, dense[:n])
 
 
-# ---------------------- DiLoCo replicator ("Replication Schemes": synchronization every n'th step)
+# ---------------------- DiLoCo replicator ("Replication Schemes": synchronises on every n-th step only)
 
 def test_diloco_cycle_closed_form():
     """Reading: between synchronisations a rank only accumulates (Algorithm 1's first line,
-    m <- beta*m + g); the n'th step extracts everything (Striding with k = s takes every
+    m <- beta*m + g); the n-th step extracts everything (Striding with k = s takes every
     position, so q = m and the momentum restarts from zero) and the replicas' q are averaged.
     With a constant gradient g the momentum after j accumulations is g*(1 - beta^j)/(1 - beta)."""
     s, n, every, beta, eta = 16, 16 * 40 + 5, 4, 0.5, 0.25
