@@ -21,12 +21,11 @@ HIPCC_FLAGS = [
 # one translation unit per kernel family, compiled side by side
 # (the longest-compiling units first)
 UNITS = [
-    # two lanes per chunk (chunk 192, 256)
-    "pair_compress_256.hip", "pair_compress_192.hip", "pair_decompress.hip",
+    # two lanes per chunk (chunk 96, 128, 192, 256)
+    "pair_compress_256.hip", "pair_compress_192.hip", "pair_compress_128.hip",
+    "pair_compress_96.hip", "pair_decompress.hip",
     # lane per chunk, top-k with fp32 values and int32 indices, by chunk size
-    "tiled_topk_s96.hip", "tiled_topk_s128_k16.hip", "tiled_topk_s128_k4.hip",
-    "tiled_topk_s128_k8.hip", "tiled_topk_s128_k1.hip", "tiled_topk_s128_k32.hip",
-    "tiled_topk_s128_k64.hip",
+    "tiled_topk_s96.hip", "tiled_topk_s128.hip",
     # matrix-core kernels (every other multiple of 32)
     "mfma_compress.hip", "mfma_decompress.hip",
     # lane per chunk: narrow payloads, Decoupled AdamW, Striding / Random

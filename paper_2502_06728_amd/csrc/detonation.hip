@@ -185,13 +185,6 @@ int detonation_compress_packed(const deto_config* cfg, int64_t n, const void* gr
                               ? (deto::launch_compress_topk_s64(a) ||
                                  deto::launch_compress_topk_s32(a) ||
                                  deto::launch_compress_topk_s16(a) ||
-                                 deto::launch_compress_topk_s96(a) ||
-                                 deto::launch_compress_topk_s128_k4(a) ||
-                                 deto::launch_compress_topk_s128_k16(a) ||
-                                 deto::launch_compress_topk_s128_k1(a) ||
-                                 deto::launch_compress_topk_s128_k8(a) ||
-                                 deto::launch_compress_topk_s128_k32(a) ||
-                                 deto::launch_compress_topk_s128_k64(a) ||
                                  deto::launch_compress_topk_packed(a) ||
                                  deto::launch_compress_topk_packed_s32(a) ||
                                  deto::launch_compress_topk_ternary(a))
@@ -205,7 +198,7 @@ int detonation_compress_packed(const deto_config* cfg, int64_t n, const void* gr
             c0 = C;   // the tail chunks rode along in the same launch
         } else {
             // no lane-per-chunk kernel for this (s, k): the two-lanes-per-chunk kernel (chunk
-            // 192, 256) or the matrix-core kernel takes the leading multiple of 32 chunks
+            // 96, 128, 192, 256) or the matrix-core kernel takes the leading multiple of 32 chunks
             c0 = deto::launch_compress_pair(a);
             if (c0 == 0) c0 = deto::launch_compress_mfma(a);
             if (c0 > 0) {
@@ -354,12 +347,7 @@ int decompress_impl(const deto_config* cfg, const deto_adamw* opt, int64_t n, in
                                  deto::launch_decompress_idx_s32(a) ||
                                  deto::launch_decompress_idx_s16(a) ||
                                  deto::launch_decompress_idx_s96(a) ||
-                                 deto::launch_decompress_idx_s128_k4(a) ||
-                                 deto::launch_decompress_idx_s128_k16(a) ||
-                                 deto::launch_decompress_idx_s128_k1(a) ||
-                                 deto::launch_decompress_idx_s128_k8(a) ||
-                                 deto::launch_decompress_idx_s128_k32(a) ||
-                                 deto::launch_decompress_idx_s128_k64(a) ||
+                                 deto::launch_decompress_idx_s128(a) ||
                                  deto::launch_decompress_idx_packed(a) ||
                                  deto::launch_decompress_idx_packed_s32(a) ||
                                  deto::launch_decompress_idx_ternary(a))

@@ -28,9 +28,14 @@
 
 namespace deto {
 
+// f(integral_constant<int, i>) for i = B .. E-1, in order.  Long ranges go in blocks of 64 so
+// that the template recursion stays shallow (a sorting network has over a thousand steps).
 template <int B, int E, class F>
 __device__ __forceinline__ void static_for(F&& f) {
-    if constexpr (B < E) {
+    if constexpr (E - B > 64) {
+        static_for<B, B + 64>(f);
+        static_for<B + 64, E>(f);
+    } else if constexpr (B < E) {
         f(std::integral_constant<int, B>{});
         static_for<B + 1, E>(f);
     }

@@ -26,60 +26,9 @@
 #include "deto_device.hip.h"
 #include "fast_dct.hip.h"
 #include "generic_kernels.hip.h"
+#include "sort_network.hip.h"
 
 namespace deto {
-
-// ---- Batcher's odd-even merge sort as a compile-time list of compare-exchanges
-template <int N>
-struct SortNet {
-    static constexpr int kCap = N * 12;   // N log^2 N / 4 compare-exchanges fit up to N = 128
-    int a[kCap];
-    int b[kCap];
-    int n;
-    constexpr SortNet() : a{}, b{}, n(0) { sort(0, N); }
-    constexpr void add(int i, int j) {
-        a[n] = i;
-        b[n] = j;
-        ++n;
-    }
-    constexpr void merge(int lo, int len, int r) {
-        const int m = r * 2;
-        if (m < len) {
-            merge(lo, len, m);
-            merge(lo + r, len, m);
-            for (int i = lo + r; i + r < lo + len; i += m) add(i, i + r);
-        } else {
-            add(lo, lo + r);
-        }
-    }
-    constexpr void sort(int lo, int len) {
-        if (len > 1) {
-            const int m = len / 2;
-            sort(lo, m);
-            sort(lo + m, m);
-            merge(lo, len, 1);
-        }
-    }
-};
-
-template <int N>
-struct SortNetHolder {
-    static constexpr SortNet<N> net{};
-};
-
-// sort descending, in registers
-template <int N>
-__device__ __forceinline__ void sort_desc(uint32_t (&k)[N]) {
-    constexpr int cnt = SortNetHolder<N>::net.n;
-    static_for<0, cnt>([&](auto I) {
-        constexpr int i = SortNetHolder<N>::net.a[I];
-        constexpr int j = SortNetHolder<N>::net.b[I];
-        const uint32_t hi = max(k[i], k[j]);
-        const uint32_t lo = min(k[i], k[j]);
-        k[i] = hi;
-        k[j] = lo;
-    });
-}
 
 // K-th largest of the union of two descending arrays of length H.
 template <int H, int K>
@@ -401,7 +350,9 @@ __device__ __forceinline__ ChunkMask<S> random_mask(uint64_t seed, uint64_t step
     return mask;
 }
 
-// Compress half (top-k) on full tiles: chunks [0, 64*n_tiles), all complete.
+// Compress half (top-k) on full tiles: chunks [0, 64*n_tiles), all complete.  Chunk sizes up
+// to 64: beyond that a chunk no longer fits one lane at two wavefronts per SIMD, and the
+// two-lanes-per-chunk kernels (pair_kernels.hip.h) take over.
 template <int S, int K, bool GRAD_BF16, int VAL = 0>
 __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void compress_tiled_topk(
     KParams p, int64_t n_tiles, TailRange tail, const void* __restrict__ grad,
@@ -435,80 +386,30 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void compress_ti
     static_for<1, S>([&](auto i) { c[i] *= p.alpha; });
     if (coeff_dbg) regs_to_global<S>(coeff_dbg + ebase + static_cast<int64_t>(lane) * S, c);
 
-    // threshold: K-th largest magnitude.  Beyond S = 64 the coefficients wait in the lane's
-    // LDS row (free by now) while their magnitudes are sorted, to stay within the registers.
-    constexpr bool kLean = S > 64;
-    // Large k at S = 128: the two 64-entry sorts plus the k-th-largest merge take minutes to
-    // compile and hundreds of registers; there the threshold comes from a binary search over
-    // the 31 magnitude bits instead (signs parked in four mask words meanwhile, so that the
-    // count per step is two instructions per coefficient: mag - cand is exact, its sign bit
-    // goes into a collector word, one popcount per 32).
-    constexpr bool kSearch = kLean && (K > 16 || (S & (S - 1)) != 0);   // or S not a power of 2
+    // threshold: K-th largest magnitude
+    static_assert(S <= 64, "a chunk and its sorted magnitudes live in one lane's registers");
     uint32_t T;
-    if constexpr (kSearch) {
-        uint32_t sgn[S / 32];
-#pragma unroll
-        for (int w = 0; w < S / 32; ++w) sgn[w] = 0u;
-        static_for<0, S>([&](auto I) {
-            constexpr int i = S - 1 - I;   // descending so that shifting lands bit i at i
-            const uint32_t b = __float_as_uint(c[i]);
-            sgn[i / 32] = (sgn[i / 32] << 1) | (b >> 31);
-            c[i] = __uint_as_float(b & 0x7FFFFFFFu);
-        });
-        T = 0u;
-        bool settled = false;   // a candidate with exactly K magnitudes at or above it separates
-#pragma unroll 1
-        for (int bit = 30; bit >= 0; --bit) {
-            const uint32_t cand = T | (1u << bit);
-            int below = 0;
-#pragma unroll
-            for (int w = 0; w < S / 32; ++w) {
-                uint32_t coll = 0u;
-#pragma unroll
-                for (int i = 0; i < 32; ++i)
-                    coll = __builtin_amdgcn_alignbit(coll, __float_as_uint(c[32 * w + i]) - cand, 31);
-                below += __popc(coll);
-            }
-            if (!settled && S - below >= K) {
-                T = cand;
-                settled = (S - below == K);
-            }
-            if (__all(settled)) break;
-        }
-        static_for<0, S>([&](auto i) {
-            c[i] = __uint_as_float(__float_as_uint(c[i]) | (((sgn[i / 32] >> (i % 32)) & 1u) << 31));
-        });
-    } else {
+    {
         uint32_t A[H], B[H];
         static_for<0, H>([&](auto i) {
             A[i] = __float_as_uint(c[i]) & 0x7FFFFFFFu;
             B[i] = __float_as_uint(c[H + i]) & 0x7FFFFFFFu;
         });
-        if constexpr (kLean) {
-            regs_to_row<S>(row, c);
-            wave_lds_sync();
-        }
         sort_desc<H>(A);
         sort_desc<H>(B);
         T = kth_largest<H, K>(A, B);
-        if constexpr (kLean) {
-            wave_lds_sync();
-            row_to_regs<S>(row, c);
-            wave_lds_sync();
-        }
     }
-    // keep magnitude >= T: the mask collects the decisions (bit i = element i kept).  Up to
-    // S = 64 a second register array u receives, in the same pass, what stays behind in the
-    // momentum (the dropped coefficients); beyond that registers are short and the kept
-    // entries of c are cleared after the payload has been written instead.
-    float u[kLean ? 1 : S];
+    // keep magnitude >= T: the mask collects the decisions (bit i = element i kept), and a
+    // second register array u receives, in the same pass, what stays behind in the momentum
+    // (the dropped coefficients)
+    float u[S];
     ChunkMask<S> mk;
 #pragma unroll
     for (int w = 0; w < ChunkMask<S>::kWords; ++w) mk.w[w] = 0u;
     static_for<0, S>([&](auto I) {
         constexpr int i = S - 1 - I;   // descending so that shifting lands bit i at i
         const bool keep = (__float_as_uint(c[i]) & 0x7FFFFFFFu) >= T;
-        if constexpr (!kLean) u[i] = keep ? 0.0f : c[i];
+        u[i] = keep ? 0.0f : c[i];
         mk.w[i / 32] = (mk.w[i / 32] << 1) | (keep ? 1u : 0u);
     });
     if (__any(mk.count() != K)) {
@@ -526,14 +427,13 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void compress_ti
             need -= take ? 1 : 0;
             const bool keep = (key > T) || take;
             mk.w[i / 32] |= (keep ? 1u : 0u) << (i % 32);
-            if constexpr (!kLean) u[i] = keep ? 0.0f : c[i];
+            u[i] = keep ? 0.0f : c[i];
         });
     }
 
     if constexpr (VAL == 1 || VAL == 2) {
         // 16-bit transfer: the payload carries the rounded coefficient, and the rounding
         // error of a kept coefficient stays behind in the momentum with the dropped ones
-        static_assert(!kLean, "16-bit payloads are built for chunk sizes up to 64");
         static_for<0, S>([&](auto i) {
             const float r = decode16<VAL>(encode16<VAL>(c[i]));
             u[i] = mk.bit(i) ? (c[i] - r) : c[i];
@@ -544,18 +444,10 @@ __global__ __launch_bounds__(kWave, TileGeom<S>::kWavesPerSimd) void compress_ti
 
     // ---- m <- m1 - q.  With q = D^T(kept coefficients) and m1 = D^T(all coefficients), the
     // residual is the inverse transform of the dropped ones.
-    if constexpr (kLean) {
-        static_for<0, S>([&](auto i) { c[i] = mk.bit(i) ? 0.0f : c[i]; });
-        c[0] *= p.alpha0;
-        static_for<1, S>([&](auto i) { c[i] *= p.alpha; });
-        FastDct<S>::dct3(c);
-        regs_to_row<S>(row, c);
-    } else {
-        u[0] *= p.alpha0;
-        static_for<1, S>([&](auto i) { u[i] *= p.alpha; });
-        FastDct<S>::dct3(u);
-        regs_to_row<S>(row, u);
-    }
+    u[0] *= p.alpha0;
+    static_for<1, S>([&](auto i) { u[i] *= p.alpha; });
+    FastDct<S>::dct3(u);
+    regs_to_row<S>(row, u);
     wave_lds_sync();
     store_tile_momentum<S>(tile, mom, ebase, lane);
 }

@@ -50,23 +50,11 @@ inline unsigned tiled_grid(int64_t tiles, int64_t n_chunks) {
 bool launch_compress_topk_s64(const CompressLaunch& a);
 bool launch_compress_topk_s32(const CompressLaunch& a);
 bool launch_compress_topk_s16(const CompressLaunch& a);
-bool launch_compress_topk_s96(const CompressLaunch& a);
 bool launch_decompress_idx_s64(const DecompressLaunch& a);
 bool launch_decompress_idx_s32(const DecompressLaunch& a);
 bool launch_decompress_idx_s16(const DecompressLaunch& a);
 bool launch_decompress_idx_s96(const DecompressLaunch& a);
-bool launch_compress_topk_s128_k4(const CompressLaunch& a);
-bool launch_compress_topk_s128_k16(const CompressLaunch& a);
-bool launch_compress_topk_s128_k1(const CompressLaunch& a);
-bool launch_compress_topk_s128_k8(const CompressLaunch& a);
-bool launch_compress_topk_s128_k32(const CompressLaunch& a);
-bool launch_compress_topk_s128_k64(const CompressLaunch& a);
-bool launch_decompress_idx_s128_k4(const DecompressLaunch& a);
-bool launch_decompress_idx_s128_k16(const DecompressLaunch& a);
-bool launch_decompress_idx_s128_k1(const DecompressLaunch& a);
-bool launch_decompress_idx_s128_k8(const DecompressLaunch& a);
-bool launch_decompress_idx_s128_k32(const DecompressLaunch& a);
-bool launch_decompress_idx_s128_k64(const DecompressLaunch& a);
+bool launch_decompress_idx_s128(const DecompressLaunch& a);
 bool launch_compress_topk_packed(const CompressLaunch& a);     // byte indices + 16-bit values
 bool launch_decompress_idx_packed(const DecompressLaunch& a);
 bool launch_compress_topk_packed_s32(const CompressLaunch& a);
@@ -109,10 +97,14 @@ int64_t launch_decompress_mfma(const DecompressLaunch& a);
 #else
 #define DETO_PAIR_S_LIST(X) X(192) X(256)
 #endif
-int64_t launch_compress_pair_192(const CompressLaunch& a);   // one translation unit each:
-int64_t launch_compress_pair_256(const CompressLaunch& a);   // the longest compiles
+int64_t launch_compress_pair_96(const CompressLaunch& a);    // one translation unit each:
+int64_t launch_compress_pair_128(const CompressLaunch& a);   // the longest compiles
+int64_t launch_compress_pair_192(const CompressLaunch& a);
+int64_t launch_compress_pair_256(const CompressLaunch& a);
 inline int64_t launch_compress_pair(const CompressLaunch& a) {
-    const int64_t c = launch_compress_pair_192(a);
+    int64_t c = launch_compress_pair_96(a);
+    if (!c) c = launch_compress_pair_128(a);
+    if (!c) c = launch_compress_pair_192(a);
     return c ? c : launch_compress_pair_256(a);
 }
 int64_t launch_decompress_pair(const DecompressLaunch& a);

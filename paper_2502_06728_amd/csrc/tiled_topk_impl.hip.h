@@ -1,11 +1,13 @@
-// Shared body of tiled_topk_s64.hip / tiled_topk_s32.hip: instantiates the top-k compress
-// kernel and the indexed decompress kernel for chunk size DETO_S and the k values in
-// DETO_K_LIST(X), and defines the two launchers named by DETO_COMPRESS_FN / DETO_DECOMPRESS_FN.
+// Shared body of the tiled_topk_s*.hip units: instantiates the top-k compress kernel and the
+// indexed decompress kernel for chunk size DETO_S and the k values in DETO_K_LIST(X), and
+// defines the two launchers named by DETO_COMPRESS_FN / DETO_DECOMPRESS_FN.  A unit that
+// does not define DETO_COMPRESS_FN has the decompress kernel only (chunk sizes above 64).
 #include "tiled_kernels.hip.h"
 #include "tiled_launch.h"
 
 namespace deto {
 
+#ifdef DETO_COMPRESS_FN
 bool DETO_COMPRESS_FN(const CompressLaunch& a) {
     if (a.p.s != DETO_S || a.p.val_dtype != 0 || a.p.idx_u8) return false;
     const unsigned grid = tiled_grid(a.tiles, a.n_chunks);
@@ -24,6 +26,7 @@ bool DETO_COMPRESS_FN(const CompressLaunch& a) {
 #undef X
     return false;
 }
+#endif
 
 bool DETO_DECOMPRESS_FN(const DecompressLaunch& a) {
     if (a.p.s != DETO_S || !a.idx || a.p.val_dtype != 0 || a.p.idx_u8 || a.p.adam) return false;

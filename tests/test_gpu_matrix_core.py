@@ -133,8 +133,8 @@ def test_olmo_1b_shard_full_size_chunk_sweep(H, s, k):
     # the OLMo-1B shard (147,095,552 parameters) at the larger chunk sizes of the Appendix B
     # sweep, in the launch configuration bench.py --chunk/--topk times; sampled chunk runs
     import dataclasses
-    from tests.test_gpu_parity import _full_size_check
+    from tests.test_gpu_parity import _full_size_check, _sample_runs
     w = dataclasses.replace(synth.workloads()["olmo-1b-1of8"], chunk=s, topk=k)
     cfg = Config(chunk=s, topk=k, decay=w.decay, lr=w.lr, sign=w.sign)
-    worst = _full_size_check(H, w, cfg, runs_count=10)
+    worst = _full_size_check(H, w, cfg, ranges=_sample_runs(-(-w.n // s), count=10))
     print(f"olmo-1b full size, chunk {s}, k {k}:", worst)
