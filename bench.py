@@ -25,6 +25,20 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 
 
+def kernel_sources_sha16() -> str:
+    """Fingerprint of the HIP sources (every file under csrc/): the counter-measured traffic
+    recorded under profiles/ is only quoted for the sources it was measured on."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2502_06728_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        if name == "membench.hip":
+            continue
+        h.update(name.encode())
+        h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def algorithmic_bytes(n: int, s: int, k: int, R: int, grad_bytes: int, param_bytes: int,
                       with_idx: bool, val_bytes: float = 4, idx_bytes: int = 4) -> dict:
     """Bytes the method itself must move per launch: compress reads g and m, writes m and
@@ -34,9 +48,9 @@ def algorithmic_bytes(n: int, s: int, k: int, R: int, grad_bytes: int, param_byt
     return {"compress": n * (grad_bytes + 8) + pay, "decompress": R * pay + 2 * n * param_bytes}
 
 
-def cpu_baseline(w, cfg_kwargs: dict, sample_params: int, every: int = 1) -> dict:
-    """The oracle as it stands, on the host cores, on the leading `sample_params` of the shard.
-    every > 1 (DiLoCo): every-1 accumulate-only steps, then the synchronising step."""
+def _oracle_step_rate(w, cfg_kwargs: dict, sample_params: int, every: int):
+    """Parameters per second of the oracle on the leading `sample_params` of the shard with the
+    thread count it is currently set to; returns (rate, n, seconds)."""
     import numpy as np
     import oracle
     from paper_2502_06728_amd import synth
@@ -58,10 +72,29 @@ def cpu_baseline(w, cfg_kwargs: dict, sample_params: int, every: int = 1) -> dic
     idx[0], val[0] = idx0, val0
     oracle.decompress_step(cfg, idx if cfg.scheme == 0 else None, val, th)
     dt = time.perf_counter() - t0
+    return every * n / dt, n, dt
+
+
+def cpu_baseline(w, cfg_kwargs: dict, sample_params: int, every: int = 1,
+                 one_core_sample: int = 1 << 23) -> dict:
+    """The oracle as it stands, on the host cores, on the leading `sample_params` of the shard,
+    and on one core on a smaller leading sample.
+    every > 1 (DiLoCo): every-1 accumulate-only steps, then the synchronising step."""
+    import oracle
+    rate, n, dt = _oracle_step_rate(w, cfg_kwargs, sample_params, every)
+    cores = oracle.threads()
+    oracle.set_threads(1)
+    try:
+        rate1, n1, dt1 = _oracle_step_rate(w, cfg_kwargs, one_core_sample, every)
+    finally:
+        oracle.set_threads(cores)
+    R = w.replicas
     what = "one full step" if every == 1 else f"{every - 1} accumulate-only steps and one full step"
-    return {"value": every * n / dt, "unit": "params/s", "cores": oracle.threads(), "kind": "oracle",
+    return {"value": rate, "unit": "params/s", "cores": cores, "kind": "oracle",
             "sample": f"leading {n} of {w.n} parameters of the same shard, {what} "
-                      f"(compress + decompress, R={R}), {dt:.1f} s, gcc -O2 + OpenMP"}
+                      f"(compress + decompress, R={R}), {dt:.1f} s, gcc -O2 + OpenMP",
+            "value_1core": rate1,
+            "sample_1core": f"leading {n1} parameters, same step, one thread, {dt1:.1f} s"}
 
 
 def main() -> int:
@@ -83,8 +116,11 @@ def main() -> int:
     ap.add_argument("--topk", type=int, default=0, help="override the workload's k")
     ap.add_argument("--replicas", type=int, default=0,
                     help="override the workload's R, the size of the replication group")
+    ap.add_argument("--no-sign", action="store_true", help="update with Q itself, not sign(Q)")
     ap.add_argument("--cpu-sample", type=int, default=1 << 28)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--sources-sha", action="store_true",
+                    help="print the fingerprint of the HIP sources (recorded with counter runs)")
     ap.add_argument("--report", action="store_true",
                     help="run every benchmark configuration and print a markdown report "
                          "(GPU rate, HBM GB/s, oracle on 1 and all host cores, paper context)")
@@ -93,6 +129,9 @@ def main() -> int:
         print("bench.py measures the one-GPU hot path only: the payload all_gather across the "
               "replication group is not part of this build, so --gpus must be 1.", file=sys.stderr)
         return 2
+    if args.sources_sha:
+        print(kernel_sources_sha16())
+        return 0
     if args.report:
         return report(args)
     print(json.dumps(run(args)))
@@ -115,6 +154,9 @@ def run(args) -> dict:
     if getattr(args, "replicas", 0):
         import dataclasses
         w = dataclasses.replace(w, replicas=args.replicas)
+    if getattr(args, "no_sign", False):
+        import dataclasses
+        w = dataclasses.replace(w, sign=False)
     diloco = args.scheme == "diloco"
     every = max(1, args.diloco_every) if diloco else 1
     if diloco:
@@ -225,14 +267,26 @@ def run(args) -> dict:
     dom_gbs = gbs_c if dom == "compress" else gbs_d
 
     # HBM bytes per launch of the dominant kernel as rocprofv3's FETCH_SIZE + WRITE_SIZE counters
-    # measured them for this workload (recorded under profiles/, not re-measured here)
-    traffic = None
+    # measured them for this workload.  Counters need a profiler run of their own, so the figure
+    # comes from the summary under profiles/; the record says which file, at which commit it
+    # was measured, and the figure is withheld if the kernels' sources have changed since.
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", f"traffic_{args.workload}_{args.scheme}.txt")
-    if os.path.exists(tpath) and not packed and not adamw and not (args.chunk or args.topk or args.dct):
+    if os.path.exists(tpath) and not packed and not adamw and not (args.chunk or args.topk or args.dct
+                                                                  or args.replicas):
+        meta, rows = {}, {}
         for line in open(tpath):
             f = line.split()
-            if len(f) == 2 and f[0] == dom:
-                traffic = float(f[1])
+            if len(f) == 3 and f[0] == "#" and f[1] in ("commit", "kernel_sources_sha16"):
+                meta[f[1]] = f[2]
+            elif len(f) == 2 and not line.startswith("#"):
+                rows[f[0]] = float(f[1])
+        now = kernel_sources_sha16()
+        stale = meta.get("kernel_sources_sha16") != now
+        traffic = None if stale else rows.get(dom)
+        traffic_source = {"file": os.path.relpath(tpath, ROOT), "measured_at_commit": meta.get("commit"),
+                          "kernel_sources_sha16": meta.get("kernel_sources_sha16"),
+                          "kernel_sources_sha16_now": now, "stale": stale}
 
     # bytes of an average step (DiLoCo: every-1 accumulations of g and m per synchronisation)
     ab_acc = n * (grad.element_size() + 8)
@@ -256,7 +310,8 @@ def run(args) -> dict:
             "decompress": {"ms": t_d, "algorithmic_bytes": ab["decompress"], "gbs": gbs_d,
                            "frac": gbs_d / HBM_PEAK_GBS}},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS, "traffic": traffic},
+                     "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS, "traffic": traffic,
+                     "traffic_source": traffic_source},
     }
     if diloco:
         out["config"]["diloco_every"] = every
@@ -302,22 +357,8 @@ def report(args) -> int:
         a.steps, a.warmup, a.no_cpu = min(args.steps, 20), 3, False
         a.cpu_sample = 1 << 26           # oracle on at most 67 M leading parameters (labelled)
         rec = run(a)
-        import oracle      # after the GPU leg, as in a plain run (the oracle brings its OpenMP pool)
         all_cores = rec["cpu_baseline"]
-        # single-threaded oracle on a smaller sample of the same shard
-        import dataclasses
-        from paper_2502_06728_amd import synth
-        threads = oracle.threads()
-        oracle.set_threads(1)
-        w = synth.workloads()[workload]
-        if scheme == "diloco":
-            w = dataclasses.replace(w, topk=w.chunk)
-        one = cpu_baseline(w, dict(chunk=w.chunk, topk=w.topk,
-                                   scheme={"topk": 0, "stride": 1, "random": 2, "diloco": 1}[scheme],
-                                   sign=w.sign, dct=dct, decay=w.decay, lr=w.lr,
-                                   weight_decay=w.weight_decay, seed=w.seed, step=0), 1 << 22,
-                           max(1, args.diloco_every) if scheme == "diloco" else 1)
-        oracle.set_threads(threads)
+        one = {"value": all_cores["value_1core"]}
         rows.append((rec, all_cores, one))
         print(f"# done {workload} {scheme}{' dct' if dct else ''}", file=sys.stderr, flush=True)
     print("| workload | scheme | params | step ms | GPU params/s | step GB/s (% of 8 TB/s) | "
@@ -335,6 +376,31 @@ def report(args) -> int:
               f"{rec['kernels']['decompress']['gbs']:.0f} | {one['value'] / 1e6:.1f} M | "
               f"{allc['value'] / 1e6:.1f} M ({allc['cores']} cores) | "
               f"{rec['value'] / allc['value']:.0f}x |")
+    print()
+    # the ViT-B/16 sweep of the benchmark configurations: chunk x top-k x sign, R = 2, on the
+    # 10.8 M-parameter shard (fp32, ragged length)
+    vit = []
+    for s_ in (32, 64, 128):
+        for k_ in (1, 4, 16, s_ // 2):
+            for sign in (True, False):
+                a = copy.copy(args)
+                a.workload, a.scheme, a.dct = "vit-b16-1of8", "topk", False
+                a.chunk, a.topk, a.no_sign = s_, k_, not sign
+                a.steps, a.warmup, a.no_cpu = min(args.steps, 50), 5, True
+                vit.append(run(a))
+        print(f"# done vit chunk {s_}", file=sys.stderr, flush=True)
+    print("ViT-B/16 sweep (vit-b16-1of8: 10,820,957 parameters, fp32, R = 2; the whole step moves "
+          "0.2 - 0.4 GB, so launch and tail effects weigh more than on the larger shards):")
+    print()
+    print("| chunk | top-k | sign | compress ms | decompress ms | step ms | GPU params/s | "
+          "step GB/s (% of 8 TB/s) |")
+    print("|---|---|---|---|---|---|---|---|")
+    for rec in vit:
+        c = rec["config"]
+        print(f"| {c['chunk']} | {c['topk']} | {'on' if c['sign'] else 'off'} | "
+              f"{rec['kernels']['compress']['ms']:.4f} | {rec['kernels']['decompress']['ms']:.4f} | "
+              f"{rec['ms_per_step']:.4f} | {rec['value'] / 1e9:.1f} G | {rec['step_hbm_gbs']:.0f} "
+              f"({100 * rec['step_hbm_frac_of_peak']:.0f} %) |")
     print()
     # chunk-size sweep of Appendix B ("DeMo Chunk Size": 16 ... 256 at compression rates 1/8 and
     # 1/16) on the OLMo-1B shard, GPU only
@@ -386,7 +452,7 @@ def report(args) -> int:
     print()
     print("Oracle: the CPU reference as it stands (plain C, double arithmetic, gcc -O2, OpenMP over "
           "chunks), one full step on the leading parameters of the same shard (all cores: up to "
-          "67 M parameters; 1 core: 4 M), rate scaled per parameter.  flat-1m fits the caches "
+          "67 M parameters; 1 core: 8 M), rate scaled per parameter.  flat-1m fits the caches "
           "and is a correctness configuration, not a bandwidth one.")
     print()
     print(PAPER_CONTEXT)

@@ -63,26 +63,28 @@ __device__ __forceinline__ void st16(f32x4* p, f32x4 v) {
     else *p = v;
 }
 
-// decompress shape: NS read-only streams + one read-modify-write stream, 8 KiB per tile each
-// (8 lane accesses of 16 bytes per stream); everything is requested before anything is used
-template <int NS, bool NTL, bool NTS>
+// decompress shape: NS read-only streams + one read-modify-write stream; a workgroup (one
+// wavefront) takes PIECE KiB of every stream (PIECE lane accesses of 16 bytes per stream; the
+// library's kernels: 8, a tile of 64 chunks); everything is requested before anything is used
+template <int NS, int PIECE, bool NTL, bool NTS>
 __global__ __launch_bounds__(64) void decompress_shape(const f32x4* __restrict__ payload,
                                                        size_t stream_stride16,
                                                        f32x4* __restrict__ params) {
-    const size_t base = static_cast<size_t>(blockIdx.x) * 512 + threadIdx.x;
-    f32x4 v[NS][8], th[8];
+    const size_t base = static_cast<size_t>(blockIdx.x) * (64 * PIECE) + threadIdx.x;
+    f32x4 v[NS][PIECE], th[PIECE];
 #pragma unroll
     for (int s = 0; s < NS; ++s)
 #pragma unroll
-        for (int i = 0; i < 8; ++i) v[s][i] = ld16<NTL>(payload + s * stream_stride16 + base + 64 * i);
+        for (int i = 0; i < PIECE; ++i)
+            v[s][i] = ld16<NTL>(payload + s * stream_stride16 + base + 64 * i);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) th[i] = ld16<NTL>(params + base + 64 * i);
+    for (int i = 0; i < PIECE; ++i) th[i] = ld16<NTL>(params + base + 64 * i);
 #pragma unroll
     for (int s = 0; s < NS; ++s)
 #pragma unroll
-        for (int i = 0; i < 8; ++i) th[i] += v[s][i];
+        for (int i = 0; i < PIECE; ++i) th[i] += v[s][i];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) st16<NTS>(params + base + 64 * i, th[i]);
+    for (int i = 0; i < PIECE; ++i) st16<NTS>(params + base + 64 * i, th[i]);
 }
 
 // compress shape: momentum 16 KiB read and rewritten, gradient 8 KiB read, 8 KiB + 8 KiB written
@@ -143,14 +145,22 @@ static int traffic_shapes(int iters) {
     const double cbytes = static_cast<double>(tiles) * 1024.0 * (24.0 + 32.0);
     int rc = 0;
     rc |= time_shape("decompress shape (8 read streams + 1 read-write), plain", dbytes, iters, [&] {
-        decompress_shape<8, false, false><<<grid, 64>>>(payload, stream16, params); });
+        decompress_shape<8, 8, false, false><<<grid, 64>>>(payload, stream16, params); });
     rc |= time_shape("decompress shape, non-temporal loads", dbytes, iters, [&] {
-        decompress_shape<8, true, false><<<grid, 64>>>(payload, stream16, params); });
+        decompress_shape<8, 8, true, false><<<grid, 64>>>(payload, stream16, params); });
     rc |= time_shape("decompress shape, non-temporal loads and stores", dbytes, iters, [&] {
-        decompress_shape<8, true, true><<<grid, 64>>>(payload, stream16, params); });
-    rc |= time_shape("read-only, 8 streams, non-temporal loads (sum kept in registers)",
-                     static_cast<double>(tiles) * 8192.0 * 8.0, iters, [&] {
-        decompress_shape<8, true, true><<<grid, 64>>>(payload, stream16, payload + 7 * stream16); });
+        decompress_shape<8, 8, true, true><<<grid, 64>>>(payload, stream16, params); });
+    // the same traffic in smaller pieces per wavefront (more, lighter wavefronts per SIMD: 72
+    // registers of data in flight at 2 KiB, 36 at 1 KiB, against 288 for a whole tile)
+    rc |= time_shape("decompress shape, non-temporal loads, 4 KiB of each stream per wavefront",
+                     dbytes, iters, [&] {
+        decompress_shape<8, 4, true, false><<<2 * grid, 64>>>(payload, stream16, params); });
+    rc |= time_shape("decompress shape, non-temporal loads, 2 KiB of each stream per wavefront",
+                     dbytes, iters, [&] {
+        decompress_shape<8, 2, true, false><<<4 * grid, 64>>>(payload, stream16, params); });
+    rc |= time_shape("decompress shape, non-temporal loads, 1 KiB of each stream per wavefront",
+                     dbytes, iters, [&] {
+        decompress_shape<8, 1, true, false><<<8 * grid, 64>>>(payload, stream16, params); });
     // compress: gradient = payload stream 0, values / indices = payload streams 1 and 2
     rc |= time_shape("compress shape (24 KiB in, 32 KiB out per tile), plain", cbytes, iters, [&] {
         compress_shape<false, false><<<grid, 64>>>(payload, mom, payload + stream16,
