@@ -197,9 +197,12 @@ int detonation_compress_packed(const deto_config* cfg, int64_t n, const void* gr
             if (rc) return rc;
             c0 = C;   // the tail chunks rode along in the same launch
         } else {
-            // no lane-per-chunk kernel for this (s, k): the two-lanes-per-chunk kernel (chunk
-            // 96, 128, 192, 256) or the matrix-core kernel takes the leading multiple of 32 chunks
-            c0 = deto::launch_compress_pair(a);
+            // no lane-per-chunk kernel for this (s, k): chunk 96, 128, 192 and 256 run with a
+            // wavefront per coefficient class (fp32 + int32 payloads, k <= s/2) or two lanes
+            // per chunk (other formats), anything else on the matrix-core kernel, which takes
+            // the leading multiple of 32 chunks
+            c0 = deto::launch_compress_split(a);
+            if (c0 == 0) c0 = deto::launch_compress_pair(a);
             if (c0 == 0) c0 = deto::launch_compress_mfma(a);
             if (c0 > 0) {
                 rc = launched();

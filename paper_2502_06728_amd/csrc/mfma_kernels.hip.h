@@ -312,10 +312,11 @@ __device__ __forceinline__ void store_tile_rows(const float* __restrict__ buf, i
 }
 
 // Chunks with ties at the k-th magnitude (need != 0 on the chunk's lanes), one at a time with
-// the whole wavefront; their LDS rows hold the coefficients.  Everything above thr_eq is kept
+// the whole wavefront; their LDS rows hold the coefficients (ROWS rows; lane tt of the calling
+// wavefront carries chunk tt's need and thresholds).  Everything above thr_eq is kept
 // and, of the entries equal to it, the `need` lowest indices.  The payload goes out and the
 // row is left holding alpha_j * remainder.
-template <int NB>
+template <int NB, int ROWS = kMfmaChunks>
 __device__ __forceinline__ void emit_tied_chunks(float* __restrict__ buf, const KParams& p,
                                                  int lane, int need, uint32_t thr_gt,
                                                  uint32_t thr_eq, int64_t chunk0,
@@ -326,7 +327,7 @@ __device__ __forceinline__ void emit_tied_chunks(float* __restrict__ buf, const 
     constexpr int S = G::S, kRow = G::kRow;
     const int k = p.k;
     if (!__any(need != 0)) return;
-    for (int tt = 0; tt < kMfmaChunks; ++tt) {
+    for (int tt = 0; tt < ROWS; ++tt) {
         const int c_need = __builtin_amdgcn_readlane(need, tt);
         if (c_need == 0) continue;
         const uint32_t c_gt = __builtin_amdgcn_readlane(thr_gt, tt);

@@ -1,0 +1,33 @@
+// Lane-per-chunk, wavefront-per-coefficient-class compress kernels (chunk size 96: 2 classes;
+// top-k selection, fp32 values + int32 indices, k <= 48).
+#include "split_kernels.hip.h"
+#include "tiled_launch.h"
+
+namespace deto {
+
+int64_t launch_compress_split_96(const CompressLaunch& a) {
+    const KParams& p = a.p;
+#ifdef DETO_TILED_ONLY_64_32
+    return 0;
+#else
+    if (p.s != 96 || p.scheme != 0 || !p.use_dct || p.val_dtype != 0 || p.idx_u8 || p.k > 48)
+        return 0;
+    const int64_t tiles = (a.n / p.s) / kWave;
+    // one workgroup per tile plus one per chunk past the last full tile
+    const int64_t grid64 = tiles + (a.n_chunks - tiles * kWave);
+    if (tiles <= 0 || grid64 > 0x7FFFFFFF) return 0;
+    const unsigned grid = static_cast<unsigned>(grid64);
+    constexpr int kThreads = SplitGeom<96, 2>::kThreads;
+    if (a.grad_bf16)
+        compress_split<96, 2, true><<<grid, kThreads, 0, a.stream>>>(
+            p, tiles, a.n, a.n_chunks, a.grad, a.mom, static_cast<int32_t*>(a.idx),
+            static_cast<float*>(a.val), a.coeff_dbg);
+    else
+        compress_split<96, 2, false><<<grid, kThreads, 0, a.stream>>>(
+            p, tiles, a.n, a.n_chunks, a.grad, a.mom, static_cast<int32_t*>(a.idx),
+            static_cast<float*>(a.val), a.coeff_dbg);
+    return a.n_chunks;   // the tail chunks ride along
+#endif
+}
+
+}  // namespace deto

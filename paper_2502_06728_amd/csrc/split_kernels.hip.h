@@ -1,0 +1,586 @@
+// Lane per chunk, wavefront per coefficient class: the compress half for chunk sizes above 64.
+//
+// A chunk of more than 64 elements does not fit one lane's registers at two wavefronts per
+// SIMD.  Splitting it between two lanes of ONE wavefront makes the lanes run different
+// half-size transforms (a DCT-II and a DCT-IV) one after the other.  Here the split is between
+// the W wavefronts of a workgroup instead: the workgroup owns a tile of 64 chunks in LDS
+// (row = chunk), lane t of EVERY wavefront works on chunk t, and wavefront w computes one class
+// of the chunk's coefficients, S/W of them, in its lanes' registers.  Every wavefront runs
+// straight-line code with no divergence, and the classes meet in LDS at workgroup barriers.
+//
+//   W = 2 (chunk 96, 128, 192), first level of the DCT-II recursion of fast_dct.hip.h:
+//     class 0: u_n = x_n + x_{S-1-n}, coefficients 2m   = dct2_{S/2}(u)
+//     class 1: w_n = x_n - x_{S-1-n}, coefficients 2m+1 = dct4_{S/2}(w)
+//   W = 4 (chunk 256), two levels:
+//     class 0: coefficients 4m   = dct2_64(u_n + u_{127-n})
+//     class 1: coefficients 4m+2 = dct4_64(u_n - u_{127-n})
+//     class 2, 3: the DCT-IV of w (length 128) by plane rotations into two DCT-IIs of length
+//              64, A (class 2) and B (class 3); after an exchange through LDS class 2 holds the
+//              coefficients 4m+1 = A_m + B_{64-m} and class 3 the coefficients
+//              4m+3 = A_{m+1} - B_{63-m}.
+// The inverse runs the same splits backwards (DCT-III / DCT-IV).
+//
+// Selection (top-k, any k at run time): every lane sorts the magnitudes of its S/W coefficients
+// with a sorting network; the sorted lists of a chunk meet in the chunk's LDS row.  For W = 4
+// the lists of classes (0,1) and (2,3) are first merged into two sorted lists of 128 (one
+// bitonic half-cleaner across the two wavefronts, then a bitonic merge network per lane).  The
+// k-th largest of the union of two sorted lists follows from a binary search over how many of
+// the k come from the first list.  A tie at the threshold sends the chunk through the
+// whole-wavefront pass that keeps the lowest indices among the equals.
+//
+// Emission: every class knows the other classes' kept sets as bit masks (exchanged through
+// LDS), so a lane can tell the payload position of each of its kept coefficients: its rank
+// among all kept coefficients of the chunk with a smaller index.  Values and indices are staged
+// in the chunk's row and leave with coalesced stores.
+#pragma once
+
+#include "fast_dct.hip.h"
+#include "generic_kernels.hip.h"
+#include "mfma_kernels.hip.h"
+#include "sort_network.hip.h"
+
+namespace deto {
+
+template <int S, int W>
+struct SplitGeom {
+    static_assert(W == 2 || W == 4, "two or four coefficient classes");
+    static_assert(S % (4 * W) == 0, "16-byte pieces per class");
+    static constexpr int Q = S / W;                 // coefficients per lane
+    static constexpr int kRow = S + 4;              // floats per LDS row (16 B of padding)
+    static constexpr int kTile = kWave * kRow;
+    static constexpr int kThreads = kWave * W;
+    static constexpr int NW = (Q + 31) / 32;        // mask words per lane
+    // payload staging inside a chunk's row: values at row[pos], indices at row[kIdx0 + pos]
+    // (k <= S/2); what a lane drops goes to a dump slot of its own past the tile
+    static constexpr int kIdx0 = S / 2 + 4;
+    static constexpr int kBufFloats = kTile + kThreads + kIdx0;
+};
+
+// index of coefficient m of class w: W*m + split_off(w)
+template <int W>
+__device__ __forceinline__ int split_off(int w) {
+    if constexpr (W == 2) return w;
+    else return ((w & 1) << 1) | (w >> 1);          // 0, 2, 1, 3
+}
+
+// Sort a bitonic sequence (first falling then rising, or the reverse) into descending order.
+template <int N>
+__device__ __forceinline__ void bitonic_merge_desc(uint32_t (&x)[N]) {
+    static_assert((N & (N - 1)) == 0, "power of two");
+#pragma unroll
+    for (int d = N / 2; d >= 1; d /= 2) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            if ((i & d) == 0) {
+                const uint32_t hi = max(x[i], x[i + d]);
+                const uint32_t lo = min(x[i], x[i + d]);
+                x[i] = hi;
+                x[i + d] = lo;
+            }
+        }
+    }
+}
+
+// k-th largest of the union of two descending lists of length L in LDS: i of the k largest
+// come from list 0 and k - i from list 1, i being the smallest count for which list0[i] (the
+// first one left out) does not exceed list1[k-i-1] (the last one taken).
+template <int L>
+__device__ __forceinline__ uint32_t kth_of_two_lists(const uint32_t* l0, const uint32_t* l1,
+                                                     int k) {
+    int lo = k > L ? k - L : 0, hi = k < L ? k : L;
+    constexpr int kSteps = L <= 63 ? 6 : (L <= 127 ? 7 : 8);   // ceil(log2(L + 1))
+#pragma unroll
+    for (int it = 0; it < kSteps; ++it) {
+        const bool open = lo < hi;
+        const int mid = (lo + hi) >> 1;
+        const uint32_t x0 = l0[open ? mid : 0];
+        const uint32_t x1 = l1[open ? k - mid - 1 : 0];
+        if (open) {
+            if (x0 > x1) lo = mid + 1;
+            else hi = mid;
+        }
+    }
+    const int n0 = lo, n1 = k - lo;
+    const uint32_t t0 = l0[n0 > 0 ? n0 - 1 : 0], t1 = l1[n1 > 0 ? n1 - 1 : 0];
+    return min(n0 > 0 ? t0 : 0xFFFFFFFFu, n1 > 0 ? t1 : 0xFFFFFFFFu);
+}
+
+// 2*word + (mag >= thr): a compare into the carry and an add with carry
+__device__ __forceinline__ uint32_t push_if_at_least(uint32_t word, uint32_t mag, uint32_t thr) {
+    asm("v_cmp_ge_u32 vcc, %1, %2\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc"
+        : "+v"(word)
+        : "v"(mag), "v"(thr)
+        : "vcc");
+    return word;
+}
+
+template <int Q>
+__device__ __forceinline__ void regs_to_lds(float* dst, const float (&v)[Q]) {
+#pragma unroll
+    for (int q = 0; q < Q / 4; ++q)
+        *reinterpret_cast<float4*>(dst + 4 * q) =
+            make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+}
+
+template <int Q>
+__device__ __forceinline__ void lds_to_regs(const float* src, float (&v)[Q]) {
+#pragma unroll
+    for (int q = 0; q < Q / 4; ++q) {
+        const float4 t = *reinterpret_cast<const float4*>(src + 4 * q);
+        v[4 * q] = t.x; v[4 * q + 1] = t.y; v[4 * q + 2] = t.z; v[4 * q + 3] = t.w;
+    }
+}
+
+// src[Q-1-i] for i < Q (a list read back to front)
+template <int Q>
+__device__ __forceinline__ void lds_to_regs_reversed(const float* src, float (&v)[Q]) {
+#pragma unroll
+    for (int q = 0; q < Q / 4; ++q) {
+        const float4 t = *reinterpret_cast<const float4*>(src + Q - 4 - 4 * q);
+        v[4 * q] = t.w; v[4 * q + 1] = t.z; v[4 * q + 2] = t.y; v[4 * q + 3] = t.x;
+    }
+}
+
+// ---- forward: the lane's class of coefficients (unscaled) from the chunk's row
+template <int S, int W>
+__device__ __forceinline__ void split_forward_local(const float* __restrict__ row, int w,
+                                                    float (&c)[S / W]) {
+    constexpr int Q = S / W;
+    if constexpr (W == 2) {
+        const float sgn = w ? -1.0f : 1.0f;
+#pragma unroll
+        for (int q = 0; q < Q / 4; ++q) {
+            const float4 a = *reinterpret_cast<const float4*>(row + 4 * q);
+            const float4 b = *reinterpret_cast<const float4*>(row + S - 4 - 4 * q);
+            c[4 * q] = fmaf(sgn, b.w, a.x);
+            c[4 * q + 1] = fmaf(sgn, b.z, a.y);
+            c[4 * q + 2] = fmaf(sgn, b.y, a.z);
+            c[4 * q + 3] = fmaf(sgn, b.x, a.w);
+        }
+        if (w == 0) FastDct<Q>::dct2(c);
+        else FastDct<Q>::dct4(c);
+    } else {
+        static_assert(S == 256, "four classes: chunk 256");
+        // four elements at a time: x[n], x[255-n], x[127-n], x[128+n] for n = 4q .. 4q+3
+        static_for<0, Q / 4>([&](auto q) {
+            const float4 f0 = *reinterpret_cast<const float4*>(row + 4 * q);
+            const float4 r1 = *reinterpret_cast<const float4*>(row + 252 - 4 * q);
+            const float4 r2 = *reinterpret_cast<const float4*>(row + 124 - 4 * q);
+            const float4 f3 = *reinterpret_cast<const float4*>(row + 128 + 4 * q);
+            const float x0[4] = {f0.x, f0.y, f0.z, f0.w};
+            const float x1[4] = {r1.w, r1.z, r1.y, r1.x};
+            const float x2[4] = {r2.w, r2.z, r2.y, r2.x};
+            const float x3[4] = {f3.x, f3.y, f3.z, f3.w};
+            static_for<0, 4>([&](auto i) {
+                constexpr int j = 4 * q + i;
+                if (w < 2) {
+                    const float sgn = w ? -1.0f : 1.0f;
+                    c[j] = fmaf(sgn, x2[i] + x3[i], x0[i] + x1[i]);
+                } else {
+                    // rotations of the DCT-IV of w (length 128): pair (w_j, w_{127-j})
+                    constexpr float cs = Rot<128, j>::c, sn = Rot<128, j>::s;
+                    const float wj = x0[i] - x1[i], wr = x2[i] - x3[i];
+                    const float av = fmaf(wj, cs, wr * sn);
+                    const float bv = fmaf(wr, cs, -(wj * sn));
+                    c[j] = (w == 2) ? av : ((j % 2) ? -bv : bv);
+                }
+            });
+        });
+        if (w == 1) FastDct<Q>::dct4(c);
+        else FastDct<Q>::dct2(c);
+    }
+}
+
+// W = 4: classes 2 and 3 hold A and B; after this class 2 holds the coefficients 4m+1 and
+// class 3 the coefficients 4m+3.  The tile rows must be free; contains workgroup barriers,
+// every wavefront calls it.
+template <int S>
+__device__ __forceinline__ void split_forward_exchange(float* __restrict__ row, int w,
+                                                       float (&c)[S / 4]) {
+    constexpr int Q = S / 4;
+    if (w >= 2) regs_to_lds<Q>(row + (w - 2) * Q, c);
+    __syncthreads();
+    if (w == 2) {
+        // c[l] = A[l] + B[64-l] for l >= 1
+        float br[Q];
+        lds_to_regs_reversed<Q>(row + Q, br);        // br[i] = B[63-i]
+        static_for<1, Q>([&](auto l) { c[l] += br[l - 1]; });
+    } else if (w == 3) {
+        // c[l] = A[l+1] - B[63-l] for l < 63, c[63] = -B[0]
+        float a[Q], d[Q];
+        lds_to_regs<Q>(row, a);
+        static_for<0, Q - 1>([&](auto l) { d[l] = a[l + 1] - c[Q - 1 - l]; });
+        d[Q - 1] = -c[0];
+#pragma unroll
+        for (int l = 0; l < Q; ++l) c[l] = d[l];
+    }
+    __syncthreads();
+}
+
+// ---- inverse: the classes' scaled coefficients back into the rows as [E | O] (W = 2) or
+// [E (128) | O even (64) | O odd (64)] (W = 4), ready for split_output.  Contains workgroup
+// barriers; the rows must be free on entry.
+template <int S, int W>
+__device__ __forceinline__ void split_inverse_to_rows(float* __restrict__ row, int w,
+                                                      float (&c)[S / W]) {
+    constexpr int Q = S / W;
+    if constexpr (W == 2) {
+        if (w == 0) FastDct<Q>::dct3(c);
+        else FastDct<Q>::dct4(c);
+        regs_to_lds<Q>(row + w * Q, c);
+        __syncthreads();
+    } else {
+        // classes 2 and 3 exchange their coefficients: v[j] = coefficient 2j+1 of the chunk,
+        // v[2l] = class 2's c[l], v[2l+1] = class 3's c[l]
+        if (w >= 2) regs_to_lds<Q>(row + 128 + (w - 2) * Q, c);
+        __syncthreads();
+        if (w == 0) {
+            FastDct<Q>::dct3(c);
+        } else if (w == 1) {
+            FastDct<Q>::dct4(c);
+        } else {
+            // four pairs' worth of the other class at a time, forwards and reversed
+            const float* other = row + 128 + (3 - w) * Q;
+            float r[Q];
+            static_for<0, Q / 4>([&](auto q) {
+                const float4 fo = *reinterpret_cast<const float4*>(other + 4 * q);
+                const float4 ro = *reinterpret_cast<const float4*>(other + Q - 4 - 4 * q);
+                const float o[4] = {fo.x, fo.y, fo.z, fo.w};          // other[l]
+                const float orv[4] = {ro.w, ro.z, ro.y, ro.x};        // other[63-l]
+                static_for<0, 8>([&](auto i) {
+                    constexpr int j = 8 * q + i;
+                    constexpr int l = j / 2, li = l - 4 * q;
+                    constexpr float cs = Rot<128, j>::c, sn = Rot<128, j>::s;
+                    // pair (v[j], v[127-j]): j even: (c2[l], c3[63-l]); j odd: (c3[l], c2[63-l])
+                    float pj, qj;
+                    if (w == 2) {
+                        pj = (j % 2) ? o[li] : c[l];
+                        qj = (j % 2) ? c[Q - 1 - l] : orv[li];
+                    } else {
+                        pj = (j % 2) ? c[l] : o[li];
+                        qj = (j % 2) ? orv[li] : c[Q - 1 - l];
+                    }
+                    const float av = fmaf(pj, cs, qj * sn);
+                    const float bv = fmaf(qj, cs, -(pj * sn));
+                    r[j] = (w == 2) ? av : ((j % 2) ? -bv : bv);
+                });
+            });
+            FastDct<Q>::dct2(r);
+#pragma unroll
+            for (int j = 0; j < Q; ++j) c[j] = r[j];
+        }
+        __syncthreads();
+        // EE | EO | A | B
+        regs_to_lds<Q>(row + w * Q, c);
+        __syncthreads();
+        float f[Q];
+        if (w == 0) {
+            float eo[Q];
+            lds_to_regs<Q>(row + Q, eo);
+#pragma unroll
+            for (int i = 0; i < Q; ++i) f[i] = c[i] + eo[i];            // E[i]
+        } else if (w == 1) {
+            float ee[Q];
+            lds_to_regs_reversed<Q>(row, ee);                            // ee[m] = EE[63-m]
+            // E[64+m] = E[127-(63-m)] = EE[63-m] - EO[63-m]
+#pragma unroll
+            for (int m = 0; m < Q; ++m) f[m] = ee[m] - c[Q - 1 - m];
+        } else if (w == 2) {
+            float br[Q];
+            lds_to_regs_reversed<Q>(row + 3 * Q, br);                    // br[i] = B[63-i]
+            f[0] = c[0];
+            static_for<1, Q>([&](auto l) { f[l] = c[l] + br[l - 1]; });   // O[2l]
+        } else {
+            float a[Q];
+            lds_to_regs<Q>(row + 2 * Q, a);
+            static_for<0, Q - 1>([&](auto l) { f[l] = a[l + 1] - c[Q - 1 - l]; });   // O[2l+1]
+            f[Q - 1] = -c[0];
+        }
+        __syncthreads();
+        regs_to_lds<Q>(row + w * Q, f);
+        __syncthreads();
+    }
+}
+
+// four consecutive elements col .. col+3 of the chunk whose row was left by
+// split_inverse_to_rows
+template <int S, int W>
+__device__ __forceinline__ float4 split_output(const float* __restrict__ row, int col) {
+    constexpr int H = S / 2;
+    const bool upper = col >= H;
+    const int n0 = upper ? S - 4 - col : col;     // elements col+i mirror n0+3-i when upper
+    const float4 e = *reinterpret_cast<const float4*>(row + n0);
+    float4 o;
+    if constexpr (W == 2) {
+        o = *reinterpret_cast<const float4*>(row + H + n0);
+    } else {
+        const float2 oe = *reinterpret_cast<const float2*>(row + H + n0 / 2);
+        const float2 oo = *reinterpret_cast<const float2*>(row + H + H / 2 + n0 / 2);
+        o = make_float4(oe.x, oo.x, oe.y, oo.y);
+    }
+    if (!upper) return make_float4(e.x + o.x, e.y + o.y, e.z + o.z, e.w + o.w);
+    return make_float4(e.w - o.w, e.z - o.z, e.y - o.y, e.x - o.x);
+}
+
+// Compress half (top-k, DCT domain, fp32 values + int32 indices, k <= S/2) on full tiles of 64
+// chunks; the chunks past the last full tile go one per surplus workgroup to the general code.
+template <int S, int W, bool GRAD_BF16>
+__global__ __launch_bounds__(kWave * W) void compress_split(
+    KParams p, int64_t tiles, int64_t n, int64_t n_chunks, const void* __restrict__ grad,
+    float* __restrict__ mom, int32_t* __restrict__ idx_out, float* __restrict__ val_out,
+    float* __restrict__ coeff_dbg) {
+    using G = SplitGeom<S, W>;
+    constexpr int Q = G::Q, kRow = G::kRow, NW = G::NW, kThreads = G::kThreads;
+    constexpr int kIdx0 = G::kIdx0, kTile = G::kTile;
+    __shared__ __attribute__((aligned(16))) float buf[G::kBufFloats];
+    __shared__ uint32_t s_mask[kWave][W][NW];    // kept sets: chunk, class, word
+    __shared__ int s_cnt[kWave][W];
+    __shared__ unsigned long long s_tie;         // chunks of the tile that took the tie pass
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int k = p.k;
+
+    const int64_t tile = blockIdx.x;
+    if (tile >= tiles) {
+        // surplus workgroups: one chunk each on the general per-chunk code (one wavefront)
+        static_assert(sizeof(GenericCompressSmem) <= sizeof(buf), "tail code borrows the tile");
+        if (tid >= kWave) return;
+        compress_generic_chunks<GRAD_BF16>(p, n, tiles * kWave + (tile - tiles), n_chunks,
+                                           gridDim.x - tiles,
+                                           *reinterpret_cast<GenericCompressSmem*>(buf), grad, mom,
+                                           idx_out, val_out, coeff_dbg);
+        return;
+    }
+    const int64_t base = tile * static_cast<int64_t>(kWave * S);
+    const int64_t chunk0 = tile * kWave;
+    float* row = &buf[lane * kRow];
+    if (tid == 0) s_tie = 0ull;
+
+    // ---- m1 = beta*m + g for the tile's 64*S contiguous elements, coalesced, into the rows
+    {
+        constexpr int kIt = Q / 4;               // 16-byte pieces per thread
+#pragma unroll
+        for (int it = 0; it < kIt; ++it) {
+            const int e4 = 4 * (tid + kThreads * it);
+            const int r = e4 / S, col = e4 - r * S;
+            const float4 m = ld_f4<false>(mom + base + e4);
+            float4 g;
+            if constexpr (GRAD_BF16) {
+                const uint2 gb = ld_u2<false>(static_cast<const uint16_t*>(grad) + base + e4);
+                g = make_float4(__uint_as_float(gb.x << 16), __uint_as_float(gb.x & 0xFFFF0000u),
+                                __uint_as_float(gb.y << 16), __uint_as_float(gb.y & 0xFFFF0000u));
+            } else {
+                g = ld_f4<false>(static_cast<const float*>(grad) + base + e4);
+            }
+            *reinterpret_cast<float4*>(&buf[r * kRow + col]) =
+                make_float4(fmaf(p.beta, m.x, g.x), fmaf(p.beta, m.y, g.y),
+                            fmaf(p.beta, m.z, g.z), fmaf(p.beta, m.w, g.w));
+        }
+    }
+    __syncthreads();
+
+    // ---- the lane's coefficients c[m] = coefficient W*m + off of chunk `lane`
+    const int off = split_off<W>(w);
+    float c[Q];
+    split_forward_local<S, W>(row, w, c);
+    __syncthreads();                              // every class has read the chunk: rows free
+    if constexpr (W == 4) split_forward_exchange<S>(row, w, c);
+    c[0] *= (w == 0) ? p.alpha0 : p.alpha;
+#pragma unroll
+    for (int m = 1; m < Q; ++m) c[m] *= p.alpha;
+    if (coeff_dbg) {
+        float* dbg = coeff_dbg + (chunk0 + lane) * S + off;
+#pragma unroll
+        for (int m = 0; m < Q; ++m) dbg[W * m] = c[m];
+    }
+
+    // ---- k-th largest magnitude T of the chunk
+    uint32_t T;
+    {
+        uint32_t a[Q];
+#pragma unroll
+        for (int m = 0; m < Q; ++m) a[m] = __float_as_uint(c[m]) & 0x7FFFFFFFu;
+        sort_desc<Q>(a);
+        uint32_t* lists = reinterpret_cast<uint32_t*>(row);
+#pragma unroll
+        for (int q = 0; q < Q / 4; ++q)
+            *reinterpret_cast<uint4*>(lists + w * Q + 4 * q) =
+                make_uint4(a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]);
+        __syncthreads();
+        if constexpr (W == 4) {
+            // classes (0,1) and (2,3): the larger half of the two lists' union to the even
+            // class, the smaller half to the odd one; each half is bitonic and is sorted in place
+            const uint32_t* partner = lists + (w ^ 1) * Q;
+#pragma unroll
+            for (int q = 0; q < Q / 4; ++q) {
+                const uint4 t = *reinterpret_cast<const uint4*>(partner + Q - 4 - 4 * q);
+                const uint32_t pr[4] = {t.w, t.z, t.y, t.x};        // partner[Q-1-i]
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    a[4 * q + i] = (w & 1) ? min(a[4 * q + i], pr[i]) : max(a[4 * q + i], pr[i]);
+            }
+            bitonic_merge_desc<Q>(a);
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < Q / 4; ++q)
+                *reinterpret_cast<uint4*>(lists + w * Q + 4 * q) =
+                    make_uint4(a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]);
+            __syncthreads();
+            T = kth_of_two_lists<2 * Q>(lists, lists + 2 * Q, k);
+        } else {
+            T = kth_of_two_lists<Q>(lists, lists + Q, k);
+        }
+    }
+
+    // ---- kept sets: magnitude >= T, unless more than k magnitudes reach T (a tie at the
+    // threshold): then only those above T, and the chunk goes through the whole-wavefront
+    // pass that adds the lowest indices among the equals
+    uint32_t own[NW];
+    auto mark = [&](uint32_t thr) -> int {
+#pragma unroll
+        for (int j = 0; j < NW; ++j) own[j] = 0u;
+        static_for<0, Q>([&](auto I) {
+            constexpr int m = Q - 1 - I;   // descending so that shifting lands bit m at m
+            own[m / 32] = push_if_at_least(own[m / 32], __float_as_uint(c[m]) & 0x7FFFFFFFu, thr);
+        });
+        int cnt = 0;
+#pragma unroll
+        for (int j = 0; j < NW; ++j) {
+            cnt += __popc(own[j]);
+            s_mask[lane][w][j] = own[j];
+        }
+        s_cnt[lane][w] = cnt;
+        __syncthreads();                          // also: every class is done with the lists
+        int total = 0;
+#pragma unroll
+        for (int j = 0; j < W; ++j) total += s_cnt[lane][j];
+        return total;
+    };
+    uint32_t thr_gt = T, thr_eq = 0xFFFFFFFFu;
+    int need = 0;
+    {
+        const int cnt = mark(T);
+        const bool tie = cnt != k;
+        if (__syncthreads_or(tie ? 1 : 0)) {
+            if (tie) {
+                thr_gt = T + 1u;     // <= 0x80000000: no magnitude reaches that
+                thr_eq = T;
+            }
+            const int above = mark(thr_gt);
+            if (tie) need = k - above;
+            // the tied chunks' coefficients in natural order in their rows, for wavefront 0
+#pragma unroll
+            for (int m = 0; m < Q; ++m) row[W * m + off] = c[m];
+            __syncthreads();
+            if (w == 0) {
+                const unsigned long long tl = __ballot(need != 0);
+                if (lane == 0) s_tie = tl;
+                emit_tied_chunks<S / 32, kWave>(buf, p, lane, need, thr_gt, thr_eq, chunk0, idx_out,
+                                                val_out, nullptr);
+            }
+            __syncthreads();
+            if (need != 0) {
+#pragma unroll
+                for (int m = 0; m < Q; ++m) c[m] = row[W * m + off];   // alpha_j * remainder
+            }
+            __syncthreads();
+        }
+    }
+
+    // ---- payload staging, remainder in (settled chunks).  The position of coefficient m of
+    // this class is the number of kept coefficients of the chunk with a smaller index: the
+    // class's own bits below m, and of another class w' its bits below m (+ 1 if that class's
+    // offset is the smaller one).
+    if (need == 0) {
+        // the other classes' bits lined up with this class's steps, and counted into the start
+        uint32_t plane0[NW], plane1[NW];
+        uint32_t start = 0u;
+#pragma unroll
+        for (int j = 0; j < NW; ++j) plane0[j] = plane1[j] = 0u;
+#pragma unroll
+        for (int o = 1; o < W; ++o) {
+            const int wo = (w + o) % W;
+            const uint32_t adj = split_off<W>(wo) < off ? 1u : 0u;
+            uint32_t ow[NW];
+#pragma unroll
+            for (int j = 0; j < NW; ++j) ow[j] = s_mask[lane][wo][j];
+            start += ow[0] & adj;
+#pragma unroll
+            for (int j = 0; j < NW; ++j) {
+                const uint32_t up = (j + 1 < NW) ? ow[j + 1] : 0u;
+                const uint32_t sh = __builtin_amdgcn_alignbit(up, ow[j], adj);
+                // add one-bit numbers into a two-bit counter per position
+                const uint32_t carry = plane0[j] & sh;
+                plane0[j] ^= sh;
+                plane1[j] |= carry;
+            }
+        }
+        char* lds = reinterpret_cast<char*>(buf);
+        const uint32_t dump = static_cast<uint32_t>(sizeof(float)) * (kTile + tid);
+        uint32_t at = static_cast<uint32_t>(sizeof(float)) * (lane * kRow + start);
+        const int idx0 = off;
+        static_for<0, Q>([&](auto m) {
+            const uint32_t kb = (own[m / 32] >> (m % 32)) & 1u;
+            const uint32_t b0 = (plane0[m / 32] >> (m % 32)) & 1u;
+            const bool keep = kb != 0u;
+            const uint32_t a = keep ? at : dump;
+            *reinterpret_cast<float*>(lds + a) = c[m];
+            *reinterpret_cast<float*>(lds + a + sizeof(float) * kIdx0) =
+                __int_as_float(idx0 + W * m);
+            at += 4u * kb + 4u * b0;
+            if constexpr (W == 4) at += 8u * ((plane1[m / 32] >> (m % 32)) & 1u);
+            c[m] = (keep ? 0.0f : c[m]) * ((m == 0 && w == 0) ? p.alpha0 : p.alpha);
+        });
+    }
+    __syncthreads();
+    {
+        // the tile's 64*k entries are contiguous in both payload arrays
+        const uint32_t magic = entry_magic(k);
+        const unsigned long long tie_chunks = s_tie;
+        float* vo = val_out + chunk0 * k;
+        int32_t* io = idx_out + chunk0 * k;
+        if (k % 4 == 0) {
+            const int quads = 16 * k;                      // 16-byte pieces of the tile
+            for (int q = tid; q < quads; q += kThreads) {
+                const uint32_t e = 4u * static_cast<uint32_t>(q);
+                const uint32_t r = __umulhi(e, magic);     // chunk of the tile, k >= 4
+                const uint32_t j = e - r * static_cast<uint32_t>(k);
+                if ((tie_chunks >> r) & 1ull) continue;    // written by the tie pass
+                const float* src = &buf[r * kRow + j];
+                st_f4<false>(vo + e, *reinterpret_cast<const float4*>(src));
+                const float4 iv = *reinterpret_cast<const float4*>(src + kIdx0);
+                *reinterpret_cast<int4*>(io + e) =
+                    make_int4(__float_as_int(iv.x), __float_as_int(iv.y), __float_as_int(iv.z),
+                              __float_as_int(iv.w));
+            }
+        } else {
+            // four entries of a lane could straddle two chunks (and the arrays need not be
+            // 16-byte aligned): one entry per lane
+            for (uint32_t e = tid; e < static_cast<uint32_t>(kWave * k); e += kThreads) {
+                const uint32_t r = (k == 1) ? e : __umulhi(e, magic);
+                const uint32_t j = e - r * static_cast<uint32_t>(k);
+                if ((tie_chunks >> r) & 1ull) continue;
+                const float* src = &buf[r * kRow + j];
+                vo[e] = src[0];
+                io[e] = __float_as_int(src[kIdx0]);
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- new momentum = inverse transform of the remainder
+    split_inverse_to_rows<S, W>(row, w, c);
+    {
+        constexpr int kIt = Q / 4;
+#pragma unroll 4
+        for (int it = 0; it < kIt; ++it) {
+            const int e4 = 4 * (tid + kThreads * it);
+            const int r = e4 / S, col = e4 - r * S;
+            st_f4<false>(mom + base + e4, split_output<S, W>(&buf[r * kRow], col));
+        }
+    }
+}
+
+}  // namespace deto

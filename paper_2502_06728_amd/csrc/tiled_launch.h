@@ -109,4 +109,17 @@ inline int64_t launch_compress_pair(const CompressLaunch& a) {
 }
 int64_t launch_decompress_pair(const DecompressLaunch& a);
 
+// Lane per chunk, wavefront per coefficient class (split_kernels.hip.h): tiles of 64 chunks,
+// fp32 + int32 payloads with k <= s/2.  Same return convention.
+int64_t launch_compress_split_96(const CompressLaunch& a);
+int64_t launch_compress_split_128(const CompressLaunch& a);
+int64_t launch_compress_split_192(const CompressLaunch& a);
+int64_t launch_compress_split_256(const CompressLaunch& a);
+inline int64_t launch_compress_split(const CompressLaunch& a) {
+    int64_t c = launch_compress_split_96(a);
+    if (!c) c = launch_compress_split_128(a);
+    if (!c) c = launch_compress_split_192(a);
+    return c ? c : launch_compress_split_256(a);
+}
+
 }  // namespace deto
