@@ -365,7 +365,8 @@ int decompress_impl(const deto_config* cfg, const deto_adamw* opt, int64_t n, in
             if (rc) return rc;
             c0 = C;   // the tail chunks rode along in the same launch
         } else {
-            c0 = deto::launch_decompress_pair(a);
+            c0 = deto::launch_decompress_split(a);
+            if (c0 == 0) c0 = deto::launch_decompress_pair(a);
             if (c0 == 0) c0 = deto::launch_decompress_mfma(a);
             if (c0 > 0) {
                 rc = launched();

@@ -1,4 +1,4 @@
-// Lane-per-chunk, wavefront-per-coefficient-class compress kernels (chunk size 192: 2 classes;
+// Lane-per-chunk, wavefront-per-coefficient-class compress kernels (chunk size 192: 4 classes;
 // top-k selection, fp32 values + int32 indices, k <= 96).
 #include "split_kernels.hip.h"
 #include "tiled_launch.h"
@@ -17,13 +17,13 @@ int64_t launch_compress_split_192(const CompressLaunch& a) {
     const int64_t grid64 = tiles + (a.n_chunks - tiles * kWave);
     if (tiles <= 0 || grid64 > 0x7FFFFFFF) return 0;
     const unsigned grid = static_cast<unsigned>(grid64);
-    constexpr int kThreads = SplitGeom<192, 2>::kThreads;
+    constexpr int kThreads = SplitGeom<192, 4>::kThreads;
     if (a.grad_bf16)
-        compress_split<192, 2, true><<<grid, kThreads, 0, a.stream>>>(
+        compress_split<192, 4, true><<<grid, kThreads, 0, a.stream>>>(
             p, tiles, a.n, a.n_chunks, a.grad, a.mom, static_cast<int32_t*>(a.idx),
             static_cast<float*>(a.val), a.coeff_dbg);
     else
-        compress_split<192, 2, false><<<grid, kThreads, 0, a.stream>>>(
+        compress_split<192, 4, false><<<grid, kThreads, 0, a.stream>>>(
             p, tiles, a.n, a.n_chunks, a.grad, a.mom, static_cast<int32_t*>(a.idx),
             static_cast<float*>(a.val), a.coeff_dbg);
     return a.n_chunks;   // the tail chunks ride along

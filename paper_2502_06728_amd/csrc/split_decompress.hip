@@ -1,0 +1,40 @@
+// Lane-per-chunk, wavefront-per-coefficient-class decompress-and-update kernels (chunk sizes 192
+// and 256: four classes; transmitted indices, fp32 values + int32 indices; plain SGD update or
+// Decoupled AdamW).
+#include "split_kernels.hip.h"
+#include "tiled_launch.h"
+
+namespace deto {
+
+int64_t launch_decompress_split(const DecompressLaunch& a) {
+    const KParams& p = a.p;
+#ifdef DETO_TILED_ONLY_64_32
+    return 0;
+#else
+    if (!a.idx || !p.use_dct || p.val_dtype != 0 || p.idx_u8) return 0;
+    const int64_t tiles = (a.n / p.s) / kWave;
+    // one workgroup per tile plus one per chunk past the last full tile
+    const int64_t grid64 = tiles + (a.n_chunks - tiles * kWave);
+    if (tiles <= 0 || grid64 > 0x7FFFFFFF) return 0;
+    const unsigned grid = static_cast<unsigned>(grid64);
+    const int32_t* idx = static_cast<const int32_t*>(a.idx);
+    const float* val = static_cast<const float*>(a.val);
+#define X(S)                                                                                    \
+    if (p.s == S) {                                                                             \
+        if (a.param_bf16)                                                                       \
+            decompress_split<S, 4, true><<<grid, 4 * kWave, 0, a.stream>>>(                     \
+                p, tiles, a.n, a.n_chunks, idx, a.idx_stride, val, a.val_stride, a.params,     \
+                a.adam, a.presign_dbg);                                                         \
+        else                                                                                    \
+            decompress_split<S, 4, false><<<grid, 4 * kWave, 0, a.stream>>>(                    \
+                p, tiles, a.n, a.n_chunks, idx, a.idx_stride, val, a.val_stride, a.params,     \
+                a.adam, a.presign_dbg);                                                         \
+        return a.n_chunks;   /* the tail chunks ride along */                                   \
+    }
+    X(192) X(256)
+#undef X
+    return 0;
+#endif
+}
+
+}  // namespace deto

@@ -8,16 +8,16 @@
 // of the chunk's coefficients, S/W of them, in its lanes' registers.  Every wavefront runs
 // straight-line code with no divergence, and the classes meet in LDS at workgroup barriers.
 //
-//   W = 2 (chunk 96, 128, 192), first level of the DCT-II recursion of fast_dct.hip.h:
+//   W = 2 (chunk 96, 128), first level of the DCT-II recursion of fast_dct.hip.h:
 //     class 0: u_n = x_n + x_{S-1-n}, coefficients 2m   = dct2_{S/2}(u)
 //     class 1: w_n = x_n - x_{S-1-n}, coefficients 2m+1 = dct4_{S/2}(w)
-//   W = 4 (chunk 256), two levels:
-//     class 0: coefficients 4m   = dct2_64(u_n + u_{127-n})
-//     class 1: coefficients 4m+2 = dct4_64(u_n - u_{127-n})
-//     class 2, 3: the DCT-IV of w (length 128) by plane rotations into two DCT-IIs of length
-//              64, A (class 2) and B (class 3); after an exchange through LDS class 2 holds the
-//              coefficients 4m+1 = A_m + B_{64-m} and class 3 the coefficients
-//              4m+3 = A_{m+1} - B_{63-m}.
+//   W = 4 (chunk 192, 256), two levels, Q = S/4:
+//     class 0: coefficients 4m   = dct2_Q(u_n + u_{S/2-1-n})
+//     class 1: coefficients 4m+2 = dct4_Q(u_n - u_{S/2-1-n})
+//     class 2, 3: the DCT-IV of w (length S/2) by plane rotations into two DCT-IIs of length
+//              Q, A (class 2) and B (class 3); after an exchange through LDS class 2 holds the
+//              coefficients 4m+1 = A_m + B_{Q-m} and class 3 the coefficients
+//              4m+3 = A_{m+1} - B_{Q-1-m}.
 // The inverse runs the same splits backwards (DCT-III / DCT-IV).
 //
 // Selection (top-k, any k at run time): every lane sorts the magnitudes of its S/W coefficients
@@ -160,13 +160,13 @@ __device__ __forceinline__ void split_forward_local(const float* __restrict__ ro
         if (w == 0) FastDct<Q>::dct2(c);
         else FastDct<Q>::dct4(c);
     } else {
-        static_assert(S == 256, "four classes: chunk 256");
-        // four elements at a time: x[n], x[255-n], x[127-n], x[128+n] for n = 4q .. 4q+3
+        constexpr int H = S / 2;
+        // four elements at a time: x[n], x[S-1-n], x[H-1-n], x[H+n] for n = 4q .. 4q+3
         static_for<0, Q / 4>([&](auto q) {
             const float4 f0 = *reinterpret_cast<const float4*>(row + 4 * q);
-            const float4 r1 = *reinterpret_cast<const float4*>(row + 252 - 4 * q);
-            const float4 r2 = *reinterpret_cast<const float4*>(row + 124 - 4 * q);
-            const float4 f3 = *reinterpret_cast<const float4*>(row + 128 + 4 * q);
+            const float4 r1 = *reinterpret_cast<const float4*>(row + S - 4 - 4 * q);
+            const float4 r2 = *reinterpret_cast<const float4*>(row + H - 4 - 4 * q);
+            const float4 f3 = *reinterpret_cast<const float4*>(row + H + 4 * q);
             const float x0[4] = {f0.x, f0.y, f0.z, f0.w};
             const float x1[4] = {r1.w, r1.z, r1.y, r1.x};
             const float x2[4] = {r2.w, r2.z, r2.y, r2.x};
@@ -177,8 +177,8 @@ __device__ __forceinline__ void split_forward_local(const float* __restrict__ ro
                     const float sgn = w ? -1.0f : 1.0f;
                     c[j] = fmaf(sgn, x2[i] + x3[i], x0[i] + x1[i]);
                 } else {
-                    // rotations of the DCT-IV of w (length 128): pair (w_j, w_{127-j})
-                    constexpr float cs = Rot<128, j>::c, sn = Rot<128, j>::s;
+                    // rotations of the DCT-IV of w (length H): pair (w_j, w_{H-1-j})
+                    constexpr float cs = Rot<H, j>::c, sn = Rot<H, j>::s;
                     const float wj = x0[i] - x1[i], wr = x2[i] - x3[i];
                     const float av = fmaf(wj, cs, wr * sn);
                     const float bv = fmaf(wr, cs, -(wj * sn));
@@ -201,12 +201,12 @@ __device__ __forceinline__ void split_forward_exchange(float* __restrict__ row, 
     if (w >= 2) regs_to_lds<Q>(row + (w - 2) * Q, c);
     __syncthreads();
     if (w == 2) {
-        // c[l] = A[l] + B[64-l] for l >= 1
+        // c[l] = A[l] + B[Q-l] for l >= 1
         float br[Q];
-        lds_to_regs_reversed<Q>(row + Q, br);        // br[i] = B[63-i]
+        lds_to_regs_reversed<Q>(row + Q, br);        // br[i] = B[Q-1-i]
         static_for<1, Q>([&](auto l) { c[l] += br[l - 1]; });
     } else if (w == 3) {
-        // c[l] = A[l+1] - B[63-l] for l < 63, c[63] = -B[0]
+        // c[l] = A[l+1] - B[Q-1-l] for l < Q-1, c[Q-1] = -B[0]
         float a[Q], d[Q];
         lds_to_regs<Q>(row, a);
         static_for<0, Q - 1>([&](auto l) { d[l] = a[l + 1] - c[Q - 1 - l]; });
@@ -232,26 +232,29 @@ __device__ __forceinline__ void split_inverse_to_rows(float* __restrict__ row, i
     } else {
         // classes 2 and 3 exchange their coefficients: v[j] = coefficient 2j+1 of the chunk,
         // v[2l] = class 2's c[l], v[2l+1] = class 3's c[l]
-        if (w >= 2) regs_to_lds<Q>(row + 128 + (w - 2) * Q, c);
+        constexpr int H = S / 2;
+        if (w >= 2) regs_to_lds<Q>(row + H + (w - 2) * Q, c);
         __syncthreads();
         if (w == 0) {
             FastDct<Q>::dct3(c);
         } else if (w == 1) {
             FastDct<Q>::dct4(c);
         } else {
-            // four pairs' worth of the other class at a time, forwards and reversed
-            const float* other = row + 128 + (3 - w) * Q;
+            // the Q rotation pairs, eight at a time: four entries of the other class from the
+            // front and four from the back
+            static_assert(Q % 8 == 0, "whole blocks of eight pairs");
+            const float* other = row + H + (3 - w) * Q;
             float r[Q];
-            static_for<0, Q / 4>([&](auto q) {
+            static_for<0, Q / 8>([&](auto q) {
                 const float4 fo = *reinterpret_cast<const float4*>(other + 4 * q);
                 const float4 ro = *reinterpret_cast<const float4*>(other + Q - 4 - 4 * q);
                 const float o[4] = {fo.x, fo.y, fo.z, fo.w};          // other[l]
-                const float orv[4] = {ro.w, ro.z, ro.y, ro.x};        // other[63-l]
+                const float orv[4] = {ro.w, ro.z, ro.y, ro.x};        // other[Q-1-l]
                 static_for<0, 8>([&](auto i) {
                     constexpr int j = 8 * q + i;
                     constexpr int l = j / 2, li = l - 4 * q;
-                    constexpr float cs = Rot<128, j>::c, sn = Rot<128, j>::s;
-                    // pair (v[j], v[127-j]): j even: (c2[l], c3[63-l]); j odd: (c3[l], c2[63-l])
+                    constexpr float cs = Rot<H, j>::c, sn = Rot<H, j>::s;
+                    // pair (v[j], v[H-1-j]): j even: (c2[l], c3[Q-1-l]); j odd: (c3[l], c2[Q-1-l])
                     float pj, qj;
                     if (w == 2) {
                         pj = (j % 2) ? o[li] : c[l];
@@ -411,22 +414,39 @@ __global__ __launch_bounds__(kWave * W) void compress_split(
         __syncthreads();
         if constexpr (W == 4) {
             // classes (0,1) and (2,3): the larger half of the two lists' union to the even
-            // class, the smaller half to the odd one; each half is bitonic and is sorted in place
+            // class, the smaller half to the odd one; each half is bitonic and is sorted in
+            // place.  Lists are padded with zeros (the smallest magnitude) to a power of two
+            // QP; the even class ends up with the QP largest, the odd one with the other
+            // 2Q - QP followed by padding, so the pair's merged list has 2Q entries again.
+            constexpr int QP = SortNet<Q>::P;
             const uint32_t* partner = lists + (w ^ 1) * Q;
-#pragma unroll
-            for (int q = 0; q < Q / 4; ++q) {
-                const uint4 t = *reinterpret_cast<const uint4*>(partner + Q - 4 - 4 * q);
-                const uint32_t pr[4] = {t.w, t.z, t.y, t.x};        // partner[Q-1-i]
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    a[4 * q + i] = (w & 1) ? min(a[4 * q + i], pr[i]) : max(a[4 * q + i], pr[i]);
-            }
-            bitonic_merge_desc<Q>(a);
+            uint32_t x[QP];
+            static_for<0, QP / 4>([&](auto q) {
+                constexpr int j0 = QP - 4 - 4 * q;               // partner's entries j0 .. j0+3
+                uint4 t = make_uint4(0u, 0u, 0u, 0u);
+                if constexpr (j0 < Q) t = *reinterpret_cast<const uint4*>(partner + j0);
+                const uint32_t theirs[4] = {t.w, t.z, t.y, t.x};  // partner[QP-1-i], i = 4q ..
+                static_for<0, 4>([&](auto e) {
+                    constexpr int i = 4 * q + e;
+                    uint32_t mine = 0u;
+                    if constexpr (i < Q) mine = a[i];
+                    x[i] = (w & 1) ? min(mine, theirs[e]) : max(mine, theirs[e]);
+                });
+            });
+            bitonic_merge_desc<QP>(x);
             __syncthreads();
+            uint32_t* merged = lists + (w >> 1) * 2 * Q + ((w & 1) ? QP : 0);
+            if ((w & 1) == 0) {
 #pragma unroll
-            for (int q = 0; q < Q / 4; ++q)
-                *reinterpret_cast<uint4*>(lists + w * Q + 4 * q) =
-                    make_uint4(a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]);
+                for (int q = 0; q < QP / 4; ++q)
+                    *reinterpret_cast<uint4*>(merged + 4 * q) =
+                        make_uint4(x[4 * q], x[4 * q + 1], x[4 * q + 2], x[4 * q + 3]);
+            } else {
+#pragma unroll
+                for (int q = 0; q < (2 * Q - QP) / 4; ++q)
+                    *reinterpret_cast<uint4*>(merged + 4 * q) =
+                        make_uint4(x[4 * q], x[4 * q + 1], x[4 * q + 2], x[4 * q + 3]);
+            }
             __syncthreads();
             T = kth_of_two_lists<2 * Q>(lists, lists + 2 * Q, k);
         } else {
@@ -579,6 +599,209 @@ __global__ __launch_bounds__(kWave * W) void compress_split(
             const int e4 = 4 * (tid + kThreads * it);
             const int r = e4 / S, col = e4 - r * S;
             st_f4<false>(mom + base + e4, split_output<S, W>(&buf[r * kRow], col));
+        }
+    }
+}
+
+// Decompress-and-update half (transmitted indices, DCT domain, fp32 values + int32 indices) on
+// full tiles of 64 chunks, W wavefronts per workgroup.
+//
+// Scatter-add: wavefront w owns the rows [64w/W, 64(w+1)/W) of the tile, so no two wavefronts
+// ever add into the same accumulator and, inside a wavefront, LDS operations complete in program
+// order: replica after replica, deterministic.  k a multiple of 4: 16-byte loads of four
+// consecutive entries of one chunk per lane, a batch of replicas requested before the first is
+// applied; a plain read-add-write when the four indices of every lane and the step from the
+// previous lane ascend strictly (what compress emits), LDS atomics otherwise (duplicates add).
+// Other k: one entry per lane, LDS atomics.  Then every class gathers its coefficients from
+// the rows, the inverse transform runs as in compress_split, and all wavefronts stream the
+// parameters (and the moments of Decoupled AdamW) through the update.
+template <int S, int W, bool PARAM_BF16>
+__global__ __launch_bounds__(kWave * W) void decompress_split(
+    KParams p, int64_t tiles, int64_t n, int64_t n_chunks, const int32_t* __restrict__ idx,
+    int64_t idx_stride, const float* __restrict__ val, int64_t val_stride,
+    void* __restrict__ params, AdamPtrs ad, float* __restrict__ presign_dbg) {
+    using G = SplitGeom<S, W>;
+    constexpr int Q = G::Q, kRow = G::kRow, kThreads = G::kThreads, kTile = G::kTile;
+    constexpr int kRowsPerWave = kWave / W;
+    __shared__ __attribute__((aligned(16))) float buf[kTile];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int k = p.k;
+
+    const int64_t tile = blockIdx.x;
+    if (tile >= tiles) {
+        static_assert(sizeof(GenericDecompressSmem) <= sizeof(buf), "tail code borrows the tile");
+        if (tid >= kWave) return;
+        decompress_generic_chunks<PARAM_BF16>(p, n, tiles * kWave + (tile - tiles), n_chunks,
+                                              gridDim.x - tiles,
+                                              *reinterpret_cast<GenericDecompressSmem*>(buf), idx,
+                                              idx_stride, val, val_stride, params, ad, presign_dbg);
+        return;
+    }
+    const int64_t base = tile * static_cast<int64_t>(kWave * S);
+    float* row = &buf[lane * kRow];
+
+    // ---- zero this wavefront's rows
+    {
+        float* mine = &buf[w * kRowsPerWave * kRow];
+        for (int v = lane; v < kRowsPerWave * kRow / 4; v += kWave)
+            *reinterpret_cast<float4*>(mine + 4 * v) = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    }
+    wave_lds_sync();
+
+    // ---- scatter-add of this wavefront's rows, replica after replica
+    {
+        const int64_t entry0 = (tile * kWave + w * kRowsPerWave) * static_cast<int64_t>(k);
+        float* rows = &buf[w * kRowsPerWave * kRow];
+        const uint32_t magic = entry_magic(k);
+        if (k % 4 == 0) {
+            const int quads = kRowsPerWave * k / 4;        // 16-byte pieces per replica
+            constexpr int kBatch = 4;                      // replicas in flight
+            for (int q0 = 0; q0 < quads; q0 += kWave) {
+                const int q = q0 + lane;
+                const bool in = q < quads;
+                const uint32_t e = 4u * static_cast<uint32_t>(in ? q : 0);
+                const uint32_t r = (k == 4) ? (e >> 2) : __umulhi(e, magic);   // row of the wavefront
+                const bool chunk_start = (e - r * static_cast<uint32_t>(k)) == 0u;
+                float* arow = rows + r * kRow;
+                for (int r0 = 0; r0 < p.R; r0 += kBatch) {
+                    int4 iv[kBatch];
+                    float4 vv[kBatch];
+#pragma unroll
+                    for (int b = 0; b < kBatch; ++b) {
+                        if (r0 + b < p.R && in) {
+                            const uint4 t = ld_u4<true>(idx + (r0 + b) * idx_stride + entry0 + e);
+                            iv[b] = make_int4(static_cast<int>(t.x), static_cast<int>(t.y),
+                                              static_cast<int>(t.z), static_cast<int>(t.w));
+                            vv[b] = ld_f4<true>(val + (r0 + b) * val_stride + entry0 + e);
+                        } else {
+                            iv[b] = make_int4(-1, -1, -1, -1);
+                            vv[b] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                        }
+                    }
+#pragma unroll
+                    for (int b = 0; b < kBatch; ++b) {
+                        if (r0 + b < p.R) {
+                            const int at[4] = {iv[b].x, iv[b].y, iv[b].z, iv[b].w};
+                            const float v[4] = {vv[b].x, vv[b].y, vv[b].z, vv[b].w};
+                            const int prev = __shfl_up(at[3], 1);
+                            const bool asc = at[0] < at[1] && at[1] < at[2] && at[2] < at[3] &&
+                                             (lane == 0 || chunk_start || prev < at[0]);
+                            if (__any(in && !asc)) {
+#pragma unroll
+                                for (int c = 0; c < 4; ++c)
+                                    if (static_cast<uint32_t>(at[c]) < static_cast<uint32_t>(S))
+                                        atomicAdd(&arow[at[c]], v[c]);
+                            } else {
+                                float old[4];
+#pragma unroll
+                                for (int c = 0; c < 4; ++c)
+                                    old[c] = (static_cast<uint32_t>(at[c]) < static_cast<uint32_t>(S))
+                                                 ? arow[at[c]] : 0.0f;
+#pragma unroll
+                                for (int c = 0; c < 4; ++c)
+                                    if (static_cast<uint32_t>(at[c]) < static_cast<uint32_t>(S))
+                                        arow[at[c]] = old[c] + v[c];
+                            }
+                            wave_lds_sync();
+                        }
+                    }
+                }
+            }
+        } else {
+            const int entries = kRowsPerWave * k;
+            for (int r = 0; r < p.R; ++r) {
+                for (int e = lane; e < entries; e += kWave) {
+                    const uint32_t rr = (k == 1) ? static_cast<uint32_t>(e)
+                                                 : __umulhi(static_cast<uint32_t>(e), magic);
+                    const int at = idx[r * idx_stride + entry0 + e];
+                    const float v = val[r * val_stride + entry0 + e];
+                    if (static_cast<uint32_t>(at) < static_cast<uint32_t>(S))
+                        atomicAdd(&rows[rr * kRow + at], v);
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- the lane's class of the averaged coefficients: a[W*m + off] * alpha_j / R
+    const int off = split_off<W>(w);
+    const float scale = p.alpha * p.inv_R;
+    float c[Q];
+    {
+        const float* src = row + off;
+#pragma unroll
+        for (int m = 0; m < Q; ++m) c[m] = src[W * m] * scale;
+        if (w == 0) c[0] = row[0] * (p.alpha0 * p.inv_R);
+    }
+    __syncthreads();
+    split_inverse_to_rows<S, W>(row, w, c);
+
+    // ---- y out of the rows, optional sign, parameter update, coalesced; the parameters (and
+    // moments) of a batch of iterations are requested before the first is used
+    {
+        constexpr int kIt = Q / 4;                // 16-byte pieces per thread
+        constexpr int kBatch = (kIt % 8 == 0) ? 8 : 4;
+        static_assert(kIt % kBatch == 0, "whole batches");
+#pragma unroll 1
+        for (int b0 = 0; b0 < kIt; b0 += kBatch) {
+            float4 old4[kBatch], m4[kBatch], v4[kBatch], x4[kBatch];
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                const int64_t i = base + 4 * (tid + kThreads * (b0 + j));
+                if constexpr (PARAM_BF16) {
+                    const uint2 pb = ld_u2<true>(static_cast<const uint16_t*>(params) + i);
+                    old4[j] = make_float4(__uint_as_float(pb.x << 16),
+                                          __uint_as_float(pb.x & 0xFFFF0000u),
+                                          __uint_as_float(pb.y << 16),
+                                          __uint_as_float(pb.y & 0xFFFF0000u));
+                } else {
+                    old4[j] = ld_f4<true>(static_cast<const float*>(params) + i);
+                }
+                x4[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                if (p.adam) {
+                    m4[j] = ld_f4<true>(ad.m + i);
+                    v4[j] = ld_f4<true>(ad.v + i);
+                    if (p.amsgrad) x4[j] = ld_f4<true>(ad.vmax + i);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                const int e4 = 4 * (tid + kThreads * (b0 + j));
+                const int r = e4 / S, col = e4 - r * S;
+                const int64_t i = base + e4;
+                const float4 y4 = split_output<S, W>(&buf[r * kRow], col);
+                if (presign_dbg) st_f4<false>(presign_dbg + i, y4);
+                const float y[4] = {y4.x, y4.y, y4.z, y4.w};
+                const float old[4] = {old4[j].x, old4[j].y, old4[j].z, old4[j].w};
+                float nw[4];
+                if (p.adam) {
+                    float m[4] = {m4[j].x, m4[j].y, m4[j].z, m4[j].w};
+                    float v[4] = {v4[j].x, v4[j].y, v4[j].z, v4[j].w};
+                    float x[4] = {x4[j].x, x4[j].y, x4[j].z, x4[j].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        nw[e] = adamw_step(p, old[e], sign_or_self(y[e], p.use_sign), m[e], v[e], x[e]);
+                    st_f4<true>(ad.m + i, make_float4(m[0], m[1], m[2], m[3]));
+                    st_f4<true>(ad.v + i, make_float4(v[0], v[1], v[2], v[3]));
+                    if (p.amsgrad) st_f4<true>(ad.vmax + i, make_float4(x[0], x[1], x[2], x[3]));
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        nw[e] = fmaf(-p.lr, sign_or_self(y[e], p.use_sign), old[e] * p.wd_scale);
+                }
+                if constexpr (PARAM_BF16) {
+                    uint2 o;
+                    o.x = pack_bf16x2(nw[0], nw[1]);
+                    o.y = pack_bf16x2(nw[2], nw[3]);
+                    *reinterpret_cast<uint2*>(static_cast<uint16_t*>(params) + i) = o;
+                } else {
+                    st_f4<true>(static_cast<float*>(params) + i,
+                                make_float4(nw[0], nw[1], nw[2], nw[3]));
+                }
+            }
         }
     }
 }

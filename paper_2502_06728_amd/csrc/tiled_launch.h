@@ -111,6 +111,7 @@ int64_t launch_decompress_pair(const DecompressLaunch& a);
 
 // Lane per chunk, wavefront per coefficient class (split_kernels.hip.h): tiles of 64 chunks,
 // fp32 + int32 payloads with k <= s/2.  Same return convention.
+int64_t launch_decompress_split(const DecompressLaunch& a);      // chunk 192, 256
 int64_t launch_compress_split_96(const CompressLaunch& a);
 int64_t launch_compress_split_128(const CompressLaunch& a);
 int64_t launch_compress_split_192(const CompressLaunch& a);
