@@ -60,18 +60,61 @@ struct SortNetHolder {
     static constexpr SortNet<N> net{};
 };
 
-// sort descending, in registers
-template <int N>
-__device__ __forceinline__ void sort_desc(uint32_t (&k)[N]) {
+// sort k[OFF .. OFF+N) descending, in registers
+template <int N, int OFF = 0, int M>
+__device__ __forceinline__ void sort_desc_range(uint32_t (&k)[M]) {
+    static_assert(OFF + N <= M, "range inside the array");
     constexpr int cnt = SortNetHolder<N>::net.n;
     static_for<0, cnt>([&](auto I) {
-        constexpr int i = SortNetHolder<N>::net.a[I];
-        constexpr int j = SortNetHolder<N>::net.b[I];
+        constexpr int i = OFF + SortNetHolder<N>::net.a[I];
+        constexpr int j = OFF + SortNetHolder<N>::net.b[I];
         const uint32_t hi = max(k[i], k[j]);
         const uint32_t lo = min(k[i], k[j]);
         k[i] = hi;
         k[j] = lo;
     });
+}
+
+template <int N>
+__device__ __forceinline__ void sort_desc(uint32_t (&k)[N]) {
+    sort_desc_range<N, 0>(k);
+}
+
+// Sort the first N entries, a bitonic sequence (first falling then rising, or the reverse),
+// into descending order.
+template <int N, int M>
+__device__ __forceinline__ void bitonic_merge_desc(uint32_t (&x)[M]) {
+    static_assert((N & (N - 1)) == 0 && N <= M, "power of two");
+#pragma unroll
+    for (int d = N / 2; d >= 1; d /= 2) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            if ((i & d) == 0) {
+                const uint32_t hi = max(x[i], x[i + d]);
+                const uint32_t lo = min(x[i], x[i + d]);
+                x[i] = hi;
+                x[i + d] = lo;
+            }
+        }
+    }
+}
+
+// The TOP largest of the N keys, descending, in k[0 .. TOP); the other entries become zero
+// (the smallest key).  Whoever only needs the k-th largest for some k <= TOP does not need
+// the full order: groups of TOP are sorted, and each further group is folded into the first
+// with one row of maxima against its mirror image (the TOP largest of the two groups, as a
+// bitonic sequence) and a bitonic merge.  N = 64: 340 / 528 / 744 / 956 instructions for
+// TOP = 4 / 8 / 16 / 32 against 1,086 for the full sort.
+template <int N, int TOP>
+__device__ __forceinline__ void sort_top_desc(uint32_t (&k)[N]) {
+    static_assert(N % TOP == 0 && (TOP & (TOP - 1)) == 0, "whole groups of a power of two");
+    static_for<0, N / TOP>([&](auto g) { sort_desc_range<TOP, g * TOP>(k); });
+    static_for<1, N / TOP>([&](auto g) {
+        static_for<0, TOP>([&](auto i) { k[i] = max(k[i], k[g * TOP + TOP - 1 - i]); });
+        bitonic_merge_desc<TOP>(k);
+    });
+#pragma unroll
+    for (int i = TOP; i < N; ++i) k[i] = 0u;
 }
 
 }  // namespace deto

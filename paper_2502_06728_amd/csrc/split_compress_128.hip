@@ -1,6 +1,10 @@
 // Lane-per-chunk, wavefront-per-coefficient-class compress kernels (chunk size 128: 2 classes;
 // top-k selection, fp32 values + int32 indices, k <= 64).
 #include "split_kernels.hip.h"
+
+#ifndef DETO_SPLIT_W
+#define DETO_SPLIT_W 2
+#endif
 #include "tiled_launch.h"
 
 namespace deto {
@@ -17,15 +21,23 @@ int64_t launch_compress_split_128(const CompressLaunch& a) {
     const int64_t grid64 = tiles + (a.n_chunks - tiles * kWave);
     if (tiles <= 0 || grid64 > 0x7FFFFFFF) return 0;
     const unsigned grid = static_cast<unsigned>(grid64);
-    constexpr int kThreads = SplitGeom<128, 2>::kThreads;
-    if (a.grad_bf16)
-        compress_split<128, 2, true><<<grid, kThreads, 0, a.stream>>>(
-            p, tiles, a.n, a.n_chunks, a.grad, a.mom, static_cast<int32_t*>(a.idx),
-            static_cast<float*>(a.val), a.coeff_dbg);
-    else
-        compress_split<128, 2, false><<<grid, kThreads, 0, a.stream>>>(
-            p, tiles, a.n, a.n_chunks, a.grad, a.mom, static_cast<int32_t*>(a.idx),
-            static_cast<float*>(a.val), a.coeff_dbg);
+    constexpr int kThreads = SplitGeom<128, DETO_SPLIT_W>::kThreads;
+    // a launch with k <= 16 sorts out only every lane's 16 largest magnitudes
+    constexpr int kQ = SplitGeom<128, DETO_SPLIT_W>::Q;
+    constexpr int kTop = (kQ % 16 == 0 && kQ > 16) ? 16 : 0;
+    int32_t* io = static_cast<int32_t*>(a.idx);
+    float* vo = static_cast<float*>(a.val);
+#define LAUNCH(BF16, TOP)                                                                  \
+    compress_split<128, DETO_SPLIT_W, BF16, TOP><<<grid, kThreads, 0, a.stream>>>(                 \
+        p, tiles, a.n, a.n_chunks, a.grad, a.mom, io, vo, a.coeff_dbg)
+    if (kTop > 0 && p.k <= kTop) {
+        if (a.grad_bf16) LAUNCH(true, kTop);
+        else LAUNCH(false, kTop);
+    } else {
+        if (a.grad_bf16) LAUNCH(true, 0);
+        else LAUNCH(false, 0);
+    }
+#undef LAUNCH
     return a.n_chunks;   // the tail chunks ride along
 #endif
 }

@@ -18,14 +18,22 @@ int64_t launch_compress_split_256(const CompressLaunch& a) {
     if (tiles <= 0 || grid64 > 0x7FFFFFFF) return 0;
     const unsigned grid = static_cast<unsigned>(grid64);
     constexpr int kThreads = SplitGeom<256, 4>::kThreads;
-    if (a.grad_bf16)
-        compress_split<256, 4, true><<<grid, kThreads, 0, a.stream>>>(
-            p, tiles, a.n, a.n_chunks, a.grad, a.mom, static_cast<int32_t*>(a.idx),
-            static_cast<float*>(a.val), a.coeff_dbg);
-    else
-        compress_split<256, 4, false><<<grid, kThreads, 0, a.stream>>>(
-            p, tiles, a.n, a.n_chunks, a.grad, a.mom, static_cast<int32_t*>(a.idx),
-            static_cast<float*>(a.val), a.coeff_dbg);
+    // a launch with k <= 16 sorts out only every lane's 16 largest magnitudes
+    constexpr int kQ = SplitGeom<256, 4>::Q;
+    constexpr int kTop = (kQ % 16 == 0 && kQ > 16) ? 16 : 0;
+    int32_t* io = static_cast<int32_t*>(a.idx);
+    float* vo = static_cast<float*>(a.val);
+#define LAUNCH(BF16, TOP)                                                                  \
+    compress_split<256, 4, BF16, TOP><<<grid, kThreads, 0, a.stream>>>(                 \
+        p, tiles, a.n, a.n_chunks, a.grad, a.mom, io, vo, a.coeff_dbg)
+    if (kTop > 0 && p.k <= kTop) {
+        if (a.grad_bf16) LAUNCH(true, kTop);
+        else LAUNCH(false, kTop);
+    } else {
+        if (a.grad_bf16) LAUNCH(true, 0);
+        else LAUNCH(false, 0);
+    }
+#undef LAUNCH
     return a.n_chunks;   // the tail chunks ride along
 #endif
 }

@@ -63,24 +63,6 @@ __device__ __forceinline__ int split_off(int w) {
     else return ((w & 1) << 1) | (w >> 1);          // 0, 2, 1, 3
 }
 
-// Sort a bitonic sequence (first falling then rising, or the reverse) into descending order.
-template <int N>
-__device__ __forceinline__ void bitonic_merge_desc(uint32_t (&x)[N]) {
-    static_assert((N & (N - 1)) == 0, "power of two");
-#pragma unroll
-    for (int d = N / 2; d >= 1; d /= 2) {
-#pragma unroll
-        for (int i = 0; i < N; ++i) {
-            if ((i & d) == 0) {
-                const uint32_t hi = max(x[i], x[i + d]);
-                const uint32_t lo = min(x[i], x[i + d]);
-                x[i] = hi;
-                x[i + d] = lo;
-            }
-        }
-    }
-}
-
 // k-th largest of the union of two descending lists of length L in LDS: i of the k largest
 // come from list 0 and k - i from list 1, i being the smallest count for which list0[i] (the
 // first one left out) does not exceed list1[k-i-1] (the last one taken).
@@ -327,8 +309,9 @@ __device__ __forceinline__ float4 split_output(const float* __restrict__ row, in
 
 // Compress half (top-k, DCT domain, fp32 values + int32 indices, k <= S/2) on full tiles of 64
 // chunks; the chunks past the last full tile go one per surplus workgroup to the general code.
-template <int S, int W, bool GRAD_BF16>
-__global__ __launch_bounds__(kWave * W) void compress_split(
+// TOP > 0: for launches with k <= TOP (see the selection step).
+template <int S, int W, bool GRAD_BF16, int TOP = 0>
+__global__ __launch_bounds__(kWave * W) __attribute__((amdgpu_waves_per_eu(2))) void compress_split(
     KParams p, int64_t tiles, int64_t n, int64_t n_chunks, const void* __restrict__ grad,
     float* __restrict__ mom, int32_t* __restrict__ idx_out, float* __restrict__ val_out,
     float* __restrict__ coeff_dbg) {
@@ -402,15 +385,26 @@ __global__ __launch_bounds__(kWave * W) void compress_split(
     // ---- k-th largest magnitude T of the chunk
     uint32_t T;
     {
+        // (the magnitudes are formed again when the kept sets are marked: keeping these
+        // copies alive across the sort would cost Q registers)
         uint32_t a[Q];
 #pragma unroll
-        for (int m = 0; m < Q; ++m) a[m] = __float_as_uint(c[m]) & 0x7FFFFFFFu;
-        sort_desc<Q>(a);
+        for (int m = 0; m < Q; ++m) {
+            a[m] = __float_as_uint(c[m]) & 0x7FFFFFFFu;
+            asm volatile("" : "+v"(a[m]));
+        }
         uint32_t* lists = reinterpret_cast<uint32_t*>(row);
+        auto publish = [&]() {
 #pragma unroll
-        for (int q = 0; q < Q / 4; ++q)
-            *reinterpret_cast<uint4*>(lists + w * Q + 4 * q) =
-                make_uint4(a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]);
+            for (int q = 0; q < Q / 4; ++q)
+                *reinterpret_cast<uint4*>(lists + w * Q + 4 * q) =
+                    make_uint4(a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]);
+        };
+        // each class contributes at most k of the k largest: a launch with k <= TOP sorts out
+        // only every lane's largest TOP (TOP = 0: the full sort)
+        if constexpr (TOP > 0) sort_top_desc<Q, TOP>(a);
+        else sort_desc<Q>(a);
+        publish();
         __syncthreads();
         if constexpr (W == 4) {
             // classes (0,1) and (2,3): the larger half of the two lists' union to the even
@@ -426,11 +420,12 @@ __global__ __launch_bounds__(kWave * W) void compress_split(
                 uint4 t = make_uint4(0u, 0u, 0u, 0u);
                 if constexpr (j0 < Q) t = *reinterpret_cast<const uint4*>(partner + j0);
                 const uint32_t theirs[4] = {t.w, t.z, t.y, t.x};  // partner[QP-1-i], i = 4q ..
+                uint4 m4 = make_uint4(0u, 0u, 0u, 0u);            // own entries 4q .. 4q+3
+                if constexpr (4 * q < Q) m4 = *reinterpret_cast<const uint4*>(lists + w * Q + 4 * q);
+                const uint32_t mine[4] = {m4.x, m4.y, m4.z, m4.w};
                 static_for<0, 4>([&](auto e) {
                     constexpr int i = 4 * q + e;
-                    uint32_t mine = 0u;
-                    if constexpr (i < Q) mine = a[i];
-                    x[i] = (w & 1) ? min(mine, theirs[e]) : max(mine, theirs[e]);
+                    x[i] = (w & 1) ? min(mine[e], theirs[e]) : max(mine[e], theirs[e]);
                 });
             });
             bitonic_merge_desc<QP>(x);
