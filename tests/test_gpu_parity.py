@@ -63,7 +63,8 @@ def test_vit_like_sweep_ragged(H, s, k, sign):
 
 
 @pytest.mark.parametrize("s,k", [(16, 2), (96, 6), (96, 96), (192, 12), (256, 16), (256, 256),
-                                 (1, 1), (2, 1), (3, 2), (65, 7), (200, 100)])
+                                 (1, 1), (2, 1), (3, 2), (65, 7), (200, 100), (128, 30), (192, 10),
+                                 (192, 96), (192, 97), (256, 6), (256, 128), (256, 129), (96, 49)])
 def test_other_chunk_sizes(H, s, k):
     cfg = Config(chunk=s, topk=k, sign=True)
     full_step(H, cfg, s * 700 + (s // 3), R=3, seed=3)
@@ -88,18 +89,27 @@ def test_chunk_size_96(H, k, bf16):
               outliers=0.01 if bf16 else 0.0)
 
 
-def test_chunk_size_96_ties(H):
-    # zero chunks tie everywhere; single spikes give coefficients of pairwise equal magnitude
-    s, k = 96, 12
-    n = s * 128
+@pytest.mark.parametrize("s,k", [(96, 12), (128, 16), (128, 64), (128, 6), (192, 24), (192, 10),
+                                 (256, 32), (256, 128), (256, 20)])
+def test_ties_above_chunk_64(H, s, k):
+    # zero chunks tie everywhere; single spikes give coefficients of pairwise equal magnitude;
+    # chunks of +-1 patterns tie in groups.  Mixed with ordinary chunks in the same tiles, so
+    # that the whole-wavefront tie pass and the staged path meet in one workgroup; a ragged tail.
+    n = s * (64 * 3 + 17) + s // 2
+    C = -(-n // s)
     cfg = Config(chunk=s, topk=k, decay=0.0)
-    g = np.zeros(n, np.float32)
-    for c in range(0, 128, 3):
-        g[c * s + (7 * c) % s] = 1.0 + c
+    rng = np.random.default_rng(s + k)
+    g = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    for c in range(0, C - 1, 3):
+        g[c * s:(c + 1) * s] = 0.0
+        if c % 2:
+            g[c * s + (7 * c) % s] = 1.0 + c
+    for c in range(1, C - 1, 11):
+        g[c * s:(c + 1) * s] = np.where(np.arange(s) % 3 == 0, 1.0, -1.0)
     m = np.zeros(n, np.float32)
     m_gpu, idx_gpu, val_gpu, coeff_gpu = H.gpu_compress(cfg, g, m)
     parity.check_compress(cfg, g, m, m_gpu, idx_gpu, val_gpu, coeff_gpu)
-    assert np.array_equal(idx_gpu.reshape(-1, k)[1], np.arange(k))
+    assert np.array_equal(idx_gpu.reshape(-1, k)[0], np.arange(k))      # an all-zero chunk
 
 
 @pytest.mark.parametrize("grad_bf16,params_bf16", [(True, True), (True, False), (False, True)])
@@ -827,7 +837,8 @@ def test_every_position_kept_in_the_raw_domain(H, scheme, s, n):
     assert np.array_equal(coeff_gpu, val_gpu)
 
 
-@pytest.mark.parametrize("s,k", [(96, 12), (96, 24), (96, 48), (128, 64), (64, 32), (16, 8)])
+@pytest.mark.parametrize("s,k", [(96, 12), (96, 24), (96, 48), (128, 64), (64, 32), (16, 8),
+                                 (192, 24), (192, 10), (256, 32), (256, 128), (256, 6)])
 def test_unordered_payloads_on_every_vector_scatter(H, s, k):
     # duplicates, disorder and out-of-range indices at the k values whose chunks straddle the
     # 64-lane vectors of the scatter (k not dividing 256) and at those that do not
