@@ -13,8 +13,8 @@ int64_t launch_compress_split_192(const CompressLaunch& a) {
     if (p.s != 192 || p.scheme != 0 || !p.use_dct || p.val_dtype != 0 || p.idx_u8 || p.k > 96)
         return 0;
     const int64_t tiles = (a.n / p.s) / kWave;
-    // one workgroup per tile plus one per chunk past the last full tile
-    const int64_t grid64 = tiles + (a.n_chunks - tiles * kWave);
+    // one workgroup per full tile and one for the chunks left over (a partial tile)
+    const int64_t grid64 = tiles + (a.n_chunks > tiles * kWave ? 1 : 0);
     if (tiles <= 0 || grid64 > 0x7FFFFFFF) return 0;
     const unsigned grid = static_cast<unsigned>(grid64);
     constexpr int kThreads = SplitGeom<192, 4>::kThreads;

@@ -13,25 +13,25 @@ int64_t launch_decompress_split(const DecompressLaunch& a) {
 #else
     if (!a.idx || !p.use_dct || p.val_dtype != 0 || p.idx_u8) return 0;
     const int64_t tiles = (a.n / p.s) / kWave;
-    // one workgroup per tile plus one per chunk past the last full tile
-    const int64_t grid64 = tiles + (a.n_chunks - tiles * kWave);
+    // one workgroup per full tile and one for the chunks left over (a partial tile)
+    const int64_t grid64 = tiles + (a.n_chunks > tiles * kWave ? 1 : 0);
     if (tiles <= 0 || grid64 > 0x7FFFFFFF) return 0;
     const unsigned grid = static_cast<unsigned>(grid64);
     const int32_t* idx = static_cast<const int32_t*>(a.idx);
     const float* val = static_cast<const float*>(a.val);
-#define X(S)                                                                                    \
+#define X(S, W)                                                                                 \
     if (p.s == S) {                                                                             \
         if (a.param_bf16)                                                                       \
-            decompress_split<S, 4, true><<<grid, 4 * kWave, 0, a.stream>>>(                     \
+            decompress_split<S, W, true><<<grid, W * kWave, 0, a.stream>>>(                     \
                 p, tiles, a.n, a.n_chunks, idx, a.idx_stride, val, a.val_stride, a.params,     \
                 a.adam, a.presign_dbg);                                                         \
         else                                                                                    \
-            decompress_split<S, 4, false><<<grid, 4 * kWave, 0, a.stream>>>(                    \
+            decompress_split<S, W, false><<<grid, W * kWave, 0, a.stream>>>(                    \
                 p, tiles, a.n, a.n_chunks, idx, a.idx_stride, val, a.val_stride, a.params,     \
                 a.adam, a.presign_dbg);                                                         \
         return a.n_chunks;   /* the tail chunks ride along */                                   \
     }
-    X(192) X(256)
+    X(192, 4) X(256, 4)
 #undef X
     return 0;
 #endif

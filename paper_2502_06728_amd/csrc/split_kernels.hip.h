@@ -328,28 +328,24 @@ __global__ __launch_bounds__(kWave * W) __attribute__((amdgpu_waves_per_eu(2))) 
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int k = p.k;
 
+    // Workgroups [0, tiles): full tiles.  The chunks left over (fewer than 64, the last of them
+    // possibly ragged: the shard need not end on a chunk boundary) form ONE partial tile: its
+    // first `live` rows are chunks, the other lanes idle; positions past the end of the shard
+    // read as zero and are never written.
     const int64_t tile = blockIdx.x;
-    if (tile >= tiles) {
-        // surplus workgroups: one chunk each on the general per-chunk code (one wavefront)
-        static_assert(sizeof(GenericCompressSmem) <= sizeof(buf), "tail code borrows the tile");
-        if (tid >= kWave) return;
-        compress_generic_chunks<GRAD_BF16>(p, n, tiles * kWave + (tile - tiles), n_chunks,
-                                           gridDim.x - tiles,
-                                           *reinterpret_cast<GenericCompressSmem*>(buf), grad, mom,
-                                           idx_out, val_out, coeff_dbg);
-        return;
-    }
+    const bool partial = tile >= tiles;    // (a partial tile can have 64 rows, the last ragged)
+    const int live = partial ? static_cast<int>(n_chunks - tiles * kWave) : kWave;
+    const bool alive = lane < live;
     const int64_t base = tile * static_cast<int64_t>(kWave * S);
     const int64_t chunk0 = tile * kWave;
     float* row = &buf[lane * kRow];
     if (tid == 0) s_tie = 0ull;
 
-    // ---- m1 = beta*m + g for the tile's 64*S contiguous elements, coalesced, into the rows
+    // ---- m1 = beta*m + g for the tile's contiguous elements, coalesced, into the rows (the
+    // rows past a partial tile's chunks become zero)
     {
         constexpr int kIt = Q / 4;               // 16-byte pieces per thread
-#pragma unroll
-        for (int it = 0; it < kIt; ++it) {
-            const int e4 = 4 * (tid + kThreads * it);
+        auto fold_piece = [&](int e4) {
             const int r = e4 / S, col = e4 - r * S;
             const float4 m = ld_f4<false>(mom + base + e4);
             float4 g;
@@ -363,6 +359,34 @@ __global__ __launch_bounds__(kWave * W) __attribute__((amdgpu_waves_per_eu(2))) 
             *reinterpret_cast<float4*>(&buf[r * kRow + col]) =
                 make_float4(fmaf(p.beta, m.x, g.x), fmaf(p.beta, m.y, g.y),
                             fmaf(p.beta, m.z, g.z), fmaf(p.beta, m.w, g.w));
+        };
+        if (!partial) {
+#pragma unroll
+            for (int it = 0; it < kIt; ++it) fold_piece(4 * (tid + kThreads * it));
+        } else {
+            for (int it = 0; it < kIt; ++it) {
+                const int e4 = 4 * (tid + kThreads * it);
+                const int64_t i0 = base + e4;
+                if (i0 + 3 < n) {
+                    fold_piece(e4);
+                } else {
+                    // the piece that straddles the end of the shard, and everything past it
+                    const int r = e4 / S, col = e4 - r * S;
+                    float x[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        x[j] = 0.0f;
+                        if (i0 + j < n) {
+                            const float g = GRAD_BF16
+                                ? bf16_to_f32(static_cast<const uint16_t*>(grad)[i0 + j])
+                                : static_cast<const float*>(grad)[i0 + j];
+                            x[j] = fmaf(p.beta, mom[i0 + j], g);
+                        }
+                    }
+                    *reinterpret_cast<float4*>(&buf[r * kRow + col]) =
+                        make_float4(x[0], x[1], x[2], x[3]);
+                }
+            }
         }
     }
     __syncthreads();
@@ -376,7 +400,7 @@ __global__ __launch_bounds__(kWave * W) __attribute__((amdgpu_waves_per_eu(2))) 
     c[0] *= (w == 0) ? p.alpha0 : p.alpha;
 #pragma unroll
     for (int m = 1; m < Q; ++m) c[m] *= p.alpha;
-    if (coeff_dbg) {
+    if (coeff_dbg && alive) {
         float* dbg = coeff_dbg + (chunk0 + lane) * S + off;
 #pragma unroll
         for (int m = 0; m < Q; ++m) dbg[W * m] = c[m];
@@ -477,7 +501,7 @@ __global__ __launch_bounds__(kWave * W) __attribute__((amdgpu_waves_per_eu(2))) 
     int need = 0;
     {
         const int cnt = mark(T);
-        const bool tie = cnt != k;
+        const bool tie = alive && cnt != k;      // the idle rows of a partial tile are all zero
         if (__syncthreads_or(tie ? 1 : 0)) {
             if (tie) {
                 thr_gt = T + 1u;     // <= 0x80000000: no magnitude reaches that
@@ -508,7 +532,7 @@ __global__ __launch_bounds__(kWave * W) __attribute__((amdgpu_waves_per_eu(2))) 
     // this class is the number of kept coefficients of the chunk with a smaller index: the
     // class's own bits below m, and of another class w' its bits below m (+ 1 if that class's
     // offset is the smaller one).
-    if (need == 0) {
+    if (need == 0 && alive) {
         // the other classes' bits lined up with this class's steps, and counted into the start
         uint32_t plane0[NW], plane1[NW];
         uint32_t start = 0u;
@@ -557,7 +581,7 @@ __global__ __launch_bounds__(kWave * W) __attribute__((amdgpu_waves_per_eu(2))) 
         float* vo = val_out + chunk0 * k;
         int32_t* io = idx_out + chunk0 * k;
         if (k % 4 == 0) {
-            const int quads = 16 * k;                      // 16-byte pieces of the tile
+            const int quads = live * k / 4;                // 16-byte pieces of the tile
             for (int q = tid; q < quads; q += kThreads) {
                 const uint32_t e = 4u * static_cast<uint32_t>(q);
                 const uint32_t r = __umulhi(e, magic);     // chunk of the tile, k >= 4
@@ -573,7 +597,7 @@ __global__ __launch_bounds__(kWave * W) __attribute__((amdgpu_waves_per_eu(2))) 
         } else {
             // four entries of a lane could straddle two chunks (and the arrays need not be
             // 16-byte aligned): one entry per lane
-            for (uint32_t e = tid; e < static_cast<uint32_t>(kWave * k); e += kThreads) {
+            for (uint32_t e = tid; e < static_cast<uint32_t>(live * k); e += kThreads) {
                 const uint32_t r = (k == 1) ? e : __umulhi(e, magic);
                 const uint32_t j = e - r * static_cast<uint32_t>(k);
                 if ((tie_chunks >> r) & 1ull) continue;
@@ -593,7 +617,16 @@ __global__ __launch_bounds__(kWave * W) __attribute__((amdgpu_waves_per_eu(2))) 
         for (int it = 0; it < kIt; ++it) {
             const int e4 = 4 * (tid + kThreads * it);
             const int r = e4 / S, col = e4 - r * S;
-            st_f4<false>(mom + base + e4, split_output<S, W>(&buf[r * kRow], col));
+            const int64_t i0 = base + e4;
+            if (!partial || i0 + 3 < n) {
+                st_f4<false>(mom + i0, split_output<S, W>(&buf[r * kRow], col));
+            } else if (i0 < n) {
+                const float4 y = split_output<S, W>(&buf[r * kRow], col);
+                const float v[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (i0 + j < n) mom[i0 + j] = v[j];
+            }
         }
     }
 }
@@ -625,16 +658,13 @@ __global__ __launch_bounds__(kWave * W) void decompress_split(
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int k = p.k;
 
+    // full tiles, then one partial tile of the chunks left over, the last of them possibly
+    // ragged (as in compress_split)
     const int64_t tile = blockIdx.x;
-    if (tile >= tiles) {
-        static_assert(sizeof(GenericDecompressSmem) <= sizeof(buf), "tail code borrows the tile");
-        if (tid >= kWave) return;
-        decompress_generic_chunks<PARAM_BF16>(p, n, tiles * kWave + (tile - tiles), n_chunks,
-                                              gridDim.x - tiles,
-                                              *reinterpret_cast<GenericDecompressSmem*>(buf), idx,
-                                              idx_stride, val, val_stride, params, ad, presign_dbg);
-        return;
-    }
+    const bool partial = tile >= tiles;    // (a partial tile can have 64 rows, the last ragged)
+    const int live = partial ? static_cast<int>(n_chunks - tiles * kWave) : kWave;
+    // rows of this wavefront's share that are chunks
+    const int my_rows = min(max(live - w * kRowsPerWave, 0), kRowsPerWave);
     const int64_t base = tile * static_cast<int64_t>(kWave * S);
     float* row = &buf[lane * kRow];
 
@@ -652,7 +682,7 @@ __global__ __launch_bounds__(kWave * W) void decompress_split(
         float* rows = &buf[w * kRowsPerWave * kRow];
         const uint32_t magic = entry_magic(k);
         if (k % 4 == 0) {
-            const int quads = kRowsPerWave * k / 4;        // 16-byte pieces per replica
+            const int quads = my_rows * k / 4;             // 16-byte pieces per replica
             constexpr int kBatch = 4;                      // replicas in flight
             for (int q0 = 0; q0 < quads; q0 += kWave) {
                 const int q = q0 + lane;
@@ -706,7 +736,7 @@ __global__ __launch_bounds__(kWave * W) void decompress_split(
                 }
             }
         } else {
-            const int entries = kRowsPerWave * k;
+            const int entries = my_rows * k;
             for (int r = 0; r < p.R; ++r) {
                 for (int e = lane; e < entries; e += kWave) {
                     const uint32_t rr = (k == 1) ? static_cast<uint32_t>(e)
@@ -746,6 +776,8 @@ __global__ __launch_bounds__(kWave * W) void decompress_split(
 #pragma unroll
             for (int j = 0; j < kBatch; ++j) {
                 const int64_t i = base + 4 * (tid + kThreads * (b0 + j));
+                old4[j] = m4[j] = v4[j] = x4[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                if (partial && i + 3 >= n) continue;   // the shard's end: handled below
                 if constexpr (PARAM_BF16) {
                     const uint2 pb = ld_u2<true>(static_cast<const uint16_t*>(params) + i);
                     old4[j] = make_float4(__uint_as_float(pb.x << 16),
@@ -767,6 +799,35 @@ __global__ __launch_bounds__(kWave * W) void decompress_split(
                 const int e4 = 4 * (tid + kThreads * (b0 + j));
                 const int r = e4 / S, col = e4 - r * S;
                 const int64_t i = base + e4;
+                if (partial && i + 3 >= n) {
+                    // the piece that straddles the end of the shard: element by element
+                    if (i < n) {
+                        const float4 y4 = split_output<S, W>(&buf[r * kRow], col);
+                        const float yv[4] = {y4.x, y4.y, y4.z, y4.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            if (i + e >= n) break;
+                            if (presign_dbg) presign_dbg[i + e] = yv[e];
+                            const float q = sign_or_self(yv[e], p.use_sign);
+                            const float th = PARAM_BF16
+                                ? bf16_to_f32(static_cast<const uint16_t*>(params)[i + e])
+                                : static_cast<const float*>(params)[i + e];
+                            float nw;
+                            if (p.adam) {
+                                float vm = p.amsgrad ? ad.vmax[i + e] : 0.0f;
+                                nw = adamw_step(p, th, q, ad.m[i + e], ad.v[i + e], vm);
+                                if (p.amsgrad) ad.vmax[i + e] = vm;
+                            } else {
+                                nw = fmaf(-p.lr, q, th * p.wd_scale);
+                            }
+                            if constexpr (PARAM_BF16)
+                                static_cast<uint16_t*>(params)[i + e] = f32_to_bf16(nw);
+                            else
+                                static_cast<float*>(params)[i + e] = nw;
+                        }
+                    }
+                    continue;
+                }
                 const float4 y4 = split_output<S, W>(&buf[r * kRow], col);
                 if (presign_dbg) st_f4<false>(presign_dbg + i, y4);
                 const float y[4] = {y4.x, y4.y, y4.z, y4.w};

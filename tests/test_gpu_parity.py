@@ -71,6 +71,21 @@ def test_other_chunk_sizes(H, s, k):
 
 
 @pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("s,k", [(96, 12), (128, 16), (128, 6), (192, 24), (256, 32), (256, 5)])
+@pytest.mark.parametrize("tail", ["63 chunks and a ragged one", "a ragged one only", "one chunk",
+                                  "63 chunks"])
+def test_partial_tiles_above_chunk_64(H, s, k, tail, bf16):
+    # the chunks past the last full 64-chunk tile form one partial tile; its last chunk may be
+    # ragged, and with 63 complete chunks before it the partial tile has all 64 rows in use
+    extra = {"63 chunks and a ragged one": 63 * s + s // 2 + 1, "a ragged one only": s - 3,
+             "one chunk": s, "63 chunks": 63 * s}[tail]
+    n = s * 64 * 2 + extra
+    cfg = Config(chunk=s, topk=k, sign=True)
+    full_step(H, cfg, n, R=3, seed=s + k, grad_bf16=bf16, params_bf16=bf16,
+              outliers=0.01 if bf16 else 0.0)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
 @pytest.mark.parametrize("k", [1, 2, 3, 4, 8, 16])
 def test_chunk_size_16(H, k, bf16):
     # the smallest chunk of the Appendix B sweep: lane-per-chunk kernels for k in {1,2,4,8}
