@@ -381,7 +381,7 @@ def report(args) -> int:
     # 10.8 M-parameter shard (fp32, ragged length)
     vit = []
     for s_ in (32, 64, 128):
-        for k_ in (1, 4, 16, s_ // 2):
+        for k_ in sorted({1, 4, 16, s_ // 2}):
             for sign in (True, False):
                 a = copy.copy(args)
                 a.workload, a.scheme, a.dct = "vit-b16-1of8", "topk", False
