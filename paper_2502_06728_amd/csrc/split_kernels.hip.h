@@ -613,19 +613,27 @@ __global__ __launch_bounds__(kWave * W) __attribute__((amdgpu_waves_per_eu(2))) 
     split_inverse_to_rows<S, W>(row, w, c);
     {
         constexpr int kIt = Q / 4;
+        if (!partial) {
 #pragma unroll 4
-        for (int it = 0; it < kIt; ++it) {
-            const int e4 = 4 * (tid + kThreads * it);
-            const int r = e4 / S, col = e4 - r * S;
-            const int64_t i0 = base + e4;
-            if (!partial || i0 + 3 < n) {
-                st_f4<false>(mom + i0, split_output<S, W>(&buf[r * kRow], col));
-            } else if (i0 < n) {
-                const float4 y = split_output<S, W>(&buf[r * kRow], col);
-                const float v[4] = {y.x, y.y, y.z, y.w};
+            for (int it = 0; it < kIt; ++it) {
+                const int e4 = 4 * (tid + kThreads * it);
+                const int r = e4 / S, col = e4 - r * S;
+                st_f4<false>(mom + base + e4, split_output<S, W>(&buf[r * kRow], col));
+            }
+        } else {
+            for (int it = 0; it < kIt; ++it) {
+                const int e4 = 4 * (tid + kThreads * it);
+                const int r = e4 / S, col = e4 - r * S;
+                const int64_t i0 = base + e4;
+                if (i0 + 3 < n) {
+                    st_f4<false>(mom + i0, split_output<S, W>(&buf[r * kRow], col));
+                } else if (i0 < n) {
+                    const float4 y = split_output<S, W>(&buf[r * kRow], col);
+                    const float v[4] = {y.x, y.y, y.z, y.w};
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (i0 + j < n) mom[i0 + j] = v[j];
+                    for (int j = 0; j < 4; ++j)
+                        if (i0 + j < n) mom[i0 + j] = v[j];
+                }
             }
         }
     }
@@ -770,14 +778,20 @@ __global__ __launch_bounds__(kWave * W) void decompress_split(
         constexpr int kIt = Q / 4;                // 16-byte pieces per thread
         constexpr int kBatch = (kIt % 8 == 0) ? 8 : 4;
         static_assert(kIt % kBatch == 0, "whole batches");
+        // (full tiles run the code without the checks against the end of the shard: with them
+        // the loads of a batch are no longer issued together)
+        auto update = [&](auto guarded_tag) {
+        constexpr bool kGuarded = decltype(guarded_tag)::value;
 #pragma unroll 1
         for (int b0 = 0; b0 < kIt; b0 += kBatch) {
             float4 old4[kBatch], m4[kBatch], v4[kBatch], x4[kBatch];
 #pragma unroll
             for (int j = 0; j < kBatch; ++j) {
                 const int64_t i = base + 4 * (tid + kThreads * (b0 + j));
-                old4[j] = m4[j] = v4[j] = x4[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-                if (partial && i + 3 >= n) continue;   // the shard's end: handled below
+                if constexpr (kGuarded) {
+                    old4[j] = m4[j] = v4[j] = x4[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                    if (i + 3 >= n) continue;   // the shard's end: handled below
+                }
                 if constexpr (PARAM_BF16) {
                     const uint2 pb = ld_u2<true>(static_cast<const uint16_t*>(params) + i);
                     old4[j] = make_float4(__uint_as_float(pb.x << 16),
@@ -799,7 +813,7 @@ __global__ __launch_bounds__(kWave * W) void decompress_split(
                 const int e4 = 4 * (tid + kThreads * (b0 + j));
                 const int r = e4 / S, col = e4 - r * S;
                 const int64_t i = base + e4;
-                if (partial && i + 3 >= n) {
+                if (kGuarded && i + 3 >= n) {
                     // the piece that straddles the end of the shard: element by element
                     if (i < n) {
                         const float4 y4 = split_output<S, W>(&buf[r * kRow], col);
@@ -859,6 +873,9 @@ __global__ __launch_bounds__(kWave * W) void decompress_split(
                 }
             }
         }
+        };
+        if (partial) update(std::true_type{});
+        else update(std::false_type{});
     }
 }
 
