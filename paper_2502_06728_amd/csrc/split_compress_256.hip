@@ -29,6 +29,10 @@ int64_t launch_compress_split_256(const CompressLaunch& a) {
     if (kTop > 0 && p.k <= kTop) {
         if (a.grad_bf16) LAUNCH(true, kTop);
         else LAUNCH(false, kTop);
+    } else if (kQ % 32 == 0 && kQ > 32 && p.k <= 32) {
+        // ... with k <= 32 the 32 largest
+        if (a.grad_bf16) LAUNCH(true, 32);
+        else LAUNCH(false, 32);
     } else {
         if (a.grad_bf16) LAUNCH(true, 0);
         else LAUNCH(false, 0);

@@ -430,7 +430,36 @@ __global__ __launch_bounds__(kWave * W) __attribute__((amdgpu_waves_per_eu(2))) 
         else sort_desc<Q>(a);
         publish();
         __syncthreads();
-        if constexpr (W == 4) {
+        if constexpr (W == 4 && TOP > 0) {
+            // only the TOP largest of each class are in the lists (k <= TOP): the TOP largest
+            // of a pair of classes are the maxima of one list against the mirror image of the
+            // other, a bitonic sequence that the even class of the pair sorts; the odd class
+            // waits.  The pair's merged list has TOP entries.
+            uint32_t x[TOP];
+            if ((w & 1) == 0) {
+                const uint32_t* mine = lists + w * Q;
+                const uint32_t* partner = lists + (w + 1) * Q;
+                static_for<0, TOP / 4>([&](auto q) {
+                    const uint4 m4 = *reinterpret_cast<const uint4*>(mine + 4 * q);
+                    const uint4 t = *reinterpret_cast<const uint4*>(partner + TOP - 4 - 4 * q);
+                    x[4 * q] = max(m4.x, t.w);
+                    x[4 * q + 1] = max(m4.y, t.z);
+                    x[4 * q + 2] = max(m4.z, t.y);
+                    x[4 * q + 3] = max(m4.w, t.x);
+                });
+                bitonic_merge_desc<TOP>(x);
+            }
+            __syncthreads();
+            if ((w & 1) == 0) {
+                uint32_t* merged = lists + (w >> 1) * 2 * Q;
+#pragma unroll
+                for (int q = 0; q < TOP / 4; ++q)
+                    *reinterpret_cast<uint4*>(merged + 4 * q) =
+                        make_uint4(x[4 * q], x[4 * q + 1], x[4 * q + 2], x[4 * q + 3]);
+            }
+            __syncthreads();
+            T = kth_of_two_lists<TOP>(lists, lists + 2 * Q, k);
+        } else if constexpr (W == 4) {
             // classes (0,1) and (2,3): the larger half of the two lists' union to the even
             // class, the smaller half to the odd one; each half is bitonic and is sorted in
             // place.  Lists are padded with zeros (the smallest magnitude) to a power of two
