@@ -498,6 +498,6 @@ const char* detonation_status_string(int status) {
     }
 }
 
-int detonation_version(void) { return 1005; }
+int detonation_version(void) { return 1006; }
 
 }  // extern "C"

@@ -1,5 +1,7 @@
 // Two lanes per chunk: kernels for the chunk sizes whose coefficients do not fit one lane
-// (192 and 256 of the paper's Appendix B sweep), top-k selection with transmitted indices.
+// (96, 128, 192 and 256 of the paper's Appendix B sweep; decompress: 192 and 256), top-k
+// selection with transmitted indices.  They take what the wavefront-per-class kernels
+// (split_kernels.hip.h) do not: the narrow payload formats and k > S/2.
 //
 // One wavefront (= one workgroup) owns a tile of 32 complete chunks as a 32 x S matrix in LDS
 // (row = chunk), like the matrix-core kernels, but the transform is the register-resident fast

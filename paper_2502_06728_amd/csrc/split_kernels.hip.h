@@ -308,7 +308,7 @@ __device__ __forceinline__ float4 split_output(const float* __restrict__ row, in
 }
 
 // Compress half (top-k, DCT domain, fp32 values + int32 indices, k <= S/2) on full tiles of 64
-// chunks; the chunks past the last full tile go one per surplus workgroup to the general code.
+// chunks; the chunks past the last full tile form one partial tile (one more workgroup).
 // TOP > 0: for launches with k <= TOP (see the selection step).
 template <int S, int W, bool GRAD_BF16, int TOP = 0>
 __global__ __launch_bounds__(kWave * W) __attribute__((amdgpu_waves_per_eu(2))) void compress_split(
