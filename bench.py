@@ -117,6 +117,9 @@ def main() -> int:
     ap.add_argument("--replicas", type=int, default=0,
                     help="override the workload's R, the size of the replication group")
     ap.add_argument("--no-sign", action="store_true", help="update with Q itself, not sign(Q)")
+    ap.add_argument("--graph", action="store_true",
+                    help="time the step as replays of one captured HIP graph (compress + decompress "
+                         "with the step counter frozen): no launch gap between the two kernels")
     ap.add_argument("--cpu-sample", type=int, default=1 << 28)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--sources-sha", action="store_true",
@@ -248,6 +251,27 @@ def run(args) -> dict:
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
+    if getattr(args, "graph", False):
+        # the same step as one HIP graph, replayed: what is left is the kernels' own time
+        assert not diloco, "--graph times the plain step"
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+
     # ms per launch; with DiLoCo only every `every`-th step runs compress + decompress
     first = cfg.step - args.steps + 1
     sync = [e for i, e in enumerate(events) if (first + i) % every == 0] or events
@@ -301,7 +325,8 @@ def run(args) -> dict:
                    "optimizer": args.optimizer, "dct_domain": bool(cfg.scheme == 0 or args.dct),
                    "grad_dtype": str(grad.dtype).split(".")[-1],
                    "param_dtype": str(params.dtype).split(".")[-1], "momentum_dtype": "float32",
-                   "sign": w.sign, "decay": w.decay, "lr": w.lr},
+                   "sign": w.sign, "decay": w.decay, "lr": w.lr,
+                   "hip_graph": bool(getattr(args, "graph", False))},
         "step_hbm_gbs": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_hbm_frac_of_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "kernels": {
@@ -376,6 +401,23 @@ def report(args) -> int:
               f"{rec['kernels']['decompress']['gbs']:.0f} | {one['value'] / 1e6:.1f} M | "
               f"{allc['value'] / 1e6:.1f} M ({allc['cores']} cores) | "
               f"{rec['value'] / allc['value']:.0f}x |")
+    print()
+    # the small shards again as replays of a captured HIP graph (no launch gap between the kernels)
+    small = []
+    for workload in ("t5-base-1of8", "vit-b16-1of8"):
+        a = copy.copy(args)
+        a.workload, a.scheme, a.dct, a.graph = workload, "topk", False, True
+        a.steps, a.warmup, a.no_cpu = min(args.steps, 50), 5, True
+        small.append(run(a))
+    print("Small shards, the step captured in a HIP graph and replayed (kernel columns: eager run of the same step):")
+    print()
+    print("| workload | compress ms | decompress ms | step ms (graph replay) | GPU params/s | step GB/s (% of 8 TB/s) |")
+    print("|---|---|---|---|---|---|")
+    for rec in small:
+        c = rec["config"]
+        print(f"| {c['workload']} | {rec['kernels']['compress']['ms']:.4f} | {rec['kernels']['decompress']['ms']:.4f} | "
+              f"{rec['ms_per_step']:.4f} | {rec['value'] / 1e9:.1f} G | {rec['step_hbm_gbs']:.0f} "
+              f"({100 * rec['step_hbm_frac_of_peak']:.0f} %) |")
     print()
     # the ViT-B/16 sweep of the benchmark configurations: chunk x top-k x sign, R = 2, on the
     # 10.8 M-parameter shard (fp32, ragged length)
