@@ -26,16 +26,22 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 
 
 def kernel_sources_sha16() -> str:
-    """Fingerprint of the HIP sources (every file under csrc/): the counter-measured traffic
-    recorded under profiles/ is only quoted for the sources it was measured on."""
+    """Fingerprint of the HIP sources (every file under csrc/, comments and blank lines left
+    out): the counter-measured traffic recorded under profiles/ is only quoted for the code it
+    was measured on."""
     import hashlib
+    import re
     h = hashlib.sha256()
     d = os.path.join(ROOT, "paper_2502_06728_amd", "csrc")
     for name in sorted(os.listdir(d)):
         if name == "membench.hip":
             continue
+        text = open(os.path.join(d, name), encoding="utf-8").read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        text = re.sub(r"//[^\n]*", "", text)
+        code = "\n".join(l.rstrip() for l in text.splitlines() if l.strip())
         h.update(name.encode())
-        h.update(open(os.path.join(d, name), "rb").read())
+        h.update(code.encode())
     return h.hexdigest()[:16]
 
 
