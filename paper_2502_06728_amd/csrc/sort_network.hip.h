@@ -101,18 +101,28 @@ __device__ __forceinline__ void bitonic_merge_desc(uint32_t (&x)[M]) {
 
 // The TOP largest of the N keys, descending, in k[0 .. TOP); the other entries become zero
 // (the smallest key).  Whoever only needs the k-th largest for some k <= TOP does not need
-// the full order: groups of TOP are sorted, and each further group is folded into the first
-// with one row of maxima against its mirror image (the TOP largest of the two groups, as a
-// bitonic sequence) and a bitonic merge.  N = 64: 340 / 528 / 744 / 956 instructions for
-// TOP = 4 / 8 / 16 / 32 against 1,086 for the full sort.
+// the full order: groups of TOP are sorted (the last one may be shorter), and each further
+// group is folded into the first with one row of maxima against its mirror image (the TOP
+// largest of the two groups, as a bitonic sequence; a short group counts as filled up with
+// zeros, which change nothing) and a bitonic merge.  N = 64: 340 / 528 / 744 / 956
+// instructions for TOP = 4 / 8 / 16 / 32 against 1,086 for the full sort.
 template <int N, int TOP>
 __device__ __forceinline__ void sort_top_desc(uint32_t (&k)[N]) {
-    static_assert(N % TOP == 0 && (TOP & (TOP - 1)) == 0, "whole groups of a power of two");
-    static_for<0, N / TOP>([&](auto g) { sort_desc_range<TOP, g * TOP>(k); });
-    static_for<1, N / TOP>([&](auto g) {
+    static_assert(TOP <= N && (TOP & (TOP - 1)) == 0, "a power of two");
+    constexpr int kFull = N / TOP, kRest = N % TOP;
+    static_for<0, kFull>([&](auto g) { sort_desc_range<TOP, g * TOP>(k); });
+    if constexpr (kRest > 0) sort_desc_range<kRest, kFull * TOP>(k);
+    static_for<1, kFull>([&](auto g) {
         static_for<0, TOP>([&](auto i) { k[i] = max(k[i], k[g * TOP + TOP - 1 - i]); });
         bitonic_merge_desc<TOP>(k);
     });
+    if constexpr (kRest > 0) {
+        // mirror image of the short group: its entry j faces position TOP - 1 - j
+        static_for<0, kRest>([&](auto j) {
+            k[TOP - 1 - j] = max(k[TOP - 1 - j], k[kFull * TOP + j]);
+        });
+        bitonic_merge_desc<TOP>(k);
+    }
 #pragma unroll
     for (int i = TOP; i < N; ++i) k[i] = 0u;
 }

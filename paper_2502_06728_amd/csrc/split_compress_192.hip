@@ -18,17 +18,18 @@ int64_t launch_compress_split_192(const CompressLaunch& a) {
     if (tiles <= 0 || grid64 > 0x7FFFFFFF) return 0;
     const unsigned grid = static_cast<unsigned>(grid64);
     constexpr int kThreads = SplitGeom<192, 4>::kThreads;
-    // a launch with k <= 16 sorts out only every lane's 16 largest magnitudes
-    constexpr int kQ = SplitGeom<192, 4>::Q;
-    constexpr int kTop = (kQ % 16 == 0 && kQ > 16) ? 16 : 0;
+    // a launch with k <= 16 (k <= 32) sorts out only every lane's 16 (32) largest magnitudes
     int32_t* io = static_cast<int32_t*>(a.idx);
     float* vo = static_cast<float*>(a.val);
 #define LAUNCH(BF16, TOP)                                                                  \
     compress_split<192, 4, BF16, TOP><<<grid, kThreads, 0, a.stream>>>(                 \
         p, tiles, a.n, a.n_chunks, a.grad, a.mom, io, vo, a.coeff_dbg)
-    if (kTop > 0 && p.k <= kTop) {
-        if (a.grad_bf16) LAUNCH(true, kTop);
-        else LAUNCH(false, kTop);
+    if (p.k <= 16) {
+        if (a.grad_bf16) LAUNCH(true, 16);
+        else LAUNCH(false, 16);
+    } else if (p.k <= 32) {
+        if (a.grad_bf16) LAUNCH(true, 32);
+        else LAUNCH(false, 32);
     } else {
         if (a.grad_bf16) LAUNCH(true, 0);
         else LAUNCH(false, 0);

@@ -51,8 +51,12 @@ struct SplitGeom {
     static constexpr int kThreads = kWave * W;
     static constexpr int NW = (Q + 31) / 32;        // mask words per lane
     // payload staging inside a chunk's row: values at row[pos], indices at row[kIdx0 + pos]
-    // (k <= S/2); what a lane drops goes to a dump slot of its own past the tile
+    // (k <= S/2); what a lane drops goes to a dump slot of its own: past the tile in general,
+    // inside its row when k <= kRowDumpMaxK leaves room there (value at row[kRowDump + w], its
+    // index kIdx0 further on in the row's padding, row[S + w])
     static constexpr int kIdx0 = S / 2 + 4;
+    static constexpr int kRowDump = S / 2 - 4;
+    static constexpr int kRowDumpMaxK = S / 2 - 4;
     static constexpr int kBufFloats = kTile + kThreads + kIdx0;
 };
 
@@ -310,17 +314,22 @@ __device__ __forceinline__ float4 split_output(const float* __restrict__ row, in
 // Compress half (top-k, DCT domain, fp32 values + int32 indices, k <= S/2) on full tiles of 64
 // chunks; the chunks past the last full tile form one partial tile (one more workgroup).
 // TOP > 0: for launches with k <= TOP (see the selection step).
+// (three workgroups per CU where the tile and the registers allow it: chunk 192 with the
+// partial sort)
 template <int S, int W, bool GRAD_BF16, int TOP = 0>
-__global__ __launch_bounds__(kWave * W) __attribute__((amdgpu_waves_per_eu(2))) void compress_split(
+__global__ __launch_bounds__(kWave * W)
+__attribute__((amdgpu_waves_per_eu((S == 192 && TOP > 0) ? 3 : 2))) void compress_split(
     KParams p, int64_t tiles, int64_t n, int64_t n_chunks, const void* __restrict__ grad,
     float* __restrict__ mom, int32_t* __restrict__ idx_out, float* __restrict__ val_out,
     float* __restrict__ coeff_dbg) {
     using G = SplitGeom<S, W>;
     constexpr int Q = G::Q, kRow = G::kRow, NW = G::NW, kThreads = G::kThreads;
     constexpr int kIdx0 = G::kIdx0, kTile = G::kTile;
-    __shared__ __attribute__((aligned(16))) float buf[G::kBufFloats];
+    // a launch with the partial sort has k <= TOP: the dump slots fit into the rows
+    constexpr bool kRowDumps = TOP > 0 && TOP <= G::kRowDumpMaxK;
+    __shared__ __attribute__((aligned(16))) float buf[kRowDumps ? G::kTile : G::kBufFloats];
     __shared__ uint32_t s_mask[kWave][W][NW];    // kept sets: chunk, class, word
-    __shared__ int s_cnt[kWave][W];
+    __shared__ uint8_t s_cnt[kWave][W];          // kept per class (at most Q <= 64)
     __shared__ unsigned long long s_tie;         // chunks of the tile that took the tie pass
 
     const int tid = threadIdx.x;
@@ -519,7 +528,7 @@ __global__ __launch_bounds__(kWave * W) __attribute__((amdgpu_waves_per_eu(2))) 
             cnt += __popc(own[j]);
             s_mask[lane][w][j] = own[j];
         }
-        s_cnt[lane][w] = cnt;
+        s_cnt[lane][w] = static_cast<uint8_t>(cnt);
         __syncthreads();                          // also: every class is done with the lists
         int total = 0;
 #pragma unroll
@@ -586,7 +595,8 @@ __global__ __launch_bounds__(kWave * W) __attribute__((amdgpu_waves_per_eu(2))) 
             }
         }
         char* lds = reinterpret_cast<char*>(buf);
-        const uint32_t dump = static_cast<uint32_t>(sizeof(float)) * (kTile + tid);
+        const uint32_t dump = static_cast<uint32_t>(sizeof(float)) *
+                              (kRowDumps ? lane * kRow + G::kRowDump + w : kTile + tid);
         uint32_t at = static_cast<uint32_t>(sizeof(float)) * (lane * kRow + start);
         const int idx0 = off;
         static_for<0, Q>([&](auto m) {
@@ -704,6 +714,22 @@ __global__ __launch_bounds__(kWave * W) void decompress_split(
     const int my_rows = min(max(live - w * kRowsPerWave, 0), kRowsPerWave);
     const int64_t base = tile * static_cast<int64_t>(kWave * S);
     float* row = &buf[lane * kRow];
+
+    // ---- the tile's bf16 parameters, requested first: they are needed only after the
+    // transform (plain update of a full tile.  fp32 parameters, or the moments of Decoupled
+    // AdamW, held that long would cost a wavefront per SIMD in registers: they are loaded
+    // where they are used)
+    constexpr int kPieces = Q / 4;                // 4-element pieces of the tile per thread
+    uint2 early[kPieces];
+    const bool params_early = PARAM_BF16 && !partial && !p.adam;
+    if constexpr (PARAM_BF16) {
+        if (params_early) {
+#pragma unroll
+            for (int it = 0; it < kPieces; ++it)
+                early[it] = ld_u2<true>(static_cast<const uint16_t*>(params) + base +
+                                        4 * (tid + kThreads * it));
+        }
+    }
 
     // ---- zero this wavefront's rows
     {
@@ -903,8 +929,33 @@ __global__ __launch_bounds__(kWave * W) void decompress_split(
             }
         }
         };
-        if (partial) update(std::true_type{});
-        else update(std::false_type{});
+        if (params_early) {
+#pragma unroll
+            for (int it = 0; it < kPieces; ++it) {
+                const int e4 = 4 * (tid + kThreads * it);
+                const int r = e4 / S, col = e4 - r * S;
+                const int64_t i = base + e4;
+                const float4 y4 = split_output<S, W>(&buf[r * kRow], col);
+                if (presign_dbg) st_f4<false>(presign_dbg + i, y4);
+                const float y[4] = {y4.x, y4.y, y4.z, y4.w};
+                const float old[4] = {__uint_as_float(early[it].x << 16),
+                                      __uint_as_float(early[it].x & 0xFFFF0000u),
+                                      __uint_as_float(early[it].y << 16),
+                                      __uint_as_float(early[it].y & 0xFFFF0000u)};
+                float nw[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    nw[e] = fmaf(-p.lr, sign_or_self(y[e], p.use_sign), old[e] * p.wd_scale);
+                uint2 o;
+                o.x = pack_bf16x2(nw[0], nw[1]);
+                o.y = pack_bf16x2(nw[2], nw[3]);
+                *reinterpret_cast<uint2*>(static_cast<uint16_t*>(params) + i) = o;
+            }
+        } else if (partial) {
+            update(std::true_type{});
+        } else {
+            update(std::false_type{});
+        }
     }
 }
 

@@ -64,7 +64,8 @@ def test_vit_like_sweep_ragged(H, s, k, sign):
 
 @pytest.mark.parametrize("s,k", [(16, 2), (96, 6), (96, 96), (192, 12), (256, 16), (256, 256),
                                  (1, 1), (2, 1), (3, 2), (65, 7), (200, 100), (128, 30), (192, 10),
-                                 (192, 96), (192, 97), (256, 6), (256, 128), (256, 129), (96, 49)])
+                                 (192, 96), (192, 97), (256, 6), (256, 128), (256, 129), (96, 49),
+                                 (192, 16), (192, 17), (192, 32), (192, 33)])
 def test_other_chunk_sizes(H, s, k):
     cfg = Config(chunk=s, topk=k, sign=True)
     full_step(H, cfg, s * 700 + (s // 3), R=3, seed=3)
