@@ -746,57 +746,79 @@ __global__ __launch_bounds__(kWave * W) void decompress_split(
         const uint32_t magic = entry_magic(k);
         if (k % 4 == 0) {
             const int quads = my_rows * k / 4;             // 16-byte pieces per replica
-            constexpr int kBatch = 4;                      // replicas in flight
-            for (int q0 = 0; q0 < quads; q0 += kWave) {
-                const int q = q0 + lane;
-                const bool in = q < quads;
-                const uint32_t e = 4u * static_cast<uint32_t>(in ? q : 0);
+            constexpr int kBatch = 4;                      // replicas per batch
+            // A step = one batch of replicas for one group of 64 pieces.  The loads of the
+            // next step are requested before the current one is applied: two batches in
+            // flight per wavefront.
+            const int n_batches = (p.R + kBatch - 1) / kBatch;
+            const int steps = ((quads + kWave - 1) / kWave) * n_batches;
+            auto piece = [&](int t, uint32_t& e, bool& in) {
+                const int q = (t / n_batches) * kWave + lane;
+                in = q < quads;
+                e = 4u * static_cast<uint32_t>(in ? q : 0);
+            };
+            auto request = [&](int t, int4 (&iv)[kBatch], float4 (&vv)[kBatch]) {
+                uint32_t e;
+                bool in;
+                piece(t, e, in);
+                const int r0 = (t % n_batches) * kBatch;
+#pragma unroll
+                for (int b = 0; b < kBatch; ++b) {
+                    if (r0 + b < p.R && in) {
+                        const uint4 x = ld_u4<true>(idx + (r0 + b) * idx_stride + entry0 + e);
+                        iv[b] = make_int4(static_cast<int>(x.x), static_cast<int>(x.y),
+                                          static_cast<int>(x.z), static_cast<int>(x.w));
+                        vv[b] = ld_f4<true>(val + (r0 + b) * val_stride + entry0 + e);
+                    } else {
+                        iv[b] = make_int4(-1, -1, -1, -1);
+                        vv[b] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                    }
+                }
+            };
+            auto apply = [&](int t, const int4 (&iv)[kBatch], const float4 (&vv)[kBatch]) {
+                uint32_t e;
+                bool in;
+                piece(t, e, in);
+                const int r0 = (t % n_batches) * kBatch;
                 const uint32_t r = (k == 4) ? (e >> 2) : __umulhi(e, magic);   // row of the wavefront
                 const bool chunk_start = (e - r * static_cast<uint32_t>(k)) == 0u;
                 float* arow = rows + r * kRow;
-                for (int r0 = 0; r0 < p.R; r0 += kBatch) {
-                    int4 iv[kBatch];
-                    float4 vv[kBatch];
 #pragma unroll
-                    for (int b = 0; b < kBatch; ++b) {
-                        if (r0 + b < p.R && in) {
-                            const uint4 t = ld_u4<true>(idx + (r0 + b) * idx_stride + entry0 + e);
-                            iv[b] = make_int4(static_cast<int>(t.x), static_cast<int>(t.y),
-                                              static_cast<int>(t.z), static_cast<int>(t.w));
-                            vv[b] = ld_f4<true>(val + (r0 + b) * val_stride + entry0 + e);
+                for (int b = 0; b < kBatch; ++b) {
+                    if (r0 + b < p.R) {
+                        const int at[4] = {iv[b].x, iv[b].y, iv[b].z, iv[b].w};
+                        const float v[4] = {vv[b].x, vv[b].y, vv[b].z, vv[b].w};
+                        const int prev = __shfl_up(at[3], 1);
+                        const bool asc = at[0] < at[1] && at[1] < at[2] && at[2] < at[3] &&
+                                         (lane == 0 || chunk_start || prev < at[0]);
+                        if (__any(in && !asc)) {
+#pragma unroll
+                            for (int c = 0; c < 4; ++c)
+                                if (static_cast<uint32_t>(at[c]) < static_cast<uint32_t>(S))
+                                    atomicAdd(&arow[at[c]], v[c]);
                         } else {
-                            iv[b] = make_int4(-1, -1, -1, -1);
-                            vv[b] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                            float old[4];
+#pragma unroll
+                            for (int c = 0; c < 4; ++c)
+                                old[c] = (static_cast<uint32_t>(at[c]) < static_cast<uint32_t>(S))
+                                             ? arow[at[c]] : 0.0f;
+#pragma unroll
+                            for (int c = 0; c < 4; ++c)
+                                if (static_cast<uint32_t>(at[c]) < static_cast<uint32_t>(S))
+                                    arow[at[c]] = old[c] + v[c];
                         }
-                    }
-#pragma unroll
-                    for (int b = 0; b < kBatch; ++b) {
-                        if (r0 + b < p.R) {
-                            const int at[4] = {iv[b].x, iv[b].y, iv[b].z, iv[b].w};
-                            const float v[4] = {vv[b].x, vv[b].y, vv[b].z, vv[b].w};
-                            const int prev = __shfl_up(at[3], 1);
-                            const bool asc = at[0] < at[1] && at[1] < at[2] && at[2] < at[3] &&
-                                             (lane == 0 || chunk_start || prev < at[0]);
-                            if (__any(in && !asc)) {
-#pragma unroll
-                                for (int c = 0; c < 4; ++c)
-                                    if (static_cast<uint32_t>(at[c]) < static_cast<uint32_t>(S))
-                                        atomicAdd(&arow[at[c]], v[c]);
-                            } else {
-                                float old[4];
-#pragma unroll
-                                for (int c = 0; c < 4; ++c)
-                                    old[c] = (static_cast<uint32_t>(at[c]) < static_cast<uint32_t>(S))
-                                                 ? arow[at[c]] : 0.0f;
-#pragma unroll
-                                for (int c = 0; c < 4; ++c)
-                                    if (static_cast<uint32_t>(at[c]) < static_cast<uint32_t>(S))
-                                        arow[at[c]] = old[c] + v[c];
-                            }
-                            wave_lds_sync();
-                        }
+                        wave_lds_sync();
                     }
                 }
+            };
+            int4 iv0[kBatch], iv1[kBatch];
+            float4 vv0[kBatch], vv1[kBatch];
+            if (steps > 0) request(0, iv0, vv0);
+            for (int t = 0; t < steps; t += 2) {
+                if (t + 1 < steps) request(t + 1, iv1, vv1);
+                apply(t, iv0, vv0);
+                if (t + 2 < steps) request(t + 2, iv0, vv0);
+                if (t + 1 < steps) apply(t + 1, iv1, vv1);
             }
         } else {
             const int entries = my_rows * k;
