@@ -314,8 +314,10 @@ __device__ __forceinline__ float4 split_output(const float* __restrict__ row, in
 // Compress half (top-k, DCT domain, fp32 values + int32 indices, k <= S/2) on full tiles of 64
 // chunks; the chunks past the last full tile form one partial tile (one more workgroup).
 // TOP > 0: for launches with k <= TOP (see the selection step).
-// (three workgroups per CU where the tile and the registers allow it: chunk 192 with the
-// partial sort)
+// Occupancy: the workgroups of a CU are each in one phase at a time (barriers), so the number
+// of workgroups per CU is what overlaps memory phases with arithmetic.  Chunk 192 with the
+// partial sort fits three (168 registers, 52 KB of LDS with the dump slots inside the rows);
+// chunk 256 two (a 64-row tile alone is 65 KB); chunk 96 / 128 four to six of two wavefronts.
 template <int S, int W, bool GRAD_BF16, int TOP = 0>
 __global__ __launch_bounds__(kWave * W)
 __attribute__((amdgpu_waves_per_eu((S == 192 && TOP > 0) ? 3 : 2))) void compress_split(
@@ -684,9 +686,12 @@ __attribute__((amdgpu_waves_per_eu((S == 192 && TOP > 0) ? 3 : 2))) void compres
 // Scatter-add: wavefront w owns the rows [64w/W, 64(w+1)/W) of the tile, so no two wavefronts
 // ever add into the same accumulator and, inside a wavefront, LDS operations complete in program
 // order: replica after replica, deterministic.  k a multiple of 4: 16-byte loads of four
-// consecutive entries of one chunk per lane, a batch of replicas requested before the first is
-// applied; a plain read-add-write when the four indices of every lane and the step from the
-// previous lane ascend strictly (what compress emits), LDS atomics otherwise (duplicates add).
+// consecutive entries of one chunk per lane, a batch of four replicas requested at a time and
+// the next batch before the current one is applied (two batches in flight per wavefront: the
+// wavefronts of a workgroup are in this phase together, so what each keeps in flight decides
+// how busy the memory is); a plain read-add-write when the four indices of every lane and the
+// step from the previous lane ascend strictly (what compress emits), LDS atomics otherwise
+// (duplicates add).
 // Other k: one entry per lane, LDS atomics.  Then every class gathers its coefficients from
 // the rows, the inverse transform runs as in compress_split, and all wavefronts stream the
 // parameters (and the moments of Decoupled AdamW) through the update.
