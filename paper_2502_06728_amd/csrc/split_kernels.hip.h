@@ -52,8 +52,10 @@ struct SplitGeom {
     static constexpr int NW = (Q + 31) / 32;        // mask words per lane
     // payload staging inside a chunk's row: values at row[pos], indices at row[kIdx0 + pos]
     // (k <= S/2); what a lane drops goes to a dump slot of its own: past the tile in general,
-    // inside its row when k <= kRowDumpMaxK leaves room there (value at row[kRowDump + w], its
-    // index kIdx0 further on in the row's padding, row[S + w])
+    // inside its row when k <= kRowDumpMaxK leaves room there (value at row[kRowDump + a], its
+    // index kIdx0 further on in the row's padding, row[S + a]; a = lane / 16 spreads the 64
+    // lanes of a wavefront over the 64 banks: the row stride is 4 banks.  The classes of a
+    // chunk share the slot: nobody reads it)
     static constexpr int kIdx0 = S / 2 + 4;
     static constexpr int kRowDump = S / 2 - 4;
     static constexpr int kRowDumpMaxK = S / 2 - 4;
@@ -598,7 +600,7 @@ __attribute__((amdgpu_waves_per_eu((S == 192 && TOP > 0) ? 3 : 2))) void compres
         }
         char* lds = reinterpret_cast<char*>(buf);
         const uint32_t dump = static_cast<uint32_t>(sizeof(float)) *
-                              (kRowDumps ? lane * kRow + G::kRowDump + w : kTile + tid);
+                              (kRowDumps ? lane * kRow + G::kRowDump + (lane >> 4) : kTile + tid);
         uint32_t at = static_cast<uint32_t>(sizeof(float)) * (lane * kRow + start);
         const int idx0 = off;
         static_for<0, Q>([&](auto m) {
