@@ -11,10 +11,18 @@
 namespace deto {
 
 // cos(pi*t/(2s)) for t in [0, 4s): every DCT-II matrix entry is alpha_j * tab[(2i+1)j mod 4s].
+// Only the first quarter period is evaluated (double precision, rounded once); the other three
+// follow by symmetry.
 __device__ __forceinline__ void build_cos_table(float* tab, int s, int lane) {
-    for (int t = lane; t < 4 * s; t += kWave)
-        tab[t] = static_cast<float>(cos(3.14159265358979323846 * static_cast<double>(t) /
-                                        (2.0 * static_cast<double>(s))));
+    for (int t = lane; t <= s; t += kWave) {
+        float c = static_cast<float>(cos(3.14159265358979323846 * static_cast<double>(t) /
+                                         (2.0 * static_cast<double>(s))));
+        if (t == s) c = 0.0f;
+        tab[t] = c;
+        tab[2 * s - t] = -c;
+        tab[2 * s + t] = -c;
+        if (t > 0) tab[4 * s - t] = c;
+    }
 }
 
 // Striding / Random: flag[e] = 1 for the positions the scheme keeps in chunk `c`.
@@ -192,6 +200,9 @@ __device__ __forceinline__ void compress_generic_chunks(
             if (p.use_dct) {
                 acc = 0.0f;
                 int ph = e;
+                // (unrolled so that the LDS reads of several terms are in flight together; the
+                // additions keep their order)
+#pragma unroll 8
                 for (int t = 0; t < s; ++t) {
                     acc = fmaf(x[t], tab[ph], acc);
                     ph += 2 * e;
@@ -210,6 +221,7 @@ __device__ __forceinline__ void compress_generic_chunks(
             for (int e = lane; e < s; e += kWave) {
                 const uint32_t me = __float_as_uint(cf[e]) & 0x7FFFFFFFu;
                 int rank = 0;
+#pragma unroll 8
                 for (int t = 0; t < s; ++t) {
                     const uint32_t o = __float_as_uint(cf[t]) & 0x7FFFFFFFu;
                     rank += (o > me || (o == me && t < e)) ? 1 : 0;
@@ -239,6 +251,7 @@ __device__ __forceinline__ void compress_generic_chunks(
             float q;
             if (p.use_dct) {
                 q = 0.0f;
+#pragma unroll 4
                 for (int j = 0; j < k; ++j) {
                     const int r = sidx[j];
                     const float a = (r == 0) ? p.alpha0 : p.alpha;
@@ -293,22 +306,46 @@ __device__ __forceinline__ void decompress_generic_chunks(
         } else {
             __syncthreads();
         }
-        // scatter-add, one replica after the other so the order of additions is fixed
-        for (int r = 0; r < p.R; ++r) {
-            for (int j = lane; j < k; j += kWave) {
-                const int at =
-                    idx ? load_payload_index(idx, r * idx_stride + c * k + j, p.idx_u8) : sidx[j];
-                if (at >= 0 && at < s) {
-                    const float v =
-                        (p.val_dtype == 3)
-                            ? ternary_decode(static_cast<const uint32_t*>(
-                                                 val)[r * val_stride +
-                                                      c * ternary_words_per_chunk(k) + (j >> 4)], j)
-                            : load_payload_value(val, r * val_stride + c * k + j, p.val_dtype);
-                    atomicAdd(&a[at], v);
+        // scatter-add, one replica after the other so the order of additions is fixed.  An
+        // entry's index and value are requested together, and (k <= 64: one entry per lane)
+        // those of four replicas before the first is added.
+        auto entry = [&](int r, int j, int& at, float& v) {
+            at = idx ? load_payload_index(idx, r * idx_stride + c * k + j, p.idx_u8) : sidx[j];
+            v = (p.val_dtype == 3)
+                    ? ternary_decode(static_cast<const uint32_t*>(
+                                         val)[r * val_stride + c * ternary_words_per_chunk(k) +
+                                              (j >> 4)], j)
+                    : load_payload_value(val, r * val_stride + c * k + j, p.val_dtype);
+        };
+        if (k <= kWave) {
+            constexpr int kBatch = 4;
+            for (int r0 = 0; r0 < p.R; r0 += kBatch) {
+                int at[kBatch];
+                float v[kBatch];
+#pragma unroll
+                for (int b = 0; b < kBatch; ++b) {
+                    at[b] = -1;
+                    v[b] = 0.0f;
+                    if (r0 + b < p.R && lane < k) entry(r0 + b, lane, at[b], v[b]);
+                }
+#pragma unroll
+                for (int b = 0; b < kBatch; ++b) {
+                    if (r0 + b < p.R) {
+                        if (at[b] >= 0 && at[b] < s) atomicAdd(&a[at[b]], v[b]);
+                        __syncthreads();
+                    }
                 }
             }
-            __syncthreads();
+        } else {
+            for (int r = 0; r < p.R; ++r) {
+                for (int j = lane; j < k; j += kWave) {
+                    int at;
+                    float v;
+                    entry(r, j, at, v);
+                    if (at >= 0 && at < s) atomicAdd(&a[at], v);
+                }
+                __syncthreads();
+            }
         }
         for (int e = lane; e < s; e += kWave) {
             const int64_t i = base + e;
@@ -317,6 +354,7 @@ __device__ __forceinline__ void decompress_generic_chunks(
             if (p.use_dct) {
                 y = 0.0f;
                 int ph = 0;
+#pragma unroll 8
                 for (int j = 0; j < s; ++j) {
                     const float al = (j == 0) ? p.alpha0 : p.alpha;
                     y = fmaf(tab[ph], al * (a[j] * p.inv_R), y);
