@@ -39,6 +39,11 @@
  *     replica offset r*stride, so the contiguous [R][C*k] buffer an all_gather returns always
  *     qualifies for fp32 + int32 payloads.  Buffers that do not meet this are still processed
  *     correctly, by general kernels that are more than ten times slower.
+ *   - Environment.  DETO_SMALL_SHARD_TILES (a count of 64-chunk tiles, default 8192; read at
+ *     every call) is the shard size up to which the compress half at chunk size 64 and 128
+ *     (top-k, fp32 + int32 payload) spreads a tile over more wavefronts: shorter launches on
+ *     small shards, a few per cent longer ones on large shards.  0 switches it off.  The
+ *     results of the two kernel choices agree to rounding.
  */
 #ifndef DETONATION_H
 #define DETONATION_H

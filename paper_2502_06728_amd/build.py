@@ -21,9 +21,9 @@ HIPCC_FLAGS = [
 # one translation unit per kernel family, compiled side by side
 # (the longest-compiling units first)
 UNITS = [
-    # a wavefront per coefficient class (chunk 96, 128, 192, 256)
+    # a wavefront per coefficient class (chunk 96, 128, 192, 256; 64 on small shards)
     "split_compress_256.hip", "split_compress_192.hip", "split_compress_128.hip",
-    "split_compress_96.hip", "split_decompress.hip",
+    "split_compress_96.hip", "split_compress_64.hip", "split_decompress.hip",
     # two lanes per chunk (chunk 96, 128, 192, 256)
     "pair_compress_256.hip", "pair_compress_192.hip", "pair_compress_128.hip",
     "pair_compress_96.hip", "pair_decompress.hip",

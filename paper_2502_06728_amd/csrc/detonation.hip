@@ -180,9 +180,11 @@ int detonation_compress_packed(const deto_config* cfg, int64_t n, const void* gr
         deto::CompressLaunch a{p, tiles, n, C, grad, grad_dtype == DETO_BF16, momentum, idx_out,
                                val_out, coeff_dbg, {0, 0, 0, 0}, st};
         stride_pattern(p, a.stride_mask);
+        // (chunk 64 on a small shard: two wavefronts per tile, see small_shard_tiles)
         const bool done = tiles == 0 ? false
                           : (p.scheme == DETO_SCHEME_TOPK)
-                              ? (deto::launch_compress_topk_s64(a) ||
+                              ? (deto::launch_compress_split_64(a) > 0 ||
+                                 deto::launch_compress_topk_s64(a) ||
                                  deto::launch_compress_topk_s32(a) ||
                                  deto::launch_compress_topk_s16(a) ||
                                  deto::launch_compress_topk_packed(a) ||

@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "deto_device.hip.h"
 
@@ -41,6 +42,22 @@ struct DecompressLaunch {
     hipStream_t stream;
     AdamPtrs adam;          // moment arrays when p.adam
 };
+
+// A shard of at most this many 64-chunk tiles counts as small: the launch is a few occupancy
+// rounds long, so what a tile takes from its first load to its last store decides the duration,
+// not the instructions per element.  The compress half then spreads a tile over more wavefronts
+// (chunk 64: two coefficient classes instead of a lane per chunk; chunk 128: four instead of
+// two).  Measured on MI355X: 4 - 13 % shorter launches at 1,300 - 8,000 tiles, 4 - 5 % longer
+// ones at 36,000.  The environment variable DETO_SMALL_SHARD_TILES overrides the limit (0: never).
+inline int64_t small_shard_tiles() {
+    const char* e = getenv("DETO_SMALL_SHARD_TILES");
+    if (e && *e) {
+        char* end = nullptr;
+        const long long v = strtoll(e, &end, 10);
+        if (end != e && v >= 0) return static_cast<int64_t>(v);
+    }
+    return 8192;
+}
 
 // grid of a launch: one workgroup per tile plus one per tail chunk
 inline unsigned tiled_grid(int64_t tiles, int64_t n_chunks) {
@@ -112,6 +129,8 @@ int64_t launch_decompress_pair(const DecompressLaunch& a);
 // Lane per chunk, wavefront per coefficient class (split_kernels.hip.h): tiles of 64 chunks,
 // fp32 + int32 payloads with k <= s/2.  Same return convention.
 int64_t launch_decompress_split(const DecompressLaunch& a);      // chunk 192, 256
+// chunk 64 on a small shard only (see small_shard_tiles); tried before the lane-per-chunk kernel
+int64_t launch_compress_split_64(const CompressLaunch& a);
 int64_t launch_compress_split_96(const CompressLaunch& a);
 int64_t launch_compress_split_128(const CompressLaunch& a);
 int64_t launch_compress_split_192(const CompressLaunch& a);

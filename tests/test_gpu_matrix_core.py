@@ -127,6 +127,7 @@ def test_decoupled_adamw(H, amsgrad, s, k):
         assert (np.abs(got - want) <= parity.TOL_F32 * np.abs(want) + parity.TOL_F32 * cfg.lr).all()
 
 
+@pytest.mark.size_dispatch
 @pytest.mark.timeout(600)
 @pytest.mark.parametrize("s,k", [(128, 64), (256, 32), (96, 12)])
 def test_olmo_1b_shard_full_size_chunk_sweep(H, s, k):

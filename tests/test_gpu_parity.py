@@ -108,6 +108,10 @@ def test_chunk_size_96(H, k, bf16):
 @pytest.mark.parametrize("s,k", [(96, 12), (128, 16), (128, 64), (128, 6), (192, 24), (192, 10),
                                  (256, 32), (256, 128), (256, 20)])
 def test_ties_above_chunk_64(H, s, k):
+    tie_case(H, s, k)
+
+
+def tie_case(H, s, k):
     # zero chunks tie everywhere; single spikes give coefficients of pairwise equal magnitude;
     # chunks of +-1 patterns tie in groups.  Mixed with ordinary chunks in the same tiles, so
     # that the whole-wavefront tie pass and the staged path meet in one workgroup; a ragged tail.
@@ -281,6 +285,7 @@ def test_deterministic_and_debug_outputs_do_not_change_results(H):
     assert np.array_equal(p1, p2)
 
 
+@pytest.mark.size_dispatch
 def test_t5_base_shard_full_size(H):
     # the T5-base-shaped 1/8 shard (27.9M parameters), chunk 64, top-k 32, R = 2
     w = synth.workloads()["t5-base-1of8"]
@@ -291,6 +296,7 @@ def test_t5_base_shard_full_size(H):
     assert st_c["chunks"] == 435_357
 
 
+@pytest.mark.size_dispatch
 @pytest.mark.parametrize("sign", [True, False])
 @pytest.mark.parametrize("s,k", [(s, k) for s in (32, 64, 128) for k in (1, 4, 16, s // 2)])
 def test_vit_b16_shard_full_size(H, s, k, sign):
@@ -380,6 +386,7 @@ def _full_size_check(H, w, cfg, ranges=None):
     return worst
 
 
+@pytest.mark.size_dispatch
 def test_olmo_1b_shard_full_size_bench_configuration(H):
     # the benchmark's workload: 147,095,552 parameters, bf16 grads/params with outliers,
     # chunk 64, top-k 32, R = 4
@@ -391,6 +398,7 @@ def test_olmo_1b_shard_full_size_bench_configuration(H):
     assert worst["chunks"] == 2_298_368      # every chunk of the shard went through the oracle
 
 
+@pytest.mark.size_dispatch
 @pytest.mark.parametrize("scheme,dct", [(SCHEME_STRIDE, False), (SCHEME_RANDOM, False),
                                         (SCHEME_STRIDE, True)])
 def test_olmo_1b_shard_full_size_striding_random(H, scheme, dct):
@@ -404,6 +412,7 @@ def test_olmo_1b_shard_full_size_striding_random(H, scheme, dct):
     assert worst["chunks"] == 2_298_368
 
 
+@pytest.mark.size_dispatch
 @pytest.mark.timeout(900)
 @pytest.mark.parametrize("scheme,dct", [(SCHEME_TOPK, False), (SCHEME_STRIDE, False),
                                         (SCHEME_RANDOM, False), (SCHEME_RANDOM, True)])
