@@ -19,7 +19,10 @@ def _kernel_choice_by_shard_size(request, monkeypatch):
     would all run the small-shard choice: unless a test asks for the library's own choice
     (marker size_dispatch: the full-size workloads) or sets the variable itself
     (tests/test_gpu_small_shards.py runs both choices), the limit is 0 here and the kernels
-    of large shards run."""
+    of large shards run.  DETO_TEST_SIZE_DISPATCH_EVERYWHERE=1 in the environment of a pytest run
+    leaves the choice to the library in every test."""
+    if os.environ.get("DETO_TEST_SIZE_DISPATCH_EVERYWHERE"):
+        return      # a run of the whole suite on the library's own choice
     if request.node.get_closest_marker("size_dispatch") is None:
         monkeypatch.setenv("DETO_SMALL_SHARD_TILES", "0")
     else:
