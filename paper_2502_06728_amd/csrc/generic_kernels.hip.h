@@ -347,19 +347,28 @@ __device__ __forceinline__ void decompress_generic_chunks(
                 __syncthreads();
             }
         }
+        if (p.use_dct) {
+            // the averaged coefficients with their scale factors, once per chunk
+            for (int e = lane; e < s; e += kWave)
+                a[e] = ((e == 0) ? p.alpha0 : p.alpha) * (a[e] * p.inv_R);
+            __syncthreads();
+        }
         for (int e = lane; e < s; e += kWave) {
             const int64_t i = base + e;
             if (i >= n) continue;
             float y;
             if (p.use_dct) {
+                // y_e = sum_j tab[(2e+1) j mod 4s] a_j, the table position kept in bytes
                 y = 0.0f;
-                int ph = 0;
+                const uint32_t period = 16u * static_cast<uint32_t>(s);
+                const uint32_t step = 4u * static_cast<uint32_t>(2 * e + 1);
+                const char* tab_bytes = reinterpret_cast<const char*>(tab);
+                uint32_t ph = 0u;
 #pragma unroll 8
                 for (int j = 0; j < s; ++j) {
-                    const float al = (j == 0) ? p.alpha0 : p.alpha;
-                    y = fmaf(tab[ph], al * (a[j] * p.inv_R), y);
-                    ph += 2 * e + 1;
-                    if (ph >= 4 * s) ph -= 4 * s;
+                    y = fmaf(*reinterpret_cast<const float*>(tab_bytes + ph), a[j], y);
+                    ph += step;
+                    ph = min(ph, ph - period);      // ph -= period where ph >= period
                 }
             } else {
                 y = a[e] * p.inv_R;
