@@ -1,6 +1,9 @@
 // Lane-per-chunk, wavefront-per-coefficient-class decompress-and-update kernels (chunk sizes 192
 // and 256: four classes; transmitted indices, fp32 values + int32 indices; plain SGD update or
-// Decoupled AdamW).
+// Decoupled AdamW).  Two classes at chunk 64, 96 and 128 for what the lane-per-chunk kernels of
+// those sizes are not instantiated for (they take k as a template argument and do not include
+// Decoupled AdamW above chunk 64): any k at run time, about a fifth slower than a lane per chunk,
+// several times faster than the matrix-core and general kernels that served such shapes before.
 #include "split_kernels.hip.h"
 #include "tiled_launch.h"
 
@@ -31,7 +34,7 @@ int64_t launch_decompress_split(const DecompressLaunch& a) {
                 a.adam, a.presign_dbg);                                                         \
         return a.n_chunks;   /* the tail chunks ride along */                                   \
     }
-    X(192, 4) X(256, 4)
+    X(192, 4) X(256, 4) X(64, 2) X(96, 2) X(128, 2)
 #undef X
     return 0;
 #endif

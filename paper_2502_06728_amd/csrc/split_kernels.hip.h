@@ -828,15 +828,33 @@ __global__ __launch_bounds__(kWave * W) void decompress_split(
                 if (t + 1 < steps) apply(t + 1, iv1, vv1);
             }
         } else {
+            // one entry per lane, LDS atomics; four groups of 64 entries requested together
             const int entries = my_rows * k;
+            constexpr int kGroups = 4;
             for (int r = 0; r < p.R; ++r) {
-                for (int e = lane; e < entries; e += kWave) {
-                    const uint32_t rr = (k == 1) ? static_cast<uint32_t>(e)
-                                                 : __umulhi(static_cast<uint32_t>(e), magic);
-                    const int at = idx[r * idx_stride + entry0 + e];
-                    const float v = val[r * val_stride + entry0 + e];
-                    if (static_cast<uint32_t>(at) < static_cast<uint32_t>(S))
-                        atomicAdd(&rows[rr * kRow + at], v);
+                const int32_t* ir = idx + r * idx_stride + entry0;
+                const float* vr = val + r * val_stride + entry0;
+                for (int e0 = 0; e0 < entries; e0 += kGroups * kWave) {
+                    int at[kGroups];
+                    float v[kGroups];
+#pragma unroll
+                    for (int g = 0; g < kGroups; ++g) {
+                        const int e = e0 + g * kWave + lane;
+                        at[g] = -1;
+                        v[g] = 0.0f;
+                        if (e < entries) {
+                            at[g] = ir[e];
+                            v[g] = vr[e];
+                        }
+                    }
+#pragma unroll
+                    for (int g = 0; g < kGroups; ++g) {
+                        const int e = e0 + g * kWave + lane;
+                        const uint32_t rr = (k == 1) ? static_cast<uint32_t>(e)
+                                                     : __umulhi(static_cast<uint32_t>(e), magic);
+                        if (e < entries && static_cast<uint32_t>(at[g]) < static_cast<uint32_t>(S))
+                            atomicAdd(&rows[rr * kRow + at[g]], v[g]);
+                    }
                 }
             }
         }

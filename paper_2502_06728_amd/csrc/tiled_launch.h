@@ -128,7 +128,7 @@ int64_t launch_decompress_pair(const DecompressLaunch& a);
 
 // Lane per chunk, wavefront per coefficient class (split_kernels.hip.h): tiles of 64 chunks,
 // fp32 + int32 payloads with k <= s/2.  Same return convention.
-int64_t launch_decompress_split(const DecompressLaunch& a);      // chunk 192, 256
+int64_t launch_decompress_split(const DecompressLaunch& a);      // chunk 192, 256; 64, 96, 128 at other k
 // chunk 64 on a small shard only (see small_shard_tiles); tried before the lane-per-chunk kernel
 int64_t launch_compress_split_64(const CompressLaunch& a);
 int64_t launch_compress_split_96(const CompressLaunch& a);
