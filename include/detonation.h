@@ -278,7 +278,7 @@ int64_t detonation_ternary_words(const deto_config* cfg, int64_t n);
 /* Static, human-readable name of a deto_status. */
 const char* detonation_status_string(int status);
 
-/* ABI version of this header: major*1000 + minor (1001: the *_packed entry points; 1002: Decoupled AdamW; 1003: DETO_TERNARY; 1004: detonation_accumulate; 1005: detonation_decompress_adamw_step_packed; 1006: R > 64 is DETO_ERR_UNSUPPORTED, payload alignment by lane access, last-error reset). */
+/* ABI version of this header: major*1000 + minor (1001: the *_packed entry points; 1002: Decoupled AdamW; 1003: DETO_TERNARY; 1004: detonation_accumulate; 1005: detonation_decompress_adamw_step_packed; 1006: R > 64 is DETO_ERR_UNSUPPORTED, payload alignment by lane access, last-error reset; 1007: kernel choice by shard size, DETO_SMALL_SHARD_TILES). */
 int detonation_version(void);
 
 #ifdef __cplusplus

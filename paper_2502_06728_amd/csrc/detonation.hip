@@ -500,6 +500,6 @@ const char* detonation_status_string(int status) {
     }
 }
 
-int detonation_version(void) { return 1006; }
+int detonation_version(void) { return 1007; }
 
 }  // extern "C"

@@ -33,7 +33,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_version_and_status_strings(lib):
-    assert binding.version() == 1006
+    assert binding.version() == 1007
     assert binding.status_string(0) == "ok"
     assert len({binding.status_string(i) for i in range(6)}) == 6
 
