@@ -575,7 +575,11 @@ def test_packed_striding_random_values_only(H):
 @pytest.mark.parametrize("amsgrad", [False, True])
 @pytest.mark.parametrize("s,k,n,params_bf16", [(64, 32, 64 * 2500 + 7, True), (64, 16, 64 * 1000, False),
                                                (32, 8, 32 * 900 + 3, False), (32, 16, 32 * 4000 + 9, True),
-                                               (32, 2, 32 * 3000, False), (32, 1, 32 * 3000 + 1, True)])
+                                               (32, 2, 32 * 3000, False), (32, 1, 32 * 3000 + 1, True),
+                                               # the wavefront-per-class decompress (any k, AdamW)
+                                               (64, 20, 64 * 700 + 9, True), (64, 5, 64 * 500 + 3, False),
+                                               (96, 10, 96 * 300 + 5, True), (96, 12, 96 * 200, False),
+                                               (128, 30, 128 * 300 + 1, False), (128, 16, 128 * 200, True)])
 def test_decoupled_adamw_steps(H, amsgrad, s, k, n, params_bf16):
     """Decoupled AdamW as the underlying optimizer (section "Decoupled AdamW"): T steps with
     local moments; every step is judged from the GPU's own state, sign decided on the GPU's
