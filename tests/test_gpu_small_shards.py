@@ -3,6 +3,7 @@ DETO_SMALL_SHARD_TILES): a small shard spreads every 64-chunk tile over more wav
 two coefficient classes instead of a lane per chunk; chunk 128: four classes instead of two).
 Both choices against the oracle on the same inputs: every k family, bf16 and fp32 storage,
 partial tiles with a ragged last chunk, ties."""
+import numpy as np
 import pytest
 
 from oracle import Config
@@ -54,3 +55,29 @@ def test_default_limit_is_between_the_benchmark_shards(H, monkeypatch):
     monkeypatch.delenv("DETO_SMALL_SHARD_TILES", raising=False)
     cfg = Config(chunk=64, topk=16, sign=True)
     full_step(H, cfg, 64 * (64 * 30 + 5) + 7, R=2, seed=5)
+
+
+def _random_shapes():
+    """Seeded shapes over the chunk sizes of the wavefront-per-class kernels: any k up to the chunk
+    size, shard lengths with every kind of tail (none, whole chunks, a ragged chunk, fewer
+    chunks than one tile), R, storage type."""
+    rng = np.random.default_rng(20250206728)
+    shapes = []
+    for i in range(48):
+        s = int(rng.choice([64, 96, 128, 192, 256]))
+        k = int(rng.integers(1, s + 1)) if i % 4 == 0 else int(rng.integers(1, s // 2 + 1))
+        tiles = int(rng.integers(0, 4))
+        tail_chunks = int(rng.integers(0, 64))
+        ragged = int(rng.integers(0, s)) if i % 3 else 0
+        n = s * (64 * tiles + tail_chunks) + ragged
+        if n == 0:
+            n = s + 1
+        shapes.append((s, k, n, int(rng.integers(1, 6)), bool(i % 2)))
+    return shapes
+
+
+@pytest.mark.parametrize("s,k,n,R,bf16", _random_shapes())
+def test_random_shapes(H, choice, s, k, n, R, bf16):
+    cfg = Config(chunk=s, topk=k, sign=bool(k % 2))
+    full_step(H, cfg, n, R=R, seed=n % 1000, grad_bf16=bf16, params_bf16=bf16,
+              outliers=0.01 if bf16 else 0.0)
