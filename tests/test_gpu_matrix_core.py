@@ -129,10 +129,12 @@ def test_decoupled_adamw(H, amsgrad, s, k):
 
 @pytest.mark.size_dispatch
 @pytest.mark.timeout(600)
-@pytest.mark.parametrize("s,k", [(128, 64), (256, 32), (96, 12)])
+@pytest.mark.parametrize("s,k", [(128, 64), (256, 32), (96, 12), (192, 24), (128, 16), (64, 20)])
 def test_olmo_1b_shard_full_size_chunk_sweep(H, s, k):
     # the OLMo-1B shard (147,095,552 parameters) at the larger chunk sizes of the Appendix B
     # sweep, in the launch configuration bench.py --chunk/--topk times; sampled chunk runs
+    # ((64, 20): a k the lane-per-chunk kernels are not instantiated for, so the two-class
+    # kernels at full size)
     import dataclasses
     from tests.test_gpu_parity import _full_size_check, _sample_runs
     w = dataclasses.replace(synth.workloads()["olmo-1b-1of8"], chunk=s, topk=k)
